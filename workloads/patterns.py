@@ -1,0 +1,126 @@
+"""Backend-pattern registries B = [(pattern p, backend d), ...] as plain data
+(paper Sec. 3 explicit pattern specification and Sec. 4.1: b = (p, d)).
+
+A pattern is a sink-rooted tree written the way the paper's pattern language
+writes it: P("relu", P("add", P("conv2d", W, W, groups=(1, 1)), W)) is
+relu(add(conv2d(*, *), *)) with the constraint 1 <= groups <= 1 on the
+convolution.  W is the wildcard: it matches any value and is not part of the
+matched subgraph.  Registration order is significant (ties are broken by it).
+
+A "backend" here is one of the kernel families of the GPU library; the oracle
+only uses the names as identifiers.
+"""
+from __future__ import annotations
+
+W = "*"
+
+# attribute names a constraint may refer to, in the order of the C enum
+ATTR_NAMES = ("groups", "kernel_h", "kernel_w", "stride_h", "stride_w",
+              "pad_h", "pad_w", "transpose_b", "axis")
+
+
+def P(op: str, *args, **constraints):
+    for k, v in constraints.items():
+        assert k in ATTR_NAMES, k
+        assert len(v) == 2
+    return (op, tuple(args), tuple(sorted((k, (int(v[0]), int(v[1])))
+                                          for k, v in constraints.items())))
+
+
+def pattern_ops(p) -> int:
+    """Number of operator (non-wildcard) nodes in a pattern."""
+    if p == W:
+        return 0
+    return 1 + sum(pattern_ops(a) for a in p[1])
+
+
+def _tails(anchor, tails):
+    """anchor followed by each listed chain of unary/binary elementwise ops;
+    a binary op takes the chain as its first operand and a wildcard second."""
+    out = []
+    for chain in tails:
+        p = anchor
+        for op in chain:
+            if op in ("bias_add", "add"):
+                p = P(op, p, W)
+            else:
+                p = P(op, p)
+        out.append(p)
+    return out
+
+
+def default_registry(variants=("igemm",)):
+    """The registry the benchmarks and the GPU parity tests use.  `variants`
+    lists the MFMA implicit-GEMM kernel variants to register as separate
+    backends (same patterns each), so that the search can pick a tile
+    configuration per layer."""
+    reg = []
+
+    def add(backend, pats):
+        reg.extend((backend, p) for p in pats)
+
+    # --- glue: every primitive elementwise / layout op alone, plus short fusions
+    ew_single = [P("bias_add", W, W), P("add", W, W), P("mul_scalar", W),
+                 P("relu", W), P("gelu", W), P("tanh", W), P("take", W, W),
+                 P("reshape", W), P("transpose", W)]
+    ew_fused = [P("relu", P("add", W, W)),
+                P("relu", P("bias_add", W, W)),
+                P("gelu", P("bias_add", W, W)),
+                P("tanh", P("bias_add", W, W)),
+                P("add", P("bias_add", W, W), W),
+                P("relu", P("add", P("bias_add", W, W), W)),
+                P("add", P("add", P("take", W, W), W), W),
+                P("transpose", P("reshape", W)),
+                P("reshape", P("transpose", W))]
+    add("eltwise", ew_single + ew_fused)
+
+    # --- row-wise reductions
+    add("rowwise", [P("softmax", W), P("layer_norm", W, W, W),
+                    P("softmax", P("mul_scalar", W)),
+                    P("layer_norm", P("add", W, W), W, W),
+                    P("layer_norm", P("add", P("bias_add", W, W), W), W, W)])
+
+    # --- direct (non-GEMM) spatial kernels: any conv incl. grouped, pools
+    conv_any = P("conv2d", W, W)
+    add("direct", _tails(conv_any, [(), ("bias_add",), ("bias_add", "relu"),
+                                    ("bias_add", "add"),
+                                    ("bias_add", "add", "relu")]))
+    add("direct", [P("max_pool2d", W), P("global_avg_pool2d", W)])
+
+    # --- MFMA implicit GEMM / GEMM variants
+    for be in variants:
+        conv = P("conv2d", W, W, groups=(1, 1))
+        add(be, _tails(conv, [(), ("bias_add",), ("bias_add", "relu"),
+                              ("bias_add", "add"),
+                              ("bias_add", "add", "relu")]))
+        dense = P("dense", W, W)
+        add(be, _tails(dense, [(), ("bias_add",), ("bias_add", "relu"),
+                               ("bias_add", "gelu"), ("bias_add", "add"),
+                               ("bias_add", "relu", "reshape")]))
+        add(be, [P("batch_matmul", W, W),
+                 P("mul_scalar", P("batch_matmul", W, W))])
+        convt = P("conv2d_transpose", W, W)
+        add(be, _tails(convt, [(), ("bias_add",), ("bias_add", "relu"),
+                               ("bias_add", "tanh")]))
+    return reg
+
+
+def small_registry():
+    """Two abstract backends over conv / bias / add / relu / tanh / mul_scalar
+    for the CPU-only placement-search tests (random DAGs)."""
+    reg = []
+    singles = [P("conv2d", W, W), P("bias_add", W, W), P("add", W, W),
+               P("relu", W), P("tanh", W), P("mul_scalar", W)]
+    reg += [("A", p) for p in singles]
+    conv = P("conv2d", W, W)
+    reg += [("B", p) for p in _tails(conv, [(), ("bias_add",),
+                                            ("bias_add", "relu"),
+                                            ("bias_add", "add", "relu"),
+                                            ("relu",), ("add", "relu")])]
+    reg += [("B", P("relu", P("add", W, W))),
+            ("B", P("relu", P("bias_add", W, W))),
+            ("B", P("add", P("relu", W), P("relu", W))),
+            ("A", P("tanh", P("add", W, W))),
+            ("A", P("mul_scalar", P("tanh", W))),
+            ("A", P("add", P("mul_scalar", W), W))]
+    return reg
