@@ -1,0 +1,194 @@
+#!/usr/bin/env python3
+"""Benchmark: batch-1 fp32 inference latency of ResNet-50 v1.5 (headline) and
+BERT-base seq 128 on one MI355X, run as a sequence of fused-operator kernels
+under the placement the library's own measurer + dynamic programme choose.
+
+    python bench.py --gpus 1 --steps 200 --warmup 20
+
+A step is one pass of the compiled kernel sequence over one synthetic input
+that is already resident in HBM.  The set-up part of the path (registration,
+match enumeration, per-subgraph cost profiling, placement search, compile) runs
+once before the timed region; its wall time is reported under "optimise".
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_F32_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
+PEAK_HBM_GBPS = 8000.0            # MI355X HBM3E
+
+
+def optimise(desc, reg, opts):
+    """register -> match -> profile -> search -> compile; returns pieces + timings."""
+    import paper_2111_00655_amd as clg
+    t0 = time.perf_counter()
+    s = clg.Session(desc, reg, device=0)
+    t1 = time.perf_counter()
+    ms = s.match()
+    t2 = time.perf_counter()
+    costs = s.profile(opts)
+    t3 = time.perf_counter()
+    total, ids = s.search(costs, 0)
+    t4 = time.perf_counter()
+    plan = s.compile(ids).bind()
+    t5 = time.perf_counter()
+    timing = dict(build_graph_s=t1 - t0, match_s=t2 - t1, profile_s=t3 - t2, search_s=t4 - t3,
+                  compile_s=t5 - t4, n_matches=len(ms), n_kernels=plan.n_kernels,
+                  predicted_ms=total / 1e6)
+    return s, plan, costs, ids, timing
+
+
+def time_steps(plan, steps, warmup):
+    import torch
+    for _ in range(warmup):
+        plan.execute()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        plan.execute()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def kernel_table(plan, reps=20):
+    """Per-kernel durations (HIP events around every launch, on the launch
+    stream), averaged over `reps` passes."""
+    import numpy as np
+    plan.execute_timed()
+    acc = np.zeros(plan.n_kernels)
+    for _ in range(reps):
+        acc += plan.execute_timed()
+    ns = acc / reps
+    rows = []
+    for k, t in zip(plan.kernels(), ns):
+        r = dict(k)
+        r["ns"] = float(t)
+        r["tflops"] = k["flops"] / t / 1e3 if t > 0 else 0.0
+        r["gbps"] = k["bytes"] / t if t > 0 else 0.0
+        rows.append(r)
+    return rows
+
+
+def roofline_of(rows):
+    """Dominant kernel family = the MFMA implicit-GEMM kernels (convolutions /
+    GEMMs): algorithmic flops of all their launches in one step over the summed
+    launch durations."""
+    mf = [r for r in rows if r["bound"] == "mfma"]
+    t = sum(r["ns"] for r in mf)
+    fl = sum(r["flops"] for r in mf)
+    achieved = fl / t / 1e3 if t > 0 else 0.0
+    return dict(bound="mfma", achieved=round(achieved, 3), peak=PEAK_MFMA_F32_TFLOPS, unit="TFLOP/s",
+                frac=round(achieved / PEAK_MFMA_F32_TFLOPS, 5), traffic=None,
+                kernel="igemm_kernel (all MFMA launches of one step)", launches=len(mf),
+                avg_launch_us=round(t / max(len(mf), 1) / 1e3, 3),
+                share_of_kernel_time=round(t / max(sum(r["ns"] for r in rows), 1), 4))
+
+
+def cpu_baseline(desc):
+    """The oracle as it stands, one full forward pass on the host cores."""
+    from oracle.graph import Graph
+    from oracle import ops
+    g = Graph(desc)
+    g.run()                                   # page in weights / warm the library
+    t0 = time.perf_counter()
+    g.run()
+    dt = time.perf_counter() - t0
+    return dict(value=round(dt * 1e3, 2), unit="ms", cores=ops.max_threads(), kind="oracle",
+                sample="one full batch-1 forward pass of the same graph (all layers), second of two runs")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--model", default="resnet50", help="headline workload (resnet50 | bert_base | ...)")
+    ap.add_argument("--no-extra", action="store_true", help="skip the secondary workloads")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--dump", default="", help="write the per-kernel table to this JSON file")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: batch-1 inference of one graph is a dependency chain and "
+              "nothing here shards across GPUs; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (torch.cuda.is_available() is False)", file=sys.stderr)
+        sys.exit(2)
+    import workloads as wl
+    from paper_2111_00655_amd import binding as B
+
+    reg = wl.default_registry(("igemm", "igemm_s", "igemm_m", "igemm_l"))
+    opts = B.ProfileOpts(warmup=10, batches=5, min_batch_us=200, max_launches=500)
+
+    desc = wl.MODEL_BUILDERS[args.model](0)
+    s, plan, costs, ids, timing = optimise(desc, reg, opts)
+    ms_per_step = time_steps(plan, args.steps, args.warmup)
+    rows = kernel_table(plan)
+    roof = roofline_of(rows)
+    kernel_only_ms = sum(r["ns"] for r in rows) / 1e6
+    empty_ns = B.clg_profile_empty(s.ctx)
+
+    extra = {}
+    if not args.no_extra:
+        for name in ("bert_base", "resnext50", "dcgan_b1", "dcgan_b64", "tiny_cnn", "resnet50"):
+            if name == args.model:
+                continue
+            d2 = wl.MODEL_BUILDERS[name](0)
+            s2, p2, _, _, t2 = optimise(d2, reg, opts)
+            ms2 = time_steps(p2, max(20, args.steps // 2), args.warmup)
+            r2 = kernel_table(p2, reps=5)
+            extra[name] = dict(ms_per_step=round(ms2, 4), kernels=p2.n_kernels,
+                               kernel_only_ms=round(sum(r["ns"] for r in r2) / 1e6, 4),
+                               mfma_tflops=roofline_of(r2)["achieved"], optimise_s=round(sum(
+                                   v for k, v in t2.items() if k.endswith("_s")), 2))
+            p2.destroy()
+            s2.close()
+
+    cpu = None if args.no_cpu else cpu_baseline(desc)
+
+    if args.dump:
+        os.makedirs(os.path.dirname(os.path.abspath(args.dump)), exist_ok=True)
+        with open(args.dump, "w") as f:
+            json.dump(dict(model=args.model, kernels=rows, timing=timing), f, indent=1)
+
+    out = {
+        "metric": f"batch-1 fp32 latency (ms) {args.model}",
+        "value": round(ms_per_step, 4),
+        "unit": "ms",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{args.model} batch 1 fp32, seeded random weights, placement from the "
+                               "library's measurer + DP over igemm{,_s,_m,_l}/direct/rowwise/eltwise",
+                   "kernels_per_step": plan.n_kernels},
+        "roofline": roof,
+        "cpu_baseline": cpu,
+        "kernel_only_ms": round(kernel_only_ms, 4),
+        "empty_launch_ns": int(empty_ns),
+        "optimise": {k: (round(v, 4) if isinstance(v, float) else v) for k, v in timing.items()},
+        "other_workloads": extra,
+    }
+    print(json.dumps(out))
+    plan.destroy()
+    s.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,321 @@
+/*
+ * collage_mi.h - C ABI of the MI355X fused-operator inference library.
+ *
+ * The library runs batch-1 fp32 DNN inference as a sequence of fused operator
+ * subgraphs, the computation whose backend placement the Collage paper
+ * (arXiv 2111.00655) optimises.  The calls follow the paper's statement of
+ * the problem (Sec. 4.1): a computation graph G, a registry B of backend
+ * patterns b = (p, d), matches (g_i, b_i), a measurer M that times one
+ * matched subgraph as one kernel (Sec. 4.2), the op-level dynamic programme
+ * of Alg. 1, and execution of G under a placement P(G).
+ *
+ * Conventions
+ *  - Every call returns a clg_status: 0 on success, negative on error.  No
+ *    exception crosses this boundary.  clg_last_error() gives a message for
+ *    the most recent failing call on the calling thread.
+ *  - Handles (clg_ctx, clg_graph, clg_plan) are opaque, created and destroyed
+ *    by the library.  A context and the objects made from it are not
+ *    thread-safe.
+ *  - "host" pointers are ordinary process memory; "device" pointers are HIP
+ *    device memory on the context's GPU.  Device buffers are OWNED BY THE
+ *    CALLER: the library borrows them and never frees them.  Constant
+ *    tensors (weights) must stay valid and unchanged for as long as the
+ *    graph, its plans or the profiler may read them.
+ *  - All tensors are dense, row-major, fp32 (token ids: int32).  Activations
+ *    are NCHW, convolution weights OIHW, transposed-convolution weights IOHW,
+ *    dense weights [units, in].
+ *  - Kernel launches go to the hipStream_t passed as `void *stream` (NULL =
+ *    the default stream) and are asynchronous; profiling calls synchronise.
+ *  - A context created with device = -1 is host-only: graph building,
+ *    registration, matching, search and plan validation work; execution and
+ *    profiling return CLG_HIP_ERROR.
+ */
+#ifndef COLLAGE_MI_H
+#define COLLAGE_MI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct clg_ctx clg_ctx;
+typedef struct clg_graph clg_graph;
+typedef struct clg_plan clg_plan;
+
+typedef enum clg_status {
+    CLG_OK = 0,
+    CLG_INVALID_ARG = -1,        /* null pointer, bad enum, bad count            */
+    CLG_SHAPE_MISMATCH = -2,     /* operand shapes do not fit the operator       */
+    CLG_NO_KERNEL = -3,          /* the backend cannot run this fused kind       */
+    CLG_NOT_A_COVER = -4,        /* placement leaves an operator uncovered       */
+    CLG_OVERLAP = -5,            /* two chosen matches share an operator         */
+    CLG_UNKNOWN_ID = -6,         /* node / backend / pattern / match id          */
+    CLG_WORKSPACE_TOO_SMALL = -7,
+    CLG_HIP_ERROR = -8,          /* a HIP call failed, or no device in this ctx  */
+    CLG_OUT_OF_MEMORY = -9,
+    CLG_IO_ERROR = -10,          /* cost-log file                                */
+    CLG_BUFFER_TOO_SMALL = -11   /* caller's output array has too few entries    */
+} clg_status;
+
+typedef enum clg_dtype { CLG_F32 = 0, CLG_I32 = 1 } clg_dtype;
+
+/* Primitive operators: the operator inventory of the evaluated workloads
+ * (Sec. 5.1: batch matmul, layer norm, softmax for transformers; convolutions
+ * and activations for vision models).  Operand order is given per kind. */
+typedef enum clg_op_kind {
+    CLG_WILDCARD = -1,              /* pattern nodes only: matches any value      */
+    CLG_OP_CONV2D = 0,              /* (x[N,C,H,W], w[O,C/G,kh,kw]); stride pad groups */
+    CLG_OP_CONV2D_TRANSPOSE = 1,    /* (x[N,C,H,W], w[C,O,kh,kw]); stride pad     */
+    CLG_OP_DENSE = 2,               /* (x[M,K], w[U,K]) -> [M,U]                  */
+    CLG_OP_BATCH_MATMUL = 3,        /* (a[B,M,K], b[B,N,K] or b[B,K,N]); transpose_b */
+    CLG_OP_BIAS_ADD = 4,            /* (x, b[C]); axis                            */
+    CLG_OP_ADD = 5,                 /* (x, y), equal shapes                       */
+    CLG_OP_MUL_SCALAR = 6,          /* (x); scalar                                */
+    CLG_OP_RELU = 7,
+    CLG_OP_GELU = 8,                /* x/2 (1 + erf(x / sqrt 2))                  */
+    CLG_OP_TANH = 9,
+    CLG_OP_SOFTMAX = 10,            /* last axis                                  */
+    CLG_OP_LAYER_NORM = 11,         /* (x, gamma[L], beta[L]); eps; last axis     */
+    CLG_OP_MAX_POOL2D = 12,         /* (x); kernel stride pad; padding = -inf     */
+    CLG_OP_GLOBAL_AVG_POOL2D = 13,  /* (x[N,C,H,W]) -> [N,C]                      */
+    CLG_OP_TAKE = 14,               /* (table[V,H], ids[L] int32) -> [L,H]        */
+    CLG_OP_RESHAPE = 15,            /* (x); dims = new shape                      */
+    CLG_OP_TRANSPOSE = 16,          /* (x); dims = permutation                    */
+    CLG_OP_COUNT = 17
+} clg_op_kind;
+
+#define CLG_MAX_DIMS 6
+
+/* Operator attributes ("attributes such as layout and kernel size", Sec. 3).
+ * Fields an operator does not use are ignored.  Zero-initialise, then set. */
+typedef struct clg_attrs {
+    int32_t stride[2];      /* conv2d, conv2d_transpose, max_pool2d           */
+    int32_t pad[2];         /* same                                           */
+    int32_t kernel[2];      /* max_pool2d window                              */
+    int32_t groups;         /* conv2d; 0 is read as 1                         */
+    int32_t axis;           /* bias_add: 1 (channel of NCHW) or -1 / last     */
+    int32_t transpose_b;    /* batch_matmul: 1 = b is [B,N,K]                 */
+    int32_t ndims;          /* reshape / transpose: entries used in dims      */
+    int64_t dims[CLG_MAX_DIMS];
+    double scalar;          /* mul_scalar                                     */
+    double eps;             /* layer_norm                                     */
+} clg_attrs;
+
+/* Attribute constraints of a pattern node (the has_attr of the paper's
+ * pattern language, Sec. 3): lo <= value <= hi. */
+typedef enum clg_attr_id {
+    CLG_ATTR_GROUPS = 0, CLG_ATTR_KERNEL_H = 1, CLG_ATTR_KERNEL_W = 2,
+    CLG_ATTR_STRIDE_H = 3, CLG_ATTR_STRIDE_W = 4, CLG_ATTR_PAD_H = 5,
+    CLG_ATTR_PAD_W = 6, CLG_ATTR_TRANSPOSE_B = 7, CLG_ATTR_AXIS = 8,
+    CLG_ATTR_COUNT = 9
+} clg_attr_id;
+
+typedef struct clg_attr_constraint {
+    int32_t attr;           /* clg_attr_id */
+    int64_t lo, hi;
+} clg_attr_constraint;
+
+#define CLG_MAX_PATTERN_ARGS 3
+#define CLG_MAX_CONSTRAINTS 4
+#define CLG_MAX_PATTERN_NODES 32
+#define CLG_MAX_MATCH_NODES 16
+
+/* One node of a pattern tree.  A pattern is an array of these in post-order:
+ * every argument index refers to an EARLIER entry, each entry is used as an
+ * argument at most once, and the last entry is the root (the sink of the
+ * matched subgraph), as in is_op('relu')(is_op('add')(conv, wildcard())). */
+typedef struct clg_pattern_node {
+    int32_t op;                               /* clg_op_kind or CLG_WILDCARD  */
+    int32_t n_args;                           /* 0 for a wildcard             */
+    int32_t args[CLG_MAX_PATTERN_ARGS];
+    int32_t n_constraints;
+    clg_attr_constraint constraints[CLG_MAX_CONSTRAINTS];
+} clg_pattern_node;
+
+/* One match (v_s, b_i) -> g of Alg. 1.  `first` is v_s: the first node of g
+ * in the order (depth, node id).  `nodes` lists g's operators by ascending
+ * node id; `binding` gives the graph node bound to each NON-wildcard pattern
+ * node, in pattern order (so its last entry is the sink). */
+typedef struct clg_match {
+    int32_t pattern;
+    int32_t backend;
+    int32_t first;
+    int32_t sink;
+    int32_t n_nodes;
+    int32_t nodes[CLG_MAX_MATCH_NODES];
+    int32_t binding[CLG_MAX_MATCH_NODES];
+} clg_match;
+
+/* Cost the measurer reports for a match its backend cannot run. */
+#define CLG_COST_INF ((int64_t)1 << 60)
+
+/* Measurer protocol (Sec. 4.2: "compilation + multiple runs on the actual
+ * hardware").  Zero in a field selects the default given in brackets. */
+typedef struct clg_profile_opts {
+    int32_t warmup;         /* untimed launches first [20]                    */
+    int32_t batches;        /* timed batches; the cost is their median [5]    */
+    int32_t min_batch_us;   /* a batch repeats the kernel until it lasts this long [200] */
+    int32_t max_launches;   /* cap on launches per batch [2000]               */
+    uint64_t seed;          /* seed of the scratch operands' contents [1]     */
+    int32_t no_cache;       /* 1: neither read nor fill the cost log [0]      */
+} clg_profile_opts;
+
+/* Per-kernel record of a compiled plan (for roofline accounting). */
+typedef struct clg_kernel_info {
+    char name[64];          /* kernel family and variant, NUL-terminated      */
+    int32_t match;          /* match id this kernel belongs to                */
+    int32_t bound;          /* 0 = MFMA contraction, 1 = HBM-bound            */
+    double flops;           /* algorithmic: 2 * MACs of the real operator     */
+    double bytes;           /* algorithmic: every operand and the output once */
+} clg_kernel_info;
+
+/* ---- context ------------------------------------------------------------ */
+/* device >= 0: HIP device ordinal; -1: host-only context.  *out owns nothing
+ * of the caller's.  Errors: INVALID_ARG, HIP_ERROR. */
+int32_t clg_create(clg_ctx **out, int32_t device);
+int32_t clg_destroy(clg_ctx *ctx);
+/* Message of the last failing call on this thread; library-owned storage,
+ * valid until the next failing call on the thread.  Never NULL. */
+const char *clg_last_error(void);
+/* ABI version of this header (major * 100 + minor). */
+int32_t clg_version(void);
+
+/* ---- computation graph G (Sec. 4.1: a DAG of tensor operators) ------------ */
+/* Nodes are added in topological order; a node's id is its insertion index
+ * (returned in *node).  Shapes are inferred when an operator is added;
+ * SHAPE_MISMATCH is returned, and the node not added, if operands do not fit. */
+int32_t clg_graph_create(clg_ctx *ctx, clg_graph **out);
+int32_t clg_graph_destroy(clg_graph *g);
+/* A run-time input.  dims: host array of ndim entries (1..CLG_MAX_DIMS). */
+int32_t clg_graph_input(clg_graph *g, int32_t dtype, int32_t ndim,
+                        const int64_t *dims, int32_t *node);
+/* A constant (weight).  dev_ptr: device memory holding the tensor, borrowed
+ * for the life of the graph and its plans; may be NULL in a host-only ctx. */
+int32_t clg_graph_const(clg_graph *g, int32_t dtype, int32_t ndim,
+                        const int64_t *dims, const void *dev_ptr, int32_t *node);
+/* An operator.  in_nodes: host array of n_in earlier node ids; attrs: host,
+ * may be NULL for operators without attributes. */
+int32_t clg_graph_op(clg_graph *g, int32_t op_kind, int32_t n_in,
+                     const int32_t *in_nodes, const clg_attrs *attrs,
+                     int32_t *node);
+/* Marks an operator's value as a graph output; outputs keep call order. */
+int32_t clg_graph_mark_output(clg_graph *g, int32_t node);
+int32_t clg_graph_num_nodes(const clg_graph *g, int32_t *n);
+/* Shape of any node: dims receives up to CLG_MAX_DIMS entries. */
+int32_t clg_graph_node_shape(const clg_graph *g, int32_t node, int32_t *dtype,
+                             int32_t *ndim, int64_t *dims);
+
+/* ---- registry B (Sec. 3 explicit pattern specification; Sec. 4.1) -------- */
+/* A backend here is one of the library's kernel families, selected by name:
+ *   "igemm"    MFMA implicit-GEMM convolution / GEMM, default tile choice
+ *   "igemm_s", "igemm_m", "igemm_l"   the same with a fixed small / medium /
+ *              large tile (kernel variants to place per layer)
+ *   "direct"   direct convolution (any groups) and pooling
+ *   "rowwise"  softmax and layer norm with fused elementwise prologue
+ *   "eltwise"  elementwise chains, embedding gather, layout copies
+ * Returns UNKNOWN_ID for any other name.  Registering a name twice returns
+ * the same id.  Registration order of patterns is significant: it is the
+ * iteration order of B in Alg. 1 and breaks ties in the search. */
+int32_t clg_register_backend(clg_ctx *ctx, const char *name, int32_t *backend);
+/* nodes: host array of n pattern nodes in post-order (see clg_pattern_node).
+ * NO_KERNEL if the backend has no kernel for that fused kind (checked on the
+ * pattern's structure; a match whose shapes the kernel cannot take is instead
+ * reported by the measurer as CLG_COST_INF). */
+int32_t clg_register_pattern(clg_ctx *ctx, int32_t backend,
+                             const clg_pattern_node *nodes, int32_t n,
+                             int32_t *pattern);
+int32_t clg_num_patterns(const clg_ctx *ctx, int32_t *n);
+
+/* ---- matches (Alg. 1: "find a subgraph g rooted at v_s that matches b_i") - */
+/* Enumerates every legal match of every registered pattern.  Legal: pattern
+ * operators bind distinct nodes, only the sink has consumers outside g, and no
+ * non-sink node is a graph output (g becomes ONE kernel).  `add` operands are
+ * tried as written, then swapped.  At most one match per (v_s, pattern) is
+ * kept: the first found scanning sinks in node order.  The list is sorted by
+ * (order of v_s, pattern id); a match id is its index in this list.  The
+ * result is stored in the graph and replaces any earlier one.
+ * out: host array of cap entries, may be NULL when cap = 0 (count only);
+ * *n receives the number of matches; BUFFER_TOO_SMALL if cap < *n > 0. */
+int32_t clg_match_all(clg_ctx *ctx, clg_graph *g, clg_match *out, size_t cap,
+                      size_t *n);
+
+/* ---- measurer M (Sec. 4.2) -------------------------------------------------- */
+/* Times one match as one kernel on the device and returns integer nanoseconds
+ * per launch (median over batches of back-to-back launches between two HIP
+ * events, after warm-up).  Non-constant operands are scratch tensors the
+ * library allocates and fills from opts->seed; constants are read in place.
+ * Results are cached by (backend, fused kind, attributes, shapes): the cost
+ * log.  opts may be NULL (all defaults, cache on).  Synchronises the device.
+ * A match the backend cannot run costs CLG_COST_INF. */
+int32_t clg_profile_match(clg_ctx *ctx, clg_graph *g, int32_t match,
+                          const clg_profile_opts *opts, int64_t *cost_ns);
+/* cost_ns: host array with one entry per match of the last clg_match_all. */
+int32_t clg_profile_all(clg_ctx *ctx, clg_graph *g,
+                        const clg_profile_opts *opts, int64_t *cost_ns,
+                        size_t cap);
+/* Cost of launching an empty kernel with the same protocol: the per-kernel
+ * dispatch floor (the context-switch cost eps of Eq. 2, for reference). */
+int32_t clg_profile_empty(clg_ctx *ctx, const clg_profile_opts *opts,
+                          int64_t *cost_ns);
+/* Cost log as a text file ("cached to the log for future usage", Sec. 4.2):
+ * one "key<TAB>nanoseconds" line per entry.  load merges into the context's
+ * log (file entries win); save writes the whole log. */
+int32_t clg_cost_log_load(clg_ctx *ctx, const char *path);
+int32_t clg_cost_log_save(const clg_ctx *ctx, const char *path);
+int32_t clg_cost_log_size(const clg_ctx *ctx, size_t *n);
+/* Cache key of a match, for inspection; buf: host, cap bytes. */
+int32_t clg_match_key(clg_ctx *ctx, clg_graph *g, int32_t match, char *buf,
+                      size_t cap);
+
+/* ---- op-level placement search (Sec. 4.2, Eq. 3 and Alg. 1) -------------- */
+/* Minimises sum_i (cost_ns[m_i] + eps_ns) over all placements (disjoint
+ * matches covering every operator).  A pure function of the graph, the match
+ * list and the numbers given: ties are broken towards the lexicographically
+ * smallest ascending match-id list, so equal cost tables give identical
+ * placements.  Entries >= CLG_COST_INF are never chosen.
+ * cost_ns: host, one entry per match.  chosen: host array of cap entries that
+ * receives the chosen match ids, ascending; *n_chosen their count; *total_ns
+ * the minimum.  NOT_A_COVER if no placement exists. */
+int32_t clg_search_dp(clg_ctx *ctx, clg_graph *g, const int64_t *cost_ns,
+                      size_t n_costs, int64_t eps_ns, int32_t *chosen,
+                      size_t cap, size_t *n_chosen, int64_t *total_ns);
+/* Sizes of the last search on this graph: operators N, most matches at one
+ * frontier P, most new frontiers from one match F, largest relaxed set S, and
+ * the number of stored sub-placements. */
+int32_t clg_search_stats(const clg_graph *g, int64_t stats[5]);
+
+/* ---- compile under a GIVEN placement and execute (Sec. 4.1, Sec. 5.1) ------- */
+/* matches: host array of n match ids (any valid placement, not only the
+ * search's).  Validates disjointness and cover (OVERLAP, NOT_A_COVER,
+ * UNKNOWN_ID), orders the groups topologically, lowers each to one kernel
+ * (NO_KERNEL if a backend cannot run its match) and plans the intermediate
+ * tensors in one workspace; tensors pass between kernels by pointer. */
+int32_t clg_compile(clg_ctx *ctx, clg_graph *g, const int32_t *matches,
+                    size_t n, clg_plan **out);
+int32_t clg_plan_destroy(clg_plan *plan);
+int32_t clg_plan_workspace_bytes(const clg_plan *plan, size_t *bytes);
+int32_t clg_plan_num_kernels(const clg_plan *plan, size_t *n);
+int32_t clg_plan_kernel_info(const clg_plan *plan, size_t index,
+                             clg_kernel_info *info);
+/* inputs: host array of device pointers, one per graph input in creation
+ * order; outputs: host array of device pointers, one per marked output, each
+ * large enough for its tensor; workspace: device memory of at least
+ * clg_plan_workspace_bytes, 256-byte aligned.  Asynchronous on `stream`.
+ * Errors: INVALID_ARG, WORKSPACE_TOO_SMALL, HIP_ERROR. */
+int32_t clg_execute(clg_plan *plan, const void *const *inputs,
+                    void *const *outputs, void *workspace, size_t ws_bytes,
+                    void *stream);
+/* As clg_execute, with a HIP event pair around every kernel on `stream`;
+ * synchronises, then writes each kernel's duration in nanoseconds to
+ * kernel_ns (host array, one entry per plan kernel). */
+int32_t clg_execute_timed(clg_plan *plan, const void *const *inputs,
+                          void *const *outputs, void *workspace,
+                          size_t ws_bytes, void *stream, int64_t *kernel_ns,
+                          size_t cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COLLAGE_MI_H */

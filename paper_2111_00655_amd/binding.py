@@ -1,0 +1,385 @@
+"""ctypes binding of libcollage_mi.so: one Python function per C entry point,
+with the same name.  Argument marshalling only; every step of the path runs in
+the library.  A failing call raises ClgError carrying the status code and the
+library's message.  The library must have been built (python -m
+paper_2111_00655_amd.build); there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libcollage_mi.so")
+
+MAX_DIMS = 6
+MAX_PATTERN_ARGS = 3
+MAX_CONSTRAINTS = 4
+MAX_MATCH_NODES = 16
+COST_INF = 1 << 60
+WILDCARD = -1
+
+OP_KINDS = ("conv2d", "conv2d_transpose", "dense", "batch_matmul", "bias_add", "add",
+            "mul_scalar", "relu", "gelu", "tanh", "softmax", "layer_norm", "max_pool2d",
+            "global_avg_pool2d", "take", "reshape", "transpose")
+OP_ID = {k: i for i, k in enumerate(OP_KINDS)}
+ATTR_ID = {k: i for i, k in enumerate(("groups", "kernel_h", "kernel_w", "stride_h", "stride_w",
+                                       "pad_h", "pad_w", "transpose_b", "axis"))}
+STATUS = {0: "OK", -1: "INVALID_ARG", -2: "SHAPE_MISMATCH", -3: "NO_KERNEL", -4: "NOT_A_COVER",
+          -5: "OVERLAP", -6: "UNKNOWN_ID", -7: "WORKSPACE_TOO_SMALL", -8: "HIP_ERROR",
+          -9: "OUT_OF_MEMORY", -10: "IO_ERROR", -11: "BUFFER_TOO_SMALL"}
+F32, I32 = 0, 1
+
+
+class ClgError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"{STATUS.get(code, code)}: {msg}")
+        self.code = code
+        self.status = STATUS.get(code, str(code))
+
+
+class Attrs(C.Structure):
+    _fields_ = [("stride", C.c_int32 * 2), ("pad", C.c_int32 * 2), ("kernel", C.c_int32 * 2),
+                ("groups", C.c_int32), ("axis", C.c_int32), ("transpose_b", C.c_int32),
+                ("ndims", C.c_int32), ("dims", C.c_int64 * MAX_DIMS), ("scalar", C.c_double),
+                ("eps", C.c_double)]
+
+
+class AttrConstraint(C.Structure):
+    _fields_ = [("attr", C.c_int32), ("lo", C.c_int64), ("hi", C.c_int64)]
+
+
+class PatternNode(C.Structure):
+    _fields_ = [("op", C.c_int32), ("n_args", C.c_int32), ("args", C.c_int32 * MAX_PATTERN_ARGS),
+                ("n_constraints", C.c_int32), ("constraints", AttrConstraint * MAX_CONSTRAINTS)]
+
+
+class Match(C.Structure):
+    _fields_ = [("pattern", C.c_int32), ("backend", C.c_int32), ("first", C.c_int32),
+                ("sink", C.c_int32), ("n_nodes", C.c_int32), ("nodes", C.c_int32 * MAX_MATCH_NODES),
+                ("binding", C.c_int32 * MAX_MATCH_NODES)]
+
+
+class ProfileOpts(C.Structure):
+    _fields_ = [("warmup", C.c_int32), ("batches", C.c_int32), ("min_batch_us", C.c_int32),
+                ("max_launches", C.c_int32), ("seed", C.c_uint64), ("no_cache", C.c_int32)]
+
+
+class KernelInfo(C.Structure):
+    _fields_ = [("name", C.c_char * 64), ("match", C.c_int32), ("bound", C.c_int32),
+                ("flops", C.c_double), ("bytes", C.c_double)]
+
+
+# every symbol include/collage_mi.h declares: name -> (restype, argtypes)
+_P = C.c_void_p
+_i32p, _i64p, _szp = C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.POINTER(C.c_size_t)
+SYMBOLS = {
+    "clg_create": (C.c_int32, [C.POINTER(_P), C.c_int32]),
+    "clg_destroy": (C.c_int32, [_P]),
+    "clg_last_error": (C.c_char_p, []),
+    "clg_version": (C.c_int32, []),
+    "clg_graph_create": (C.c_int32, [_P, C.POINTER(_P)]),
+    "clg_graph_destroy": (C.c_int32, [_P]),
+    "clg_graph_input": (C.c_int32, [_P, C.c_int32, C.c_int32, _i64p, _i32p]),
+    "clg_graph_const": (C.c_int32, [_P, C.c_int32, C.c_int32, _i64p, _P, _i32p]),
+    "clg_graph_op": (C.c_int32, [_P, C.c_int32, C.c_int32, _i32p, C.POINTER(Attrs), _i32p]),
+    "clg_graph_mark_output": (C.c_int32, [_P, C.c_int32]),
+    "clg_graph_num_nodes": (C.c_int32, [_P, _i32p]),
+    "clg_graph_node_shape": (C.c_int32, [_P, C.c_int32, _i32p, _i32p, _i64p]),
+    "clg_register_backend": (C.c_int32, [_P, C.c_char_p, _i32p]),
+    "clg_register_pattern": (C.c_int32, [_P, C.c_int32, C.POINTER(PatternNode), C.c_int32, _i32p]),
+    "clg_num_patterns": (C.c_int32, [_P, _i32p]),
+    "clg_match_all": (C.c_int32, [_P, _P, C.POINTER(Match), C.c_size_t, _szp]),
+    "clg_profile_match": (C.c_int32, [_P, _P, C.c_int32, C.POINTER(ProfileOpts), _i64p]),
+    "clg_profile_all": (C.c_int32, [_P, _P, C.POINTER(ProfileOpts), _i64p, C.c_size_t]),
+    "clg_profile_empty": (C.c_int32, [_P, C.POINTER(ProfileOpts), _i64p]),
+    "clg_cost_log_load": (C.c_int32, [_P, C.c_char_p]),
+    "clg_cost_log_save": (C.c_int32, [_P, C.c_char_p]),
+    "clg_cost_log_size": (C.c_int32, [_P, _szp]),
+    "clg_match_key": (C.c_int32, [_P, _P, C.c_int32, C.c_char_p, C.c_size_t]),
+    "clg_search_dp": (C.c_int32, [_P, _P, _i64p, C.c_size_t, C.c_int64, _i32p, C.c_size_t, _szp, _i64p]),
+    "clg_search_stats": (C.c_int32, [_P, _i64p]),
+    "clg_compile": (C.c_int32, [_P, _P, _i32p, C.c_size_t, C.POINTER(_P)]),
+    "clg_plan_destroy": (C.c_int32, [_P]),
+    "clg_plan_workspace_bytes": (C.c_int32, [_P, _szp]),
+    "clg_plan_num_kernels": (C.c_int32, [_P, _szp]),
+    "clg_plan_kernel_info": (C.c_int32, [_P, C.c_size_t, C.POINTER(KernelInfo)]),
+    "clg_execute": (C.c_int32, [_P, C.POINTER(_P), C.POINTER(_P), _P, C.c_size_t, _P]),
+    "clg_execute_timed": (C.c_int32, [_P, C.POINTER(_P), C.POINTER(_P), _P, C.c_size_t, _P, _i64p, C.c_size_t]),
+}
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is not built: run python -m paper_2111_00655_amd.build")
+        _lib = C.CDLL(LIB_PATH)
+        for name, (res, args) in SYMBOLS.items():
+            fn = getattr(_lib, name)
+            fn.restype = res
+            fn.argtypes = args
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise ClgError(rc, (lib().clg_last_error() or b"").decode(errors="replace"))
+
+
+def _dims(shape):
+    return (C.c_int64 * len(shape))(*[int(d) for d in shape])
+
+
+# ---- context ----------------------------------------------------------------------
+def clg_version():
+    return lib().clg_version()
+
+
+def clg_last_error():
+    return (lib().clg_last_error() or b"").decode(errors="replace")
+
+
+def clg_create(device=0):
+    h = _P()
+    _check(lib().clg_create(C.byref(h), int(device)))
+    return h
+
+
+def clg_destroy(ctx):
+    _check(lib().clg_destroy(ctx))
+
+
+# ---- graph --------------------------------------------------------------------------
+def clg_graph_create(ctx):
+    h = _P()
+    _check(lib().clg_graph_create(ctx, C.byref(h)))
+    return h
+
+
+def clg_graph_destroy(g):
+    _check(lib().clg_graph_destroy(g))
+
+
+def clg_graph_input(g, dtype, shape):
+    node = C.c_int32()
+    _check(lib().clg_graph_input(g, int(dtype), len(shape), _dims(shape), C.byref(node)))
+    return node.value
+
+
+def clg_graph_const(g, dtype, shape, dev_ptr):
+    node = C.c_int32()
+    _check(lib().clg_graph_const(g, int(dtype), len(shape), _dims(shape), _P(dev_ptr or 0), C.byref(node)))
+    return node.value
+
+
+def make_attrs(**kw):
+    a = Attrs()
+    for k in ("stride", "pad", "kernel"):
+        if k in kw:
+            v = kw[k]
+            getattr(a, k)[0], getattr(a, k)[1] = int(v[0]), int(v[1])
+    a.groups = int(kw.get("groups", 1))
+    a.axis = int(kw.get("axis", 1))
+    a.transpose_b = 1 if kw.get("transpose_b", True) else 0
+    if "dims" in kw:
+        a.ndims = len(kw["dims"])
+        for i, d in enumerate(kw["dims"]):
+            a.dims[i] = int(d)
+    a.scalar = float(kw.get("scalar", 0.0))
+    a.eps = float(kw.get("eps", 0.0))
+    return a
+
+
+def clg_graph_op(g, op_kind, in_nodes, attrs=None):
+    node = C.c_int32()
+    kind = OP_ID[op_kind] if isinstance(op_kind, str) else int(op_kind)
+    arr = (C.c_int32 * len(in_nodes))(*[int(i) for i in in_nodes])
+    _check(lib().clg_graph_op(g, kind, len(in_nodes), arr, C.byref(attrs) if attrs is not None else None,
+                              C.byref(node)))
+    return node.value
+
+
+def clg_graph_mark_output(g, node):
+    _check(lib().clg_graph_mark_output(g, int(node)))
+
+
+def clg_graph_num_nodes(g):
+    n = C.c_int32()
+    _check(lib().clg_graph_num_nodes(g, C.byref(n)))
+    return n.value
+
+
+def clg_graph_node_shape(g, node):
+    dt, nd = C.c_int32(), C.c_int32()
+    dims = (C.c_int64 * MAX_DIMS)()
+    _check(lib().clg_graph_node_shape(g, int(node), C.byref(dt), C.byref(nd), dims))
+    return dt.value, tuple(dims[i] for i in range(nd.value))
+
+
+# ---- registry ------------------------------------------------------------------------
+def clg_register_backend(ctx, name):
+    b = C.c_int32()
+    _check(lib().clg_register_backend(ctx, name.encode(), C.byref(b)))
+    return b.value
+
+
+def flatten_pattern(pat):
+    """Nested pattern (op, args, constraints) / "*" -> PatternNode array in
+    post-order (arguments left to right, then the node; root last)."""
+    nodes = []
+
+    def rec(p):
+        n = PatternNode()
+        if p == "*":
+            n.op = WILDCARD
+            nodes.append(n)
+            return len(nodes) - 1
+        op, args, cons = p
+        idx = [rec(a) for a in args]
+        n.op = OP_ID[op]
+        n.n_args = len(idx)
+        for k, i in enumerate(idx):
+            n.args[k] = i
+        n.n_constraints = len(cons)
+        for k, (name, (lo, hi)) in enumerate(cons):
+            n.constraints[k].attr = ATTR_ID[name]
+            n.constraints[k].lo = lo
+            n.constraints[k].hi = hi
+        nodes.append(n)
+        return len(nodes) - 1
+
+    rec(pat)
+    return (PatternNode * len(nodes))(*nodes)
+
+
+def clg_register_pattern(ctx, backend, pattern):
+    arr = pattern if isinstance(pattern, C.Array) else flatten_pattern(pattern)
+    pid = C.c_int32()
+    _check(lib().clg_register_pattern(ctx, int(backend), arr, len(arr), C.byref(pid)))
+    return pid.value
+
+
+def clg_num_patterns(ctx):
+    n = C.c_int32()
+    _check(lib().clg_num_patterns(ctx, C.byref(n)))
+    return n.value
+
+
+# ---- matches ------------------------------------------------------------------------
+def clg_match_all(ctx, g):
+    n = C.c_size_t()
+    _check(lib().clg_match_all(ctx, g, None, 0, C.byref(n)))
+    arr = (Match * max(n.value, 1))()
+    _check(lib().clg_match_all(ctx, g, arr, n.value, C.byref(n)))
+    return [arr[i] for i in range(n.value)]
+
+
+# ---- measurer ------------------------------------------------------------------------
+def clg_profile_match(ctx, g, match, opts=None):
+    c = C.c_int64()
+    _check(lib().clg_profile_match(ctx, g, int(match), C.byref(opts) if opts is not None else None, C.byref(c)))
+    return c.value
+
+
+def clg_profile_all(ctx, g, n_matches, opts=None):
+    out = np.zeros(max(n_matches, 1), np.int64)
+    _check(lib().clg_profile_all(ctx, g, C.byref(opts) if opts is not None else None,
+                                 out.ctypes.data_as(_i64p), n_matches))
+    return out[:n_matches]
+
+
+def clg_profile_empty(ctx, opts=None):
+    c = C.c_int64()
+    _check(lib().clg_profile_empty(ctx, C.byref(opts) if opts is not None else None, C.byref(c)))
+    return c.value
+
+
+def clg_cost_log_load(ctx, path):
+    _check(lib().clg_cost_log_load(ctx, os.fsencode(path)))
+
+
+def clg_cost_log_save(ctx, path):
+    _check(lib().clg_cost_log_save(ctx, os.fsencode(path)))
+
+
+def clg_cost_log_size(ctx):
+    n = C.c_size_t()
+    _check(lib().clg_cost_log_size(ctx, C.byref(n)))
+    return n.value
+
+
+def clg_match_key(ctx, g, match):
+    buf = C.create_string_buffer(1024)
+    _check(lib().clg_match_key(ctx, g, int(match), buf, len(buf)))
+    return buf.value.decode()
+
+
+# ---- search ------------------------------------------------------------------------
+def clg_search_dp(ctx, g, cost_ns, eps_ns=0):
+    cost = np.ascontiguousarray(cost_ns, dtype=np.int64)
+    n_nodes = clg_graph_num_nodes(g)
+    chosen = np.zeros(max(n_nodes, 1), np.int32)
+    n, total = C.c_size_t(), C.c_int64()
+    _check(lib().clg_search_dp(ctx, g, cost.ctypes.data_as(_i64p), cost.size, int(eps_ns),
+                               chosen.ctypes.data_as(_i32p), chosen.size, C.byref(n), C.byref(total)))
+    return total.value, tuple(int(v) for v in chosen[:n.value])
+
+
+def clg_search_stats(g):
+    s = (C.c_int64 * 5)()
+    _check(lib().clg_search_stats(g, s))
+    return dict(N=s[0], P=s[1], F=s[2], S=s[3], states=s[4])
+
+
+# ---- compile / execute ------------------------------------------------------------------
+def clg_compile(ctx, g, matches):
+    ids = np.ascontiguousarray(matches, dtype=np.int32)
+    h = _P()
+    _check(lib().clg_compile(ctx, g, ids.ctypes.data_as(_i32p), ids.size, C.byref(h)))
+    return h
+
+
+def clg_plan_destroy(plan):
+    _check(lib().clg_plan_destroy(plan))
+
+
+def clg_plan_workspace_bytes(plan):
+    n = C.c_size_t()
+    _check(lib().clg_plan_workspace_bytes(plan, C.byref(n)))
+    return n.value
+
+
+def clg_plan_num_kernels(plan):
+    n = C.c_size_t()
+    _check(lib().clg_plan_num_kernels(plan, C.byref(n)))
+    return n.value
+
+
+def clg_plan_kernel_info(plan, index):
+    info = KernelInfo()
+    _check(lib().clg_plan_kernel_info(plan, int(index), C.byref(info)))
+    return dict(name=info.name.decode(), match=info.match, bound=("mfma", "hbm")[info.bound],
+                flops=info.flops, bytes=info.bytes)
+
+
+def _ptr_array(ptrs):
+    return (_P * max(len(ptrs), 1))(*[_P(int(p)) for p in ptrs])
+
+
+def clg_execute(plan, inputs, outputs, workspace, ws_bytes, stream=0):
+    """inputs / outputs: sequences of device addresses (ints); workspace: device address."""
+    _check(lib().clg_execute(plan, _ptr_array(inputs), _ptr_array(outputs), _P(int(workspace) or None),
+                             int(ws_bytes), _P(int(stream) or None)))
+
+
+def clg_execute_timed(plan, inputs, outputs, workspace, ws_bytes, stream=0):
+    n = clg_plan_num_kernels(plan)
+    ns = np.zeros(max(n, 1), np.int64)
+    _check(lib().clg_execute_timed(plan, _ptr_array(inputs), _ptr_array(outputs), _P(int(workspace) or None),
+                                   int(ws_bytes), _P(int(stream) or None), ns.ctypes.data_as(_i64p), ns.size))
+    return ns[:n]

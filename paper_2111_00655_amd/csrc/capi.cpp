@@ -1,0 +1,392 @@
+// The C ABI (include/collage_mi.h): argument checking and marshalling only.
+#include <cstdio>
+#include <new>
+
+#include <hip/hip_runtime_api.h>
+
+#include "core.h"
+
+using namespace clg;
+
+#define CLG_TRY try {
+#define CLG_CATCH                                                                     \
+    } catch (const std::bad_alloc &) {                                                \
+        return fail(CLG_OUT_OF_MEMORY, "host allocation failed");                     \
+    } catch (const std::exception &e) {                                               \
+        return fail(CLG_INVALID_ARG, "internal error: %s", e.what());                 \
+    } catch (...) {                                                                   \
+        return fail(CLG_INVALID_ARG, "internal error");                               \
+    }
+#define NEED(p) do { if (!(p)) return fail(CLG_INVALID_ARG, "%s: %s is null", __func__, #p); } while (0)
+
+extern "C" {
+
+int32_t clg_version(void) { return 100; }
+const char *clg_last_error(void) { return last_error(); }
+
+int32_t clg_create(clg_ctx **out, int32_t device) {
+    CLG_TRY
+    NEED(out);
+    *out = nullptr;
+    if (device < -1) return fail(CLG_INVALID_ARG, "device %d", device);
+    clg_ctx *c = new clg_ctx();
+    c->c.device = device;
+    if (device >= 0) {
+        int n = 0;
+        hipError_t e = hipGetDeviceCount(&n);
+        if (e != hipSuccess || device >= n) {
+            delete c;
+            return fail(CLG_HIP_ERROR, "device %d is not available (%d devices: %s)", device, n,
+                        hipGetErrorString(e));
+        }
+        if ((e = hipSetDevice(device)) != hipSuccess) {
+            delete c;
+            return fail(CLG_HIP_ERROR, "hipSetDevice(%d): %s", device, hipGetErrorString(e));
+        }
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && cus > 0)
+            c->c.n_cus = cus;
+    }
+    *out = c;
+    return CLG_OK;
+    CLG_CATCH
+}
+
+int32_t clg_destroy(clg_ctx *ctx) {
+    if (!ctx) return CLG_OK;
+    if (ctx->c.prof_ptr) (void)hipFree(ctx->c.prof_ptr);
+    delete ctx;
+    return CLG_OK;
+}
+
+int32_t clg_graph_create(clg_ctx *ctx, clg_graph **out) {
+    CLG_TRY
+    NEED(ctx); NEED(out);
+    *out = new clg_graph();
+    (*out)->g.ctx = &ctx->c;
+    return CLG_OK;
+    CLG_CATCH
+}
+
+int32_t clg_graph_destroy(clg_graph *g) {
+    delete g;
+    return CLG_OK;
+}
+
+static int32_t add_leaf(clg_graph *g, int32_t kind, int32_t dtype, int32_t ndim, const int64_t *dims,
+                        const void *ptr, int32_t *node) {
+    NEED(g); NEED(dims); NEED(node);
+    if (dtype != CLG_F32 && dtype != CLG_I32) return fail(CLG_INVALID_ARG, "dtype %d", dtype);
+    if (ndim < 1 || ndim > CLG_MAX_DIMS) return fail(CLG_INVALID_ARG, "ndim %d", ndim);
+    Node nd;
+    nd.kind = kind;
+    nd.dtype = dtype;
+    nd.shape.ndim = ndim;
+    for (int i = 0; i < ndim; ++i) {
+        if (dims[i] < 1) return fail(CLG_INVALID_ARG, "dims[%d] = %lld", i, (long long)dims[i]);
+        nd.shape.d[i] = dims[i];
+    }
+    if (nd.shape.numel() > ((int64_t)1 << 31)) return fail(CLG_INVALID_ARG, "tensor has more than 2^31 elements");
+    nd.dev_ptr = ptr;
+    if (kind == NODE_INPUT) nd.input_index = g->g.n_inputs++;
+    g->g.nodes.push_back(nd);
+    g->g.finalized = false;
+    g->g.matched = false;
+    *node = (int32_t)g->g.nodes.size() - 1;
+    return CLG_OK;
+}
+
+int32_t clg_graph_input(clg_graph *g, int32_t dtype, int32_t ndim, const int64_t *dims, int32_t *node) {
+    CLG_TRY
+    return add_leaf(g, NODE_INPUT, dtype, ndim, dims, nullptr, node);
+    CLG_CATCH
+}
+
+int32_t clg_graph_const(clg_graph *g, int32_t dtype, int32_t ndim, const int64_t *dims, const void *dev_ptr,
+                        int32_t *node) {
+    CLG_TRY
+    return add_leaf(g, NODE_CONST, dtype, ndim, dims, dev_ptr, node);
+    CLG_CATCH
+}
+
+int32_t clg_graph_op(clg_graph *g, int32_t op_kind, int32_t n_in, const int32_t *in_nodes, const clg_attrs *attrs,
+                     int32_t *node) {
+    CLG_TRY
+    NEED(g); NEED(node);
+    if (n_in < 1 || n_in > 3) return fail(CLG_INVALID_ARG, "n_in %d", n_in);
+    NEED(in_nodes);
+    Node nd;
+    nd.kind = op_kind;
+    for (int i = 0; i < n_in; ++i) {
+        if (in_nodes[i] < 0 || in_nodes[i] >= (int32_t)g->g.nodes.size())
+            return fail(CLG_UNKNOWN_ID, "operand %d: node id %d", i, in_nodes[i]);
+        nd.in.push_back(in_nodes[i]);
+    }
+    if (attrs) nd.attrs = *attrs;
+    const int32_t rc = infer_shape(g->g, op_kind, nd.in, nd.attrs, &nd.shape, &nd.dtype);
+    if (rc != CLG_OK) return rc;
+    g->g.nodes.push_back(nd);
+    g->g.finalized = false;
+    g->g.matched = false;
+    *node = (int32_t)g->g.nodes.size() - 1;
+    return CLG_OK;
+    CLG_CATCH
+}
+
+int32_t clg_graph_mark_output(clg_graph *g, int32_t node) {
+    CLG_TRY
+    NEED(g);
+    if (node < 0 || node >= (int32_t)g->g.nodes.size()) return fail(CLG_UNKNOWN_ID, "node id %d", node);
+    if (!g->g.nodes[node].is_op()) return fail(CLG_INVALID_ARG, "node %d is not an operator", node);
+    for (int32_t o : g->g.outputs)
+        if (o == node) return fail(CLG_INVALID_ARG, "node %d is already an output", node);
+    g->g.outputs.push_back(node);
+    g->g.finalized = false;
+    g->g.matched = false;
+    return CLG_OK;
+    CLG_CATCH
+}
+
+int32_t clg_graph_num_nodes(const clg_graph *g, int32_t *n) {
+    NEED(g); NEED(n);
+    *n = (int32_t)g->g.nodes.size();
+    return CLG_OK;
+}
+
+int32_t clg_graph_node_shape(const clg_graph *g, int32_t node, int32_t *dtype, int32_t *ndim, int64_t *dims) {
+    NEED(g); NEED(ndim); NEED(dims);
+    if (node < 0 || node >= (int32_t)g->g.nodes.size()) return fail(CLG_UNKNOWN_ID, "node id %d", node);
+    const Node &nd = g->g.nodes[node];
+    if (dtype) *dtype = nd.dtype;
+    *ndim = nd.shape.ndim;
+    for (int i = 0; i < nd.shape.ndim; ++i) dims[i] = nd.shape.d[i];
+    return CLG_OK;
+}
+
+int32_t clg_register_backend(clg_ctx *ctx, const char *name, int32_t *backend) {
+    CLG_TRY
+    NEED(ctx); NEED(name); NEED(backend);
+    static const struct { const char *name; int32_t family, tile; } kKnown[] = {
+        {"igemm", FAM_IGEMM, TILE_AUTO}, {"igemm_s", FAM_IGEMM, TILE_S}, {"igemm_m", FAM_IGEMM, TILE_M},
+        {"igemm_l", FAM_IGEMM, TILE_L}, {"direct", FAM_DIRECT, 0}, {"rowwise", FAM_ROWWISE, 0},
+        {"eltwise", FAM_ELTWISE, 0}};
+    const std::string s(name);
+    for (size_t i = 0; i < ctx->c.backends.size(); ++i)
+        if (ctx->c.backends[i].name == s) {
+            *backend = (int32_t)i;
+            return CLG_OK;
+        }
+    for (auto &k : kKnown)
+        if (s == k.name) {
+            ctx->c.backends.push_back(Backend{s, k.family, k.tile});
+            *backend = (int32_t)ctx->c.backends.size() - 1;
+            return CLG_OK;
+        }
+    return fail(CLG_UNKNOWN_ID, "no kernel family is called '%s'", name);
+    CLG_CATCH
+}
+
+int32_t clg_register_pattern(clg_ctx *ctx, int32_t backend, const clg_pattern_node *nodes, int32_t n,
+                             int32_t *pattern) {
+    CLG_TRY
+    NEED(ctx); NEED(nodes); NEED(pattern);
+    if (backend < 0 || backend >= (int32_t)ctx->c.backends.size()) return fail(CLG_UNKNOWN_ID, "backend id %d", backend);
+    if (n < 1 || n > CLG_MAX_PATTERN_NODES) return fail(CLG_INVALID_ARG, "pattern has %d nodes", n);
+    Pattern p;
+    p.backend = backend;
+    p.nodes.assign(nodes, nodes + n);
+    const int32_t rc = check_pattern(ctx->c, &p);
+    if (rc != CLG_OK) return rc;
+    ctx->c.patterns.push_back(std::move(p));
+    *pattern = (int32_t)ctx->c.patterns.size() - 1;
+    return CLG_OK;
+    CLG_CATCH
+}
+
+int32_t clg_num_patterns(const clg_ctx *ctx, int32_t *n) {
+    NEED(ctx); NEED(n);
+    *n = (int32_t)ctx->c.patterns.size();
+    return CLG_OK;
+}
+
+int32_t clg_match_all(clg_ctx *ctx, clg_graph *g, clg_match *out, size_t cap, size_t *n) {
+    CLG_TRY
+    NEED(ctx); NEED(g); NEED(n);
+    if (g->g.ctx != &ctx->c) return fail(CLG_INVALID_ARG, "graph belongs to another context");
+    const int32_t rc = match_all(ctx->c, g->g);
+    if (rc != CLG_OK) return rc;
+    *n = g->g.matches.size();
+    if (cap == 0 && !out) return CLG_OK;
+    NEED(out);
+    if (cap < *n) return fail(CLG_BUFFER_TOO_SMALL, "%zu matches, room for %zu", *n, cap);
+    for (size_t i = 0; i < *n; ++i) {
+        const MatchRec &m = g->g.matches[i];
+        clg_match &o = out[i];
+        std::memset(&o, 0, sizeof o);
+        o.pattern = m.pattern;
+        o.backend = m.backend;
+        o.first = m.first;
+        o.sink = m.sink;
+        o.n_nodes = (int32_t)m.nodes.size();
+        for (size_t k = 0; k < m.nodes.size(); ++k) {
+            o.nodes[k] = m.nodes[k];
+            o.binding[k] = m.binding[k];
+        }
+    }
+    return CLG_OK;
+    CLG_CATCH
+}
+
+int32_t clg_profile_match(clg_ctx *ctx, clg_graph *g, int32_t match, const clg_profile_opts *opts, int64_t *cost_ns) {
+    CLG_TRY
+    NEED(ctx); NEED(g); NEED(cost_ns);
+    if (g->g.ctx != &ctx->c) return fail(CLG_INVALID_ARG, "graph belongs to another context");
+    return profile_match(ctx->c, g->g, match, opts, cost_ns);
+    CLG_CATCH
+}
+
+int32_t clg_profile_all(clg_ctx *ctx, clg_graph *g, const clg_profile_opts *opts, int64_t *cost_ns, size_t cap) {
+    CLG_TRY
+    NEED(ctx); NEED(g); NEED(cost_ns);
+    if (g->g.ctx != &ctx->c) return fail(CLG_INVALID_ARG, "graph belongs to another context");
+    if (!g->g.matched) return fail(CLG_INVALID_ARG, "clg_match_all has not been called on this graph");
+    if (cap < g->g.matches.size()) return fail(CLG_BUFFER_TOO_SMALL, "%zu matches, room for %zu", g->g.matches.size(), cap);
+    for (size_t i = 0; i < g->g.matches.size(); ++i) {
+        const int32_t rc = profile_match(ctx->c, g->g, (int32_t)i, opts, &cost_ns[i]);
+        if (rc != CLG_OK) return rc;
+    }
+    return CLG_OK;
+    CLG_CATCH
+}
+
+int32_t clg_profile_empty(clg_ctx *ctx, const clg_profile_opts *opts, int64_t *cost_ns) {
+    CLG_TRY
+    NEED(ctx); NEED(cost_ns);
+    return profile_empty(ctx->c, opts, cost_ns);
+    CLG_CATCH
+}
+
+int32_t clg_cost_log_load(clg_ctx *ctx, const char *path) {
+    CLG_TRY
+    NEED(ctx); NEED(path);
+    return cost_log_load(ctx->c, path);
+    CLG_CATCH
+}
+
+int32_t clg_cost_log_save(const clg_ctx *ctx, const char *path) {
+    CLG_TRY
+    NEED(ctx); NEED(path);
+    return cost_log_save(ctx->c, path);
+    CLG_CATCH
+}
+
+int32_t clg_cost_log_size(const clg_ctx *ctx, size_t *n) {
+    NEED(ctx); NEED(n);
+    *n = ctx->c.cost_log.size();
+    return CLG_OK;
+}
+
+int32_t clg_match_key(clg_ctx *ctx, clg_graph *g, int32_t match, char *buf, size_t cap) {
+    CLG_TRY
+    NEED(ctx); NEED(g); NEED(buf);
+    if (!g->g.matched) return fail(CLG_INVALID_ARG, "clg_match_all has not been called on this graph");
+    KernelCall c;
+    const int32_t rc = lower_match(ctx->c, g->g, match, &c);
+    if (rc != CLG_OK) return rc;
+    if (c.key.size() + 1 > cap) return fail(CLG_BUFFER_TOO_SMALL, "key needs %zu bytes", c.key.size() + 1);
+    std::memcpy(buf, c.key.c_str(), c.key.size() + 1);
+    return CLG_OK;
+    CLG_CATCH
+}
+
+int32_t clg_search_dp(clg_ctx *ctx, clg_graph *g, const int64_t *cost_ns, size_t n_costs, int64_t eps_ns,
+                      int32_t *chosen, size_t cap, size_t *n_chosen, int64_t *total_ns) {
+    CLG_TRY
+    NEED(ctx); NEED(g); NEED(n_chosen); NEED(total_ns);
+    if (g->g.ctx != &ctx->c) return fail(CLG_INVALID_ARG, "graph belongs to another context");
+    if (!g->g.matched) return fail(CLG_INVALID_ARG, "clg_match_all has not been called on this graph");
+    if (n_costs != g->g.matches.size())
+        return fail(CLG_INVALID_ARG, "%zu costs for %zu matches", n_costs, g->g.matches.size());
+    if (n_costs) NEED(cost_ns);
+    std::vector<int32_t> sel;
+    const int32_t rc = search_dp(g->g, ctx->c.patterns.size(), cost_ns, eps_ns, &sel, total_ns);
+    if (rc != CLG_OK) return rc;
+    *n_chosen = sel.size();
+    if (sel.size() > cap) return fail(CLG_BUFFER_TOO_SMALL, "%zu chosen matches, room for %zu", sel.size(), cap);
+    if (!sel.empty()) NEED(chosen);
+    for (size_t i = 0; i < sel.size(); ++i) chosen[i] = sel[i];
+    return CLG_OK;
+    CLG_CATCH
+}
+
+int32_t clg_search_stats(const clg_graph *g, int64_t stats[5]) {
+    NEED(g); NEED(stats);
+    for (int i = 0; i < 5; ++i) stats[i] = g->g.stats[i];
+    return CLG_OK;
+}
+
+int32_t clg_compile(clg_ctx *ctx, clg_graph *g, const int32_t *matches, size_t n, clg_plan **out) {
+    CLG_TRY
+    NEED(ctx); NEED(g); NEED(out);
+    *out = nullptr;
+    if (n) NEED(matches);
+    if (g->g.ctx != &ctx->c) return fail(CLG_INVALID_ARG, "graph belongs to another context");
+    clg_plan *p = new clg_plan();
+    const int32_t rc = compile_plan(ctx->c, g->g, matches, n, &p->p);
+    if (rc != CLG_OK) {
+        delete p;
+        return rc;
+    }
+    *out = p;
+    return CLG_OK;
+    CLG_CATCH
+}
+
+int32_t clg_plan_destroy(clg_plan *plan) {
+    delete plan;
+    return CLG_OK;
+}
+
+int32_t clg_plan_workspace_bytes(const clg_plan *plan, size_t *bytes) {
+    NEED(plan); NEED(bytes);
+    *bytes = plan->p.workspace_bytes;
+    return CLG_OK;
+}
+
+int32_t clg_plan_num_kernels(const clg_plan *plan, size_t *n) {
+    NEED(plan); NEED(n);
+    *n = plan->p.calls.size();
+    return CLG_OK;
+}
+
+int32_t clg_plan_kernel_info(const clg_plan *plan, size_t index, clg_kernel_info *info) {
+    NEED(plan); NEED(info);
+    if (index >= plan->p.calls.size()) return fail(CLG_UNKNOWN_ID, "kernel index %zu", index);
+    const KernelCall &c = plan->p.calls[index];
+    std::memset(info, 0, sizeof *info);
+    std::snprintf(info->name, sizeof info->name, "%s", c.name.c_str());
+    info->match = c.match;
+    info->bound = c.bound;
+    info->flops = c.flops;
+    info->bytes = c.bytes;
+    return CLG_OK;
+}
+
+int32_t clg_execute(clg_plan *plan, const void *const *inputs, void *const *outputs, void *workspace,
+                    size_t ws_bytes, void *stream) {
+    CLG_TRY
+    NEED(plan);
+    return execute_plan(plan->p, inputs, outputs, workspace, ws_bytes, stream, nullptr);
+    CLG_CATCH
+}
+
+int32_t clg_execute_timed(clg_plan *plan, const void *const *inputs, void *const *outputs, void *workspace,
+                          size_t ws_bytes, void *stream, int64_t *kernel_ns, size_t cap) {
+    CLG_TRY
+    NEED(plan); NEED(kernel_ns);
+    if (cap < plan->p.calls.size()) return fail(CLG_BUFFER_TOO_SMALL, "%zu kernels, room for %zu", plan->p.calls.size(), cap);
+    return execute_plan(plan->p, inputs, outputs, workspace, ws_bytes, stream, kernel_ns);
+    CLG_CATCH
+}
+
+}  // extern "C"

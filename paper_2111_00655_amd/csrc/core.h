@@ -1,0 +1,186 @@
+// Internal data structures of the host side: graph G, registry B, matches,
+// lowered kernel calls and plans.  Nothing here crosses the C ABI.
+#pragma once
+
+#include <cstdint>
+#include <cstring>
+#include <map>
+#include <string>
+#include <vector>
+
+#include "../../include/collage_mi.h"
+#include "kernels.h"
+
+namespace clg {
+
+// ---- errors -------------------------------------------------------------------
+// Records the message for clg_last_error() and returns `code`.
+int32_t fail(int32_t code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+void set_error(const char *msg);
+
+// ---- graph -----------------------------------------------------------------------
+enum NodeKind : int32_t { NODE_INPUT = -3, NODE_CONST = -2 };   // else clg_op_kind
+
+struct Shape {
+    int32_t ndim = 0;
+    int64_t d[CLG_MAX_DIMS] = {0, 0, 0, 0, 0, 0};
+    int64_t numel() const {
+        int64_t n = 1;
+        for (int i = 0; i < ndim; ++i) n *= d[i];
+        return n;
+    }
+    bool operator==(const Shape &o) const {
+        if (ndim != o.ndim) return false;
+        for (int i = 0; i < ndim; ++i)
+            if (d[i] != o.d[i]) return false;
+        return true;
+    }
+    std::string str() const;
+};
+
+struct Node {
+    int32_t kind = 0;                 // NODE_INPUT, NODE_CONST or clg_op_kind
+    std::vector<int32_t> in;
+    clg_attrs attrs{};
+    Shape shape;
+    int32_t dtype = CLG_F32;
+    const void *dev_ptr = nullptr;    // constants only (borrowed)
+    int32_t input_index = -1;         // inputs: position in the inputs[] array
+    bool is_op() const { return kind >= 0; }
+};
+
+struct MatchRec {
+    int32_t pattern = 0, backend = 0, first = 0, sink = 0;
+    std::vector<int32_t> nodes;       // ascending node id
+    std::vector<int32_t> binding;     // op pattern nodes in pattern order
+    std::vector<int32_t> wild;        // graph value bound to each pattern node
+                                      // (all pattern nodes, wildcards included)
+};
+
+struct Context;
+
+struct Graph {
+    Context *ctx = nullptr;
+    std::vector<Node> nodes;
+    std::vector<int32_t> outputs;
+    int32_t n_inputs = 0;
+    // derived (rebuilt lazily by finalize())
+    bool finalized = false;
+    std::vector<std::vector<int32_t>> consumers;
+    std::vector<int32_t> depth;
+    std::vector<int32_t> op_ids;      // operator nodes by ascending id
+    std::vector<int32_t> order;       // operator nodes sorted by (depth, id)
+    std::vector<int32_t> rank;        // node -> position in order, -1 for leaves
+    std::vector<char> is_output;
+    // last enumeration / search
+    std::vector<MatchRec> matches;
+    bool matched = false;
+    int64_t stats[5] = {0, 0, 0, 0, 0};
+    void finalize();
+};
+
+// ---- registry ------------------------------------------------------------------------
+enum Family : int32_t { FAM_IGEMM = 0, FAM_DIRECT = 1, FAM_ROWWISE = 2, FAM_ELTWISE = 3 };
+
+struct Backend {
+    std::string name;
+    int32_t family = 0;
+    int32_t tile = 0;                 // igemm: 0 auto, 1 small, 2 medium, 3 large
+};
+
+struct Pattern {
+    int32_t backend = 0;
+    std::vector<clg_pattern_node> nodes;   // post-order, root last
+    // chain view, computed at registration: chain[0] = anchor ... back() = root;
+    // main_arg[t] = which argument of chain[t] holds chain[t-1] (-1 for the anchor)
+    std::vector<int32_t> chain;
+    std::vector<int32_t> main_arg;
+};
+
+struct Context {
+    int32_t device = -1;
+    std::vector<Backend> backends;
+    std::vector<Pattern> patterns;
+    std::map<std::string, int64_t> cost_log;
+    int32_t n_cus = 256;
+    void *prof_ptr = nullptr;         // measurer's scratch operands (device)
+    size_t prof_bytes = 0;
+};
+
+// ---- lowering: one match -> one kernel call -------------------------------------------
+// Where an operand pointer comes from at execution time.
+struct Operand {
+    int32_t node = -1;                // graph value
+};
+
+enum CallKind : int32_t {
+    CALL_GEMM = 0, CALL_DIRECT_CONV, CALL_POOL, CALL_GAP, CALL_ROWWISE,
+    CALL_ELTWISE, CALL_LAYOUT
+};
+
+struct KernelCall {
+    int32_t kind = 0;
+    int32_t match = -1;
+    std::string name;
+    std::string key;                  // cost-log key: backend|fused kind|attrs|shapes
+    double flops = 0, bytes = 0;
+    int32_t bound = 1;                // 0 MFMA, 1 HBM
+    size_t scratch_bytes = 0;         // per-call device scratch (split-K partials)
+    bool gemm_swap = false;           // GEMM: A = second graph operand (weights), B = first
+    int32_t out_node = -1;
+    // pointer slots to fill at execution: each refers to a graph value
+    int32_t a_node = -1, b_node = -1, c_node = -1;     // main operands
+    int32_t epi_nodes[kMaxEpi];                        // operand of each epilogue step or -1
+    // kernel arguments with the pointer fields still null
+    GemmArgs gemm{};
+    DirectConvArgs dconv{};
+    PoolArgs pool{};
+    RowwiseArgs row{};
+    EltwiseArgs elt{};
+    LayoutArgs layout{};
+    KernelCall() { for (auto &e : epi_nodes) e = -1; }
+};
+
+// Builds the kernel call of match `m`.  Returns CLG_OK, or CLG_NO_KERNEL (with
+// a message) when the backend's family cannot run this match.
+int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, KernelCall *out);
+// Structure check at registration time.
+int32_t check_pattern(const Context &ctx, Pattern *p);
+
+// ---- plan -----------------------------------------------------------------------------
+struct Plan {
+    Context *ctx = nullptr;
+    Graph *graph = nullptr;
+    std::vector<KernelCall> calls;
+    std::vector<int64_t> value_offset;     // node -> workspace byte offset, -1 none
+    std::vector<int32_t> value_output;     // node -> index in outputs[], -1 none
+    std::vector<int64_t> scratch_offset;   // call -> workspace byte offset of its scratch
+    size_t workspace_bytes = 0;
+};
+
+int32_t launch_call(const KernelCall &c, const void *a, const void *b, const void *c3,
+                    void *out, const void *const *epi_ptrs, void *scratch, void *stream);
+
+// shape inference for one operator; returns CLG_OK or SHAPE_MISMATCH / INVALID_ARG
+int32_t infer_shape(const Graph &g, int32_t kind, const std::vector<int32_t> &in,
+                    const clg_attrs &a, Shape *out, int32_t *dtype);
+int64_t attr_value(const Graph &g, int32_t node, int32_t attr, bool *ok);
+const char *op_name(int32_t kind);
+
+int32_t match_all(Context &ctx, Graph &g);
+int32_t compile_plan(Context &ctx, Graph &g, const int32_t *ids, size_t n, Plan *plan);
+int32_t execute_plan(Plan &p, const void *const *inputs, void *const *outputs, void *workspace,
+                     size_t ws_bytes, void *stream, int64_t *kernel_ns);
+int32_t profile_match(Context &ctx, Graph &g, int32_t match, const clg_profile_opts *opts, int64_t *cost_ns);
+int32_t profile_empty(Context &ctx, const clg_profile_opts *opts, int64_t *cost_ns);
+int32_t cost_log_load(Context &ctx, const char *path);
+int32_t cost_log_save(const Context &ctx, const char *path);
+const char *last_error();
+int32_t search_dp(Graph &g, size_t n_patterns, const int64_t *cost, int64_t eps,
+                  std::vector<int32_t> *chosen, int64_t *total);
+
+}  // namespace clg
+
+struct clg_ctx { clg::Context c; };
+struct clg_graph { clg::Graph g; };
+struct clg_plan { clg::Plan p; };

@@ -1,0 +1,54 @@
+// Device-side helpers shared by the gfx950 kernels: the fused elementwise
+// program, wavefront (64-lane) reductions.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "kernels.h"
+
+namespace clg {
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float gelu_erf(float v) {
+    return 0.5f * v * (1.0f + erff(v * 0.70710678118654752f));
+}
+
+// Applies the fused steps to one value.  `off` is the element's offset in the
+// output tensor (EPI_ADD operands have the output's shape); `chan` its channel
+// for EPI_BIAS.  The program sits in the kernel-argument segment, so the loop
+// and its switch are wave-uniform.
+__device__ __forceinline__ float apply_steps(const Epilogue &e, float v, int64_t off, int chan) {
+#pragma unroll 1
+    for (int s = 0; s < e.n; ++s) {
+        const EpiStep st = e.s[s];
+        switch (st.op) {
+        case EPI_BIAS: v += st.ptr[chan]; break;
+        case EPI_ADD: v += st.ptr[off]; break;
+        case EPI_RELU: v = v > 0.f ? v : 0.f; break;
+        case EPI_GELU: v = gelu_erf(v); break;
+        case EPI_TANH: v = tanhf(v); break;
+        case EPI_SCALE: v *= st.scalar; break;
+        default: break;
+        }
+    }
+    return v;
+}
+
+__device__ __forceinline__ int chan_of(const Epilogue &e, int64_t off) {
+    return e.bias_c ? (int)((off / e.bias_inner) % e.bias_c) : 0;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int m = kWave / 2; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+    return v;
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int m = kWave / 2; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, kWave));
+    return v;
+}
+
+}  // namespace clg

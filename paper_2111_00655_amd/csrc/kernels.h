@@ -1,0 +1,140 @@
+// Argument blocks and host-callable launchers of the gfx950 kernel set.
+// Plain structs only, so the host-side planner can fill them without HIP
+// headers.  Every launcher validates nothing: the planner (lower.cpp) is
+// responsible for shapes that fit what the kernel and its grid assume.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+
+namespace clg {
+
+// ---- fused epilogue / prologue program ----------------------------------------------
+// A short list of elementwise steps applied, in order and in registers, to
+// each value a kernel produces (epilogue) or consumes (row-wise prologue).
+// This is how conv+bias(+residual)+ReLU, dense+bias+GELU and longer
+// elementwise tails (paper Sec. 5.5: Conv+ReLU, Conv+Add+ReLU, Add+ReLU, and
+// fusions of more than ten operators) become one kernel.
+constexpr int kMaxEpi = 8;
+
+enum EpiOp : int32_t {
+    EPI_NONE = 0,
+    EPI_BIAS = 1,     // v += ptr[channel]
+    EPI_ADD = 2,      // v += ptr[offset]           (same shape as the output)
+    EPI_RELU = 3,
+    EPI_GELU = 4,     // erf form
+    EPI_TANH = 5,
+    EPI_SCALE = 6     // v *= scalar
+};
+
+struct EpiStep {
+    int32_t op;
+    float scalar;
+    const float *ptr;
+};
+
+struct Epilogue {
+    int32_t n;
+    // channel of output offset o for EPI_BIAS: (o / bias_inner) % bias_c
+    int32_t bias_inner;
+    int32_t bias_c;
+    int32_t pad_;
+    EpiStep s[kMaxEpi];
+};
+
+// ---- MFMA implicit GEMM ----------------------------------------------------------------
+// C[i][j] = sum_k A(i,k) * B(k,j), fp32 MFMA, fp32 accumulate, epilogue in
+// registers.  j is the memory-contiguous output index.
+enum GemmMode : int32_t {
+    GM_NT = 0,     // A[M,K] and B[N,K], both K-contiguous (dense; batch_matmul with b = [B,N,K])
+    GM_NN = 1,     // A[M,K] K-contiguous, B[K,N] N-contiguous (batch_matmul with b = [B,K,N])
+    GM_CONV = 2,   // A = weights [Cout, Cin*KH*KW]; B = im2col gather of x; i = cout, j = pixel
+    GM_CONVT = 3   // transposed conv as stride*stride sub-pixel phases, one phase per grid.z slice
+};
+
+enum GemmTile : int32_t { TILE_AUTO = 0, TILE_S = 1, TILE_M = 2, TILE_L = 3 };
+
+struct GemmArgs {
+    int32_t mode, tile, splitk, batch;
+    int32_t M, N, K;
+    int32_t lda, ldb, ldc;
+    int64_t strideA, strideB, strideC;     // per batch, in elements
+    const float *A;
+    const float *B;
+    float *C;
+    float *partial;                        // split-K partial sums [splitk][numel(C)]
+    int64_t c_numel;
+    // convolution geometry (GM_CONV, GM_CONVT)
+    int32_t Nimg, Cin, H, W, Cout, KH, KW, sh, sw, ph, pw, HO, WO;
+    int32_t bias_on_row;                   // 1: channel = i (conv), 0: channel = j (dense)
+    Epilogue epi;
+};
+
+// ---- direct convolution (any groups) -----------------------------------------------------
+struct DirectConvArgs {
+    const float *x;
+    const float *w;
+    float *y;
+    int32_t N, C, H, W, O, KH, KW, sh, sw, ph, pw, G, HO, WO;
+    Epilogue epi;
+};
+
+struct PoolArgs {
+    const float *x;
+    float *y;
+    int32_t mode;                          // 0 max pool, 1 global average
+    int32_t NC, H, W, KH, KW, sh, sw, ph, pw, HO, WO;
+};
+
+// ---- row-wise reductions ------------------------------------------------------------------
+struct RowwiseArgs {
+    int32_t mode;                          // 0 softmax, 1 layer norm
+    int32_t rows, len;
+    float eps;
+    const float *x;
+    const float *gamma;
+    const float *beta;
+    float *y;
+    Epilogue pro;                          // applied to x first; channel = column
+};
+
+// ---- elementwise chain / gather --------------------------------------------------------------
+struct EltwiseArgs {
+    const float *x;                        // source tensor, or the table when ids != null
+    const int32_t *ids;                    // take: row ids
+    float *y;
+    int64_t numel;
+    int32_t row_len;                       // take: hidden size
+    int32_t table_rows;                    // take: rows of the table (ids are clamped into it)
+    Epilogue epi;
+};
+
+// ---- layout copy: y[o] = x[sum_d idx_d(o) * in_stride[d]] --------------------------------------
+struct LayoutArgs {
+    const float *x;
+    float *y;
+    int64_t numel;
+    int32_t ndim;
+    int64_t out_dims[6];
+    int64_t in_strides[6];
+};
+
+// Launchers: enqueue on `stream` (a hipStream_t) and return the hipError_t
+// of the launch as an int (0 = success).
+int launch_gemm(const GemmArgs &a, void *stream);
+int launch_direct_conv(const DirectConvArgs &a, void *stream);
+int launch_pool(const PoolArgs &a, void *stream);
+int launch_rowwise(const RowwiseArgs &a, void *stream);
+int launch_eltwise(const EltwiseArgs &a, void *stream);
+int launch_layout(const LayoutArgs &a, void *stream);
+// Scratch-operand fill for the measurer: uniform values in [-1, 1) from a
+// counter hash of (seed, index); ids: zeros.
+int launch_fill(float *p, int64_t n, uint64_t seed, void *stream);
+int launch_empty(void *stream);
+
+// Tile choice and split-K factor the GEMM launcher will use for these sizes
+// (resolved at plan time so that the scratch size is known).
+void gemm_resolve(GemmArgs *a, int n_cus);
+size_t gemm_scratch_bytes(const GemmArgs &a);
+
+}  // namespace clg

@@ -1,0 +1,319 @@
+// Memory-bound kernels of the fused-operator set for gfx950: elementwise
+// chains and embedding gather, softmax / layer norm with a fused prologue
+// (wavefront shuffle reductions, one 64-lane wave per row), direct convolution
+// for grouped and small-channel layers, pooling, layout copies.
+//
+// These operators move O(1) flops per byte (paper Sec. 5.1 lists them as the
+// non-contraction part of the workloads), so the design rule is: every tensor
+// is read once and written once, with consecutive lanes on consecutive
+// addresses; anything elementwise rides along in registers.
+#include <algorithm>
+
+#include <hip/hip_runtime.h>
+
+#include "device_common.h"
+
+namespace clg {
+
+// ------------------------------------------------------------------ elementwise
+// y = steps(x) (or steps(table[ids])).  VEC = 4: numel % 4 == 0, and the four
+// elements of a float4 share a bias channel layout the kernel can index:
+// inner % 4 == 0 (same channel) or inner == 1 with C % 4 == 0 (four channels).
+template <int VEC>
+__global__ __launch_bounds__(256) void eltwise_kernel(EltwiseArgs a) {
+    const int64_t n = a.numel / VEC;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const int64_t off = i * VEC;
+        float v[VEC];
+        const float *src = a.x + off;
+        if (a.ids) {
+            const int64_t row = off / a.row_len, col = off % a.row_len;
+            int id = a.ids[row];
+            id = id < 0 ? 0 : (id >= a.table_rows ? a.table_rows - 1 : id);
+            src = a.x + (int64_t)id * a.row_len + col;
+        }
+        if constexpr (VEC == 4) {
+            const float4 t = *reinterpret_cast<const float4 *>(src);
+            v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+        } else {
+            v[0] = src[0];
+        }
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) v[q] = apply_steps(a.epi, v[q], off + q, chan_of(a.epi, off + q));
+        if constexpr (VEC == 4) {
+            *reinterpret_cast<float4 *>(a.y + off) = make_float4(v[0], v[1], v[2], v[3]);
+        } else {
+            a.y[off] = v[0];
+        }
+    }
+}
+
+static bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+
+int launch_eltwise(const EltwiseArgs &a, void *stream) {
+    bool vec = a.numel % 4 == 0 && aligned16(a.x) && aligned16(a.y) && (!a.ids || a.row_len % 4 == 0);
+    for (int s = 0; s < a.epi.n; ++s)
+        if (a.epi.s[s].op == EPI_ADD && !aligned16(a.epi.s[s].ptr)) vec = false;
+    const int64_t items = vec ? a.numel / 4 : a.numel;
+    const int block = 256;
+    const int grid = (int)std::min<int64_t>((items + block - 1) / block, 256 * 16);
+    if (vec)
+        hipLaunchKernelGGL(eltwise_kernel<4>, dim3(grid), dim3(block), 0, (hipStream_t)stream, a);
+    else
+        hipLaunchKernelGGL(eltwise_kernel<1>, dim3(grid), dim3(block), 0, (hipStream_t)stream, a);
+    return (int)hipGetLastError();
+}
+
+// --------------------------------------------------------------- softmax / LN
+// One wave per row; the row (after the fused prologue) is held in registers:
+// ITEMS values per lane, element c = lane + 64 * t.  Reads x once, writes y
+// once.  Softmax: max, sum of exp, normalise.  Layer norm: mean, then the
+// biased variance of the centred values, then scale and shift.
+template <int ITEMS>
+__global__ __launch_bounds__(256) void rowwise_kernel(RowwiseArgs a) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int row = blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (row >= a.rows) return;
+    const float *xr = a.x + (int64_t)row * a.len;
+    float *yr = a.y + (int64_t)row * a.len;
+    float v[ITEMS];
+#pragma unroll
+    for (int t = 0; t < ITEMS; ++t) {
+        const int c = lane + kWave * t;
+        v[t] = 0.f;
+        if (c < a.len) v[t] = apply_steps(a.pro, xr[c], (int64_t)row * a.len + c, c);
+    }
+    if (a.mode == 0) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < ITEMS; ++t)
+            if (lane + kWave * t < a.len) mx = fmaxf(mx, v[t]);
+        mx = wave_max(mx);
+        float sum = 0.f;
+#pragma unroll
+        for (int t = 0; t < ITEMS; ++t) {
+            v[t] = (lane + kWave * t < a.len) ? expf(v[t] - mx) : 0.f;
+            sum += v[t];
+        }
+        sum = wave_sum(sum);
+        const float inv = 1.0f / sum;
+#pragma unroll
+        for (int t = 0; t < ITEMS; ++t)
+            if (lane + kWave * t < a.len) yr[lane + kWave * t] = v[t] * inv;
+    } else {
+        float sum = 0.f;
+#pragma unroll
+        for (int t = 0; t < ITEMS; ++t) sum += v[t];          // padding lanes hold 0
+        const float mean = wave_sum(sum) / (float)a.len;
+        float sq = 0.f;
+#pragma unroll
+        for (int t = 0; t < ITEMS; ++t) {
+            const float d = (lane + kWave * t < a.len) ? v[t] - mean : 0.f;
+            v[t] = d;
+            sq += d * d;
+        }
+        const float var = wave_sum(sq) / (float)a.len;
+        const float inv = 1.0f / sqrtf(var + a.eps);
+#pragma unroll
+        for (int t = 0; t < ITEMS; ++t) {
+            const int c = lane + kWave * t;
+            if (c < a.len) yr[c] = v[t] * inv * a.gamma[c] + a.beta[c];
+        }
+    }
+}
+
+// Rows longer than 64 * 32: same arithmetic, the row is re-read per pass.
+__global__ __launch_bounds__(256) void rowwise_long_kernel(RowwiseArgs a) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int row = blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (row >= a.rows) return;
+    const float *xr = a.x + (int64_t)row * a.len;
+    float *yr = a.y + (int64_t)row * a.len;
+    auto val = [&](int c) { return apply_steps(a.pro, xr[c], (int64_t)row * a.len + c, c); };
+    if (a.mode == 0) {
+        float mx = -INFINITY;
+        for (int c = lane; c < a.len; c += kWave) mx = fmaxf(mx, val(c));
+        mx = wave_max(mx);
+        float sum = 0.f;
+        for (int c = lane; c < a.len; c += kWave) sum += expf(val(c) - mx);
+        sum = wave_sum(sum);
+        const float inv = 1.0f / sum;
+        for (int c = lane; c < a.len; c += kWave) yr[c] = expf(val(c) - mx) * inv;
+    } else {
+        float sum = 0.f;
+        for (int c = lane; c < a.len; c += kWave) sum += val(c);
+        const float mean = wave_sum(sum) / (float)a.len;
+        float sq = 0.f;
+        for (int c = lane; c < a.len; c += kWave) {
+            const float d = val(c) - mean;
+            sq += d * d;
+        }
+        const float inv = 1.0f / sqrtf(wave_sum(sq) / (float)a.len + a.eps);
+        for (int c = lane; c < a.len; c += kWave) yr[c] = (val(c) - mean) * inv * a.gamma[c] + a.beta[c];
+    }
+}
+
+int launch_rowwise(const RowwiseArgs &a, void *stream) {
+    const int block = 256, rows_per_block = block / kWave;
+    const dim3 grid((a.rows + rows_per_block - 1) / rows_per_block);
+    const int items = (a.len + kWave - 1) / kWave;
+    hipStream_t s = (hipStream_t)stream;
+    if (items <= 1) hipLaunchKernelGGL(rowwise_kernel<1>, grid, dim3(block), 0, s, a);
+    else if (items <= 2) hipLaunchKernelGGL(rowwise_kernel<2>, grid, dim3(block), 0, s, a);
+    else if (items <= 4) hipLaunchKernelGGL(rowwise_kernel<4>, grid, dim3(block), 0, s, a);
+    else if (items <= 8) hipLaunchKernelGGL(rowwise_kernel<8>, grid, dim3(block), 0, s, a);
+    else if (items <= 16) hipLaunchKernelGGL(rowwise_kernel<16>, grid, dim3(block), 0, s, a);
+    else if (items <= 32) hipLaunchKernelGGL(rowwise_kernel<32>, grid, dim3(block), 0, s, a);
+    else hipLaunchKernelGGL(rowwise_long_kernel, grid, dim3(block), 0, s, a);
+    return (int)hipGetLastError();
+}
+
+// ------------------------------------------------------------ direct convolution
+// One thread per output pixel and COB consecutive output channels of one group:
+// every input value loaded is used COB times; the weights of those channels are
+// wave-uniform (scalar loads).  blockIdx.y = channel block, blockIdx.z = image.
+template <int COB>
+__global__ __launch_bounds__(256) void direct_conv_kernel(DirectConvArgs a) {
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    const int npix = a.HO * a.WO;
+    const int Cg = a.C / a.G, Og = a.O / a.G;
+    const int co0 = blockIdx.y * COB;
+    const int g = co0 / Og;
+    const int n = blockIdx.z;
+    if (p >= npix) return;
+    const int oh = p / a.WO, ow = p % a.WO;
+    float acc[COB];
+#pragma unroll
+    for (int j = 0; j < COB; ++j) acc[j] = 0.f;
+    const float *xg = a.x + ((int64_t)n * a.C + (int64_t)g * Cg) * a.H * a.W;
+    const float *wg = a.w + (int64_t)co0 * Cg * a.KH * a.KW;
+    const int wstride = Cg * a.KH * a.KW;
+    for (int ci = 0; ci < Cg; ++ci) {
+        for (int kh = 0; kh < a.KH; ++kh) {
+            const int ih = oh * a.sh - a.ph + kh;
+            if (ih < 0 || ih >= a.H) continue;
+            for (int kw = 0; kw < a.KW; ++kw) {
+                const int iw = ow * a.sw - a.pw + kw;
+                if (iw < 0 || iw >= a.W) continue;
+                const float xv = xg[((int64_t)ci * a.H + ih) * a.W + iw];
+                const float *wp = wg + (ci * a.KH + kh) * a.KW + kw;
+#pragma unroll
+                for (int j = 0; j < COB; ++j) acc[j] = fmaf(xv, wp[j * wstride], acc[j]);
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < COB; ++j) {
+        const int co = co0 + j;
+        const int64_t off = ((int64_t)n * a.O + co) * npix + p;
+        a.y[off] = apply_steps(a.epi, acc[j], off, co);
+    }
+}
+
+int launch_direct_conv(const DirectConvArgs &a, void *stream) {
+    const int npix = a.HO * a.WO;
+    const int Og = a.O / a.G;
+    const int block = npix >= 256 ? 256 : (npix > 64 ? 128 : 64);
+    hipStream_t s = (hipStream_t)stream;
+    if (Og % 4 == 0) {
+        const dim3 grid((npix + block - 1) / block, a.O / 4, a.N);
+        hipLaunchKernelGGL(direct_conv_kernel<4>, grid, dim3(block), 0, s, a);
+    } else {
+        const dim3 grid((npix + block - 1) / block, a.O, a.N);
+        hipLaunchKernelGGL(direct_conv_kernel<1>, grid, dim3(block), 0, s, a);
+    }
+    return (int)hipGetLastError();
+}
+
+// ------------------------------------------------------------------------ pooling
+__global__ __launch_bounds__(256) void max_pool_kernel(PoolArgs a) {
+    const int64_t total = (int64_t)a.NC * a.HO * a.WO;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const int ow = (int)(i % a.WO), oh = (int)((i / a.WO) % a.HO);
+    const int64_t nc = i / ((int64_t)a.WO * a.HO);
+    const float *xp = a.x + nc * a.H * a.W;
+    float best = -INFINITY;
+    for (int kh = 0; kh < a.KH; ++kh) {
+        const int ih = oh * a.sh - a.ph + kh;
+        if (ih < 0 || ih >= a.H) continue;
+        for (int kw = 0; kw < a.KW; ++kw) {
+            const int iw = ow * a.sw - a.pw + kw;
+            if (iw < 0 || iw >= a.W) continue;
+            best = fmaxf(best, xp[(int64_t)ih * a.W + iw]);
+        }
+    }
+    a.y[i] = best;
+}
+
+// one wave per (n, c) plane
+__global__ __launch_bounds__(256) void global_avg_pool_kernel(PoolArgs a) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int nc = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+    if (nc >= a.NC) return;
+    const int hw = a.H * a.W;
+    const float *xp = a.x + (int64_t)nc * hw;
+    float sum = 0.f;
+    for (int i = lane; i < hw; i += kWave) sum += xp[i];
+    sum = wave_sum(sum);
+    if (lane == 0) a.y[nc] = sum / (float)hw;
+}
+
+int launch_pool(const PoolArgs &a, void *stream) {
+    hipStream_t s = (hipStream_t)stream;
+    if (a.mode == 0) {
+        const int64_t total = (int64_t)a.NC * a.HO * a.WO;
+        hipLaunchKernelGGL(max_pool_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, a);
+    } else {
+        hipLaunchKernelGGL(global_avg_pool_kernel, dim3((a.NC + 3) / 4), dim3(256), 0, s, a);
+    }
+    return (int)hipGetLastError();
+}
+
+// --------------------------------------------------------------------- layout copy
+__global__ __launch_bounds__(256) void layout_kernel(LayoutArgs a) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; o < a.numel; o += stride) {
+        int64_t rem = o, src = 0;
+        for (int d = a.ndim - 1; d >= 0; --d) {
+            const int64_t q = rem / a.out_dims[d];
+            src += (rem - q * a.out_dims[d]) * a.in_strides[d];
+            rem = q;
+        }
+        a.y[o] = a.x[src];
+    }
+}
+
+int launch_layout(const LayoutArgs &a, void *stream) {
+    const int grid = (int)std::min<int64_t>((a.numel + 255) / 256, 256 * 16);
+    hipLaunchKernelGGL(layout_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, a);
+    return (int)hipGetLastError();
+}
+
+// ------------------------------------------------------- measurer scratch operands
+__global__ __launch_bounds__(256) void fill_kernel(float *p, int64_t n, uint64_t seed) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        uint64_t z = seed + 0x9E3779B97F4A7C15ull * (uint64_t)(i + 1);    // splitmix64 finaliser
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+        z ^= z >> 31;
+        p[i] = (float)((z >> 40) & 0xFFFFFF) * (2.0f / 16777216.0f) - 1.0f;
+    }
+}
+
+int launch_fill(float *p, int64_t n, uint64_t seed, void *stream) {
+    const int grid = (int)std::min<int64_t>((n + 255) / 256, 256 * 16);
+    hipLaunchKernelGGL(fill_kernel, dim3(grid > 0 ? grid : 1), dim3(256), 0, (hipStream_t)stream, p, n, seed);
+    return (int)hipGetLastError();
+}
+
+__global__ void empty_kernel() {}
+
+int launch_empty(void *stream) {
+    hipLaunchKernelGGL(empty_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream);
+    return (int)hipGetLastError();
+}
+
+}  // namespace clg

@@ -1,0 +1,463 @@
+// Lowering: a backend pattern's structure check at registration, and the
+// translation of one match into one kernel call (paper Sec. 4.2: a matched
+// subgraph is "single or multiple operators (operator fusion) that will be
+// lowered to a single low-level kernel").
+//
+// Every pattern the kernel families accept is a chain: an anchor operator
+// whose arguments are all wildcards, followed by operators that each take the
+// previous one as exactly one argument.  The anchor decides the kernel
+// (contraction, row-wise reduction, elementwise, layout copy); the rest of the
+// chain becomes the in-register epilogue (or, for softmax / layer norm at the
+// end of the chain, the prologue).
+#include <algorithm>
+#include <cstdio>
+
+#include "core.h"
+
+namespace clg {
+
+namespace {
+
+bool is_elementwise(int32_t op) {
+    return op == CLG_OP_BIAS_ADD || op == CLG_OP_ADD || op == CLG_OP_MUL_SCALAR ||
+           op == CLG_OP_RELU || op == CLG_OP_GELU || op == CLG_OP_TANH;
+}
+bool is_contraction(int32_t op) {
+    return op == CLG_OP_CONV2D || op == CLG_OP_CONV2D_TRANSPOSE || op == CLG_OP_DENSE ||
+           op == CLG_OP_BATCH_MATMUL;
+}
+bool is_layout(int32_t op) { return op == CLG_OP_RESHAPE || op == CLG_OP_TRANSPOSE; }
+bool is_rowwise(int32_t op) { return op == CLG_OP_SOFTMAX || op == CLG_OP_LAYER_NORM; }
+
+}  // namespace
+
+int32_t check_pattern(const Context &ctx, Pattern *p) {
+    const int n = (int)p->nodes.size();
+    if (n < 1 || n > CLG_MAX_PATTERN_NODES) return fail(CLG_INVALID_ARG, "pattern has %d nodes", n);
+    std::vector<int> used(n, 0);
+    for (int i = 0; i < n; ++i) {
+        const clg_pattern_node &pn = p->nodes[i];
+        if (pn.op != CLG_WILDCARD && (pn.op < 0 || pn.op >= CLG_OP_COUNT))
+            return fail(CLG_INVALID_ARG, "pattern node %d: bad op kind %d", i, pn.op);
+        if (pn.n_args < 0 || pn.n_args > CLG_MAX_PATTERN_ARGS || (pn.op == CLG_WILDCARD && pn.n_args))
+            return fail(CLG_INVALID_ARG, "pattern node %d: bad argument count", i);
+        if (pn.n_constraints < 0 || pn.n_constraints > CLG_MAX_CONSTRAINTS)
+            return fail(CLG_INVALID_ARG, "pattern node %d: bad constraint count", i);
+        for (int c = 0; c < pn.n_constraints; ++c)
+            if (pn.constraints[c].attr < 0 || pn.constraints[c].attr >= CLG_ATTR_COUNT)
+                return fail(CLG_INVALID_ARG, "pattern node %d: bad attribute id", i);
+        for (int k = 0; k < pn.n_args; ++k) {
+            if (pn.args[k] < 0 || pn.args[k] >= i)
+                return fail(CLG_INVALID_ARG, "pattern node %d: argument %d is not an earlier node", i, k);
+            if (used[pn.args[k]]++)
+                return fail(CLG_INVALID_ARG, "pattern node %d is used twice (not a tree)", pn.args[k]);
+        }
+    }
+    for (int i = 0; i < n - 1; ++i)
+        if (!used[i]) return fail(CLG_INVALID_ARG, "pattern node %d is unreachable from the root", i);
+    if (p->nodes[n - 1].op == CLG_WILDCARD) return fail(CLG_INVALID_ARG, "the root is a wildcard");
+
+    // chain view
+    p->chain.clear();
+    p->main_arg.clear();
+    int cur = n - 1;
+    for (;;) {
+        const clg_pattern_node &pn = p->nodes[cur];
+        int main = -1, n_ops = 0;
+        for (int k = 0; k < pn.n_args; ++k)
+            if (p->nodes[pn.args[k]].op != CLG_WILDCARD) {
+                main = k;
+                ++n_ops;
+            }
+        if (n_ops > 1)
+            return fail(CLG_NO_KERNEL, "no kernel family fuses a pattern that branches at %s", op_name(pn.op));
+        p->chain.push_back(cur);
+        p->main_arg.push_back(main);
+        if (n_ops == 0) break;
+        cur = pn.args[main];
+    }
+    std::reverse(p->chain.begin(), p->chain.end());
+    // main_arg[t] currently says where chain[t]'s child sits; after the reverse
+    // the entry of chain[t] must describe chain[t-1]: it already does, as it was
+    // pushed together with its node.
+    std::reverse(p->main_arg.begin(), p->main_arg.end());
+
+    const Backend &be = ctx.backends[p->backend];
+    const int len = (int)p->chain.size();
+    auto kind = [&](int t) { return p->nodes[p->chain[t]].op; };
+    const int32_t k0 = kind(0), kl = kind(len - 1);
+    auto tail_ok = [&](int from, int to) {   // elementwise ops taking the chain as operand 0 (add: either)
+        for (int t = from; t < to; ++t) {
+            const int32_t k = kind(t);
+            if (k == CLG_OP_RESHAPE && t == len - 1 && to == len) continue;
+            if (!is_elementwise(k)) return false;
+            if (t > 0 && k == CLG_OP_BIAS_ADD && p->main_arg[t] != 0) return false;
+        }
+        return true;
+    };
+    if (len - 1 > kMaxEpi) return fail(CLG_NO_KERNEL, "pattern has more than %d fused steps", kMaxEpi);
+    bool ok = false;
+    switch (be.family) {
+    case FAM_IGEMM:
+        ok = is_contraction(k0) && tail_ok(1, len);
+        break;
+    case FAM_DIRECT:
+        ok = (k0 == CLG_OP_CONV2D && tail_ok(1, len)) ||
+             (len == 1 && (k0 == CLG_OP_MAX_POOL2D || k0 == CLG_OP_GLOBAL_AVG_POOL2D));
+        break;
+    case FAM_ROWWISE:
+        ok = is_rowwise(kl) && (len == 1 || (p->main_arg[len - 1] == 0 && is_elementwise(k0) &&
+                                             tail_ok(1, len - 1)));
+        break;
+    case FAM_ELTWISE: {
+        if (is_layout(k0)) {
+            int n_tr = 0;
+            ok = true;
+            for (int t = 0; t < len; ++t) {
+                ok = ok && is_layout(kind(t));
+                n_tr += kind(t) == CLG_OP_TRANSPOSE;
+            }
+            ok = ok && n_tr <= 1;
+        } else {
+            ok = (is_elementwise(k0) || k0 == CLG_OP_TAKE) && tail_ok(1, len) &&
+                 kl != CLG_OP_RESHAPE;
+        }
+        break;
+    }
+    default:
+        break;
+    }
+    if (!ok) {
+        std::string s;
+        for (int t = 0; t < len; ++t) s += std::string(t ? "+" : "") + op_name(kind(t));
+        return fail(CLG_NO_KERNEL, "backend %s has no kernel for the fused kind %s", be.name.c_str(), s.c_str());
+    }
+    return CLG_OK;
+}
+
+namespace {
+
+struct ChainView {
+    const Graph &g;
+    const Pattern &p;
+    const MatchRec &m;
+    int len() const { return (int)p.chain.size(); }
+    int32_t op(int t) const { return p.nodes[p.chain[t]].op; }
+    int32_t node(int t) const { return m.wild[p.chain[t]]; }                 // graph node of chain[t]
+    int32_t arg(int t, int k) const { return m.wild[p.nodes[p.chain[t]].args[k]]; }  // graph value of its k-th pattern arg
+    int32_t other(int t) const { return arg(t, 1 - p.main_arg[t]); }          // binary op: the non-chain operand
+};
+
+// Appends the step of elementwise chain op t to `e`.  `as_anchor`: the op's
+// own operand 0 is the running value.
+int32_t add_step(const ChainView &cv, int t, bool as_anchor, Epilogue *e, int32_t *epi_nodes) {
+    const int32_t k = cv.op(t);
+    if (k == CLG_OP_RESHAPE) return CLG_OK;
+    if (e->n >= kMaxEpi) return fail(CLG_NO_KERNEL, "too many fused steps");
+    EpiStep &s = e->s[e->n];
+    s.scalar = 0.f;
+    s.ptr = nullptr;
+    int32_t operand = -1;
+    const Node &nd = cv.g.nodes[cv.node(t)];
+    switch (k) {
+    case CLG_OP_BIAS_ADD: {
+        s.op = EPI_BIAS;
+        operand = cv.arg(t, 1);
+        const Shape &xs = nd.shape;
+        const int ax = nd.attrs.axis >= 0 ? nd.attrs.axis : xs.ndim + nd.attrs.axis;
+        int64_t inner = 1;
+        for (int d = ax + 1; d < xs.ndim; ++d) inner *= xs.d[d];
+        const int64_t c = xs.d[ax];
+        if (e->bias_c && (e->bias_c != c || e->bias_inner != inner))
+            return fail(CLG_NO_KERNEL, "bias_add steps with different channel layouts in one kernel");
+        e->bias_c = (int32_t)c;
+        e->bias_inner = (int32_t)inner;
+        break;
+    }
+    case CLG_OP_ADD:
+        s.op = EPI_ADD;
+        operand = as_anchor ? cv.arg(t, 1) : cv.other(t);
+        break;
+    case CLG_OP_MUL_SCALAR:
+        s.op = EPI_SCALE;
+        s.scalar = (float)nd.attrs.scalar;
+        break;
+    case CLG_OP_RELU: s.op = EPI_RELU; break;
+    case CLG_OP_GELU: s.op = EPI_GELU; break;
+    case CLG_OP_TANH: s.op = EPI_TANH; break;
+    default:
+        return fail(CLG_NO_KERNEL, "%s cannot be a fused step", op_name(k));
+    }
+    epi_nodes[e->n] = operand;
+    ++e->n;
+    return CLG_OK;
+}
+
+std::string shape_key(const Graph &g, int32_t v) { return g.nodes[v].shape.str(); }
+
+}  // namespace
+
+int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, KernelCall *out) {
+    if (match_id < 0 || match_id >= (int32_t)g.matches.size())
+        return fail(CLG_UNKNOWN_ID, "match id %d", match_id);
+    const MatchRec &m = g.matches[match_id];
+    const Pattern &p = ctx.patterns[m.pattern];
+    const Backend &be = ctx.backends[p.backend];
+    const ChainView cv{g, p, m};
+    const int len = cv.len();
+    KernelCall c;
+    c.match = match_id;
+    c.out_node = m.sink;
+    const Shape &out_shape = g.nodes[m.sink].shape;
+    const int32_t k0 = cv.op(0);
+    const Node &anchor = g.nodes[cv.node(0)];
+
+    // operands counted once each for the algorithmic byte count
+    std::vector<int32_t> ext;
+    auto use = [&](int32_t v) {
+        if (v >= 0 && std::find(ext.begin(), ext.end(), v) == ext.end()) ext.push_back(v);
+    };
+    std::string kinds;
+    for (int t = 0; t < len; ++t) kinds += std::string(t ? "+" : "") + op_name(cv.op(t));
+    char abuf[160];
+    std::snprintf(abuf, sizeof abuf, "s%dx%d,p%dx%d,g%d,tb%d,k%dx%d", anchor.attrs.stride[0], anchor.attrs.stride[1],
+                  anchor.attrs.pad[0], anchor.attrs.pad[1], anchor.attrs.groups > 0 ? anchor.attrs.groups : 1,
+                  anchor.attrs.transpose_b ? 1 : 0, anchor.attrs.kernel[0], anchor.attrs.kernel[1]);
+
+    Epilogue epi{};
+    int32_t rc = CLG_OK;
+
+    if (is_contraction(k0)) {
+        const int32_t xa = cv.arg(0, 0), wb = cv.arg(0, 1);
+        const Shape &xs = g.nodes[xa].shape, &ws = g.nodes[wb].shape, &ys = anchor.shape;
+        use(xa);
+        use(wb);
+        for (int t = 1; t < len; ++t) {
+            if ((rc = add_step(cv, t, false, &epi, c.epi_nodes)) != CLG_OK) return rc;
+        }
+        for (int s = 0; s < epi.n; ++s) use(c.epi_nodes[s]);
+        // where the channel of a bias step lives
+        const bool conv_like = (k0 == CLG_OP_CONV2D || k0 == CLG_OP_CONV2D_TRANSPOSE);
+        if (epi.bias_c) {
+            const int64_t want_inner = conv_like ? ys.d[2] * ys.d[3] : 1;
+            const int64_t want_c = conv_like ? ys.d[1] : ys.d[ys.ndim - 1];
+            if (k0 == CLG_OP_BATCH_MATMUL || epi.bias_inner != want_inner || epi.bias_c != want_c)
+                return fail(CLG_NO_KERNEL, "bias_add axis does not match the kernel's channel dimension");
+        }
+        double macs = 0;
+        if (be.family == FAM_DIRECT) {
+            if (k0 != CLG_OP_CONV2D) return fail(CLG_NO_KERNEL, "direct backend runs conv2d only");
+            DirectConvArgs &a = c.dconv;
+            a.N = (int)xs.d[0]; a.C = (int)xs.d[1]; a.H = (int)xs.d[2]; a.W = (int)xs.d[3];
+            a.O = (int)ws.d[0]; a.KH = (int)ws.d[2]; a.KW = (int)ws.d[3];
+            a.sh = anchor.attrs.stride[0]; a.sw = anchor.attrs.stride[1];
+            a.ph = anchor.attrs.pad[0]; a.pw = anchor.attrs.pad[1];
+            a.G = anchor.attrs.groups > 0 ? anchor.attrs.groups : 1;
+            a.HO = (int)ys.d[2]; a.WO = (int)ys.d[3];
+            a.epi = epi;
+            c.kind = CALL_DIRECT_CONV;
+            c.name = "direct_conv";
+            macs = (double)ys.numel() * (a.C / a.G) * a.KH * a.KW;
+            c.bound = 1;
+        } else {
+            GemmArgs &a = c.gemm;
+            a.tile = be.tile;
+            a.batch = 1;
+            a.epi = epi;
+            a.c_numel = ys.numel();
+            if (k0 == CLG_OP_DENSE) {
+                a.mode = GM_NT;
+                a.M = (int)xs.d[0]; a.K = (int)xs.d[1]; a.N = (int)ws.d[0];
+                a.lda = a.K; a.ldb = a.K; a.ldc = a.N;
+                a.bias_on_row = 0;
+                c.name = "gemm_nt";
+            } else if (k0 == CLG_OP_BATCH_MATMUL) {
+                const bool tb = anchor.attrs.transpose_b != 0;
+                a.mode = tb ? GM_NT : GM_NN;
+                a.batch = (int)xs.d[0];
+                a.M = (int)xs.d[1]; a.K = (int)xs.d[2]; a.N = (int)ys.d[2];
+                a.lda = a.K; a.ldb = tb ? a.K : a.N; a.ldc = a.N;
+                a.strideA = (int64_t)a.M * a.K; a.strideB = (int64_t)a.N * a.K; a.strideC = (int64_t)a.M * a.N;
+                c.name = tb ? "bmm_nt" : "bmm_nn";
+            } else if (k0 == CLG_OP_CONV2D) {
+                const int G = anchor.attrs.groups > 0 ? anchor.attrs.groups : 1;
+                if (G != 1) return fail(CLG_NO_KERNEL, "implicit-GEMM conv needs groups = 1 (got %d)", G);
+                a.Nimg = (int)xs.d[0]; a.Cin = (int)xs.d[1]; a.H = (int)xs.d[2]; a.W = (int)xs.d[3];
+                a.Cout = (int)ws.d[0]; a.KH = (int)ws.d[2]; a.KW = (int)ws.d[3];
+                a.sh = anchor.attrs.stride[0]; a.sw = anchor.attrs.stride[1];
+                a.ph = anchor.attrs.pad[0]; a.pw = anchor.attrs.pad[1];
+                a.HO = (int)ys.d[2]; a.WO = (int)ys.d[3];
+                a.bias_on_row = 1;
+                c.gemm_swap = true;
+                if (a.KH == 1 && a.KW == 1 && a.sh == 1 && a.sw == 1 && a.ph == 0 && a.pw == 0) {
+                    // 1x1 stride-1 convolution is a plain GEMM per image: W[Cout,Cin] * X[Cin,H*W]
+                    a.mode = GM_NN;
+                    a.batch = a.Nimg;
+                    a.M = a.Cout; a.N = a.H * a.W; a.K = a.Cin;
+                    a.lda = a.K; a.ldb = a.N; a.ldc = a.N;
+                    a.strideA = 0; a.strideB = (int64_t)a.Cin * a.N; a.strideC = (int64_t)a.Cout * a.N;
+                } else {
+                    a.mode = GM_CONV;
+                    a.M = a.Cout; a.N = a.Nimg * a.HO * a.WO; a.K = a.Cin * a.KH * a.KW;
+                    a.lda = a.K;
+                }
+                c.name = "conv_igemm";
+            } else {
+                a.mode = GM_CONVT;
+                a.Nimg = (int)xs.d[0]; a.Cin = (int)xs.d[1]; a.H = (int)xs.d[2]; a.W = (int)xs.d[3];
+                a.Cout = (int)ws.d[1]; a.KH = (int)ws.d[2]; a.KW = (int)ws.d[3];
+                a.sh = anchor.attrs.stride[0]; a.sw = anchor.attrs.stride[1];
+                a.ph = anchor.attrs.pad[0]; a.pw = anchor.attrs.pad[1];
+                a.HO = (int)ys.d[2]; a.WO = (int)ys.d[3];
+                if (a.KH % a.sh || a.KW % a.sw || a.HO % a.sh || a.WO % a.sw)
+                    return fail(CLG_NO_KERNEL, "transposed conv kernel needs kernel and output sizes divisible by the stride");
+                a.batch = a.sh * a.sw;                       // sub-pixel phases
+                a.M = a.Cout; a.N = a.Nimg * (a.HO / a.sh) * (a.WO / a.sw);
+                a.K = a.Cin * (a.KH / a.sh) * (a.KW / a.sw);
+                a.bias_on_row = 1;
+                c.gemm_swap = true;
+                c.name = "convt_igemm";
+            }
+            macs = (double)a.batch * a.M * a.N * a.K;
+            if ((double)a.M * a.N > 2.0e9 || a.K < 1) return fail(CLG_NO_KERNEL, "GEMM dimensions out of range");
+            gemm_resolve(&a, ctx.n_cus);
+            c.scratch_bytes = gemm_scratch_bytes(a);
+            c.kind = CALL_GEMM;
+            c.bound = 0;
+            static const char *tn[] = {"auto", "s", "m", "l"};
+            c.name += std::string("_") + tn[a.tile] + (a.splitk > 1 ? "_k" + std::to_string(a.splitk) : "");
+        }
+        c.a_node = xa;
+        c.b_node = wb;
+        c.flops = 2.0 * macs;
+    } else if (k0 == CLG_OP_MAX_POOL2D || k0 == CLG_OP_GLOBAL_AVG_POOL2D) {
+        const int32_t xa = cv.arg(0, 0);
+        const Shape &xs = g.nodes[xa].shape;
+        use(xa);
+        PoolArgs &a = c.pool;
+        a.NC = (int)(xs.d[0] * xs.d[1]); a.H = (int)xs.d[2]; a.W = (int)xs.d[3];
+        if (k0 == CLG_OP_MAX_POOL2D) {
+            a.mode = 0;
+            a.KH = anchor.attrs.kernel[0]; a.KW = anchor.attrs.kernel[1];
+            a.sh = anchor.attrs.stride[0]; a.sw = anchor.attrs.stride[1];
+            a.ph = anchor.attrs.pad[0]; a.pw = anchor.attrs.pad[1];
+            a.HO = (int)anchor.shape.d[2]; a.WO = (int)anchor.shape.d[3];
+            c.name = "max_pool";
+        } else {
+            a.mode = 1;
+            a.HO = a.WO = 1;
+            c.name = "global_avg_pool";
+        }
+        c.kind = CALL_POOL;
+        c.a_node = xa;
+    } else if (is_rowwise(cv.op(len - 1))) {
+        RowwiseArgs &a = c.row;
+        const Node &root = g.nodes[cv.node(len - 1)];
+        const Shape &xs = root.shape;
+        a.len = (int)xs.d[xs.ndim - 1];
+        a.rows = (int)(xs.numel() / a.len);
+        int32_t xa;
+        if (len == 1) {
+            xa = cv.arg(0, 0);
+        } else {
+            xa = cv.arg(0, 0);
+            for (int t = 0; t < len - 1; ++t)
+                if ((rc = add_step(cv, t, t == 0, &epi, c.epi_nodes)) != CLG_OK) return rc;
+            if (epi.bias_c && (epi.bias_inner != 1 || epi.bias_c != a.len))
+                return fail(CLG_NO_KERNEL, "row-wise prologue bias must run along the last axis");
+        }
+        use(xa);
+        for (int s = 0; s < epi.n; ++s) use(c.epi_nodes[s]);
+        a.pro = epi;
+        if (cv.op(len - 1) == CLG_OP_SOFTMAX) {
+            a.mode = 0;
+            c.name = "softmax";
+        } else {
+            a.mode = 1;
+            a.eps = (float)root.attrs.eps;
+            c.b_node = cv.arg(len - 1, 1);
+            c.c_node = cv.arg(len - 1, 2);
+            use(c.b_node);
+            use(c.c_node);
+            c.name = "layer_norm";
+        }
+        if (epi.n) c.name += "_pro" + std::to_string(epi.n);
+        c.kind = CALL_ROWWISE;
+        c.a_node = xa;
+    } else if (is_layout(k0)) {
+        LayoutArgs &a = c.layout;
+        const int32_t xa = cv.arg(0, 0);
+        use(xa);
+        a.numel = out_shape.numel();
+        a.ndim = 1;
+        a.out_dims[0] = a.numel;
+        a.in_strides[0] = 1;
+        for (int t = 0; t < len; ++t) {
+            if (cv.op(t) != CLG_OP_TRANSPOSE) continue;
+            const Node &tr = g.nodes[cv.node(t)];
+            const Shape &src = g.nodes[tr.in[0]].shape;     // contiguous view being permuted
+            int64_t st[CLG_MAX_DIMS];
+            int64_t acc = 1;
+            for (int d = src.ndim - 1; d >= 0; --d) {
+                st[d] = acc;
+                acc *= src.d[d];
+            }
+            a.ndim = src.ndim;
+            for (int d = 0; d < src.ndim; ++d) {
+                a.out_dims[d] = tr.shape.d[d];
+                a.in_strides[d] = st[tr.attrs.dims[d]];
+            }
+        }
+        c.kind = CALL_LAYOUT;
+        c.name = a.ndim == 1 ? "copy" : "permute_copy";
+        c.a_node = xa;
+    } else if (is_elementwise(k0) || k0 == CLG_OP_TAKE) {
+        EltwiseArgs &a = c.elt;
+        a.numel = out_shape.numel();
+        const int32_t xa = cv.arg(0, 0);
+        int start = 0;
+        if (k0 == CLG_OP_TAKE) {
+            c.b_node = cv.arg(0, 1);
+            a.row_len = (int)g.nodes[xa].shape.d[1];
+            a.table_rows = (int)g.nodes[xa].shape.d[0];
+            start = 1;
+            c.name = "take";
+        } else {
+            c.name = "eltwise";
+            use(xa);
+        }
+        for (int t = start; t < len; ++t)
+            if ((rc = add_step(cv, t, t == 0, &epi, c.epi_nodes)) != CLG_OK) return rc;
+        for (int s = 0; s < epi.n; ++s) use(c.epi_nodes[s]);
+        if (c.b_node >= 0) use(c.b_node);
+        a.epi = epi;
+        c.name += std::to_string(epi.n);
+        c.kind = CALL_ELTWISE;
+        c.a_node = xa;
+    } else {
+        return fail(CLG_NO_KERNEL, "no kernel for a pattern anchored at %s", op_name(k0));
+    }
+
+    // algorithmic bytes: every distinct operand and the output once
+    double bytes = 4.0 * (double)out_shape.numel();
+    for (int32_t v : ext) bytes += 4.0 * (double)g.nodes[v].shape.numel();
+    if (k0 == CLG_OP_TAKE) bytes += 4.0 * (double)out_shape.numel();   // the gathered rows, not the table
+    c.bytes = bytes;
+
+    std::string key = be.name + "|" + kinds + "|" + abuf + "|";
+    key += shape_key(g, c.a_node);
+    for (int32_t v : ext)
+        if (v != c.a_node) key += shape_key(g, v);
+    key += "->" + out_shape.str();
+    for (int s = 0; s < epi.n; ++s)
+        if (epi.s[s].op == EPI_SCALE) {
+            char sb[32];
+            std::snprintf(sb, sizeof sb, "|x%.9g", (double)epi.s[s].scalar);
+            key += sb;
+        }
+    c.key = key;
+    *out = c;
+    return CLG_OK;
+}
+
+}  // namespace clg

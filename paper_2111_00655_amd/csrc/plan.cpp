@@ -1,0 +1,247 @@
+// Placement -> kernel sequence (paper Sec. 4.1: a placement is a set of
+// disjoint matches covering G; Sec. 5.1: tensors are handed between backends
+// by pointer, without copies), and its execution on a HIP stream.
+#include <algorithm>
+
+#include <hip/hip_runtime_api.h>
+
+#include "core.h"
+
+namespace clg {
+
+namespace {
+
+constexpr int64_t kAlign = 256;
+int64_t round_up(int64_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+// First-fit allocator over one linear workspace; tracks the peak.
+struct Arena {
+    struct Block { int64_t off, size; };
+    std::vector<Block> live;     // sorted by offset
+    int64_t peak = 0;
+    int64_t alloc(int64_t bytes) {
+        const int64_t size = round_up(std::max<int64_t>(bytes, 1));
+        int64_t off = 0;
+        size_t pos = 0;
+        for (; pos < live.size(); ++pos) {
+            if (live[pos].off - off >= size) break;
+            off = live[pos].off + live[pos].size;
+        }
+        live.insert(live.begin() + (long)pos, Block{off, size});
+        peak = std::max(peak, off + size);
+        return off;
+    }
+    void release(int64_t off) {
+        for (size_t i = 0; i < live.size(); ++i)
+            if (live[i].off == off) {
+                live.erase(live.begin() + (long)i);
+                return;
+            }
+    }
+};
+
+std::vector<int32_t> operands_of(const KernelCall &c) {
+    std::vector<int32_t> v;
+    for (int32_t x : {c.a_node, c.b_node, c.c_node})
+        if (x >= 0) v.push_back(x);
+    for (int32_t x : c.epi_nodes)
+        if (x >= 0) v.push_back(x);
+    return v;
+}
+
+}  // namespace
+
+int32_t compile_plan(Context &ctx, Graph &g, const int32_t *ids, size_t n, Plan *plan) {
+    g.finalize();
+    if (!g.matched) return fail(CLG_INVALID_ARG, "clg_match_all has not been called on this graph");
+    const int n_nodes = (int)g.nodes.size();
+    std::vector<int32_t> owner(n_nodes, -1);
+    for (size_t i = 0; i < n; ++i) {
+        if (ids[i] < 0 || ids[i] >= (int32_t)g.matches.size())
+            return fail(CLG_UNKNOWN_ID, "match id %d (the graph has %zu matches)", ids[i], g.matches.size());
+        for (int32_t v : g.matches[ids[i]].nodes) {
+            if (owner[v] >= 0)
+                return fail(CLG_OVERLAP, "matches %d and %d both contain node %d", owner[v], ids[i], v);
+            owner[v] = ids[i];
+        }
+    }
+    for (int32_t v : g.op_ids)
+        if (owner[v] < 0) return fail(CLG_NOT_A_COVER, "operator node %d (%s) is not covered", v, op_name(g.nodes[v].kind));
+
+    // a group reads other groups only through their sinks, so ordering groups
+    // by the position of their sink is a topological order of the quotient graph
+    std::vector<int32_t> seq(ids, ids + n);
+    std::sort(seq.begin(), seq.end(), [&](int32_t a, int32_t b) {
+        return g.rank[g.matches[a].sink] < g.rank[g.matches[b].sink];
+    });
+
+    plan->ctx = &ctx;
+    plan->graph = &g;
+    plan->calls.clear();
+    for (int32_t id : seq) {
+        KernelCall c;
+        const int32_t rc = lower_match(ctx, g, id, &c);
+        if (rc != CLG_OK) return rc;
+        plan->calls.push_back(std::move(c));
+    }
+
+    // every operand must be a leaf or the sink of an earlier group
+    const size_t nc = plan->calls.size();
+    std::vector<int32_t> produced_at(n_nodes, -1);
+    for (size_t i = 0; i < nc; ++i) {
+        for (int32_t v : operands_of(plan->calls[i])) {
+            if (!g.nodes[v].is_op()) continue;
+            if (produced_at[v] < 0)
+                return fail(CLG_INVALID_ARG, "kernel %zu reads node %d before any kernel has produced it", i, v);
+        }
+        produced_at[plan->calls[i].out_node] = (int32_t)i;
+    }
+
+    // workspace: one buffer per group output that is not a graph output, reused
+    // once its last reader has run; per-call scratch lives for its call only
+    plan->value_offset.assign(n_nodes, -1);
+    plan->value_output.assign(n_nodes, -1);
+    plan->scratch_offset.assign(nc, -1);
+    for (size_t k = 0; k < g.outputs.size(); ++k) plan->value_output[g.outputs[k]] = (int32_t)k;
+    std::vector<int32_t> last_use(n_nodes, -1);
+    for (size_t i = 0; i < nc; ++i)
+        for (int32_t v : operands_of(plan->calls[i])) last_use[v] = (int32_t)i;
+    Arena arena;
+    for (size_t i = 0; i < nc; ++i) {
+        const KernelCall &c = plan->calls[i];
+        if (plan->value_output[c.out_node] < 0)
+            plan->value_offset[c.out_node] = arena.alloc(4 * g.nodes[c.out_node].shape.numel());
+        if (c.scratch_bytes) {
+            plan->scratch_offset[i] = arena.alloc((int64_t)c.scratch_bytes);
+            arena.release(plan->scratch_offset[i]);
+        }
+        for (int32_t v : operands_of(c))
+            if (last_use[v] == (int32_t)i && plan->value_offset[v] >= 0) {
+                arena.release(plan->value_offset[v]);
+                last_use[v] = -2;            // released once, even if read twice by this call
+            }
+        if (last_use[c.out_node] < 0 && plan->value_offset[c.out_node] >= 0)
+            arena.release(plan->value_offset[c.out_node]);     // value nobody reads
+    }
+    plan->workspace_bytes = (size_t)arena.peak;
+    return CLG_OK;
+}
+
+int32_t launch_call(const KernelCall &c, const void *a, const void *b, const void *c3, void *out,
+                    const void *const *epi_ptrs, void *scratch, void *stream) {
+    auto bind = [&](Epilogue e) {
+        for (int s = 0; s < e.n; ++s) e.s[s].ptr = (const float *)epi_ptrs[s];
+        return e;
+    };
+    int err = 0;
+    switch (c.kind) {
+    case CALL_GEMM: {
+        GemmArgs k = c.gemm;
+        k.A = (const float *)a; k.B = (const float *)b; k.C = (float *)out;
+        if (c.gemm_swap) {                               // A = weights, B = activations
+            k.A = (const float *)b; k.B = (const float *)a;
+        }
+        k.partial = (float *)scratch;
+        k.epi = bind(c.gemm.epi);
+        err = launch_gemm(k, stream);
+        break;
+    }
+    case CALL_DIRECT_CONV: {
+        DirectConvArgs k = c.dconv;
+        k.x = (const float *)a; k.w = (const float *)b; k.y = (float *)out;
+        k.epi = bind(c.dconv.epi);
+        err = launch_direct_conv(k, stream);
+        break;
+    }
+    case CALL_POOL: {
+        PoolArgs k = c.pool;
+        k.x = (const float *)a; k.y = (float *)out;
+        err = launch_pool(k, stream);
+        break;
+    }
+    case CALL_ROWWISE: {
+        RowwiseArgs k = c.row;
+        k.x = (const float *)a; k.gamma = (const float *)b; k.beta = (const float *)c3; k.y = (float *)out;
+        k.pro = bind(c.row.pro);
+        err = launch_rowwise(k, stream);
+        break;
+    }
+    case CALL_ELTWISE: {
+        EltwiseArgs k = c.elt;
+        k.x = (const float *)a; k.ids = (const int32_t *)b; k.y = (float *)out;
+        k.epi = bind(c.elt.epi);
+        err = launch_eltwise(k, stream);
+        break;
+    }
+    case CALL_LAYOUT: {
+        LayoutArgs k = c.layout;
+        k.x = (const float *)a; k.y = (float *)out;
+        err = launch_layout(k, stream);
+        break;
+    }
+    default:
+        return fail(CLG_INVALID_ARG, "unknown call kind %d", c.kind);
+    }
+    if (err != 0)
+        return fail(CLG_HIP_ERROR, "launch of %s failed: %s", c.name.c_str(), hipGetErrorString((hipError_t)err));
+    return CLG_OK;
+}
+
+int32_t execute_plan(Plan &p, const void *const *inputs, void *const *outputs, void *workspace,
+                     size_t ws_bytes, void *stream, int64_t *kernel_ns) {
+    Context &ctx = *p.ctx;
+    Graph &g = *p.graph;
+    if (ctx.device < 0) return fail(CLG_HIP_ERROR, "host-only context: no device to execute on");
+    if (ws_bytes < p.workspace_bytes)
+        return fail(CLG_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, the plan needs %zu", ws_bytes, p.workspace_bytes);
+    if (p.workspace_bytes && !workspace) return fail(CLG_INVALID_ARG, "workspace is null");
+    if (((uintptr_t)workspace & 255) != 0) return fail(CLG_INVALID_ARG, "workspace is not 256-byte aligned");
+    if ((g.n_inputs && !inputs) || (!g.outputs.empty() && !outputs)) return fail(CLG_INVALID_ARG, "inputs/outputs is null");
+    for (int i = 0; i < g.n_inputs; ++i)
+        if (!inputs[i]) return fail(CLG_INVALID_ARG, "input %d is null", i);
+    for (size_t i = 0; i < g.outputs.size(); ++i)
+        if (!outputs[i]) return fail(CLG_INVALID_ARG, "output %zu is null", i);
+
+    auto ptr_of = [&](int32_t v) -> const void * {
+        if (v < 0) return nullptr;
+        const Node &nd = g.nodes[v];
+        if (nd.kind == NODE_CONST) return nd.dev_ptr;
+        if (nd.kind == NODE_INPUT) return inputs[nd.input_index];
+        if (p.value_output[v] >= 0) return outputs[p.value_output[v]];
+        return (const char *)workspace + p.value_offset[v];
+    };
+    std::vector<hipEvent_t> ev;
+    if (kernel_ns) {
+        ev.resize(2 * p.calls.size());
+        for (auto &e : ev)
+            if (hipEventCreate(&e) != hipSuccess) return fail(CLG_HIP_ERROR, "hipEventCreate failed");
+    }
+    int32_t rc = CLG_OK;
+    for (size_t i = 0; i < p.calls.size() && rc == CLG_OK; ++i) {
+        const KernelCall &c = p.calls[i];
+        const void *epi[kMaxEpi];
+        for (int s = 0; s < kMaxEpi; ++s) epi[s] = ptr_of(c.epi_nodes[s]);
+        for (int32_t v : {c.a_node, c.b_node, c.c_node})
+            if (v >= 0 && !ptr_of(v)) rc = fail(CLG_INVALID_ARG, "constant node %d has no device pointer", v);
+        if (rc != CLG_OK) break;
+        void *scratch = p.scratch_offset[i] >= 0 ? (char *)workspace + p.scratch_offset[i] : nullptr;
+        if (kernel_ns) (void)hipEventRecord(ev[2 * i], (hipStream_t)stream);
+        rc = launch_call(c, ptr_of(c.a_node), ptr_of(c.b_node), ptr_of(c.c_node),
+                         const_cast<void *>(ptr_of(c.out_node)), epi, scratch, stream);
+        if (kernel_ns) (void)hipEventRecord(ev[2 * i + 1], (hipStream_t)stream);
+    }
+    if (kernel_ns) {
+        if (rc == CLG_OK && hipStreamSynchronize((hipStream_t)stream) != hipSuccess)
+            rc = fail(CLG_HIP_ERROR, "stream synchronisation failed: %s", hipGetErrorString(hipGetLastError()));
+        for (size_t i = 0; i < p.calls.size() && rc == CLG_OK; ++i) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, ev[2 * i], ev[2 * i + 1]) != hipSuccess)
+                rc = fail(CLG_HIP_ERROR, "hipEventElapsedTime failed");
+            kernel_ns[i] = (int64_t)((double)ms * 1.0e6 + 0.5);
+        }
+        for (auto &e : ev) (void)hipEventDestroy(e);
+    }
+    return rc;
+}
+
+}  // namespace clg

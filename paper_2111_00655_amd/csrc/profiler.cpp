@@ -1,0 +1,211 @@
+// The measurer M of paper Sec. 4.2: "takes a backend placement strategy and
+// returns its actual run-time cost", queried at the granularity of one matched
+// subgraph = one kernel, with "compilation + multiple runs on the actual
+// hardware" and results cached in a log.
+//
+// Protocol: warm-up launches, then `batches` timed batches of back-to-back
+// launches between two HIP events; the cost is the median batch time per
+// launch, rounded once to integer nanoseconds.  The figure is launch-inclusive
+// (it contains the dispatch gap between consecutive kernels), so the search
+// can use eps = 0.
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <fstream>
+
+#include <hip/hip_runtime_api.h>
+
+#include "core.h"
+
+namespace clg {
+
+namespace {
+
+// One growing device allocation held by the context and reused across matches.
+int32_t ensure_block(Context &ctx, size_t need) {
+    if (need <= ctx.prof_bytes) return CLG_OK;
+    if (ctx.prof_ptr) (void)hipFree(ctx.prof_ptr);
+    ctx.prof_ptr = nullptr;
+    ctx.prof_bytes = 0;
+    if (hipMalloc(&ctx.prof_ptr, need) != hipSuccess) {
+        (void)hipGetLastError();
+        ctx.prof_ptr = nullptr;
+        return fail(CLG_OUT_OF_MEMORY, "profiler scratch allocation of %zu bytes failed", need);
+    }
+    ctx.prof_bytes = need;
+    return CLG_OK;
+}
+
+struct Opts { int warmup, batches, min_batch_us, max_launches; uint64_t seed; bool cache; };
+
+Opts resolve(const clg_profile_opts *o) {
+    Opts r{20, 5, 200, 2000, 1, true};
+    if (!o) return r;
+    if (o->warmup > 0) r.warmup = o->warmup;
+    if (o->batches > 0) r.batches = o->batches;
+    if (o->min_batch_us > 0) r.min_batch_us = o->min_batch_us;
+    if (o->max_launches > 0) r.max_launches = o->max_launches;
+    if (o->seed) r.seed = o->seed;
+    r.cache = o->no_cache == 0;
+    return r;
+}
+
+int32_t hip_fail(const char *what, hipError_t e) {
+    return fail(CLG_HIP_ERROR, "%s: %s", what, hipGetErrorString(e));
+}
+
+// Times `launch` (which enqueues the kernel once on the default stream).
+template <class F>
+int32_t time_launches(const Opts &o, F &&launch, int64_t *cost_ns) {
+    hipEvent_t e0, e1;
+    hipError_t he;
+    if ((he = hipEventCreate(&e0)) != hipSuccess) return hip_fail("hipEventCreate", he);
+    if ((he = hipEventCreate(&e1)) != hipSuccess) { (void)hipEventDestroy(e0); return hip_fail("hipEventCreate", he); }
+    int32_t rc = CLG_OK;
+    auto run = [&](int n, double *ms_total) -> int32_t {
+        (void)hipEventRecord(e0, nullptr);
+        for (int i = 0; i < n; ++i) {
+            const int32_t r = launch();
+            if (r != CLG_OK) return r;
+        }
+        (void)hipEventRecord(e1, nullptr);
+        if ((he = hipEventSynchronize(e1)) != hipSuccess) return hip_fail("hipEventSynchronize", he);
+        float ms = 0.f;
+        if ((he = hipEventElapsedTime(&ms, e0, e1)) != hipSuccess) return hip_fail("hipEventElapsedTime", he);
+        *ms_total = ms;
+        return CLG_OK;
+    };
+    double ms = 0;
+    rc = run(o.warmup, &ms);
+    int n = 10;
+    if (rc == CLG_OK) {
+        const double per_us = std::max(ms * 1000.0 / o.warmup, 0.05);
+        n = (int)std::min<double>(o.max_launches, std::max(5.0, std::ceil(o.min_batch_us / per_us)));
+    }
+    std::vector<double> per;
+    for (int b = 0; b < o.batches && rc == CLG_OK; ++b) {
+        rc = run(n, &ms);
+        per.push_back(ms * 1.0e6 / n);
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc != CLG_OK) return rc;
+    std::sort(per.begin(), per.end());
+    *cost_ns = std::max<int64_t>(1, (int64_t)std::llround(per[per.size() / 2]));
+    return CLG_OK;
+}
+
+}  // namespace
+
+int32_t profile_empty(Context &ctx, const clg_profile_opts *opts, int64_t *cost_ns) {
+    if (ctx.device < 0) return fail(CLG_HIP_ERROR, "host-only context: no device to profile on");
+    const Opts o = resolve(opts);
+    return time_launches(o, [&]() -> int32_t {
+        const int e = launch_empty(nullptr);
+        return e ? hip_fail("empty kernel launch", (hipError_t)e) : CLG_OK;
+    }, cost_ns);
+}
+
+int32_t profile_match(Context &ctx, Graph &g, int32_t match, const clg_profile_opts *opts, int64_t *cost_ns) {
+    if (ctx.device < 0) return fail(CLG_HIP_ERROR, "host-only context: no device to profile on");
+    if (!g.matched) return fail(CLG_INVALID_ARG, "clg_match_all has not been called on this graph");
+    const Opts o = resolve(opts);
+    KernelCall c;
+    const int32_t lrc = lower_match(ctx, g, match, &c);
+    if (lrc == CLG_NO_KERNEL) {
+        *cost_ns = CLG_COST_INF;
+        return CLG_OK;
+    }
+    if (lrc != CLG_OK) return lrc;
+    if (o.cache) {
+        auto it = ctx.cost_log.find(c.key);
+        if (it != ctx.cost_log.end()) {
+            *cost_ns = it->second;
+            return CLG_OK;
+        }
+    }
+    // operands: constants in place, everything else in one scratch block
+    std::vector<int32_t> vals;
+    for (int32_t v : {c.a_node, c.b_node, c.c_node}) vals.push_back(v);
+    for (int32_t v : c.epi_nodes) vals.push_back(v);
+    vals.push_back(c.out_node);
+    std::vector<size_t> offs(vals.size(), 0);
+    size_t total = 0;
+    auto up = [](size_t b) { return (b + 255) / 256 * 256; };
+    for (size_t i = 0; i < vals.size(); ++i) {
+        const int32_t v = vals[i];
+        if (v < 0) continue;
+        const bool is_out = i + 1 == vals.size();
+        if (!is_out && g.nodes[v].kind == NODE_CONST) {
+            if (!g.nodes[v].dev_ptr) return fail(CLG_INVALID_ARG, "constant node %d has no device pointer", v);
+            continue;
+        }
+        offs[i] = total;
+        total += up(4 * (size_t)g.nodes[v].shape.numel());
+    }
+    const size_t scratch_off = total;
+    total += up(c.scratch_bytes);
+    int32_t rc = ensure_block(ctx, std::max<size_t>(total, 256));
+    if (rc != CLG_OK) return rc;
+    char *base = (char *)ctx.prof_ptr;
+    std::vector<const void *> ptrs(vals.size(), nullptr);
+    for (size_t i = 0; i < vals.size(); ++i) {
+        const int32_t v = vals[i];
+        if (v < 0) continue;
+        const bool is_out = i + 1 == vals.size();
+        if (!is_out && g.nodes[v].kind == NODE_CONST) {
+            ptrs[i] = g.nodes[v].dev_ptr;
+            continue;
+        }
+        ptrs[i] = base + offs[i];
+        if (is_out) continue;
+        const int64_t n = g.nodes[v].shape.numel();
+        hipError_t he;
+        if (g.nodes[v].dtype == CLG_I32) {
+            if ((he = hipMemsetAsync(base + offs[i], 0, 4 * (size_t)n, nullptr)) != hipSuccess)
+                return hip_fail("hipMemsetAsync", he);
+        } else {
+            const int e = launch_fill((float *)(base + offs[i]), n, o.seed + 7919u * (uint64_t)i, nullptr);
+            if (e) return hip_fail("fill kernel", (hipError_t)e);
+        }
+    }
+    void *scratch = c.scratch_bytes ? base + scratch_off : nullptr;
+    const void *epi[kMaxEpi];
+    for (int s = 0; s < kMaxEpi; ++s) epi[s] = ptrs[3 + s];
+    rc = time_launches(o, [&]() -> int32_t {
+        return launch_call(c, ptrs[0], ptrs[1], ptrs[2], const_cast<void *>(ptrs.back()), epi, scratch, nullptr);
+    }, cost_ns);
+    if (rc != CLG_OK) return rc;
+    if (o.cache) ctx.cost_log[c.key] = *cost_ns;
+    return CLG_OK;
+}
+
+int32_t cost_log_load(Context &ctx, const char *path) {
+    std::ifstream f(path);
+    if (!f) return fail(CLG_IO_ERROR, "cannot open %s", path);
+    std::string line;
+    size_t lineno = 0;
+    while (std::getline(f, line)) {
+        ++lineno;
+        if (line.empty() || line[0] == '#') continue;
+        const size_t tab = line.rfind('\t');
+        if (tab == std::string::npos) return fail(CLG_IO_ERROR, "%s:%zu: no tab", path, lineno);
+        char *end = nullptr;
+        const long long v = std::strtoll(line.c_str() + tab + 1, &end, 10);
+        if (end == line.c_str() + tab + 1 || v < 0) return fail(CLG_IO_ERROR, "%s:%zu: bad cost", path, lineno);
+        ctx.cost_log[line.substr(0, tab)] = (int64_t)v;
+    }
+    return CLG_OK;
+}
+
+int32_t cost_log_save(const Context &ctx, const char *path) {
+    std::ofstream f(path);
+    if (!f) return fail(CLG_IO_ERROR, "cannot open %s for writing", path);
+    f << "# fused-kernel cost log: key<TAB>nanoseconds per launch\n";
+    for (auto &kv : ctx.cost_log) f << kv.first << '\t' << kv.second << '\n';
+    f.flush();
+    if (!f) return fail(CLG_IO_ERROR, "write to %s failed", path);
+    return CLG_OK;
+}
+
+}  // namespace clg

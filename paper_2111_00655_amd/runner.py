@@ -1,0 +1,135 @@
+"""Marshals a graph description and a pattern registry into the C-ABI calls.
+
+PyTorch is used here for device memory and the current HIP stream only; every
+step of the path (matching, profiling, search, compilation, execution) runs in
+libcollage_mi.so.  With device=None the session is host-only: no torch, no
+device pointers; matching, search and plan validation still work.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import binding as B
+
+
+class Session:
+    def __init__(self, desc, registry, device=0):
+        self.desc = desc
+        self.registry = list(registry)
+        self.device = device
+        self.ctx = B.clg_create(-1 if device is None else device)
+        self.graph = B.clg_graph_create(self.ctx)
+        self._torch = None
+        self._keep = []          # device tensors the graph borrows
+        self.matches = None
+        if device is not None:
+            import torch
+            self._torch = torch
+            torch.cuda.set_device(device)
+        # registry B, in order
+        self.pattern_ids = []
+        for backend, pat in self.registry:
+            bid = B.clg_register_backend(self.ctx, backend)
+            self.pattern_ids.append(B.clg_register_pattern(self.ctx, bid, pat))
+        # graph G
+        self.input_nodes = []
+        for nid, nd in enumerate(desc.nodes):
+            kind = nd["kind"]
+            if kind == "input":
+                dt = B.I32 if nd["dtype"] == "int32" else B.F32
+                got = B.clg_graph_input(self.graph, dt, nd["shape"])
+                self.input_nodes.append(nid)
+            elif kind == "const":
+                arr = desc.tensors[nid]
+                dt = B.I32 if arr.dtype == np.int32 else B.F32
+                ptr = 0
+                if self._torch is not None:
+                    t = self._torch.from_numpy(arr).to(f"cuda:{device}")
+                    self._keep.append(t)
+                    ptr = t.data_ptr()
+                got = B.clg_graph_const(self.graph, dt, arr.shape, ptr)
+            else:
+                a = nd["attrs"]
+                got = B.clg_graph_op(self.graph, kind, nd["inputs"], B.make_attrs(**a))
+            assert got == nid
+        for o in desc.outputs:
+            B.clg_graph_mark_output(self.graph, o)
+        self.out_shapes = [B.clg_graph_node_shape(self.graph, o)[1] for o in desc.outputs]
+
+    # ---- steps of the path -----------------------------------------------------
+    def match(self):
+        self.matches = B.clg_match_all(self.ctx, self.graph)
+        return self.matches
+
+    def profile(self, opts=None):
+        if self.matches is None:
+            self.match()
+        return B.clg_profile_all(self.ctx, self.graph, len(self.matches), opts)
+
+    def search(self, costs, eps=0):
+        return B.clg_search_dp(self.ctx, self.graph, costs, eps)
+
+    def compile(self, match_ids):
+        return Plan(self, B.clg_compile(self.ctx, self.graph, list(match_ids)))
+
+    def close(self):
+        if self.graph is not None:
+            B.clg_graph_destroy(self.graph)
+            B.clg_destroy(self.ctx)
+            self.graph = self.ctx = None
+            self._keep = []
+
+
+class Plan:
+    def __init__(self, session, handle):
+        self.s = session
+        self.h = handle
+        self.ws_bytes = B.clg_plan_workspace_bytes(handle)
+        self.n_kernels = B.clg_plan_num_kernels(handle)
+        self._ws = None
+        self._in = None
+        self._out = None
+
+    def kernels(self):
+        return [B.clg_plan_kernel_info(self.h, i) for i in range(self.n_kernels)]
+
+    def bind(self, feeds=None):
+        """Allocates workspace, inputs and outputs on the device (torch)."""
+        s = self.s
+        torch = s._torch
+        if torch is None:
+            raise RuntimeError("host-only session cannot execute")
+        dev = f"cuda:{s.device}"
+        feeds = feeds or s.desc.feeds
+        self._in = [torch.from_numpy(np.ascontiguousarray(feeds[n])).to(dev) for n in s.input_nodes]
+        self._out = [torch.empty(shp, dtype=torch.float32, device=dev) for shp in s.out_shapes]
+        self._ws = torch.empty(max(self.ws_bytes, 256), dtype=torch.uint8, device=dev)
+        assert self._ws.data_ptr() % 256 == 0
+        return self
+
+    def _args(self):
+        if self._ws is None:
+            self.bind()
+        stream = self.s._torch.cuda.current_stream().cuda_stream
+        return ([t.data_ptr() for t in self._in], [t.data_ptr() for t in self._out],
+                self._ws.data_ptr(), self._ws.numel(), stream)
+
+    def execute(self):
+        """One asynchronous pass over the kernel sequence."""
+        B.clg_execute(self.h, *self._args())
+
+    def execute_timed(self):
+        return B.clg_execute_timed(self.h, *self._args())
+
+    def run(self, feeds=None):
+        """Execute once and return the outputs as numpy arrays."""
+        if feeds is not None or self._ws is None:
+            self.bind(feeds)
+        self.execute()
+        self.s._torch.cuda.synchronize()
+        return [t.cpu().numpy() for t in self._out]
+
+    def destroy(self):
+        if self.h is not None:
+            B.clg_plan_destroy(self.h)
+            self.h = None

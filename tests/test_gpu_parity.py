@@ -1,0 +1,393 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs.  Bars (fp32): max|gpu - ref| / max|ref| <= 1e-4 per
+fused op and <= 1e-3 on a network's final outputs; placements bit-exact.
+"""
+import numpy as np
+import pytest
+
+import workloads as wl
+from workloads.patterns import P, W
+import paper_2111_00655_amd as clg
+from paper_2111_00655_amd import binding as B
+from oracle.graph import Graph, norm_err
+from oracle.match import enumerate_matches
+from oracle import search
+
+pytestmark = pytest.mark.gpu
+
+OP_TOL = 1e-4
+NET_TOL = 1e-3
+IGEMM = ("igemm", "igemm_s", "igemm_m", "igemm_l")
+
+
+def rng_for(*key):
+    return np.random.default_rng([int(k) for k in key])
+
+
+def f32(r, *shape, scale=1.0):
+    return (r.standard_normal(shape) * scale).astype(np.float32)
+
+
+def run_single_group(desc, backend, pattern, tol=OP_TOL, extra=()):
+    """The graph's operators form exactly one match of `pattern`: run it as one
+    kernel of `backend` and compare with the oracle."""
+    reg = [(backend, pattern)] + list(extra)
+    s = clg.Session(desc, reg, device=0)
+    ms = s.match()
+    full = [i for i, m in enumerate(ms) if m.pattern == 0 and m.n_nodes == len(desc.op_nodes())]
+    assert len(full) == 1, [(m.pattern, m.n_nodes) for m in ms]
+    plan = s.compile(full)
+    assert plan.n_kernels == 1
+    got = plan.run()
+    ref = Graph(desc).run()
+    err = max(norm_err(a, b) for a, b in zip(got, ref))
+    again = plan.run()
+    assert all(np.array_equal(a, b) for a, b in zip(got, again)), "not deterministic"
+    name = plan.kernels()[0]["name"]
+    plan.destroy()
+    s.close()
+    assert err <= tol, (name, err)
+    return name, err
+
+
+def tail_pattern(anchor, tail):
+    p = anchor
+    for op in tail:
+        p = P(op, p, W) if op in ("bias_add", "add") else P(op, p)
+    return p
+
+
+# ------------------------------------------------------------------ convolution
+CONV_CASES = [
+    # cin, cout, h, w, k, stride, pad, tail
+    (3, 16, 32, 32, 3, 1, 1, ("bias_add", "relu")),            # tiny-CNN layer 1 (K = 27)
+    (16, 32, 32, 32, 3, 1, 1, ("bias_add", "add", "relu")),
+    (3, 64, 56, 56, 7, 2, 3, ("bias_add", "relu")),            # stem shape class (K = 147), reduced image
+    (64, 64, 28, 28, 1, 1, 0, ("bias_add", "relu")),           # 1x1: plain GEMM path
+    (64, 96, 14, 14, 1, 2, 0, ("bias_add",)),                  # 1x1 stride 2 projection
+    (32, 48, 28, 28, 3, 2, 1, ("bias_add", "relu")),           # 3x3 stride 2
+    (40, 72, 9, 7, 3, 1, 1, ()),                               # ragged M, N, K; no epilogue
+    (128, 130, 7, 7, 3, 1, 1, ("bias_add", "add")),            # N = 49 < one tile
+    (512, 64, 7, 7, 1, 1, 0, ("bias_add", "add", "relu")),     # long K, small M*N: split-K
+]
+
+
+def conv_desc(case, seed, batch=1, groups=1):
+    cin, cout, h, w, k, s, p, tail = case
+    r = rng_for(seed, cin, cout, h, k)
+    d = wl.GraphDesc("conv_case")
+    x = d.input(f32(r, batch, cin, h, w))
+    wt = d.const(f32(r, cout, cin // groups, k, k, scale=(2.0 / (cin // groups * k * k)) ** 0.5))
+    y = d.op("conv2d", [x, wt], stride=(s, s), pad=(p, p), groups=groups)
+    ho, wo = (h + 2 * p - k) // s + 1, (w + 2 * p - k) // s + 1
+    for op in tail:
+        if op == "bias_add":
+            y = d.op("bias_add", [y, d.const(f32(r, cout))], axis=1)
+        elif op == "add":
+            y = d.op("add", [y, d.input(f32(r, batch, cout, ho, wo))])
+        else:
+            y = d.op(op, [y])
+    d.mark_output(y)
+    return d, tail_pattern(P("conv2d", W, W), tail)
+
+
+@pytest.mark.parametrize("backend", IGEMM + ("direct",))
+@pytest.mark.parametrize("ci", range(len(CONV_CASES)))
+def test_conv2d_fused(ci, backend):
+    d, pat = conv_desc(CONV_CASES[ci], 10 + ci)
+    run_single_group(d, backend, pat)
+
+
+def test_conv2d_batched_igemm():
+    d, pat = conv_desc((8, 24, 12, 10, 3, 1, 1, ("bias_add", "relu")), 77, batch=3)
+    run_single_group(d, "igemm", pat)
+    d, pat = conv_desc((16, 24, 10, 10, 1, 1, 0, ("bias_add", "relu")), 78, batch=3)
+    run_single_group(d, "igemm_m", pat)
+
+
+@pytest.mark.parametrize("case", [(128, 128, 28, 28, 3, 1, 1, 32), (256, 256, 14, 14, 3, 2, 1, 32),
+                                  (64, 64, 9, 9, 3, 1, 1, 16), (12, 18, 8, 8, 3, 1, 1, 6)])
+def test_grouped_conv_direct(case):
+    cin, cout, h, w, k, s, p, g = case
+    d, pat = conv_desc((cin, cout, h, w, k, s, p, ("bias_add", "relu")), 5, groups=g)
+    run_single_group(d, "direct", pat)
+
+
+def test_grouped_conv_is_refused_by_igemm():
+    d, pat = conv_desc((8, 8, 6, 6, 3, 1, 1, ()), 5, groups=2)
+    s = clg.Session(d, [("igemm", pat)], device=0)
+    ms = s.match()
+    assert len(ms) == 1
+    assert B.clg_profile_match(s.ctx, s.graph, 0) >= B.COST_INF
+    with pytest.raises(clg.ClgError) as e:
+        s.compile([0])
+    assert e.value.status == "NO_KERNEL"
+    s.close()
+
+
+# ------------------------------------------------------- transposed convolution
+@pytest.mark.parametrize("backend", IGEMM)
+@pytest.mark.parametrize("case", [(1, 64, 32, 4, ("bias_add", "relu")), (2, 32, 16, 8, ("bias_add", "relu")),
+                                  (3, 16, 3, 16, ("bias_add", "tanh")), (1, 24, 40, 5, ())])
+def test_conv2d_transpose_fused(case, backend):
+    batch, cin, cout, h, tail = case
+    r = rng_for(3, cin, cout, h)
+    d = wl.GraphDesc("convt_case")
+    x = d.input(f32(r, batch, cin, h, h))
+    wt = d.const(f32(r, cin, cout, 4, 4, scale=0.05))
+    y = d.op("conv2d_transpose", [x, wt], stride=(2, 2), pad=(1, 1))
+    for op in tail:
+        y = d.op("bias_add", [y, d.const(f32(r, cout))], axis=1) if op == "bias_add" else d.op(op, [y])
+    d.mark_output(y)
+    run_single_group(d, backend, tail_pattern(P("conv2d_transpose", W, W), tail))
+
+
+# ------------------------------------------------------------- dense / bmm
+DENSE_CASES = [(128, 768, 768, ("bias_add",)), (128, 768, 3072, ("bias_add", "gelu")),
+               (128, 3072, 768, ("bias_add", "add")), (1, 2048, 1000, ("bias_add",)),
+               (1, 32, 10, ("bias_add",)), (5, 100, 130, ("bias_add", "relu")), (130, 27, 70, ())]
+
+
+@pytest.mark.parametrize("backend", IGEMM)
+@pytest.mark.parametrize("ci", range(len(DENSE_CASES)))
+def test_dense_fused(ci, backend):
+    m, k, n, tail = DENSE_CASES[ci]
+    r = rng_for(4, m, k, n)
+    d = wl.GraphDesc("dense_case")
+    x = d.input(f32(r, m, k))
+    y = d.op("dense", [x, d.const(f32(r, n, k, scale=k ** -0.5))])
+    for op in tail:
+        if op == "bias_add":
+            y = d.op("bias_add", [y, d.const(f32(r, n))], axis=-1)
+        elif op == "add":
+            y = d.op("add", [y, d.input(f32(r, m, n))])
+        else:
+            y = d.op(op, [y])
+    d.mark_output(y)
+    run_single_group(d, backend, tail_pattern(P("dense", W, W), tail))
+
+
+def test_dense_bias_relu_reshape():
+    r = rng_for(8)
+    d = wl.GraphDesc("dense_rs")
+    y = d.op("dense", [d.input(f32(r, 2, 20)), d.const(f32(r, 64, 20))])
+    y = d.op("bias_add", [y, d.const(f32(r, 64))], axis=-1)
+    y = d.op("relu", [y])
+    y = d.op("reshape", [y], dims=(2, 4, 4, 4))
+    d.mark_output(y)
+    run_single_group(d, "igemm", P("reshape", P("relu", P("bias_add", P("dense", W, W), W))))
+
+
+@pytest.mark.parametrize("backend", IGEMM)
+@pytest.mark.parametrize("case", [(12, 128, 128, 64, True, True), (12, 128, 64, 128, False, False),
+                                  (3, 70, 33, 50, True, False), (2, 33, 70, 21, False, True)])
+def test_batch_matmul(case, backend):
+    b, m, n, k, tb, scale = case
+    r = rng_for(6, b, m, n, k)
+    d = wl.GraphDesc("bmm_case")
+    a = d.input(f32(r, b, m, k))
+    bm = d.input(f32(r, b, n, k) if tb else f32(r, b, k, n))
+    y = d.op("batch_matmul", [a, bm], transpose_b=tb)
+    pat = P("batch_matmul", W, W)
+    if scale:
+        y = d.op("mul_scalar", [y], scalar=0.125)
+        pat = P("mul_scalar", pat)
+    d.mark_output(y)
+    run_single_group(d, backend, pat)
+
+
+# --------------------------------------------------------------- row-wise
+@pytest.mark.parametrize("shape", [(12, 128, 128), (1, 1000), (1, 10), (3, 7, 65), (2, 2100), (5, 300)])
+def test_softmax(shape):
+    r = rng_for(7, *shape)
+    d = wl.GraphDesc("softmax_case")
+    d.mark_output(d.op("softmax", [d.input(f32(r, *shape, scale=3.0))]))
+    run_single_group(d, "rowwise", P("softmax", W), tol=1e-5)
+    d = wl.GraphDesc("softmax_scaled")
+    y = d.op("mul_scalar", [d.input(f32(r, *shape, scale=9.0))], scalar=0.125)
+    d.mark_output(d.op("softmax", [y]))
+    run_single_group(d, "rowwise", P("softmax", P("mul_scalar", W)), tol=1e-5)
+
+
+@pytest.mark.parametrize("shape", [(128, 768), (4, 48), (3, 2100), (1, 64), (7, 65)])
+def test_layer_norm(shape):
+    r = rng_for(9, *shape)
+    L = shape[-1]
+    g, b = (1 + 0.02 * r.standard_normal(L)).astype(np.float32), f32(r, L, scale=0.02)
+    d = wl.GraphDesc("ln_case")
+    d.mark_output(d.op("layer_norm", [d.input(f32(r, *shape) + np.float32(0.5)), d.const(g), d.const(b)], eps=1e-12))
+    run_single_group(d, "rowwise", P("layer_norm", W, W, W), tol=2e-5)
+    d = wl.GraphDesc("ln_res")
+    y = d.op("bias_add", [d.input(f32(r, *shape)), d.const(f32(r, L))], axis=-1)
+    y = d.op("add", [y, d.input(f32(r, *shape))])
+    d.mark_output(d.op("layer_norm", [y, d.const(g), d.const(b)], eps=1e-12))
+    run_single_group(d, "rowwise", P("layer_norm", P("add", P("bias_add", W, W), W), W, W), tol=2e-5)
+
+
+# ---------------------------------------------------------- elementwise / glue
+def test_elementwise_chains():
+    r = rng_for(11)
+    shape = (2, 6, 5, 7)                     # numel not a multiple of 4
+    for sh in (shape, (1, 8, 4, 4)):
+        d = wl.GraphDesc("ew")
+        y = d.op("bias_add", [d.input(f32(r, *sh)), d.const(f32(r, sh[1]))], axis=1)
+        y = d.op("add", [y, d.input(f32(r, *sh))])
+        d.mark_output(d.op("relu", [y]))
+        run_single_group(d, "eltwise", P("relu", P("add", P("bias_add", W, W), W)), tol=1e-6)
+    for op in ("relu", "gelu", "tanh"):
+        d = wl.GraphDesc(op)
+        d.mark_output(d.op(op, [d.input(f32(r, 128, 3072 if op == "gelu" else 33, scale=2.0))]))
+        run_single_group(d, "eltwise", P(op, W), tol=1e-6)
+    d = wl.GraphDesc("add_first_operand_is_residual")
+    a = d.input(f32(r, 3, 50))
+    y = d.op("relu", [d.op("add", [a, d.op("mul_scalar", [d.input(f32(r, 3, 50))], scalar=0.5)])])
+    d.mark_output(y)
+    run_single_group(d, "eltwise", P("relu", P("add", P("mul_scalar", W), W)), tol=1e-6)
+    d = wl.GraphDesc("bias_last_axis")
+    d.mark_output(d.op("gelu", [d.op("bias_add", [d.input(f32(r, 9, 50)), d.const(f32(r, 50))], axis=-1)]))
+    run_single_group(d, "eltwise", P("gelu", P("bias_add", W, W)), tol=1e-6)
+
+
+def test_take_and_embedding_sum():
+    r = rng_for(12)
+    tab = f32(r, 100, 24)
+    ids = r.integers(0, 100, 17).astype(np.int32)
+    d = wl.GraphDesc("take")
+    d.mark_output(d.op("take", [d.const(tab), d.input(ids)]))
+    run_single_group(d, "eltwise", P("take", W, W), tol=0.0)
+    d = wl.GraphDesc("take_sum")
+    e = d.op("take", [d.const(tab), d.input(ids)])
+    e = d.op("add", [e, d.input(f32(r, 17, 24))])
+    d.mark_output(d.op("add", [e, d.input(f32(r, 17, 24))]))
+    run_single_group(d, "eltwise", P("add", P("add", P("take", W, W), W), W), tol=1e-6)
+
+
+def test_layout_copies():
+    r = rng_for(13)
+    x = f32(r, 16, 96)
+    d = wl.GraphDesc("split_heads")
+    d.mark_output(d.op("transpose", [d.op("reshape", [d.input(x)], dims=(16, 12, 8))], dims=(1, 0, 2)))
+    run_single_group(d, "eltwise", P("transpose", P("reshape", W)), tol=0.0)
+    d = wl.GraphDesc("merge_heads")
+    d.mark_output(d.op("reshape", [d.op("transpose", [d.input(f32(r, 12, 16, 8))], dims=(1, 0, 2))], dims=(16, 96)))
+    run_single_group(d, "eltwise", P("reshape", P("transpose", W)), tol=0.0)
+    d = wl.GraphDesc("perm4")
+    d.mark_output(d.op("transpose", [d.input(f32(r, 2, 3, 5, 7))], dims=(0, 3, 1, 2)))
+    run_single_group(d, "eltwise", P("transpose", W), tol=0.0)
+    d = wl.GraphDesc("reshape")
+    d.mark_output(d.op("reshape", [d.input(f32(r, 6, 35))], dims=(2, 3, 5, 7)))
+    run_single_group(d, "eltwise", P("reshape", W), tol=0.0)
+
+
+def test_pools():
+    r = rng_for(14)
+    d = wl.GraphDesc("maxpool")
+    d.mark_output(d.op("max_pool2d", [d.input(f32(r, 2, 5, 15, 13))], kernel=(3, 3), stride=(2, 2), pad=(1, 1)))
+    run_single_group(d, "direct", P("max_pool2d", W), tol=0.0)
+    d = wl.GraphDesc("gap")
+    d.mark_output(d.op("global_avg_pool2d", [d.input(f32(r, 2, 37, 7, 7))]))
+    run_single_group(d, "direct", P("global_avg_pool2d", W), tol=1e-6)
+
+
+# ---------------------------------------------------------- whole graphs
+def _session_and_oracle(desc, reg):
+    s = clg.Session(desc, reg, device=0)
+    g = Graph(desc)
+    oms = enumerate_matches(g, reg)
+    lms = s.match()
+    assert [(m.pattern, m.first) for m in lms] == [(m.pattern, m.first) for m in oms]
+    return s, g, oms
+
+
+def test_tiny_cnn_every_placement_matches_the_oracle():
+    desc = wl.tiny_cnn(0)
+    reg = wl.default_registry()
+    s, g, oms = _session_and_oracle(desc, reg)
+    ref = g.run()
+    placements = list(search.all_placements(g, oms))
+    assert len(placements) == 2048
+    pick = np.random.default_rng(5).permutation(len(placements))[:256]
+    worst = 0.0
+    for pi in list(pick) + [0, len(placements) - 1]:
+        plan = s.compile(placements[pi])
+        got = plan.run()
+        plan.destroy()
+        worst = max(worst, max(norm_err(a, b) for a, b in zip(got, ref)))
+    assert worst <= NET_TOL, worst
+    s.close()
+
+
+def _variants():
+    return wl.default_registry(("igemm", "igemm_s", "igemm_m", "igemm_l"))
+
+
+@pytest.mark.parametrize("name", ["tiny_cnn", "resnet50", "resnext50", "bert_base", "dcgan_b1", "dcgan_b64"])
+def test_model_under_searched_placement(name):
+    """Profile every candidate subgraph, search, compile, execute; compare the
+    network outputs with the oracle and the placement with the oracle's DP on
+    the same cost table."""
+    desc = wl.MODEL_BUILDERS[name](0)
+    reg = _variants()
+    s, g, oms = _session_and_oracle(desc, reg)
+    opts = B.ProfileOpts(warmup=3, batches=3, min_batch_us=50, max_launches=50)
+    costs = s.profile(opts)
+    assert np.all(costs > 0)
+    got_search = s.search(costs, 0)
+    assert got_search == search.dp(g, reg, oms, costs, 0)          # bit-exact placement
+    plan = s.compile(got_search[1])
+    got = plan.run()
+    ref = g.run()
+    errs = [norm_err(a, b) for a, b in zip(got, ref)]
+    print(name, "kernels", plan.n_kernels, "errors", errs, "cost_ns", got_search[0])
+    assert max(errs) <= NET_TOL, errs
+    # the all-single-operator placement computes the same thing
+    singles = [i for i, m in enumerate(oms) if len(m.nodes) == 1]
+    first_single = {}
+    for i in singles:
+        first_single.setdefault(oms[i].nodes[0], i)
+    plan1 = s.compile(sorted(first_single.values()))
+    got1 = plan1.run()
+    assert max(norm_err(a, b) for a, b in zip(got1, ref)) <= NET_TOL
+    plan.destroy()
+    plan1.destroy()
+    s.close()
+
+
+def test_profiler_is_repeatable_and_cached():
+    desc = wl.resnet50(0, image=64, blocks=(1,))
+    reg = wl.default_registry()
+    s = clg.Session(desc, reg, device=0)
+    ms = s.match()
+    conv = [i for i, m in enumerate(ms) if m.n_nodes == 3 and reg[m.pattern][0] == "igemm"][0]
+    nocache = B.ProfileOpts(no_cache=1)
+    a = [B.clg_profile_match(s.ctx, s.graph, conv, nocache) for _ in range(5)]
+    assert (max(a) - min(a)) / float(np.median(a)) < 0.25, a
+    assert B.clg_cost_log_size(s.ctx) == 0
+    c1 = B.clg_profile_match(s.ctx, s.graph, conv)
+    assert B.clg_cost_log_size(s.ctx) == 1
+    assert B.clg_profile_match(s.ctx, s.graph, conv) == c1            # served from the log
+    assert B.clg_profile_empty(s.ctx) > 0
+    s.close()
+
+
+def test_execute_argument_errors():
+    desc = wl.tiny_cnn(0)
+    reg = wl.default_registry()
+    s = clg.Session(desc, reg, device=0)
+    ms = s.match()
+    _, ids = s.search(wl.synthetic_costs(len(ms), 0), 0)
+    plan = s.compile(ids).bind()
+    ins, outs, ws, nbytes, stream = plan._args()
+    with pytest.raises(clg.ClgError) as e:
+        B.clg_execute(plan.h, ins, outs, ws, plan.ws_bytes - 1, stream)
+    assert e.value.status == "WORKSPACE_TOO_SMALL"
+    with pytest.raises(clg.ClgError) as e:
+        B.clg_execute(plan.h, ins, outs, ws + 4, nbytes, stream)
+    assert e.value.status == "INVALID_ARG"
+    with pytest.raises(clg.ClgError) as e:
+        B.clg_execute(plan.h, [0], outs, ws, nbytes, stream)
+    assert e.value.status == "INVALID_ARG"
+    ns = plan.execute_timed()
+    assert len(ns) == plan.n_kernels and np.all(ns > 0)
+    plan.destroy()
+    s.close()
