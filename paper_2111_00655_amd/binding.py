@@ -118,6 +118,14 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is not built: run python -m paper_2111_00655_amd.build")
+        # PyTorch ships its own copy of the HIP runtime under the same soname.  The
+        # process must end up with ONE runtime that both PyTorch (device memory,
+        # streams) and this library use, and PyTorch only works with its own: load
+        # PyTorch first so that the library binds to the copy already in memory.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         _lib = C.CDLL(LIB_PATH)
         for name, (res, args) in SYMBOLS.items():
             fn = getattr(_lib, name)

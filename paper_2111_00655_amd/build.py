@@ -19,7 +19,8 @@ BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libcollage_mi.so")
 
 SOURCES = ["graph.cpp", "matcher.cpp", "search.cpp", "lower.cpp", "plan.cpp",
-           "profiler.cpp", "capi.cpp", "kernels_gemm.hip", "kernels_misc.hip"]
+           "profiler.cpp", "capi.cpp", "kernels_gemm.hip", "gemm_fast_mm.hip", "gemm_fast_conv.hip",
+           "kernels_misc.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra", "-Wno-unused-parameter",

@@ -25,10 +25,9 @@
 #include <hip/hip_runtime.h>
 
 #include "device_common.h"
+#include "gemm_fast.h"
 
 namespace clg {
-
-typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 namespace {
 
@@ -326,7 +325,7 @@ int64_t count_tiles(const GemmArgs &a, int tile) {
 
 // Tile: the largest whose grid still gives every CU a workgroup, else the
 // smallest.  Split-K: only when even the chosen tile leaves most CUs idle and K
-// is long enough to give every split at least four slices.
+// is long enough to leave every split at least 128 values of k.
 void gemm_resolve(GemmArgs *a, int n_cus) {
     const bool fixed = a->tile != TILE_AUTO;
     if (!fixed) {
@@ -334,17 +333,12 @@ void gemm_resolve(GemmArgs *a, int n_cus) {
         else if (count_tiles(*a, TILE_M) >= (int64_t)n_cus) a->tile = TILE_M;
         else a->tile = TILE_S;
     }
-    int bm, bn, bk;
-    tile_dims(a->tile, &bm, &bn, &bk);
     const int64_t tiles = count_tiles(*a, a->tile);
-    const int slices = (a->K + bk - 1) / bk;
     int split = 1;
     if (tiles * 2 <= n_cus) {
         split = (int)std::min<int64_t>((n_cus + tiles - 1) / tiles, 16);
-        split = std::min(split, std::max(1, slices / 4));
+        split = std::min(split, std::max(1, a->K / 128));
     }
-    // every split must own at least one slice
-    while (split > 1 && (int64_t)(split - 1) * ((slices + split - 1) / split) >= slices) --split;
     a->splitk = split;
 }
 
@@ -352,13 +346,23 @@ size_t gemm_scratch_bytes(const GemmArgs &a) {
     return a.splitk > 1 ? (size_t)a.splitk * (size_t)a.c_numel * sizeof(float) : 0;
 }
 
+static bool al16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+
 int launch_gemm(const GemmArgs &a, void *stream) {
     hipStream_t s = (hipStream_t)stream;
     int err;
+    const bool a_vec = a.K % 4 == 0 && a.lda % 4 == 0 && a.strideA % 4 == 0 && al16(a.A);
     switch (a.mode) {
-    case GM_NT: err = launch_mode<GM_NT>(a, s); break;
-    case GM_NN: err = launch_mode<GM_NN>(a, s); break;
-    case GM_CONV: err = launch_mode<GM_CONV>(a, s); break;
+    case GM_NT:
+        err = launch_fast_mm(a, a_vec && a.ldb % 4 == 0 && a.strideB % 4 == 0 && al16(a.B), s);
+        break;
+    case GM_NN:
+        err = launch_fast_mm(a, a_vec && a.N % 4 == 0 && a.ldb % 4 == 0 && a.strideB % 4 == 0 && al16(a.B), s);
+        break;
+    case GM_CONV:
+        if (a.KH * a.KW <= 64) err = launch_fast_conv(a, a_vec, s);
+        else err = launch_mode<GM_CONV>(a, s);
+        break;
     default: err = launch_mode<GM_CONVT>(a, s); break;
     }
     if (err) return err;
