@@ -168,7 +168,7 @@ int32_t clg_register_backend(clg_ctx *ctx, const char *name, int32_t *backend) {
     NEED(ctx); NEED(name); NEED(backend);
     static const struct { const char *name; int32_t family, tile; } kKnown[] = {
         {"igemm", FAM_IGEMM, TILE_AUTO}, {"igemm_s", FAM_IGEMM, TILE_S}, {"igemm_m", FAM_IGEMM, TILE_M},
-        {"igemm_l", FAM_IGEMM, TILE_L}, {"direct", FAM_DIRECT, 0}, {"rowwise", FAM_ROWWISE, 0},
+        {"igemm_l", FAM_IGEMM, TILE_L}, {"igemm_s8", FAM_IGEMM, TILE_S8}, {"igemm_s16", FAM_IGEMM, TILE_S16}, {"direct", FAM_DIRECT, 0}, {"rowwise", FAM_ROWWISE, 0},
         {"eltwise", FAM_ELTWISE, 0}};
     const std::string s(name);
     for (size_t i = 0; i < ctx->c.backends.size(); ++i)

@@ -32,9 +32,10 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 enum FastMode : int { F_NT = 0, F_NN = 1, F_CONV = 2 };
 
-template <int BM_, int BN_, int BK_, int WGM_, int WGN_, int WGK_>
+template <int BM_, int BN_, int BK_, int WGM_, int WGN_, int WGK_, int PD_>
 struct FastTile {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WGM = WGM_, WGN = WGN_, WGK = WGK_;
+    static constexpr int PD = PD_;                          // K slices whose loads are in flight at once
     static constexpr int NT = WGM * WGN * WGK * kWave;
     static constexpr int WTM = BM / WGM, WTN = BN / WGN;
     static constexpr int TM = WTM / 32, TN = WTN / 32;
@@ -46,16 +47,20 @@ struct FastTile {
     static constexpr int B_S = BK * BN / NT;                // scalars per thread (conv gather)
     static constexpr int SMEM_A = BM * LDR;
     static constexpr int SMEM_B = (BN * LDR > BK * LDK) ? BN * LDR : BK * LDK;
-    static constexpr int RED = (WGK > 1) ? WGK * TM * TN * 16 * kWave : 0;
+    static constexpr int RED_WAVES = WGK > 8 ? 8 : WGK;     // waves whose accumulators sit in LDS at once
+    static constexpr int RED = (WGK > 1) ? RED_WAVES * TM * TN * 16 * kWave : 0;
     static constexpr int SMEM = (SMEM_A + SMEM_B > RED) ? SMEM_A + SMEM_B : RED;
+    static constexpr int EPT = (WGK > 1) ? TM * TN * 16 * kWave / NT : 0;   // outputs per thread after the K-wave sum
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA");
     static_assert(BM * BK / 4 % NT == 0 && BN * BK / 4 % NT == 0, "tile must divide among the threads");
     static_assert(NT % BN == 0 && G % WGK == 0 && BK % 8 == 0, "tile shape");
+    static_assert(WGK == 1 || (WGM == 1 && WGN == 1 && TM * TN * 16 * kWave % NT == 0), "K-split tiles are one wave tile");
+    static_assert(WGK <= 16, "at most two reduction rounds");
 };
 
-using FTileS = FastTile<32, 32, 64, 1, 1, 4>;
-using FTileM = FastTile<64, 64, 64, 2, 2, 1>;
-using FTileL = FastTile<128, 128, 32, 2, 2, 1>;
+using FTileS = FastTile<32, 32, 64, 1, 1, 4, 1>;       // 4 waves share K inside the workgroup
+using FTileM = FastTile<64, 64, 64, 2, 2, 1, 1>;
+using FTileL = FastTile<128, 128, 32, 2, 2, 1, 1>;
 
 // blockIdx.x -> tile index such that the ids an XCD receives (id % 8 under
 // round-robin dispatch) form one contiguous range of tiles.
@@ -112,9 +117,47 @@ __global__ __launch_bounds__(T::NT) void gemm_fast_kernel(GemmArgs p) {
                         mask |= (uint64_t)1 << (kh * kw_n + kw);
     }
 
-    float4 ra[T::A_V];
-    float4 rb[(MODE == F_CONV) ? 1 : T::B_V];
-    float rs[(MODE == F_CONV) ? T::B_S : 1];
+    // ---- K-split tiles: the outputs this thread will finish are known now, so the
+    // operands of their fused steps (bias, residual) are fetched before the main
+    // loop instead of at its end, where their latency would be exposed
+    constexpr int EPT = T::EPT > 0 ? T::EPT : 1;
+    int64_t e_off[EPT];
+    int e_chan[EPT];
+    float e_pre[EPT][kMaxEpi];
+    if (T::WGK > 1) {
+#pragma unroll
+        for (int t = 0; t < EPT; ++t) {
+            const int e = tid + t * T::NT;
+            const int l = e % kWave, r = (e / kWave) % 16, blk = e / (16 * kWave);
+            const int i = i0 + (blk / T::TN) * 32 + 8 * (r / 4) + 4 * (l / 32) + (r % 4);
+            const int j = j0 + (blk % T::TN) * 32 + (l & 31);
+            e_off[t] = -1;
+            e_chan[t] = p.bias_on_row ? i : j;
+            if (i < p.M && j < p.N) {
+                if (MODE == F_CONV) {
+                    const int hw = p.HO * p.WO;
+                    const int n = j / hw, q = j - n * hw;
+                    e_off[t] = ((int64_t)n * p.Cout + i) * hw + q;
+                } else {
+                    e_off[t] = (int64_t)batch * p.strideC + (int64_t)i * p.ldc + j;
+                }
+            }
+#pragma unroll
+            for (int st = 0; st < kMaxEpi; ++st) {
+                float v = 0.f;
+                if (p.splitk == 1 && st < p.epi.n && e_off[t] >= 0) {
+                    if (p.epi.s[st].op == EPI_BIAS) v = p.epi.s[st].ptr[e_chan[t]];
+                    else if (p.epi.s[st].op == EPI_ADD) v = p.epi.s[st].ptr[e_off[t]];
+                }
+                e_pre[t][st] = v;
+            }
+        }
+    }
+
+    // register staging: PD slices deep
+    float4 ra[T::PD][T::A_V];
+    float4 rb[T::PD][(MODE == F_CONV) ? 1 : T::B_V];
+    float rs[T::PD][(MODE == F_CONV) ? T::B_S : 1];
 
     auto load_rows = [&](const float *base, int ld, int row0, int rows, int k0, float4 *dst, int count) {
         // [row][k] operand: float4 e covers row e / (BK/4), k-chunk e % (BK/4)
@@ -137,7 +180,7 @@ __global__ __launch_bounds__(T::NT) void gemm_fast_kernel(GemmArgs p) {
             dst[r] = v;
         }
     };
-    auto load_slice = [&](int s) {
+    auto load_slice = [&](int s, float4 *ra, float4 *rb, float *rs) {
         const int k0 = s * T::BK;
         load_rows(A, p.lda, i0, p.M, k0, ra, T::A_V);
         if (MODE == F_NT) {
@@ -174,7 +217,7 @@ __global__ __launch_bounds__(T::NT) void gemm_fast_kernel(GemmArgs p) {
             }
         }
     };
-    auto store_slice = [&]() {
+    auto store_slice = [&](const float4 *ra, const float4 *rb, const float *rs) {
 #pragma unroll
         for (int r = 0; r < T::A_V; ++r) {
             const int e = tid + r * T::NT;
@@ -207,11 +250,7 @@ __global__ __launch_bounds__(T::NT) void gemm_fast_kernel(GemmArgs p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.f;
 
-    if (s_begin < s_end) load_slice(s_begin);
-    for (int s = s_begin; s < s_end; ++s) {
-        store_slice();
-        __syncthreads();
-        if (s + 1 < s_end) load_slice(s + 1);
+    auto multiply_slice = [&]() {
 #pragma unroll
         for (int gg = 0; gg < T::GW; ++gg) {
             const int kb = (wk * T::GW + gg) * 8 + 4 * half;
@@ -239,7 +278,24 @@ __global__ __launch_bounds__(T::NT) void gemm_fast_kernel(GemmArgs p) {
                     for (int tn = 0; tn < T::TN; ++tn)
                         acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[tm][q], fb[tn][q], acc[tm][tn], 0, 0, 0);
         }
-        __syncthreads();
+    };
+
+    // software pipeline over K: the loads of the next PD slices are always in
+    // flight, so a workgroup pays the memory latency about once, not per slice
+#pragma unroll
+    for (int d = 0; d < T::PD; ++d)
+        if (s_begin + d < s_end) load_slice(s_begin + d, ra[d], rb[d], rs[d]);
+    for (int s = s_begin; s < s_end; s += T::PD) {
+#pragma unroll
+        for (int d = 0; d < T::PD; ++d) {
+            if (s + d < s_end) {
+                store_slice(ra[d], rb[d], rs[d]);
+                __syncthreads();
+                if (s + d + T::PD < s_end) load_slice(s + d + T::PD, ra[d], rb[d], rs[d]);
+                multiply_slice();
+                __syncthreads();
+            }
+        }
     }
 
     // ---- write-back: accumulator register r of lane l is row 8*(r/4) + 4*(l/32) + r%4,
@@ -272,21 +328,63 @@ __global__ __launch_bounds__(T::NT) void gemm_fast_kernel(GemmArgs p) {
     } else {
         float *red = smem;      // operand buffers are dead: the loop ended on a barrier
         constexpr int PER_WAVE = T::TM * T::TN * 16 * kWave;
-        if (s_begin >= s_end) __syncthreads();
+        if (T::WGK > 8) {
+            // first round: waves 8.. park their accumulators, waves 0..7 add their partner's
+            if (wk >= 8) {
 #pragma unroll
-        for (int tm = 0; tm < T::TM; ++tm)
+                for (int tm = 0; tm < T::TM; ++tm)
 #pragma unroll
-            for (int tn = 0; tn < T::TN; ++tn)
+                    for (int tn = 0; tn < T::TN; ++tn)
 #pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    red[wk * PER_WAVE + ((tm * T::TN + tn) * 16 + r) * kWave + lane] = acc[tm][tn][r];
+                        for (int r = 0; r < 16; ++r)
+                            red[(wk - 8) * PER_WAVE + ((tm * T::TN + tn) * 16 + r) * kWave + lane] = acc[tm][tn][r];
+            }
+            __syncthreads();
+            if (wk < 8 && wk + 8 < T::WGK) {
+#pragma unroll
+                for (int tm = 0; tm < T::TM; ++tm)
+#pragma unroll
+                    for (int tn = 0; tn < T::TN; ++tn)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            acc[tm][tn][r] += red[wk * PER_WAVE + ((tm * T::TN + tn) * 16 + r) * kWave + lane];
+            }
+            __syncthreads();
+        }
+        if (wk < T::RED_WAVES) {
+#pragma unroll
+            for (int tm = 0; tm < T::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < T::TN; ++tn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        red[wk * PER_WAVE + ((tm * T::TN + tn) * 16 + r) * kWave + lane] = acc[tm][tn][r];
+        }
         __syncthreads();
-        for (int e = tid; e < PER_WAVE; e += T::NT) {
+#pragma unroll
+        for (int t = 0; t < EPT; ++t) {
+            const int e = tid + t * T::NT;
             float v = 0.f;
 #pragma unroll
-            for (int w = 0; w < T::WGK; ++w) v += red[w * PER_WAVE + e];
-            const int l = e % kWave, r = (e / kWave) % 16, blk = e / (16 * kWave);
-            emit(i0 + (blk / T::TN) * 32 + 8 * (r / 4) + 4 * (l / 32) + (r % 4), j0 + (blk % T::TN) * 32 + (l & 31), v);
+            for (int w = 0; w < T::RED_WAVES; ++w) v += red[w * PER_WAVE + e];
+            if (e_off[t] < 0) continue;
+            if (p.splitk > 1) {
+                p.partial[(int64_t)ks * p.c_numel + e_off[t]] = v;
+            } else {
+#pragma unroll
+                for (int st = 0; st < kMaxEpi; ++st) {
+                    if (st >= p.epi.n) break;
+                    switch (p.epi.s[st].op) {
+                    case EPI_BIAS: case EPI_ADD: v += e_pre[t][st]; break;
+                    case EPI_RELU: v = v > 0.f ? v : 0.f; break;
+                    case EPI_GELU: v = gelu_erf(v); break;
+                    case EPI_TANH: v = tanhf(v); break;
+                    case EPI_SCALE: v *= p.epi.s[st].scalar; break;
+                    default: break;
+                    }
+                }
+                p.C[e_off[t]] = v;
+            }
         }
     }
 }
@@ -302,7 +400,7 @@ int launch_fast_tile(const GemmArgs &a, hipStream_t s) {
 template <int MODE, int KH, int KW, bool VEC>
 int launch_fast(const GemmArgs &a, hipStream_t s) {
     switch (a.tile) {
-    case TILE_S: return launch_fast_tile<MODE, KH, KW, VEC, FTileS>(a, s);
+    case TILE_S: case TILE_S8: case TILE_S16: return launch_fast_tile<MODE, KH, KW, VEC, FTileS>(a, s);
     case TILE_L: return launch_fast_tile<MODE, KH, KW, VEC, FTileL>(a, s);
     default: return launch_fast_tile<MODE, KH, KW, VEC, FTileM>(a, s);
     }

@@ -42,6 +42,20 @@ struct Epilogue {
     EpiStep s[kMaxEpi];
 };
 
+// The common form of a fused tail, recognised on the host: [scale] [bias]
+// [residual add] [one activation], in that order.  Anything else keeps
+// EF_GENERIC and is interpreted step by step.
+enum EpiFastFlags : int32_t {
+    EF_SCALE = 1, EF_BIAS = 2, EF_ADD = 4, EF_RELU = 8, EF_GELU = 16, EF_TANH = 32, EF_GENERIC = 64
+};
+
+struct EpiFast {
+    int32_t flags;
+    float scale;
+    const float *bias;
+    const float *add;
+};
+
 // ---- MFMA implicit GEMM ----------------------------------------------------------------
 // C[i][j] = sum_k A(i,k) * B(k,j), fp32 MFMA, fp32 accumulate, epilogue in
 // registers.  j is the memory-contiguous output index.
@@ -52,7 +66,7 @@ enum GemmMode : int32_t {
     GM_CONVT = 3   // transposed conv as stride*stride sub-pixel phases, one phase per grid.z slice
 };
 
-enum GemmTile : int32_t { TILE_AUTO = 0, TILE_S = 1, TILE_M = 2, TILE_L = 3 };
+enum GemmTile : int32_t { TILE_AUTO = 0, TILE_S = 1, TILE_M = 2, TILE_L = 3, TILE_S8 = 4, TILE_S16 = 5 };
 
 struct GemmArgs {
     int32_t mode, tile, splitk, batch;
@@ -67,7 +81,9 @@ struct GemmArgs {
     // convolution geometry (GM_CONV, GM_CONVT)
     int32_t Nimg, Cin, H, W, Cout, KH, KW, sh, sw, ph, pw, HO, WO;
     int32_t bias_on_row;                   // 1: channel = i (conv), 0: channel = j (dense)
+    int32_t patch_sz;                      // 3x3 kernel: floats per channel of the LDS input patch
     Epilogue epi;
+    EpiFast ef;                            // filled by launch_gemm from epi
 };
 
 // ---- direct convolution (any groups) -----------------------------------------------------

@@ -26,6 +26,7 @@
 
 #include "device_common.h"
 #include "gemm_fast.h"
+#include "gemm_lean.h"
 
 namespace clg {
 
@@ -301,7 +302,7 @@ int launch_tile(const GemmArgs &a, hipStream_t s) {
 template <int MODE>
 int launch_mode(const GemmArgs &a, hipStream_t s) {
     switch (a.tile) {
-    case TILE_S: return launch_tile<MODE, TileS>(a, s);
+    case TILE_S: case TILE_S8: case TILE_S16: return launch_tile<MODE, TileS>(a, s);
     case TILE_L: return launch_tile<MODE, TileL>(a, s);
     default: return launch_tile<MODE, TileM>(a, s);
     }
@@ -309,7 +310,7 @@ int launch_mode(const GemmArgs &a, hipStream_t s) {
 
 void tile_dims(int tile, int *bm, int *bn, int *bk) {
     switch (tile) {
-    case TILE_S: *bm = TileS::BM; *bn = TileS::BN; *bk = TileS::BK; break;
+    case TILE_S: case TILE_S8: case TILE_S16: *bm = TileS::BM; *bn = TileS::BN; *bk = TileS::BK; break;
     case TILE_L: *bm = TileL::BM; *bn = TileL::BN; *bk = TileL::BK; break;
     default: *bm = TileM::BM; *bn = TileM::BN; *bk = TileM::BK; break;
     }
@@ -348,20 +349,45 @@ size_t gemm_scratch_bytes(const GemmArgs &a) {
 
 static bool al16(const void *p) { return ((uintptr_t)p & 15) == 0; }
 
-int launch_gemm(const GemmArgs &a, void *stream) {
+// Recognises the common form [scale] [bias] [add] [activation] of a fused tail.
+static EpiFast make_epi_fast(const Epilogue &e) {
+    EpiFast f{0, 1.f, nullptr, nullptr};
+    int stage = 0;      // 0 scale, 1 bias, 2 add, 3 activation, 4 done
+    for (int i = 0; i < e.n; ++i) {
+        const EpiStep &st = e.s[i];
+        if (st.op == EPI_SCALE && stage <= 0) { f.flags |= EF_SCALE; f.scale = st.scalar; stage = 1; }
+        else if (st.op == EPI_BIAS && stage <= 1) { f.flags |= EF_BIAS; f.bias = st.ptr; stage = 2; }
+        else if (st.op == EPI_ADD && stage <= 2) { f.flags |= EF_ADD; f.add = st.ptr; stage = 3; }
+        else if (st.op == EPI_RELU && stage <= 3) { f.flags |= EF_RELU; stage = 4; }
+        else if (st.op == EPI_GELU && stage <= 3) { f.flags |= EF_GELU; stage = 4; }
+        else if (st.op == EPI_TANH && stage <= 3) { f.flags |= EF_TANH; stage = 4; }
+        else return EpiFast{EF_GENERIC, 1.f, nullptr, nullptr};
+    }
+    return f;
+}
+
+int launch_gemm(const GemmArgs &a_in, void *stream) {
     hipStream_t s = (hipStream_t)stream;
+    GemmArgs a = a_in;
+    a.ef = make_epi_fast(a.epi);
     int err;
     const bool a_vec = a.K % 4 == 0 && a.lda % 4 == 0 && a.strideA % 4 == 0 && al16(a.A);
     switch (a.mode) {
     case GM_NT:
-        err = launch_fast_mm(a, a_vec && a.ldb % 4 == 0 && a.strideB % 4 == 0 && al16(a.B), s);
+        err = launch_lean_mm(a, s);
+        if (err == -1) err = launch_fast_mm(a, a_vec && a.ldb % 4 == 0 && a.strideB % 4 == 0 && al16(a.B), s);
         break;
     case GM_NN:
-        err = launch_fast_mm(a, a_vec && a.N % 4 == 0 && a.ldb % 4 == 0 && a.strideB % 4 == 0 && al16(a.B), s);
+        err = launch_lean_mm(a, s);
+        if (err == -1)
+            err = launch_fast_mm(a, a_vec && a.N % 4 == 0 && a.ldb % 4 == 0 && a.strideB % 4 == 0 && al16(a.B), s);
         break;
     case GM_CONV:
-        if (a.KH * a.KW <= 64) err = launch_fast_conv(a, a_vec, s);
-        else err = launch_mode<GM_CONV>(a, s);
+        err = launch_lean_conv3x3(a, s);
+        if (err == -1) {
+            if (a.KH * a.KW <= 64) err = launch_fast_conv(a, a_vec, s);
+            else err = launch_mode<GM_CONV>(a, s);
+        }
         break;
     default: err = launch_mode<GM_CONVT>(a, s); break;
     }

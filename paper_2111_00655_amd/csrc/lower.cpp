@@ -324,7 +324,7 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
             c.scratch_bytes = gemm_scratch_bytes(a);
             c.kind = CALL_GEMM;
             c.bound = 0;
-            static const char *tn[] = {"auto", "s", "m", "l"};
+            static const char *tn[] = {"auto", "s", "m", "l", "s8", "s16"};
             c.name += std::string("_") + tn[a.tile] + (a.splitk > 1 ? "_k" + std::to_string(a.splitk) : "");
         }
         c.a_node = xa;

@@ -17,7 +17,7 @@ pytestmark = pytest.mark.gpu
 
 OP_TOL = 1e-4
 NET_TOL = 1e-3
-IGEMM = ("igemm", "igemm_s", "igemm_m", "igemm_l")
+IGEMM = ("igemm", "igemm_s", "igemm_s8", "igemm_s16", "igemm_m", "igemm_l")
 
 
 def rng_for(*key):
