@@ -128,7 +128,7 @@ def main():
     import workloads as wl
     from paper_2111_00655_amd import binding as B
 
-    reg = wl.default_registry(("igemm", "igemm_s", "igemm_m", "igemm_l"))
+    reg = wl.default_registry(("igemm", "igemm_s", "igemm_s8", "igemm_s16", "igemm_m", "igemm_l"))
     opts = B.ProfileOpts(warmup=10, batches=5, min_batch_us=200, max_launches=500)
 
     desc = wl.MODEL_BUILDERS[args.model](0)

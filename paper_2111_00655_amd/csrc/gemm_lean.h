@@ -68,7 +68,8 @@ struct LeanTile {
     static constexpr int RED_WAVES = WGK > 8 ? 8 : WGK;
     static constexpr int PER_WAVE = TM * TN * 16 * kWave;
     static constexpr int RED = (WGK > 1) ? RED_WAVES * PER_WAVE : 0;
-    static constexpr int SMEM = (SMEM_A + SMEM_B > RED) ? SMEM_A + SMEM_B : RED;
+    static constexpr int STAGE = SMEM_A + SMEM_B;            // one operand buffer; the kernel keeps two
+    static constexpr int SMEM = (2 * STAGE > RED) ? 2 * STAGE : RED;
     static constexpr int EPT = (WGK > 1) ? PER_WAVE / NT : 0;
     static_assert(WTM % 32 == 0 && WTN % 32 == 0 && BK % 8 == 0 && G % WGK == 0, "tile shape");
     static_assert(BM * BK / 4 % NT == 0 && BN * BK / 4 % NT == 0, "tile must divide among the threads");
@@ -123,8 +124,6 @@ __device__ __forceinline__ float sum_k_waves(const float *red, int e) {
 template <int MODE, class T>
 __global__ __launch_bounds__(T::NT) void mm_lean_kernel(GemmArgs p) {
     extern __shared__ float smem[];
-    float *As = smem;
-    float *Bs = smem + T::SMEM_A;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
@@ -142,8 +141,8 @@ __global__ __launch_bounds__(T::NT) void mm_lean_kernel(GemmArgs p) {
     const int per = (slices + p.splitk - 1) / p.splitk;
     const int s_begin = ks * per, s_end = min(slices, s_begin + per);
 
-    const float *A = p.A + (int64_t)batch * p.strideA + (int64_t)s_begin * T::BK;
-    const float *B = p.B + (int64_t)batch * p.strideB +
+    const float *const A = p.A + (int64_t)batch * p.strideA + (int64_t)s_begin * T::BK;
+    const float *const B = p.B + (int64_t)batch * p.strideB +
                      (MODE == F_NN ? (int64_t)s_begin * T::BK * p.ldb : (int64_t)s_begin * T::BK);
     const int64_t b_step = (MODE == F_NN) ? (int64_t)T::BK * p.ldb : (int64_t)T::BK;
 
@@ -185,13 +184,39 @@ __global__ __launch_bounds__(T::NT) void mm_lean_kernel(GemmArgs p) {
         }
     }
 
-    f32x4 ra[T::A_V], rb[T::B_V];
-#define CLG_MM_LOAD_SLICE()                                                                     \
+    // Software pipeline over the K slices of this workgroup: two LDS operand
+    // buffers and two register sets.  While slice n is multiplied out of LDS
+    // buffer n%2, slice n+1 moves from registers to the other buffer and the
+    // loads of slice n+3 are issued, so a load has two slices of MFMA work to
+    // arrive and there is one barrier per slice.  Loads past the last slice are
+    // clamped to it (in bounds, unused), which keeps the loop free of branches.
+    const int nsl = s_end - s_begin;
+    f32x4 ra[2][T::A_V], rb[2][T::B_V];
+#define CLG_MM_LOAD(set, n)                                                                     \
     do {                                                                                        \
+        const int sl_ = min((n), nsl - 1);                                                      \
+        const float *a_ = A + (int64_t)sl_ * T::BK;                                             \
+        const float *b_ = B + (int64_t)sl_ * b_step;                                            \
         _Pragma("unroll") for (int r = 0; r < T::A_V; ++r)                                      \
-            ra[r] = *reinterpret_cast<const f32x4 *>(A + offA[r]);                             \
+            ra[set][r] = *reinterpret_cast<const f32x4 *>(a_ + offA[r]);                        \
         _Pragma("unroll") for (int r = 0; r < T::B_V; ++r)                                      \
-            rb[r] = *reinterpret_cast<const f32x4 *>(B + offB[r]);                             \
+            rb[set][r] = *reinterpret_cast<const f32x4 *>(b_ + offB[r]);                        \
+        __builtin_amdgcn_sched_barrier(0);   /* keep the loads ahead of the MFMAs */            \
+    } while (0)
+#define CLG_MM_STORE(set, buf)                                                                  \
+    do {                                                                                        \
+        float *as_ = smem + (buf) * T::STAGE, *bs_ = as_ + T::SMEM_A;                            \
+        _Pragma("unroll") for (int r = 0; r < T::A_V; ++r) {                                    \
+            const int e = tid + r * T::NT;                                                      \
+            *reinterpret_cast<f32x4 *>(&as_[(e / (T::BK / 4)) * T::LDR + (e % (T::BK / 4)) * 4]) = ra[set][r]; \
+        }                                                                                       \
+        _Pragma("unroll") for (int r = 0; r < T::B_V; ++r) {                                    \
+            const int e = tid + r * T::NT;                                                      \
+            if (MODE == F_NT)                                                                   \
+                *reinterpret_cast<f32x4 *>(&bs_[(e / (T::BK / 4)) * T::LDR + (e % (T::BK / 4)) * 4]) = rb[set][r]; \
+            else                                                                                \
+                *reinterpret_cast<f32x4 *>(&bs_[(e / (T::BN / 4)) * T::LDK + (e % (T::BN / 4)) * 4]) = rb[set][r]; \
+        }                                                                                       \
     } while (0)
 
     floatx16 acc[T::TM][T::TN];
@@ -202,27 +227,9 @@ __global__ __launch_bounds__(T::NT) void mm_lean_kernel(GemmArgs p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.f;
 
-    if (s_begin < s_end) CLG_MM_LOAD_SLICE();
-    for (int s = s_begin; s < s_end; ++s) {
-#pragma unroll
-        for (int r = 0; r < T::A_V; ++r) {
-            const int e = tid + r * T::NT;
-            *reinterpret_cast<f32x4 *>(&As[(e / (T::BK / 4)) * T::LDR + (e % (T::BK / 4)) * 4]) = ra[r];
-        }
-#pragma unroll
-        for (int r = 0; r < T::B_V; ++r) {
-            const int e = tid + r * T::NT;
-            if (MODE == F_NT)
-                *reinterpret_cast<f32x4 *>(&Bs[(e / (T::BK / 4)) * T::LDR + (e % (T::BK / 4)) * 4]) = rb[r];
-            else
-                *reinterpret_cast<f32x4 *>(&Bs[(e / (T::BN / 4)) * T::LDK + (e % (T::BN / 4)) * 4]) = rb[r];
-        }
-        __syncthreads();
-        if (s + 1 < s_end) {
-            A += T::BK;
-            B += b_step;
-            CLG_MM_LOAD_SLICE();
-        }
+    auto multiply = [&](int buf) {
+        const float *As = smem + buf * T::STAGE;
+        const float *Bs = As + T::SMEM_A;
 #pragma unroll
         for (int gg = 0; gg < T::GW; ++gg) {
             const int kb = (wk * T::GW + gg) * 8 + 4 * half;
@@ -250,8 +257,30 @@ __global__ __launch_bounds__(T::NT) void mm_lean_kernel(GemmArgs p) {
                     for (int tn = 0; tn < T::TN; ++tn)
                         acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[tm][q], fb[tn][q], acc[tm][tn], 0, 0, 0);
         }
+    };
+
+    if (nsl > 0) {
+        CLG_MM_LOAD(0, 0);
+        CLG_MM_LOAD(1, 1);
+        CLG_MM_STORE(0, 0);
+        CLG_MM_LOAD(0, 2);
+        __syncthreads();
+        int n = 0;
+        for (; n + 1 < nsl; n += 2) {    // two slices per trip, no branch inside
+            CLG_MM_STORE(1, 1);          // slice n+1
+            CLG_MM_LOAD(1, n + 3);
+            multiply(0);                 // slice n
+            __syncthreads();
+            CLG_MM_STORE(0, 0);          // slice n+2 (a clamped repeat after the last one: unused)
+            CLG_MM_LOAD(0, n + 4);
+            multiply(1);                 // slice n+1
+            __syncthreads();
+        }
+        if (n < nsl) multiply(0);        // odd count: the last slice sits in buffer 0
         __syncthreads();
     }
+#undef CLG_MM_LOAD
+#undef CLG_MM_STORE
 
     if constexpr (T::WGK > 1) {
         park_k_waves<T>(smem, acc[0][0], wk, lane);
