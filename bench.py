@@ -27,16 +27,22 @@ PEAK_MFMA_F32_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
 PEAK_HBM_GBPS = 8000.0            # MI355X HBM3E
 
 
-def optimise(desc, reg, opts):
-    """register -> match -> profile -> search -> compile; returns pieces + timings."""
+def optimise(desc, reg, opts, cost_log=""):
+    """register -> match -> profile -> search -> compile; returns pieces + timings.
+    With a cost log file, measured costs are reused from / added to it."""
     import paper_2111_00655_amd as clg
+    from paper_2111_00655_amd import binding as B
     t0 = time.perf_counter()
     s = clg.Session(desc, reg, device=0)
+    if cost_log and os.path.exists(cost_log):
+        B.clg_cost_log_load(s.ctx, cost_log)
     t1 = time.perf_counter()
     ms = s.match()
     t2 = time.perf_counter()
     costs = s.profile(opts)
     t3 = time.perf_counter()
+    if cost_log:
+        B.clg_cost_log_save(s.ctx, cost_log)
     total, ids = s.search(costs, 0)
     t4 = time.perf_counter()
     plan = s.compile(ids).bind()
@@ -115,6 +121,7 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--dump", default="", help="write the per-kernel table to this JSON file")
+    ap.add_argument("--cost-log", default="", help="cost-log file: reuse measured subgraph costs from it, add new ones")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: batch-1 inference of one graph is a dependency chain and "
@@ -128,11 +135,11 @@ def main():
     import workloads as wl
     from paper_2111_00655_amd import binding as B
 
-    reg = wl.default_registry(("igemm", "igemm_s", "igemm_s8", "igemm_s16", "igemm_m", "igemm_l"))
+    reg = wl.default_registry(("igemm", "igemm_s", "igemm_s8", "igemm_s16", "igemm_m", "igemm_l", "igemm_s_nk", "igemm_s8_nk", "igemm_s16_nk"))
     opts = B.ProfileOpts(warmup=10, batches=5, min_batch_us=200, max_launches=500)
 
     desc = wl.MODEL_BUILDERS[args.model](0)
-    s, plan, costs, ids, timing = optimise(desc, reg, opts)
+    s, plan, costs, ids, timing = optimise(desc, reg, opts, args.cost_log)
     ms_per_step = time_steps(plan, args.steps, args.warmup)
     rows = kernel_table(plan)
     roof = roofline_of(rows)

@@ -155,7 +155,7 @@ typedef struct clg_match {
  * hardware").  Zero in a field selects the default given in brackets. */
 typedef struct clg_profile_opts {
     int32_t warmup;         /* untimed launches first [20]                    */
-    int32_t batches;        /* timed batches; the cost is their median [5]    */
+    int32_t batches;        /* timed batches; the cost is the fastest one [7] */
     int32_t min_batch_us;   /* a batch repeats the kernel until it lasts this long [200] */
     int32_t max_launches;   /* cap on launches per batch [2000]               */
     uint64_t seed;          /* seed of the scratch operands' contents [1]     */
@@ -210,8 +210,11 @@ int32_t clg_graph_node_shape(const clg_graph *g, int32_t node, int32_t *dtype,
 /* ---- registry B (Sec. 3 explicit pattern specification; Sec. 4.1) -------- */
 /* A backend here is one of the library's kernel families, selected by name:
  *   "igemm"    MFMA implicit-GEMM convolution / GEMM, default tile choice
- *   "igemm_s", "igemm_m", "igemm_l"   the same with a fixed small / medium /
- *              large tile (kernel variants to place per layer)
+ *   "igemm_s", "igemm_s8", "igemm_s16", "igemm_m", "igemm_l"   the same with a
+ *              fixed tile: 32x32 outputs with 4 / 8 / 16 waves sharing K, 64x64,
+ *              128x128 (kernel variants for the search to place per layer)
+ *   "igemm_s_nk", "igemm_s8_nk", "igemm_s16_nk"   those tiles, never splitting
+ *              K across workgroups (no second reduction kernel)
  *   "direct"   direct convolution (any groups) and pooling
  *   "rowwise"  softmax and layer norm with fused elementwise prologue
  *   "eltwise"  elementwise chains, embedding gather, layout copies
@@ -243,8 +246,8 @@ int32_t clg_match_all(clg_ctx *ctx, clg_graph *g, clg_match *out, size_t cap,
 
 /* ---- measurer M (Sec. 4.2) -------------------------------------------------- */
 /* Times one match as one kernel on the device and returns integer nanoseconds
- * per launch (median over batches of back-to-back launches between two HIP
- * events, after warm-up).  Non-constant operands are scratch tensors the
+ * per launch (fastest of several batches of back-to-back launches between two
+ * HIP events, after warm-up).  Non-constant operands are scratch tensors the
  * library allocates and fills from opts->seed; constants are read in place.
  * Results are cached by (backend, fused kind, attributes, shapes): the cost
  * log.  opts may be NULL (all defaults, cache on).  Synchronises the device.

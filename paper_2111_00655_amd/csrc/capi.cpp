@@ -166,10 +166,11 @@ int32_t clg_graph_node_shape(const clg_graph *g, int32_t node, int32_t *dtype, i
 int32_t clg_register_backend(clg_ctx *ctx, const char *name, int32_t *backend) {
     CLG_TRY
     NEED(ctx); NEED(name); NEED(backend);
-    static const struct { const char *name; int32_t family, tile; } kKnown[] = {
-        {"igemm", FAM_IGEMM, TILE_AUTO}, {"igemm_s", FAM_IGEMM, TILE_S}, {"igemm_m", FAM_IGEMM, TILE_M},
-        {"igemm_l", FAM_IGEMM, TILE_L}, {"igemm_s8", FAM_IGEMM, TILE_S8}, {"igemm_s16", FAM_IGEMM, TILE_S16}, {"direct", FAM_DIRECT, 0}, {"rowwise", FAM_ROWWISE, 0},
-        {"eltwise", FAM_ELTWISE, 0}};
+    static const struct { const char *name; int32_t family, tile, no_split; } kKnown[] = {
+        {"igemm", FAM_IGEMM, TILE_AUTO, 0}, {"igemm_s", FAM_IGEMM, TILE_S, 0}, {"igemm_m", FAM_IGEMM, TILE_M, 0},
+        {"igemm_l", FAM_IGEMM, TILE_L, 0}, {"igemm_s8", FAM_IGEMM, TILE_S8, 0}, {"igemm_s16", FAM_IGEMM, TILE_S16, 0},
+        {"igemm_s_nk", FAM_IGEMM, TILE_S, 1}, {"igemm_s8_nk", FAM_IGEMM, TILE_S8, 1}, {"igemm_s16_nk", FAM_IGEMM, TILE_S16, 1},
+        {"direct", FAM_DIRECT, 0, 0}, {"rowwise", FAM_ROWWISE, 0, 0}, {"eltwise", FAM_ELTWISE, 0, 0}};
     const std::string s(name);
     for (size_t i = 0; i < ctx->c.backends.size(); ++i)
         if (ctx->c.backends[i].name == s) {
@@ -178,7 +179,7 @@ int32_t clg_register_backend(clg_ctx *ctx, const char *name, int32_t *backend) {
         }
     for (auto &k : kKnown)
         if (s == k.name) {
-            ctx->c.backends.push_back(Backend{s, k.family, k.tile});
+            ctx->c.backends.push_back(Backend{s, k.family, k.tile, k.no_split});
             *backend = (int32_t)ctx->c.backends.size() - 1;
             return CLG_OK;
         }

@@ -85,7 +85,8 @@ enum Family : int32_t { FAM_IGEMM = 0, FAM_DIRECT = 1, FAM_ROWWISE = 2, FAM_ELTW
 struct Backend {
     std::string name;
     int32_t family = 0;
-    int32_t tile = 0;                 // igemm: 0 auto, 1 small, 2 medium, 3 large
+    int32_t tile = 0;                 // igemm: GemmTile
+    int32_t no_split = 0;             // igemm: 1 = never split K across workgroups
 };
 
 struct Pattern {

@@ -16,22 +16,20 @@ __device__ __forceinline__ float gelu_erf(float v) {
 
 // Applies the fused steps to one value.  `off` is the element's offset in the
 // output tensor (EPI_ADD operands have the output's shape); `chan` its channel
-// for EPI_BIAS.  The program sits in the kernel-argument segment; the loop is
-// fully unrolled so that every step is read at a constant offset (a run-time
-// index would make the compiler copy the program to scratch memory), and the
-// tests are wave-uniform.
+// for EPI_BIAS.  The program sits in the kernel-argument segment, so the loop
+// and its tests are wave-uniform; the loop is kept rolled on purpose: unrolled,
+// the interpreter multiplies the code size of every kernel that calls it per
+// value, and a small kernel then spends its time on instruction-cache misses.
 __device__ __forceinline__ float apply_steps(const Epilogue &e, float v, int64_t off, int chan) {
-#pragma unroll
-    for (int s = 0; s < kMaxEpi; ++s) {
-        if (s < e.n) {
-            const int op = e.s[s].op;
-            if (op == EPI_BIAS) v += e.s[s].ptr[chan];
-            else if (op == EPI_ADD) v += e.s[s].ptr[off];
-            else if (op == EPI_RELU) v = v > 0.f ? v : 0.f;
-            else if (op == EPI_GELU) v = gelu_erf(v);
-            else if (op == EPI_TANH) v = tanhf(v);
-            else if (op == EPI_SCALE) v *= e.s[s].scalar;
-        }
+#pragma unroll 1
+    for (int s = 0; s < e.n; ++s) {
+        const int op = e.s[s].op;
+        if (op == EPI_BIAS) v += e.s[s].ptr[chan];
+        else if (op == EPI_ADD) v += e.s[s].ptr[off];
+        else if (op == EPI_RELU) v = v > 0.f ? v : 0.f;
+        else if (op == EPI_GELU) v = gelu_erf(v);
+        else if (op == EPI_TANH) v = tanhf(v);
+        else if (op == EPI_SCALE) v *= e.s[s].scalar;
     }
     return v;
 }

@@ -321,6 +321,7 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
             macs = (double)a.batch * a.M * a.N * a.K;
             if ((double)a.M * a.N > 2.0e9 || a.K < 1) return fail(CLG_NO_KERNEL, "GEMM dimensions out of range");
             gemm_resolve(&a, ctx.n_cus);
+            if (be.no_split) a.splitk = 1;
             c.scratch_bytes = gemm_scratch_bytes(a);
             c.kind = CALL_GEMM;
             c.bound = 0;

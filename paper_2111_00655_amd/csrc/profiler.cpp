@@ -4,8 +4,11 @@
 // hardware" and results cached in a log.
 //
 // Protocol: warm-up launches, then `batches` timed batches of back-to-back
-// launches between two HIP events; the cost is the median batch time per
-// launch, rounded once to integer nanoseconds.  The figure is launch-inclusive
+// launches between two HIP events; the cost is the smallest batch time per
+// launch, rounded once to integer nanoseconds.  (The smallest, not the median:
+// on a shared host the enqueueing thread is descheduled for milliseconds at a
+// time, which inflates whole batches by 2-3x; such a stall can only add time,
+// so the undisturbed batch is the fastest one.)  The figure is launch-inclusive
 // (it contains the dispatch gap between consecutive kernels), so the search
 // can use eps = 0.
 #include <algorithm>
@@ -39,7 +42,7 @@ int32_t ensure_block(Context &ctx, size_t need) {
 struct Opts { int warmup, batches, min_batch_us, max_launches; uint64_t seed; bool cache; };
 
 Opts resolve(const clg_profile_opts *o) {
-    Opts r{20, 5, 200, 2000, 1, true};
+    Opts r{20, 7, 200, 2000, 1, true};
     if (!o) return r;
     if (o->warmup > 0) r.warmup = o->warmup;
     if (o->batches > 0) r.batches = o->batches;
@@ -90,8 +93,7 @@ int32_t time_launches(const Opts &o, F &&launch, int64_t *cost_ns) {
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
     if (rc != CLG_OK) return rc;
-    std::sort(per.begin(), per.end());
-    *cost_ns = std::max<int64_t>(1, (int64_t)std::llround(per[per.size() / 2]));
+    *cost_ns = std::max<int64_t>(1, (int64_t)std::llround(*std::min_element(per.begin(), per.end())));
     return CLG_OK;
 }
 
