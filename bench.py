@@ -135,7 +135,8 @@ def main():
     import workloads as wl
     from paper_2111_00655_amd import binding as B
 
-    reg = wl.default_registry(("igemm", "igemm_s", "igemm_s8", "igemm_s16", "igemm_m", "igemm_l", "igemm_s_nk", "igemm_s8_nk", "igemm_s16_nk"))
+    reg = wl.default_registry(("igemm", "igemm_s", "igemm_s8", "igemm_s16", "igemm_m", "igemm_l", "igemm_s_nk", "igemm_s8_nk", "igemm_s16_nk",
+                               "igemm_r32", "igemm_r16"))
     opts = B.ProfileOpts(warmup=10, batches=5, min_batch_us=200, max_launches=500)
 
     desc = wl.MODEL_BUILDERS[args.model](0)
@@ -183,7 +184,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"{args.model} batch 1 fp32, seeded random weights, placement from the "
-                               "library's measurer + DP over igemm{,_s,_m,_l}/direct/rowwise/eltwise",
+                               "library's measurer + DP over the igemm tile variants, direct, rowwise and eltwise kernels",
                    "kernels_per_step": plan.n_kernels},
         "roofline": roof,
         "cpu_baseline": cpu,

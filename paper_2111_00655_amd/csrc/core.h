@@ -128,6 +128,7 @@ struct KernelCall {
     int32_t bound = 1;                // 0 MFMA, 1 HBM
     size_t scratch_bytes = 0;         // per-call device scratch (split-K partials)
     bool gemm_swap = false;           // GEMM: A = second graph operand (weights), B = first
+    size_t pack_bytes = 0;            // register-fed conv: size of the re-packed copy of the weights (b_node)
     int32_t out_node = -1;
     // pointer slots to fill at execution: each refers to a graph value
     int32_t a_node = -1, b_node = -1, c_node = -1;     // main operands
@@ -156,11 +157,19 @@ struct Plan {
     std::vector<int64_t> value_offset;     // node -> workspace byte offset, -1 none
     std::vector<int32_t> value_output;     // node -> index in outputs[], -1 none
     std::vector<int64_t> scratch_offset;   // call -> workspace byte offset of its scratch
+    std::vector<void *> packed;            // call -> re-packed weights (device memory owned by the plan) or null
     size_t workspace_bytes = 0;
+    Plan() = default;
+    Plan(const Plan &) = delete;
+    Plan &operator=(const Plan &) = delete;
+    ~Plan();
 };
 
+// `packed`: the re-packed weights when c.pack_bytes != 0 (see pack_weights), else ignored.
 int32_t launch_call(const KernelCall &c, const void *a, const void *b, const void *c3,
-                    void *out, const void *const *epi_ptrs, void *scratch, void *stream);
+                    void *out, const void *const *epi_ptrs, void *scratch, const void *packed, void *stream);
+// Runs the weight re-packing kernel of call `c` (c.pack_bytes != 0): w -> dst.
+int32_t pack_weights(const KernelCall &c, const void *w, void *dst, void *stream);
 
 // shape inference for one operator; returns CLG_OK or SHAPE_MISMATCH / INVALID_ARG
 int32_t infer_shape(const Graph &g, int32_t kind, const std::vector<int32_t> &in,

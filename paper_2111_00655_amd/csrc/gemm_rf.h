@@ -1,0 +1,266 @@
+// Register-fed fp32 MFMA convolution kernels for gfx950 (no LDS staging).
+//
+// At batch 1 the deep layers of the CNN workloads (paper Sec. 5.1) have few
+// output pixels (14x14, 7x7) and long reductions (K up to 4608).  With one
+// 32x32 output tile per workgroup such a layer has a few dozen tiles: most of
+// the 256 compute units idle unless K is split across workgroups, which costs a
+// second kernel to add the partial sums.  Splitting K across the WAVES of one
+// workgroup has no operand reuse between waves, so staging operands through LDS
+// buys nothing there.  These kernels therefore
+//  * feed the MFMAs straight from global memory: the weights are re-packed once
+//    (when a plan is compiled) into the order in which lanes consume them, so a
+//    wave's A operand for four MFMAs is one 16-byte load per lane, 1 KB
+//    contiguous per wave; the B operand (input pixels) is one 4-byte load per
+//    lane and MFMA, lanes running along consecutive pixels;
+//  * have no barrier and no LDS access inside the K loop; the K-waves meet once,
+//    in LDS, to add their accumulators;
+//  * come with 32x32 tiles (v_mfma_f32_32x32x2_f32) and 16x16 tiles
+//    (v_mfma_f32_16x16x4_f32): the small tile gives a 14x14 layer 200+
+//    workgroups without any split across workgroups.
+//
+// K order.  MFMA number n of a tile contracts NSLOT input channels (NSLOT = 2
+// or 4 k-slots of the instruction: lane / TS) at one filter tap:
+//   n = cq * TAPS + t,  channel = cq * NSLOT + slot,  tap t = kh * KW + kw.
+// Packed weights: [m-tile][group g][lane][4], element q of group g = MFMA 4g+q,
+// lane = slot * TS + row; zero beyond Cout, Cin and the last MFMA, so padded
+// work adds exact zeros.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "device_common.h"
+#include "gemm_lean.h"
+
+namespace clg {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+template <int TS>
+struct RfMfma;
+
+template <>
+struct RfMfma<32> {
+    typedef floatx16 acc_t;
+    static constexpr int NSLOT = 2, NACC = 16;
+    static __device__ __forceinline__ acc_t mma(float a, float b, acc_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+    }
+    // accumulator register g of a lane in slot s holds this row of the tile (column = lane % 32)
+    static __device__ __forceinline__ int row(int g, int s) { return 8 * (g / 4) + 4 * s + (g % 4); }
+};
+
+template <>
+struct RfMfma<16> {
+    typedef floatx4 acc_t;
+    static constexpr int NSLOT = 4, NACC = 4;
+    static __device__ __forceinline__ acc_t mma(float a, float b, acc_t c) {
+        return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ int row(int g, int s) { return 4 * s + g; }
+};
+
+// TAPK: 1 = 1x1 filter without padding, 9 = 3x3 filter, 0 = any filter (tap
+// geometry computed per MFMA).  TAPK 1 and 9 need Cin % NSLOT == 0.
+// Work units per wave ("chunks"): 16 MFMAs (TAPK 1), 36 MFMAs = all taps of
+// four channel groups (TAPK 9), 4 MFMAs (TAPK 0).
+template <int TAPK>
+struct RfChunk {
+    static constexpr int GROUPS = TAPK == 1 ? 4 : (TAPK == 9 ? 9 : 1);
+};
+
+template <int TS, int TAPK, int WGK>
+__global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
+    using MF = RfMfma<TS>;
+    typedef typename MF::acc_t acc_t;
+    constexpr int NSLOT = MF::NSLOT, NACC = MF::NACC;
+    constexpr int NT = WGK * kWave;
+    constexpr int PER_WAVE = NACC * kWave;                  // outputs of a tile
+    constexpr int EPT = (PER_WAVE + NT - 1) / NT;           // outputs finished per thread
+    extern __shared__ float red[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int w = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int r = lane % TS, s = lane / TS;
+
+    const int npix = p.HO * p.WO;
+    const int tiles_n = (npix + TS - 1) / TS;
+    const int tiles_m = (p.Cout + TS - 1) / TS;
+    const int tile = xcd_remap(blockIdx.x, gridDim.x);
+    // neighbouring workgroups share the larger operand: weights rows (i-major) or pixels (j-major)
+    const int mt = p.rf_jmajor ? tile % tiles_m : tile / tiles_n;
+    const int nt = p.rf_jmajor ? tile / tiles_m : tile % tiles_n;
+    const int i0 = mt * TS, j0 = nt * TS;
+    const int img = blockIdx.y;
+    const int ks = blockIdx.z;
+
+    const int jp = min(j0 + r, npix - 1);
+    const int oh = (int)(((uint64_t)(uint32_t)jp * p.rf_wo_magic) >> 32);
+    const int ow = jp - oh * p.WO;
+    const int ih0 = oh * p.sh - p.ph, iw0 = ow * p.sw - p.pw;
+    const int HW = p.H * p.W;
+    const float *const x_img = p.B + (int64_t)img * p.Cin * HW;
+    const f32x4 *const Ap = reinterpret_cast<const f32x4 *>(p.A) + (int64_t)mt * p.rf_ngtot * kWave + lane;
+    const int nch = p.rf_nch;                                // chunks per wave
+    const int c0 = (ks * WGK + w) * nch;                     // this wave's first chunk
+    const int cq_last = (p.Cin + NSLOT - 1) / NSLOT - 1;
+
+    // outputs this thread finishes, and the operands of their fused tail
+    int64_t e_off[EPT];
+    float e_bias[EPT], e_add[EPT];
+#pragma unroll
+    for (int t = 0; t < EPT; ++t) {
+        const int e = tid + t * NT;
+        const int l = e % kWave, g = e / kWave;
+        const int i = i0 + MF::row(g, l / TS), j = j0 + l % TS;
+        e_off[t] = (e < PER_WAVE && i < p.Cout && j < npix) ? ((int64_t)img * p.Cout + i) * npix + j : -1;
+        e_bias[t] = 0.f;
+        e_add[t] = 0.f;
+        if (p.splitk == 1 && e_off[t] >= 0) {
+            if (p.ef.flags & EF_BIAS) e_bias[t] = p.ef.bias[i];
+            if (p.ef.flags & EF_ADD) e_add[t] = p.ef.add[e_off[t]];
+        }
+    }
+
+    acc_t acc;
+#pragma unroll
+    for (int g = 0; g < NACC; ++g) acc[g] = 0.f;
+
+    if constexpr (TAPK == 1) {
+        // ---- 1x1: MFMA n contracts channels n*NSLOT .. n*NSLOT+NSLOT-1 at this lane's pixel
+        const int lane_off = s * HW + ih0 * p.W + iw0;
+        const int64_t cq_step = (int64_t)NSLOT * HW;
+        f32x4 a[2][4];
+        float b[2][16];
+#define CLG_RF_LOAD(set, c)                                                                   \
+    do {                                                                                      \
+        const int ch_ = min((c), nch - 1) + c0;                                               \
+        _Pragma("unroll") for (int u = 0; u < 4; ++u) a[set][u] = Ap[(int64_t)(ch_ * 4 + u) * kWave]; \
+        _Pragma("unroll") for (int u = 0; u < 16; ++u) {                                      \
+            const int cq_ = min(ch_ * 16 + u, cq_last);                                       \
+            b[set][u] = x_img[cq_ * cq_step + lane_off];                                      \
+        }                                                                                     \
+        __builtin_amdgcn_sched_barrier(0);   /* all loads of a chunk go out before its MFMAs */ \
+    } while (0)
+#define CLG_RF_MMA(set)                                                                       \
+    do {                                                                                      \
+        _Pragma("unroll") for (int u = 0; u < 16; ++u) acc = MF::mma(a[set][u / 4][u % 4], b[set][u], acc); \
+    } while (0)
+        CLG_RF_LOAD(0, 0);
+        int c = 0;
+        for (; c + 1 < nch; c += 2) {
+            CLG_RF_LOAD(1, c + 1);
+            CLG_RF_MMA(0);
+            CLG_RF_LOAD(0, c + 2);
+            CLG_RF_MMA(1);
+        }
+        if (c < nch) CLG_RF_MMA(0);
+#undef CLG_RF_LOAD
+#undef CLG_RF_MMA
+    } else if constexpr (TAPK == 9) {
+        // ---- 3x3: the nine tap offsets of this lane's pixel are fixed; a chunk is
+        // four channel groups x nine taps
+        int voff[9];
+        bool ok[9];
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+            const int ih = ih0 + t / 3, iw = iw0 + t % 3;
+            ok[t] = ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
+            voff[t] = s * HW + (ok[t] ? ih * p.W + iw : 0);
+        }
+        const int64_t cq_step = (int64_t)NSLOT * HW;
+        for (int c = 0; c < nch; ++c) {
+            const int ch = c0 + c;
+            f32x4 a[9];
+            float b[36];
+#pragma unroll
+            for (int u = 0; u < 9; ++u) a[u] = Ap[(int64_t)(ch * 9 + u) * kWave];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float *xc = x_img + min(ch * 4 + q, cq_last) * cq_step;
+#pragma unroll
+                for (int t = 0; t < 9; ++t) {
+                    const float v = xc[voff[t]];
+                    b[q * 9 + t] = v;
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);       // all 45 loads go out before the first MFMA waits
+#pragma unroll
+            for (int u = 0; u < 36; ++u) b[u] = ok[u % 9] ? b[u] : 0.f;
+#pragma unroll
+            for (int u = 0; u < 36; ++u) acc = MF::mma(a[u / 4][u % 4], b[u], acc);
+        }
+    } else {
+        // ---- any filter: tap geometry per MFMA; (cq, kh, kw) advance with n
+        const int taps = p.KH * p.KW;
+        const int nm = p.rf_nm;
+        int n = c0 * 4;
+        int cq = n / taps, t = n - cq * taps;
+        int kh = t / p.KW, kw = t - kh * p.KW;
+        for (int c = 0; c < nch; ++c) {
+            const f32x4 a = Ap[(int64_t)(c0 + c) * kWave];
+            float b[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int ch = cq * NSLOT + s;
+                const int ih = ih0 + kh, iw = iw0 + kw;
+                const bool ok = n < nm && ch < p.Cin && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
+                const float v = x_img[ok ? (int64_t)ch * HW + ih * p.W + iw : 0];
+                b[q] = ok ? v : 0.f;
+                ++n;
+                if (++kw == p.KW) {
+                    kw = 0;
+                    if (++kh == p.KH) {
+                        kh = 0;
+                        ++cq;
+                    }
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc = MF::mma(a[q], b[q], acc);
+        }
+    }
+
+    // ---- the K-waves add their accumulators in LDS, in wave order
+    if constexpr (WGK > 1) {
+#pragma unroll
+        for (int g = 0; g < NACC; ++g) red[w * PER_WAVE + g * kWave + lane] = acc[g];
+        __syncthreads();
+    }
+#pragma unroll
+    for (int t = 0; t < EPT; ++t) {
+        float v;
+        if constexpr (WGK > 1) {
+            const int e = min(tid + t * NT, PER_WAVE - 1);
+            v = 0.f;
+#pragma unroll
+            for (int ww = 0; ww < WGK; ++ww) v += red[ww * PER_WAVE + e];
+        } else {
+            v = acc[t];
+        }
+        if (e_off[t] >= 0) {
+            if (p.splitk > 1) p.partial[(int64_t)ks * p.c_numel + e_off[t]] = v;
+            else p.C[e_off[t]] = finish_value(p, v, e_bias[t], e_add[t]);
+        }
+    }
+}
+
+// Weight re-packing (once per compiled kernel): w is [Cout][Cin][KH*KW].
+template <int TS>
+__global__ void rf_pack_kernel(const float *w, float *dst, int Cout, int Cin, int taps, int nm, int ngtot, int64_t total) {
+    constexpr int NSLOT = RfMfma<TS>::NSLOT;
+    const int64_t d = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (d >= total) return;
+    const int q = (int)(d & 3), lane = (int)((d >> 2) & 63);
+    const int64_t gg = d >> 8;
+    const int g = (int)(gg % ngtot), mt = (int)(gg / ngtot);
+    const int n = 4 * g + q;
+    const int cq = n / taps, t = n - cq * taps;
+    const int i = mt * TS + lane % TS, ch = cq * NSLOT + lane / TS;
+    dst[d] = (n < nm && i < Cout && ch < Cin) ? w[((int64_t)i * Cin + ch) * taps + t] : 0.f;
+}
+
+// gemm_rf.hip
+int launch_rf_conv(const GemmArgs &a, hipStream_t s);
+
+}  // namespace clg

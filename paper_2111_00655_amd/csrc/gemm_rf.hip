@@ -1,0 +1,97 @@
+// Instantiations, planning and dispatch of the register-fed convolution kernels.
+#include <algorithm>
+
+#include "gemm_rf.h"
+
+namespace clg {
+
+namespace {
+
+template <int TS, int TAPK, int WGK>
+int launch_rf_one(const GemmArgs &a, hipStream_t s) {
+    const int npix = a.HO * a.WO;
+    const int tiles = ((a.Cout + TS - 1) / TS) * ((npix + TS - 1) / TS);
+    const size_t lds = WGK > 1 ? (size_t)WGK * RfMfma<TS>::NACC * kWave * sizeof(float) : 0;
+    hipLaunchKernelGGL((conv_rf_kernel<TS, TAPK, WGK>), dim3(tiles, a.Nimg, a.splitk), dim3(WGK * kWave), lds, s, a);
+    return (int)hipGetLastError();
+}
+
+template <int TS, int TAPK>
+int launch_rf_wgk(const GemmArgs &a, hipStream_t s) {
+    switch (a.rf_wgk) {
+    case 1: return launch_rf_one<TS, TAPK, 1>(a, s);
+    case 2: return launch_rf_one<TS, TAPK, 2>(a, s);
+    case 4: return launch_rf_one<TS, TAPK, 4>(a, s);
+    case 8: return launch_rf_one<TS, TAPK, 8>(a, s);
+    case 16: return launch_rf_one<TS, TAPK, 16>(a, s);
+    default: return (int)hipErrorInvalidValue;
+    }
+}
+
+template <int TS>
+int launch_rf_tap(const GemmArgs &a, hipStream_t s) {
+    switch (a.rf_tapk) {
+    case 1: return launch_rf_wgk<TS, 1>(a, s);
+    case 9: return launch_rf_wgk<TS, 9>(a, s);
+    default: return launch_rf_wgk<TS, 0>(a, s);
+    }
+}
+
+int chunk_mfmas(int tapk) { return tapk == 1 ? 16 : (tapk == 9 ? 36 : 4); }
+int chunk_groups(int tapk) { return tapk == 1 ? 4 : (tapk == 9 ? 9 : 1); }
+
+}  // namespace
+
+int launch_rf_conv(const GemmArgs &a, hipStream_t s) {
+    return a.rf_ts == 32 ? launch_rf_tap<32>(a, s) : launch_rf_tap<16>(a, s);
+}
+
+bool rf_resolve(GemmArgs *a, int ts, int epi_flags, int n_cus) {
+    (void)n_cus;
+    if (a->mode != GM_CONV || (epi_flags & EF_GENERIC)) return false;
+    const int nslot = ts == 32 ? 2 : 4;
+    const int64_t npix = (int64_t)a->HO * a->WO;
+    if (npix * a->WO >= ((int64_t)1 << 32)) return false;             // multiply-high division range
+    if ((int64_t)a->Cin * a->H * a->W >= ((int64_t)1 << 30)) return false;   // 32-bit lane offsets
+    const int taps = a->KH * a->KW;
+    const int ncq = (a->Cin + nslot - 1) / nslot;
+    int tapk = 0;
+    if (a->Cin % nslot == 0) {
+        if (taps == 1 && a->ph == 0 && a->pw == 0) tapk = 1;
+        else if (a->KH == 3 && a->KW == 3) tapk = 9;
+    }
+    const int nm = ncq * taps;
+    const int nc = (nm + chunk_mfmas(tapk) - 1) / chunk_mfmas(tapk);   // chunks per tile
+    int wgk = 1;
+    while (wgk < 16 && wgk < nc) wgk *= 2;
+    a->rf_ts = ts;
+    a->rf_tapk = tapk;
+    a->rf_wgk = wgk;
+    a->rf_nch = (nc + wgk - 1) / wgk;
+    a->splitk = 1;
+    a->rf_ngtot = wgk * a->splitk * a->rf_nch * chunk_groups(tapk);
+    a->rf_nm = nm;
+    a->rf_jmajor = (int64_t)a->Cin * a->H * a->W > (int64_t)a->Cout * a->K ? 1 : 0;
+    a->rf_wo_magic = (((uint64_t)1 << 32) / (uint64_t)a->WO) + 1;
+    return true;
+}
+
+size_t rf_pack_bytes(const GemmArgs &a) {
+    if (!a.rf_ts) return 0;
+    const size_t tiles_m = (size_t)(a.Cout + a.rf_ts - 1) / a.rf_ts;
+    return tiles_m * (size_t)a.rf_ngtot * 256 * sizeof(float);
+}
+
+int launch_rf_pack(const GemmArgs &a, const float *w, float *dst, void *stream) {
+    const int64_t total = (int64_t)(rf_pack_bytes(a) / sizeof(float));
+    const unsigned blocks = (unsigned)((total + 255) / 256);
+    if (a.rf_ts == 32)
+        hipLaunchKernelGGL((rf_pack_kernel<32>), dim3(blocks), dim3(256), 0, (hipStream_t)stream, w, dst, a.Cout, a.Cin,
+                           a.KH * a.KW, a.rf_nm, a.rf_ngtot, total);
+    else
+        hipLaunchKernelGGL((rf_pack_kernel<16>), dim3(blocks), dim3(256), 0, (hipStream_t)stream, w, dst, a.Cout, a.Cin,
+                           a.KH * a.KW, a.rf_nm, a.rf_ngtot, total);
+    return (int)hipGetLastError();
+}
+
+}  // namespace clg

@@ -66,7 +66,10 @@ enum GemmMode : int32_t {
     GM_CONVT = 3   // transposed conv as stride*stride sub-pixel phases, one phase per grid.z slice
 };
 
-enum GemmTile : int32_t { TILE_AUTO = 0, TILE_S = 1, TILE_M = 2, TILE_L = 3, TILE_S8 = 4, TILE_S16 = 5 };
+enum GemmTile : int32_t {
+    TILE_AUTO = 0, TILE_S = 1, TILE_M = 2, TILE_L = 3, TILE_S8 = 4, TILE_S16 = 5,
+    TILE_R32 = 6, TILE_R16 = 7     // register-fed convolution kernels, 32x32 / 16x16 tiles (gemm_rf.h)
+};
 
 struct GemmArgs {
     int32_t mode, tile, splitk, batch;
@@ -82,6 +85,11 @@ struct GemmArgs {
     int32_t Nimg, Cin, H, W, Cout, KH, KW, sh, sw, ph, pw, HO, WO;
     int32_t bias_on_row;                   // 1: channel = i (conv), 0: channel = j (dense)
     int32_t patch_sz;                      // 3x3 kernel: floats per channel of the LDS input patch
+    // register-fed convolution (gemm_rf.h); rf_ts = 0: not used.  A then points at the packed weights.
+    int32_t rf_ts, rf_tapk, rf_wgk;        // tile edge 32|16, tap mode 1|9|0, K-waves per workgroup
+    int32_t rf_nch, rf_ngtot, rf_nm;       // chunks per wave, packed groups per m-tile, MFMAs per tile
+    int32_t rf_jmajor, rf_pad_;
+    uint64_t rf_wo_magic;                  // floor(2^32 / WO) + 1: pixel / WO by multiply-high
     Epilogue epi;
     EpiFast ef;                            // filled by launch_gemm from epi
 };
@@ -152,5 +160,14 @@ int launch_empty(void *stream);
 // (resolved at plan time so that the scratch size is known).
 void gemm_resolve(GemmArgs *a, int n_cus);
 size_t gemm_scratch_bytes(const GemmArgs &a);
+
+// Register-fed convolution: decides whether the kernel runs this GM_CONV
+// problem with tile edge `ts` (32 or 16) and a tail of `epi_flags`
+// (EpiFastFlags); if so fills the rf_* fields and the split and returns true.
+bool rf_resolve(GemmArgs *a, int ts, int epi_flags, int n_cus);
+size_t rf_pack_bytes(const GemmArgs &a);
+// Packs conv weights w [Cout][Cin][KH][KW] into dst (rf_pack_bytes) for the kernel.
+int launch_rf_pack(const GemmArgs &a, const float *w, float *dst, void *stream);
+int epi_fast_flags(const Epilogue &e);
 
 }  // namespace clg

@@ -27,6 +27,7 @@
 #include "device_common.h"
 #include "gemm_fast.h"
 #include "gemm_lean.h"
+#include "gemm_rf.h"
 
 namespace clg {
 
@@ -366,10 +367,13 @@ static EpiFast make_epi_fast(const Epilogue &e) {
     return f;
 }
 
+int epi_fast_flags(const Epilogue &e) { return make_epi_fast(e).flags; }
+
 int launch_gemm(const GemmArgs &a_in, void *stream) {
     hipStream_t s = (hipStream_t)stream;
     GemmArgs a = a_in;
     a.ef = make_epi_fast(a.epi);
+    if (a.rf_ts) return launch_rf_conv(a, s);
     int err;
     const bool a_vec = a.K % 4 == 0 && a.lda % 4 == 0 && a.strideA % 4 == 0 && al16(a.A);
     switch (a.mode) {

@@ -262,6 +262,8 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
         } else {
             GemmArgs &a = c.gemm;
             a.tile = be.tile;
+            const bool want_rf = a.tile == TILE_R32 || a.tile == TILE_R16;
+            bool rf = false;
             a.batch = 1;
             a.epi = epi;
             a.c_numel = ys.numel();
@@ -289,7 +291,16 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
                 a.HO = (int)ys.d[2]; a.WO = (int)ys.d[3];
                 a.bias_on_row = 1;
                 c.gemm_swap = true;
-                if (a.KH == 1 && a.KW == 1 && a.sh == 1 && a.sw == 1 && a.ph == 0 && a.pw == 0) {
+                // register-fed kernel: needs constant weights (re-packed once) and a common-form tail
+                if (want_rf && g.nodes[wb].kind == NODE_CONST) {
+                    a.mode = GM_CONV;
+                    a.M = a.Cout; a.N = a.Nimg * a.HO * a.WO; a.K = a.Cin * a.KH * a.KW;
+                    a.lda = a.K;
+                    rf = rf_resolve(&a, a.tile == TILE_R32 ? 32 : 16, epi_fast_flags(epi), ctx.n_cus);
+                }
+                if (rf) {
+                    c.pack_bytes = rf_pack_bytes(a);
+                } else if (a.KH == 1 && a.KW == 1 && a.sh == 1 && a.sw == 1 && a.ph == 0 && a.pw == 0) {
                     // 1x1 stride-1 convolution is a plain GEMM per image: W[Cout,Cin] * X[Cin,H*W]
                     a.mode = GM_NN;
                     a.batch = a.Nimg;
@@ -320,13 +331,19 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
             }
             macs = (double)a.batch * a.M * a.N * a.K;
             if ((double)a.M * a.N > 2.0e9 || a.K < 1) return fail(CLG_NO_KERNEL, "GEMM dimensions out of range");
-            gemm_resolve(&a, ctx.n_cus);
-            if (be.no_split) a.splitk = 1;
-            c.scratch_bytes = gemm_scratch_bytes(a);
             c.kind = CALL_GEMM;
             c.bound = 0;
-            static const char *tn[] = {"auto", "s", "m", "l", "s8", "s16"};
-            c.name += std::string("_") + tn[a.tile] + (a.splitk > 1 ? "_k" + std::to_string(a.splitk) : "");
+            if (rf) {
+                c.scratch_bytes = gemm_scratch_bytes(a);
+                c.name = "conv_rf" + std::to_string(a.rf_ts) + "_t" + std::to_string(a.rf_tapk) + "_w" + std::to_string(a.rf_wgk);
+            } else {
+                if (want_rf) a.tile = TILE_S8;           // what the register-fed kernels do not run goes to the LDS-tiled ones
+                gemm_resolve(&a, ctx.n_cus);
+                if (be.no_split) a.splitk = 1;
+                c.scratch_bytes = gemm_scratch_bytes(a);
+                static const char *tn[] = {"auto", "s", "m", "l", "s8", "s16"};
+                c.name += std::string("_") + tn[a.tile] + (a.splitk > 1 ? "_k" + std::to_string(a.splitk) : "");
+            }
         }
         c.a_node = xa;
         c.b_node = wb;

@@ -124,11 +124,45 @@ int32_t compile_plan(Context &ctx, Graph &g, const int32_t *ids, size_t n, Plan 
             arena.release(plan->value_offset[c.out_node]);     // value nobody reads
     }
     plan->workspace_bytes = (size_t)arena.peak;
+
+    // kernels that read their weights in a packed order get a private copy,
+    // written once here and owned by the plan
+    plan->packed.assign(nc, nullptr);
+    if (ctx.device >= 0) {
+        bool any = false;
+        for (size_t i = 0; i < nc; ++i) {
+            const KernelCall &c = plan->calls[i];
+            if (!c.pack_bytes) continue;
+            const void *w = g.nodes[c.b_node].dev_ptr;
+            if (!w) return fail(CLG_INVALID_ARG, "constant node %d has no device pointer", c.b_node);
+            if (hipMalloc(&plan->packed[i], c.pack_bytes) != hipSuccess) {
+                (void)hipGetLastError();
+                plan->packed[i] = nullptr;
+                return fail(CLG_OUT_OF_MEMORY, "allocation of %zu bytes for packed weights failed", c.pack_bytes);
+            }
+            const int32_t rc = pack_weights(c, w, plan->packed[i], nullptr);
+            if (rc != CLG_OK) return rc;
+            any = true;
+        }
+        if (any && hipStreamSynchronize(nullptr) != hipSuccess)
+            return fail(CLG_HIP_ERROR, "weight packing failed: %s", hipGetErrorString(hipGetLastError()));
+    }
+    return CLG_OK;
+}
+
+Plan::~Plan() {
+    for (void *p : packed)
+        if (p) (void)hipFree(p);
+}
+
+int32_t pack_weights(const KernelCall &c, const void *w, void *dst, void *stream) {
+    const int err = launch_rf_pack(c.gemm, (const float *)w, (float *)dst, stream);
+    if (err != 0) return fail(CLG_HIP_ERROR, "weight packing launch failed: %s", hipGetErrorString((hipError_t)err));
     return CLG_OK;
 }
 
 int32_t launch_call(const KernelCall &c, const void *a, const void *b, const void *c3, void *out,
-                    const void *const *epi_ptrs, void *scratch, void *stream) {
+                    const void *const *epi_ptrs, void *scratch, const void *packed, void *stream) {
     auto bind = [&](Epilogue e) {
         for (int s = 0; s < e.n; ++s) e.s[s].ptr = (const float *)epi_ptrs[s];
         return e;
@@ -140,6 +174,10 @@ int32_t launch_call(const KernelCall &c, const void *a, const void *b, const voi
         k.A = (const float *)a; k.B = (const float *)b; k.C = (float *)out;
         if (c.gemm_swap) {                               // A = weights, B = activations
             k.A = (const float *)b; k.B = (const float *)a;
+        }
+        if (c.pack_bytes) {
+            if (!packed) return fail(CLG_INVALID_ARG, "%s needs packed weights, none were prepared", c.name.c_str());
+            k.A = (const float *)packed;
         }
         k.partial = (float *)scratch;
         k.epi = bind(c.gemm.epi);
@@ -227,7 +265,7 @@ int32_t execute_plan(Plan &p, const void *const *inputs, void *const *outputs, v
         void *scratch = p.scratch_offset[i] >= 0 ? (char *)workspace + p.scratch_offset[i] : nullptr;
         if (kernel_ns) (void)hipEventRecord(ev[2 * i], (hipStream_t)stream);
         rc = launch_call(c, ptr_of(c.a_node), ptr_of(c.b_node), ptr_of(c.c_node),
-                         const_cast<void *>(ptr_of(c.out_node)), epi, scratch, stream);
+                         const_cast<void *>(ptr_of(c.out_node)), epi, scratch, p.packed[i], stream);
         if (kernel_ns) (void)hipEventRecord(ev[2 * i + 1], (hipStream_t)stream);
     }
     if (kernel_ns) {

@@ -147,6 +147,8 @@ int32_t profile_match(Context &ctx, Graph &g, int32_t match, const clg_profile_o
     }
     const size_t scratch_off = total;
     total += up(c.scratch_bytes);
+    const size_t pack_off = total;
+    total += up(c.pack_bytes);
     int32_t rc = ensure_block(ctx, std::max<size_t>(total, 256));
     if (rc != CLG_OK) return rc;
     char *base = (char *)ctx.prof_ptr;
@@ -172,10 +174,17 @@ int32_t profile_match(Context &ctx, Graph &g, int32_t match, const clg_profile_o
         }
     }
     void *scratch = c.scratch_bytes ? base + scratch_off : nullptr;
+    const void *packed = nullptr;
+    if (c.pack_bytes) {                      // one-time weight re-packing is not part of the measured cost
+        if (g.nodes[c.b_node].kind != NODE_CONST) return fail(CLG_INVALID_ARG, "packed weights must be a constant");
+        rc = pack_weights(c, ptrs[1], base + pack_off, nullptr);
+        if (rc != CLG_OK) return rc;
+        packed = base + pack_off;
+    }
     const void *epi[kMaxEpi];
     for (int s = 0; s < kMaxEpi; ++s) epi[s] = ptrs[3 + s];
     rc = time_launches(o, [&]() -> int32_t {
-        return launch_call(c, ptrs[0], ptrs[1], ptrs[2], const_cast<void *>(ptrs.back()), epi, scratch, nullptr);
+        return launch_call(c, ptrs[0], ptrs[1], ptrs[2], const_cast<void *>(ptrs.back()), epi, scratch, packed, nullptr);
     }, cost_ns);
     if (rc != CLG_OK) return rc;
     if (o.cache) ctx.cost_log[c.key] = *cost_ns;

@@ -18,6 +18,7 @@ pytestmark = pytest.mark.gpu
 OP_TOL = 1e-4
 NET_TOL = 1e-3
 IGEMM = ("igemm", "igemm_s", "igemm_s8", "igemm_s16", "igemm_m", "igemm_l")
+RF = ("igemm_r32", "igemm_r16")          # register-fed convolution kernels (packed weights)
 
 
 def rng_for(*key):
@@ -69,6 +70,9 @@ CONV_CASES = [
     (40, 72, 9, 7, 3, 1, 1, ()),                               # ragged M, N, K; no epilogue
     (128, 130, 7, 7, 3, 1, 1, ("bias_add", "add")),            # N = 49 < one tile
     (512, 64, 7, 7, 1, 1, 0, ("bias_add", "add", "relu")),     # long K, small M*N: split-K
+    (256, 40, 14, 14, 3, 2, 1, ("bias_add", "relu")),          # long K 3x3 stride 2: sixteen K-waves, several chunks each
+    (5, 10, 8, 8, 5, 1, 2, ("bias_add", "tanh")),              # odd channel count, 5x5 filter
+    (1024, 48, 6, 6, 1, 1, 0, ("bias_add",)),                  # 1x1 with K = 1024: two chunks per wave
 ]
 
 
@@ -91,11 +95,13 @@ def conv_desc(case, seed, batch=1, groups=1):
     return d, tail_pattern(P("conv2d", W, W), tail)
 
 
-@pytest.mark.parametrize("backend", IGEMM + ("direct",))
+@pytest.mark.parametrize("backend", IGEMM + RF + ("direct",))
 @pytest.mark.parametrize("ci", range(len(CONV_CASES)))
 def test_conv2d_fused(ci, backend):
     d, pat = conv_desc(CONV_CASES[ci], 10 + ci)
-    run_single_group(d, backend, pat)
+    name, _ = run_single_group(d, backend, pat)
+    if backend in RF:
+        assert name.startswith("conv_rf"), name
 
 
 def test_conv2d_batched_igemm():
@@ -103,6 +109,14 @@ def test_conv2d_batched_igemm():
     run_single_group(d, "igemm", pat)
     d, pat = conv_desc((16, 24, 10, 10, 1, 1, 0, ("bias_add", "relu")), 78, batch=3)
     run_single_group(d, "igemm_m", pat)
+
+
+@pytest.mark.parametrize("backend", RF)
+def test_conv2d_batched_register_fed(backend):
+    for seed, case in enumerate([(8, 24, 12, 10, 3, 1, 1, ("bias_add", "relu")), (16, 24, 10, 10, 1, 2, 0, ("bias_add", "add")),
+                                 (3, 20, 17, 13, 7, 2, 3, ("bias_add", "relu"))]):
+        d, pat = conv_desc(case, 80 + seed, batch=3)
+        run_single_group(d, backend, pat)
 
 
 @pytest.mark.parametrize("case", [(128, 128, 28, 28, 3, 1, 1, 32), (256, 256, 14, 14, 3, 2, 1, 32),
@@ -318,7 +332,7 @@ def test_tiny_cnn_every_placement_matches_the_oracle():
 
 
 def _variants():
-    return wl.default_registry(("igemm", "igemm_s", "igemm_m", "igemm_l"))
+    return wl.default_registry(("igemm", "igemm_s", "igemm_m", "igemm_l", "igemm_r32", "igemm_r16"))
 
 
 @pytest.mark.parametrize("name", ["tiny_cnn", "resnet50", "resnext50", "bert_base", "dcgan_b1", "dcgan_b64"])
