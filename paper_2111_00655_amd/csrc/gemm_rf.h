@@ -24,6 +24,14 @@
 // Packed weights: [m-tile][group g][lane][4], element q of group g = MFMA 4g+q,
 // lane = slot * TS + row; zero beyond Cout, Cin and the last MFMA, so padded
 // work adds exact zeros.
+//
+// Grouped convolution (ResNeXt, paper Sec. 5.1): the TS output channels of an
+// m-tile belong to one or a few consecutive channel groups; the tile contracts
+// the input channels of exactly those groups (rf_cin_tile of them, starting at
+// the first group's first channel), and the packed weights hold zeros where a
+// row's group and a channel's group differ.  With 4 channels per group a 16-row
+// tile spans 4 groups and a quarter of its MFMA work is useful; from 16
+// channels per group on none is wasted.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -99,11 +107,13 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
     const int ow = jp - oh * p.WO;
     const int ih0 = oh * p.sh - p.ph, iw0 = ow * p.sw - p.pw;
     const int HW = p.H * p.W;
-    const float *const x_img = p.B + (int64_t)img * p.Cin * HW;
+    const int cbase = p.rf_groups > 1 ? (i0 / p.rf_cpg_out) * p.rf_cpg_in : 0;
+    const int cin = min(p.rf_cin_tile, p.Cin - cbase);       // input channels this m-tile contracts
+    const float *const x_img = p.B + ((int64_t)img * p.Cin + cbase) * HW;
     const f32x4 *const Ap = reinterpret_cast<const f32x4 *>(p.A) + (int64_t)mt * p.rf_ngtot * kWave + lane;
     const int nch = p.rf_nch;                                // chunks per wave
     const int c0 = (ks * WGK + w) * nch;                     // this wave's first chunk
-    const int cq_last = (p.Cin + NSLOT - 1) / NSLOT - 1;
+    const int cq_last = (cin + NSLOT - 1) / NSLOT - 1;
 
     // outputs this thread finishes, and the operands of their fused tail
     int64_t e_off[EPT];
@@ -204,7 +214,7 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
             for (int q = 0; q < 4; ++q) {
                 const int ch = cq * NSLOT + s;
                 const int ih = ih0 + kh, iw = iw0 + kw;
-                const bool ok = n < nm && ch < p.Cin && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
+                const bool ok = n < nm && ch < cin && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
                 const float v = x_img[ok ? (int64_t)ch * HW + ih * p.W + iw : 0];
                 b[q] = ok ? v : 0.f;
                 ++n;
@@ -245,19 +255,30 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
     }
 }
 
-// Weight re-packing (once per compiled kernel): w is [Cout][Cin][KH*KW].
+// Weight re-packing (once per compiled kernel): w is [Cout][Cin / groups][KH*KW].
 template <int TS>
-__global__ void rf_pack_kernel(const float *w, float *dst, int Cout, int Cin, int taps, int nm, int ngtot, int64_t total) {
+__global__ void rf_pack_kernel(const float *w, float *dst, GemmArgs p, int64_t total) {
     constexpr int NSLOT = RfMfma<TS>::NSLOT;
     const int64_t d = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (d >= total) return;
+    const int taps = p.KH * p.KW;
     const int q = (int)(d & 3), lane = (int)((d >> 2) & 63);
     const int64_t gg = d >> 8;
-    const int g = (int)(gg % ngtot), mt = (int)(gg / ngtot);
+    const int g = (int)(gg % p.rf_ngtot), mt = (int)(gg / p.rf_ngtot);
     const int n = 4 * g + q;
     const int cq = n / taps, t = n - cq * taps;
-    const int i = mt * TS + lane % TS, ch = cq * NSLOT + lane / TS;
-    dst[d] = (n < nm && i < Cout && ch < Cin) ? w[((int64_t)i * Cin + ch) * taps + t] : 0.f;
+    const int i = mt * TS + lane % TS, cl = cq * NSLOT + lane / TS;      // output channel, channel within the tile's span
+    float v = 0.f;
+    if (n < p.rf_nm && i < p.Cout && cl < p.rf_cin_tile) {
+        if (p.rf_groups > 1) {
+            const int ch = (mt * TS / p.rf_cpg_out) * p.rf_cpg_in + cl;  // input channel
+            const int grp = i / p.rf_cpg_out;
+            if (ch / p.rf_cpg_in == grp) v = w[((int64_t)i * p.rf_cpg_in + (ch - grp * p.rf_cpg_in)) * taps + t];
+        } else {
+            v = w[((int64_t)i * p.Cin + cl) * taps + t];
+        }
+    }
+    dst[d] = v;
 }
 
 // gemm_rf.hip

@@ -46,7 +46,7 @@ int launch_rf_conv(const GemmArgs &a, hipStream_t s) {
     return a.rf_ts == 32 ? launch_rf_tap<32>(a, s) : launch_rf_tap<16>(a, s);
 }
 
-bool rf_resolve(GemmArgs *a, int ts, int epi_flags, int n_cus) {
+bool rf_resolve(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves) {
     (void)n_cus;
     if (a->mode != GM_CONV || (epi_flags & EF_GENERIC)) return false;
     const int nslot = ts == 32 ? 2 : 4;
@@ -54,16 +54,30 @@ bool rf_resolve(GemmArgs *a, int ts, int epi_flags, int n_cus) {
     if (npix * a->WO >= ((int64_t)1 << 32)) return false;             // multiply-high division range
     if ((int64_t)a->Cin * a->H * a->W >= ((int64_t)1 << 30)) return false;   // 32-bit lane offsets
     const int taps = a->KH * a->KW;
-    const int ncq = (a->Cin + nslot - 1) / nslot;
+    // grouped: an m-tile contracts the channels of the groups its rows belong to
+    const int groups = a->rf_groups > 1 ? a->rf_groups : 1;
+    int cin_tile = a->Cin;
+    if (groups > 1) {
+        if (a->Cin % groups || a->Cout % groups) return false;
+        const int cpg_in = a->Cin / groups, cpg_out = a->Cout / groups;
+        if (ts % cpg_out != 0 && cpg_out % ts != 0) return false;
+        cin_tile = (ts > cpg_out ? ts / cpg_out : 1) * cpg_in;
+        a->rf_cpg_in = cpg_in;
+        a->rf_cpg_out = cpg_out;
+    }
+    a->rf_groups = groups;
+    a->rf_cin_tile = cin_tile;
+    const int ncq = (cin_tile + nslot - 1) / nslot;
     int tapk = 0;
-    if (a->Cin % nslot == 0) {
+    if (cin_tile % nslot == 0 && (groups == 1 || a->rf_cpg_in % nslot == 0)) {
         if (taps == 1 && a->ph == 0 && a->pw == 0) tapk = 1;
         else if (a->KH == 3 && a->KW == 3) tapk = 9;
     }
     const int nm = ncq * taps;
     const int nc = (nm + chunk_mfmas(tapk) - 1) / chunk_mfmas(tapk);   // chunks per tile
     int wgk = 1;
-    while (wgk < 16 && wgk < nc) wgk *= 2;
+    if (waves == 1 || waves == 2 || waves == 4 || waves == 8 || waves == 16) wgk = waves;
+    else while (wgk < 16 && wgk < nc) wgk *= 2;
     a->rf_ts = ts;
     a->rf_tapk = tapk;
     a->rf_wgk = wgk;
@@ -86,11 +100,9 @@ int launch_rf_pack(const GemmArgs &a, const float *w, float *dst, void *stream) 
     const int64_t total = (int64_t)(rf_pack_bytes(a) / sizeof(float));
     const unsigned blocks = (unsigned)((total + 255) / 256);
     if (a.rf_ts == 32)
-        hipLaunchKernelGGL((rf_pack_kernel<32>), dim3(blocks), dim3(256), 0, (hipStream_t)stream, w, dst, a.Cout, a.Cin,
-                           a.KH * a.KW, a.rf_nm, a.rf_ngtot, total);
+        hipLaunchKernelGGL((rf_pack_kernel<32>), dim3(blocks), dim3(256), 0, (hipStream_t)stream, w, dst, a, total);
     else
-        hipLaunchKernelGGL((rf_pack_kernel<16>), dim3(blocks), dim3(256), 0, (hipStream_t)stream, w, dst, a.Cout, a.Cin,
-                           a.KH * a.KW, a.rf_nm, a.rf_ngtot, total);
+        hipLaunchKernelGGL((rf_pack_kernel<16>), dim3(blocks), dim3(256), 0, (hipStream_t)stream, w, dst, a, total);
     return (int)hipGetLastError();
 }
 

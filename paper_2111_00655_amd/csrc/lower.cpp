@@ -283,7 +283,8 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
                 c.name = tb ? "bmm_nt" : "bmm_nn";
             } else if (k0 == CLG_OP_CONV2D) {
                 const int G = anchor.attrs.groups > 0 ? anchor.attrs.groups : 1;
-                if (G != 1) return fail(CLG_NO_KERNEL, "implicit-GEMM conv needs groups = 1 (got %d)", G);
+                if (G != 1 && !want_rf)
+                    return fail(CLG_NO_KERNEL, "the LDS-tiled implicit-GEMM conv needs groups = 1 (got %d)", G);
                 a.Nimg = (int)xs.d[0]; a.Cin = (int)xs.d[1]; a.H = (int)xs.d[2]; a.W = (int)xs.d[3];
                 a.Cout = (int)ws.d[0]; a.KH = (int)ws.d[2]; a.KW = (int)ws.d[3];
                 a.sh = anchor.attrs.stride[0]; a.sw = anchor.attrs.stride[1];
@@ -296,8 +297,12 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
                     a.mode = GM_CONV;
                     a.M = a.Cout; a.N = a.Nimg * a.HO * a.WO; a.K = a.Cin * a.KH * a.KW;
                     a.lda = a.K;
+                    a.rf_groups = G;
                     rf = rf_resolve(&a, a.tile == TILE_R32 ? 32 : 16, epi_fast_flags(epi), ctx.n_cus);
                 }
+                if (G != 1 && !rf)
+                    return fail(CLG_NO_KERNEL, "the register-fed conv runs %d groups only with constant weights, a common-form "
+                                "tail and channels per group that divide, or are a multiple of, the tile edge", G);
                 if (rf) {
                     c.pack_bytes = rf_pack_bytes(a);
                 } else if (a.KH == 1 && a.KW == 1 && a.sh == 1 && a.sw == 1 && a.ph == 0 && a.pw == 0) {
@@ -330,6 +335,7 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
                 c.name = "convt_igemm";
             }
             macs = (double)a.batch * a.M * a.N * a.K;
+            if (rf && a.rf_groups > 1) macs /= a.rf_groups;
             if ((double)a.M * a.N > 2.0e9 || a.K < 1) return fail(CLG_NO_KERNEL, "GEMM dimensions out of range");
             c.kind = CALL_GEMM;
             c.bound = 0;

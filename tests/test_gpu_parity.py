@@ -127,6 +127,19 @@ def test_grouped_conv_direct(case):
     run_single_group(d, "direct", pat)
 
 
+@pytest.mark.parametrize("backend", RF)
+@pytest.mark.parametrize("case", [(128, 128, 28, 28, 3, 1, 1, 32), (256, 256, 14, 14, 3, 2, 1, 32), (512, 512, 7, 7, 3, 1, 1, 32),
+                                  (64, 64, 9, 9, 3, 1, 1, 16), (24, 48, 8, 8, 3, 1, 1, 6), (32, 32, 6, 6, 1, 1, 0, 2),
+                                  (64, 128, 7, 7, 5, 1, 2, 2)])
+def test_grouped_conv_register_fed(case, backend):
+    """Grouped convolution on the MFMA kernels: m-tiles that span several groups
+    (4 channels per group), exactly one, or a part of one (64 output channels per group)."""
+    cin, cout, h, w, k, s, p, g = case
+    d, pat = conv_desc((cin, cout, h, w, k, s, p, ("bias_add", "relu")), 6, groups=g, batch=2 if cin == 24 else 1)
+    name, _ = run_single_group(d, backend, pat)
+    assert name.startswith("conv_rf"), name
+
+
 def test_grouped_conv_is_refused_by_igemm():
     d, pat = conv_desc((8, 8, 6, 6, 3, 1, 1, ()), 5, groups=2)
     s = clg.Session(d, [("igemm", pat)], device=0)

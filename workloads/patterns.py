@@ -14,6 +14,9 @@ from __future__ import annotations
 
 W = "*"
 
+# igemm variants whose conv2d patterns carry no groups = 1 constraint
+GROUPED_CONV_BACKENDS = ("igemm_r32", "igemm_r16")
+
 # attribute names a constraint may refer to, in the order of the C enum
 ATTR_NAMES = ("groups", "kernel_h", "kernel_w", "stride_h", "stride_w",
               "pad_h", "pad_w", "transpose_b", "axis")
@@ -89,7 +92,8 @@ def default_registry(variants=("igemm",)):
 
     # --- MFMA implicit GEMM / GEMM variants
     for be in variants:
-        conv = P("conv2d", W, W, groups=(1, 1))
+        # the register-fed kernels also run grouped convolutions
+        conv = P("conv2d", W, W) if be in GROUPED_CONV_BACKENDS else P("conv2d", W, W, groups=(1, 1))
         add(be, _tails(conv, [(), ("bias_add",), ("bias_add", "relu"),
                               ("bias_add", "add"),
                               ("bias_add", "add", "relu")]))
