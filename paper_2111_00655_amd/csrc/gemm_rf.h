@@ -255,6 +255,136 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
     }
 }
 
+// ---- dense: y[m][n] = sum_k x[m][k] * w[n][k] -------------------------------------------------
+// The weights are the A operand (rows i = n, packed), the activations the B
+// operand (columns j = m): lane (slot s, column r) reads 16 bytes of row j0 + r,
+// k = (g * NSLOT + s) * 4 .. + 3, and element q feeds MFMA q of group g; the
+// packed weights follow that k order.  A chunk is four groups (16 MFMAs).
+// Needs K % (4 * NSLOT) == 0, lda % 4 == 0 and 16-byte aligned x.
+// The tile is finished through LDS with rows and columns swapped, so that
+// consecutive threads store consecutive n (the contiguous index of y).
+template <int TS>
+struct RfPark;          // where accumulator register g of lane (s, r) is parked: rows spread over LDS banks
+template <>
+struct RfPark<32> {
+    static constexpr int PERW = 1056;
+    static __device__ __forceinline__ int at(int g, int s, int r) { return g * 66 + s * 33 + r; }
+    static __device__ __forceinline__ int of(int row, int col) { return at(4 * (row / 8) + row % 4, (row / 4) % 2, col); }
+};
+template <>
+struct RfPark<16> {
+    static constexpr int PERW = 320;
+    static __device__ __forceinline__ int at(int g, int s, int r) { return g * 81 + s * 20 + r; }
+    static __device__ __forceinline__ int of(int row, int col) { return at(row % 4, row / 4, col); }
+};
+
+template <int TS, int WGK>
+__global__ __launch_bounds__(WGK *kWave) void dense_rf_kernel(GemmArgs p) {
+    using MF = RfMfma<TS>;
+    using PK = RfPark<TS>;
+    typedef typename MF::acc_t acc_t;
+    constexpr int NSLOT = MF::NSLOT, NACC = MF::NACC;
+    constexpr int NT = WGK * kWave;
+    constexpr int OUTS = TS * TS;
+    constexpr int EPT = (OUTS + NT - 1) / NT;
+    extern __shared__ float red[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int w = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int r = lane % TS, s = lane / TS;
+
+    const int tiles_j = (p.M + TS - 1) / TS;
+    const int tiles_i = (p.N + TS - 1) / TS;
+    const int tile = xcd_remap(blockIdx.x, gridDim.x);
+    const int mt = p.rf_jmajor ? tile % tiles_i : tile / tiles_j;     // weight-row tile
+    const int nt = p.rf_jmajor ? tile / tiles_i : tile % tiles_j;     // activation-row tile
+    const int i0 = mt * TS, j0 = nt * TS;
+    const int ks = blockIdx.z;
+
+    const f32x4 *const Ap = reinterpret_cast<const f32x4 *>(p.B) + (int64_t)mt * p.rf_ngtot * kWave + lane;
+    const f32x4 *const Xp = reinterpret_cast<const f32x4 *>(p.A + (int64_t)min(j0 + r, p.M - 1) * p.lda) + s;
+    const int nch = p.rf_nch;
+    const int c0 = (ks * WGK + w) * nch;
+    const int g_last = p.K / (4 * NSLOT) - 1;
+
+    // outputs this thread finishes: row (n) runs fastest over the threads
+    const int tile_base = p.cs_len ? (i0 / p.cs_len) * (int)p.cs_stride + i0 % p.cs_len : i0;
+    int64_t e_off[EPT];
+    float e_bias[EPT], e_add[EPT];
+    int e_idx[EPT];
+#pragma unroll
+    for (int t = 0; t < EPT; ++t) {
+        const int e = min(tid + t * NT, OUTS - 1);
+        const int row = e % TS, col = e / TS;
+        e_idx[t] = PK::of(row, col);
+        const bool ok = tid + t * NT < OUTS && i0 + row < p.N && j0 + col < p.M;
+        e_off[t] = ok ? (int64_t)(j0 + col) * p.ldc + tile_base + row : -1;
+        e_bias[t] = 0.f;
+        e_add[t] = 0.f;
+        if (p.splitk == 1 && ok) {
+            if (p.ef.flags & EF_BIAS) e_bias[t] = p.ef.bias[i0 + row];
+            if (p.ef.flags & EF_ADD) e_add[t] = p.ef.add[e_off[t]];
+        }
+    }
+
+    acc_t acc;
+#pragma unroll
+    for (int g = 0; g < NACC; ++g) acc[g] = 0.f;
+
+    f32x4 a[2][4], b[2][4];
+#define CLG_RFD_LOAD(set, c)                                                                  \
+    do {                                                                                      \
+        const int ch_ = min((c), nch - 1) + c0;                                               \
+        _Pragma("unroll") for (int u = 0; u < 4; ++u) a[set][u] = Ap[(int64_t)(ch_ * 4 + u) * kWave]; \
+        _Pragma("unroll") for (int u = 0; u < 4; ++u) b[set][u] = Xp[min(ch_ * 4 + u, g_last) * NSLOT]; \
+        __builtin_amdgcn_sched_barrier(0);                                                    \
+    } while (0)
+#define CLG_RFD_MMA(set)                                                                      \
+    do {                                                                                      \
+        _Pragma("unroll") for (int u = 0; u < 16; ++u) acc = MF::mma(a[set][u / 4][u % 4], b[set][u / 4][u % 4], acc); \
+    } while (0)
+    CLG_RFD_LOAD(0, 0);
+    int c = 0;
+    for (; c + 1 < nch; c += 2) {
+        CLG_RFD_LOAD(1, c + 1);
+        CLG_RFD_MMA(0);
+        CLG_RFD_LOAD(0, c + 2);
+        CLG_RFD_MMA(1);
+    }
+    if (c < nch) CLG_RFD_MMA(0);
+#undef CLG_RFD_LOAD
+#undef CLG_RFD_MMA
+
+#pragma unroll
+    for (int g = 0; g < NACC; ++g) red[w * PK::PERW + PK::at(g, s, r)] = acc[g];
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < EPT; ++t) {
+        float v = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < WGK; ++ww) v += red[ww * PK::PERW + e_idx[t]];
+        if (e_off[t] >= 0) {
+            if (p.splitk > 1) p.partial[(int64_t)ks * p.c_numel + e_off[t]] = v;
+            else p.C[e_off[t]] = finish_value(p, v, e_bias[t], e_add[t]);
+        }
+    }
+}
+
+// Dense weights w [N][K] -> [n-tile][group][lane][4] in the k order above.
+template <int TS>
+__global__ void rf_pack_dense_kernel(const float *w, float *dst, GemmArgs p, int64_t total) {
+    constexpr int NSLOT = RfMfma<TS>::NSLOT;
+    const int64_t d = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (d >= total) return;
+    const int q = (int)(d & 3), lane = (int)((d >> 2) & 63);
+    const int64_t gg = d >> 8;
+    const int g = (int)(gg % p.rf_ngtot), mt = (int)(gg / p.rf_ngtot);
+    const int i = mt * TS + lane % TS;
+    const int k = (g * NSLOT + lane / TS) * 4 + q;
+    dst[d] = (i < p.N && k < p.K) ? w[(int64_t)i * p.ldb + k] : 0.f;
+}
+
 // Weight re-packing (once per compiled kernel): w is [Cout][Cin / groups][KH*KW].
 template <int TS>
 __global__ void rf_pack_kernel(const float *w, float *dst, GemmArgs p, int64_t total) {

@@ -37,13 +37,68 @@ int launch_rf_tap(const GemmArgs &a, hipStream_t s) {
     }
 }
 
+template <int TS, int WGK>
+int launch_rfd_one(const GemmArgs &a, hipStream_t s) {
+    const int tiles = ((a.N + TS - 1) / TS) * ((a.M + TS - 1) / TS);
+    const size_t lds = (size_t)WGK * RfPark<TS>::PERW * sizeof(float);
+    if (lds > 64 * 1024) {
+        static bool raised = false;              // more than 64 KB of dynamic LDS has to be allowed per kernel, once
+        if (!raised) {
+            const hipError_t e = hipFuncSetAttribute((const void *)dense_rf_kernel<TS, WGK>,
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return (int)e;
+            raised = true;
+        }
+    }
+    hipLaunchKernelGGL((dense_rf_kernel<TS, WGK>), dim3(tiles, 1, a.splitk), dim3(WGK * kWave), lds, s, a);
+    return (int)hipGetLastError();
+}
+
+template <int TS>
+int launch_rfd_wgk(const GemmArgs &a, hipStream_t s) {
+    switch (a.rf_wgk) {
+    case 1: return launch_rfd_one<TS, 1>(a, s);
+    case 2: return launch_rfd_one<TS, 2>(a, s);
+    case 4: return launch_rfd_one<TS, 4>(a, s);
+    case 8: return launch_rfd_one<TS, 8>(a, s);
+    case 16: return launch_rfd_one<TS, 16>(a, s);
+    default: return (int)hipErrorInvalidValue;
+    }
+}
+
 int chunk_mfmas(int tapk) { return tapk == 1 ? 16 : (tapk == 9 ? 36 : 4); }
 int chunk_groups(int tapk) { return tapk == 1 ? 4 : (tapk == 9 ? 9 : 1); }
 
 }  // namespace
 
 int launch_rf_conv(const GemmArgs &a, hipStream_t s) {
+    if (a.rf_tapk == -1) {
+        if (((uintptr_t)a.A & 15) != 0) return (int)hipErrorInvalidValue;      // activations are read 16 bytes at a time
+        return a.rf_ts == 32 ? launch_rfd_wgk<32>(a, s) : launch_rfd_wgk<16>(a, s);
+    }
     return a.rf_ts == 32 ? launch_rf_tap<32>(a, s) : launch_rf_tap<16>(a, s);
+}
+
+bool rf_resolve_dense(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves) {
+    (void)n_cus;
+    if (a->mode != GM_NT || a->batch != 1 || (epi_flags & EF_GENERIC)) return false;
+    const int nslot = ts == 32 ? 2 : 4;
+    if (a->K % (4 * nslot) || a->lda % 4) return false;
+    if (a->cs_len && a->cs_len % ts) return false;           // a tile's columns must stay within one block of the split
+    const int ng = a->K / (4 * nslot);                       // weight groups (4 MFMAs each)
+    const int nc = (ng + 3) / 4;                             // chunks per tile
+    int wgk = 1;
+    if (waves == 1 || waves == 2 || waves == 4 || waves == 8 || waves == 16) wgk = waves;
+    else while (wgk < 16 && wgk < nc) wgk *= 2;
+    a->rf_ts = ts;
+    a->rf_tapk = -1;
+    a->rf_wgk = wgk;
+    a->rf_nch = (nc + wgk - 1) / wgk;
+    a->splitk = 1;
+    a->rf_ngtot = wgk * a->splitk * a->rf_nch * 4;
+    a->rf_nm = ng * 4;
+    a->rf_jmajor = a->M > a->N ? 1 : 0;
+    return true;
 }
 
 bool rf_resolve(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves) {
@@ -92,13 +147,20 @@ bool rf_resolve(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves) {
 
 size_t rf_pack_bytes(const GemmArgs &a) {
     if (!a.rf_ts) return 0;
-    const size_t tiles_m = (size_t)(a.Cout + a.rf_ts - 1) / a.rf_ts;
+    const size_t tiles_m = (size_t)((a.rf_tapk == -1 ? a.N : a.Cout) + a.rf_ts - 1) / a.rf_ts;
     return tiles_m * (size_t)a.rf_ngtot * 256 * sizeof(float);
 }
 
 int launch_rf_pack(const GemmArgs &a, const float *w, float *dst, void *stream) {
     const int64_t total = (int64_t)(rf_pack_bytes(a) / sizeof(float));
     const unsigned blocks = (unsigned)((total + 255) / 256);
+    if (a.rf_tapk == -1) {
+        if (a.rf_ts == 32)
+            hipLaunchKernelGGL((rf_pack_dense_kernel<32>), dim3(blocks), dim3(256), 0, (hipStream_t)stream, w, dst, a, total);
+        else
+            hipLaunchKernelGGL((rf_pack_dense_kernel<16>), dim3(blocks), dim3(256), 0, (hipStream_t)stream, w, dst, a, total);
+        return (int)hipGetLastError();
+    }
     if (a.rf_ts == 32)
         hipLaunchKernelGGL((rf_pack_kernel<32>), dim3(blocks), dim3(256), 0, (hipStream_t)stream, w, dst, a, total);
     else

@@ -273,6 +273,9 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
                 a.lda = a.K; a.ldb = a.K; a.ldc = a.N;
                 a.bias_on_row = 0;
                 c.name = "gemm_nt";
+                if (want_rf && g.nodes[wb].kind == NODE_CONST)
+                    rf = rf_resolve_dense(&a, a.tile == TILE_R32 ? 32 : 16, epi_fast_flags(epi), ctx.n_cus);
+                if (rf) c.pack_bytes = rf_pack_bytes(a);
             } else if (k0 == CLG_OP_BATCH_MATMUL) {
                 const bool tb = anchor.attrs.transpose_b != 0;
                 a.mode = tb ? GM_NT : GM_NN;
@@ -341,7 +344,9 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
             c.bound = 0;
             if (rf) {
                 c.scratch_bytes = gemm_scratch_bytes(a);
-                c.name = "conv_rf" + std::to_string(a.rf_ts) + "_t" + std::to_string(a.rf_tapk) + "_w" + std::to_string(a.rf_wgk);
+                c.name = (a.rf_tapk == -1 ? "dense_rf" + std::to_string(a.rf_ts)
+                                          : "conv_rf" + std::to_string(a.rf_ts) + "_t" + std::to_string(a.rf_tapk)) +
+                         "_w" + std::to_string(a.rf_wgk);
             } else {
                 if (want_rf) a.tile = TILE_S8;           // what the register-fed kernels do not run goes to the LDS-tiled ones
                 gemm_resolve(&a, ctx.n_cus);

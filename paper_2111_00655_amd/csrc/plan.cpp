@@ -177,7 +177,8 @@ int32_t launch_call(const KernelCall &c, const void *a, const void *b, const voi
         }
         if (c.pack_bytes) {
             if (!packed) return fail(CLG_INVALID_ARG, "%s needs packed weights, none were prepared", c.name.c_str());
-            k.A = (const float *)packed;
+            if (c.gemm.rf_tapk == -1) k.B = (const float *)packed;      // dense: the weights are the second operand
+            else k.A = (const float *)packed;
         }
         k.partial = (float *)scratch;
         k.epi = bind(c.gemm.epi);

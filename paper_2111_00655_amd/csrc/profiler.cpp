@@ -3,9 +3,12 @@
 // subgraph = one kernel, with "compilation + multiple runs on the actual
 // hardware" and results cached in a log.
 //
-// Protocol: warm-up launches, then `batches` timed batches of back-to-back
-// launches between two HIP events; the cost is the smallest batch time per
-// launch, rounded once to integer nanoseconds.  (The smallest, not the median:
+// Protocol: a few launches to size the batches, one untimed batch (the
+// measurer's host work between two candidates leaves the GPU idle long enough
+// for its clocks to drop; a whole batch of launches brings them back up), then
+// `batches` timed batches of back-to-back launches between two HIP events; the
+// cost is the smallest batch time per launch, rounded once to integer
+// nanoseconds.  (The smallest, not the median:
 // on a shared host the enqueueing thread is descheduled for milliseconds at a
 // time, which inflates whole batches by 2-3x; such a stall can only add time,
 // so the undisturbed batch is the fastest one.)  The figure is launch-inclusive
@@ -85,6 +88,7 @@ int32_t time_launches(const Opts &o, F &&launch, int64_t *cost_ns) {
         const double per_us = std::max(ms * 1000.0 / o.warmup, 0.05);
         n = (int)std::min<double>(o.max_launches, std::max(5.0, std::ceil(o.min_batch_us / per_us)));
     }
+    if (rc == CLG_OK) rc = run(n, &ms);          // untimed: clocks and caches reach their steady state
     std::vector<double> per;
     for (int b = 0; b < o.batches && rc == CLG_OK; ++b) {
         rc = run(n, &ms);

@@ -172,10 +172,13 @@ def test_conv2d_transpose_fused(case, backend):
 # ------------------------------------------------------------- dense / bmm
 DENSE_CASES = [(128, 768, 768, ("bias_add",)), (128, 768, 3072, ("bias_add", "gelu")),
                (128, 3072, 768, ("bias_add", "add")), (1, 2048, 1000, ("bias_add",)),
-               (1, 32, 10, ("bias_add",)), (5, 100, 130, ("bias_add", "relu")), (130, 27, 70, ())]
+               (1, 32, 10, ("bias_add",)), (5, 100, 130, ("bias_add", "relu")), (130, 27, 70, ()),
+               (70, 4096, 50, ("bias_add", "relu")), (33, 48, 40, ("bias_add", "tanh"))]
+# which of them the register-fed dense kernel takes (K a multiple of 16); the others fall back to the LDS-tiled kernel
+DENSE_RF = {0, 1, 2, 3, 4, 7, 8}
 
 
-@pytest.mark.parametrize("backend", IGEMM)
+@pytest.mark.parametrize("backend", IGEMM + RF)
 @pytest.mark.parametrize("ci", range(len(DENSE_CASES)))
 def test_dense_fused(ci, backend):
     m, k, n, tail = DENSE_CASES[ci]
@@ -191,7 +194,9 @@ def test_dense_fused(ci, backend):
         else:
             y = d.op(op, [y])
     d.mark_output(y)
-    run_single_group(d, backend, tail_pattern(P("dense", W, W), tail))
+    name, _ = run_single_group(d, backend, tail_pattern(P("dense", W, W), tail))
+    if backend in RF:
+        assert name.startswith("dense_rf") == (ci in DENSE_RF), name
 
 
 def test_dense_bias_relu_reshape():
