@@ -173,7 +173,9 @@ __global__ __launch_bounds__(T::NT) void mm_lean_kernel(GemmArgs p) {
             const int e = tid + t * T::NT;
             const int l = e % kWave, r = e / kWave;
             const int i = i0 + 8 * (r / 4) + 4 * (l / 32) + (r % 4), j = j0 + (l & 31);
-            e_off[t] = (i < p.M && j < p.N) ? (int64_t)batch * p.strideC + (int64_t)i * p.ldc + j : -1;
+            // cs_len: column j lives in block j / cs_len of the output (a result stored split into heads)
+            const int64_t jo = p.cs_len ? (int64_t)(j / p.cs_len) * p.cs_stride + j % p.cs_len : j;
+            e_off[t] = (i < p.M && j < p.N) ? (int64_t)batch * p.strideC + (int64_t)i * p.ldc + jo : -1;
             e_chan[t] = p.bias_on_row ? i : j;
             e_bias[t] = 0.f;
             e_add[t] = 0.f;

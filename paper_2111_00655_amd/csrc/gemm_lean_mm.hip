@@ -35,6 +35,18 @@ int launch_mm_mode(const GemmArgs &a, hipStream_t s) {
 
 }  // namespace
 
+bool lean_mm_shape_ok(const GemmArgs &a, int epi_flags) {
+    if (epi_flags & EF_GENERIC) return false;
+    if (a.lda % 4 || a.ldb % 4 || a.strideA % 4 || a.strideB % 4) return false;
+    if (a.mode == GM_NN && (a.N % 4 != 0 || a.N < 4)) return false;
+    if (a.mode != GM_NT && a.mode != GM_NN) return false;
+    switch (a.tile) {
+    case TILE_S16: case TILE_S8: case TILE_S: return a.K % 64 == 0;
+    case TILE_L: return a.K % 32 == 0;
+    default: return a.K % 64 == 0;
+    }
+}
+
 int launch_lean_mm(const GemmArgs &a, hipStream_t s) {
     if (a.ef.flags & EF_GENERIC) return -1;
     if (a.lda % 4 || a.ldb % 4 || a.strideA % 4 || a.strideB % 4 || !al16(a.A) || !al16(a.B)) return -1;

@@ -177,5 +177,7 @@ size_t rf_pack_bytes(const GemmArgs &a);
 // Packs conv weights w [Cout][Cin][KH][KW] into dst (rf_pack_bytes) for the kernel.
 int launch_rf_pack(const GemmArgs &a, const float *w, float *dst, void *stream);
 int epi_fast_flags(const Epilogue &e);
+// Whether the lean matrix-product kernel takes these sizes (pointer alignment aside).
+bool lean_mm_shape_ok(const GemmArgs &a, int epi_flags);
 
 }  // namespace clg

@@ -379,6 +379,7 @@ int launch_gemm(const GemmArgs &a_in, void *stream) {
     switch (a.mode) {
     case GM_NT:
         err = launch_lean_mm(a, s);
+        if (err == -1 && a.cs_len) return (int)hipErrorInvalidValue;     // only the lean kernel stores column blocks
         if (err == -1) err = launch_fast_mm(a, a_vec && a.ldb % 4 == 0 && a.strideB % 4 == 0 && al16(a.B), s);
         break;
     case GM_NN:

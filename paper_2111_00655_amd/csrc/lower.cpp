@@ -100,6 +100,15 @@ int32_t check_pattern(const Context &ctx, Pattern *p) {
     switch (be.family) {
     case FAM_IGEMM:
         ok = is_contraction(k0) && tail_ok(1, len);
+        // a result stored in a permuted order: dense ... reshape transpose (split into heads),
+        // batch_matmul ... transpose reshape (heads merged); the exact forms are checked per match
+        if (!ok && len >= 3) {
+            const int32_t ka = kind(len - 2), kb = kind(len - 1);
+            const bool split = k0 == CLG_OP_DENSE && ka == CLG_OP_RESHAPE && kb == CLG_OP_TRANSPOSE;
+            const bool merge = k0 == CLG_OP_BATCH_MATMUL && ka == CLG_OP_TRANSPOSE && kb == CLG_OP_RESHAPE;
+            ok = (split || merge) && tail_ok(1, len - 2);
+            for (int t = 1; t < len - 2; ++t) ok = ok && kind(t) != CLG_OP_RESHAPE;
+        }
         break;
     case FAM_DIRECT:
         ok = (k0 == CLG_OP_CONV2D && tail_ok(1, len)) ||
@@ -232,9 +241,16 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
         const Shape &xs = g.nodes[xa].shape, &ws = g.nodes[wb].shape, &ys = anchor.shape;
         use(xa);
         use(wb);
-        for (int t = 1; t < len; ++t) {
+        // trailing reshape + transpose (or transpose + reshape): the result is stored permuted
+        const bool permuted = len >= 3 && is_layout(cv.op(len - 1)) && is_layout(cv.op(len - 2));
+        const int n_tail = permuted ? len - 2 : len;
+        for (int t = 1; t < n_tail; ++t) {
             if ((rc = add_step(cv, t, false, &epi, c.epi_nodes)) != CLG_OK) return rc;
         }
+        if (permuted)
+            for (int s = 0; s < epi.n; ++s)
+                if (epi.s[s].op == EPI_ADD)
+                    return fail(CLG_NO_KERNEL, "a residual add cannot be fused in front of a permuted store");
         for (int s = 0; s < epi.n; ++s) use(c.epi_nodes[s]);
         // where the channel of a bias step lives
         const bool conv_like = (k0 == CLG_OP_CONV2D || k0 == CLG_OP_CONV2D_TRANSPOSE);
@@ -273,6 +289,16 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
                 a.lda = a.K; a.ldb = a.K; a.ldc = a.N;
                 a.bias_on_row = 0;
                 c.name = "gemm_nt";
+                if (permuted) {
+                    // [M, H*D] -> reshape [M, H, D] -> transpose (1, 0, 2) -> [H, M, D]
+                    const Node &rs = g.nodes[cv.node(len - 2)], &tr = g.nodes[cv.node(len - 1)];
+                    if (rs.shape.ndim != 3 || rs.shape.d[0] != a.M || rs.shape.d[1] * rs.shape.d[2] != a.N ||
+                        tr.attrs.dims[0] != 1 || tr.attrs.dims[1] != 0 || tr.attrs.dims[2] != 2)
+                        return fail(CLG_NO_KERNEL, "dense stores only the head split [M, H*D] -> [H, M, D] permuted");
+                    a.ldc = (int)rs.shape.d[2];
+                    a.cs_len = (int)rs.shape.d[2];
+                    a.cs_stride = (int64_t)a.M * rs.shape.d[2];
+                }
                 if (want_rf && g.nodes[wb].kind == NODE_CONST)
                     rf = rf_resolve_dense(&a, a.tile == TILE_R32 ? 32 : 16, epi_fast_flags(epi), ctx.n_cus);
                 if (rf) c.pack_bytes = rf_pack_bytes(a);
@@ -284,6 +310,16 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
                 a.lda = a.K; a.ldb = tb ? a.K : a.N; a.ldc = a.N;
                 a.strideA = (int64_t)a.M * a.K; a.strideB = (int64_t)a.N * a.K; a.strideC = (int64_t)a.M * a.N;
                 c.name = tb ? "bmm_nt" : "bmm_nn";
+                if (permuted) {
+                    // [B, M, N] -> transpose (1, 0, 2) -> [M, B, N] -> reshape [M, B*N]
+                    const Node &tr = g.nodes[cv.node(len - 2)], &rs = g.nodes[cv.node(len - 1)];
+                    if (tr.attrs.dims[0] != 1 || tr.attrs.dims[1] != 0 || tr.attrs.dims[2] != 2 || rs.shape.ndim != 2 ||
+                        rs.shape.d[0] != a.M || rs.shape.d[1] != (int64_t)a.batch * a.N)
+                        return fail(CLG_NO_KERNEL, "batch_matmul stores only the head merge [B, M, N] -> [M, B*N] permuted");
+                    a.ldc = a.batch * a.N;
+                    a.strideC = a.N;
+                    c.name += "_merge";
+                }
             } else if (k0 == CLG_OP_CONV2D) {
                 const int G = anchor.attrs.groups > 0 ? anchor.attrs.groups : 1;
                 if (G != 1 && !want_rf)
@@ -346,11 +382,19 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
                 c.scratch_bytes = gemm_scratch_bytes(a);
                 c.name = (a.rf_tapk == -1 ? "dense_rf" + std::to_string(a.rf_ts)
                                           : "conv_rf" + std::to_string(a.rf_ts) + "_t" + std::to_string(a.rf_tapk)) +
-                         "_w" + std::to_string(a.rf_wgk);
+                         "_w" + std::to_string(a.rf_wgk) + (a.cs_len ? "_split" : "");
             } else {
                 if (want_rf) a.tile = TILE_S8;           // what the register-fed kernels do not run goes to the LDS-tiled ones
                 gemm_resolve(&a, ctx.n_cus);
                 if (be.no_split) a.splitk = 1;
+                if (a.cs_len) {
+                    // only the lean kernel's K-wave tiles place columns block by block, and the
+                    // split-K reduction derives a bias channel from the plain offset
+                    a.splitk = 1;
+                    if (!lean_mm_shape_ok(a, epi_fast_flags(epi)) || a.tile == TILE_M || a.tile == TILE_L)
+                        return fail(CLG_NO_KERNEL, "this tile does not store a head-split result");
+                    c.name += "_split";
+                }
                 c.scratch_bytes = gemm_scratch_bytes(a);
                 static const char *tn[] = {"auto", "s", "m", "l", "s8", "s16"};
                 c.name += std::string("_") + tn[a.tile] + (a.splitk > 1 ? "_k" + std::to_string(a.splitk) : "");

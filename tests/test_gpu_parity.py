@@ -199,6 +199,51 @@ def test_dense_fused(ci, backend):
         assert name.startswith("dense_rf") == (ci in DENSE_RF), name
 
 
+@pytest.mark.parametrize("backend", ("igemm", "igemm_s", "igemm_s8", "igemm_s16") + RF)
+@pytest.mark.parametrize("case", [(128, 768, 12, 64), (70, 64, 3, 32), (5, 128, 2, 16)])
+def test_dense_stored_split_into_heads(case, backend):
+    """transpose(reshape(bias_add(dense))) as one kernel: [M, H*D] is stored as [H, M, D]."""
+    m, k, h, dd = case
+    r = rng_for(14, m, k, h)
+    d = wl.GraphDesc("dense_split")
+    y = d.op("dense", [d.input(f32(r, m, k)), d.const(f32(r, h * dd, k, scale=k ** -0.5))])
+    y = d.op("bias_add", [y, d.const(f32(r, h * dd))], axis=-1)
+    y = d.op("reshape", [y], dims=(m, h, dd))
+    y = d.op("transpose", [y], dims=(1, 0, 2))
+    d.mark_output(y)
+    name, _ = run_single_group(d, backend, P("transpose", P("reshape", P("bias_add", P("dense", W, W), W))))
+    assert "_split" in name, name
+
+
+@pytest.mark.parametrize("backend", IGEMM)
+@pytest.mark.parametrize("case", [(12, 128, 128, 64), (3, 70, 33, 20), (2, 33, 64, 8)])
+def test_batch_matmul_stored_with_heads_merged(case, backend):
+    """reshape(transpose(batch_matmul)) as one kernel: [B, M, N] is stored as [M, B*N]."""
+    b, m, k, n = case
+    r = rng_for(15, b, m, k, n)
+    d = wl.GraphDesc("bmm_merge")
+    y = d.op("batch_matmul", [d.input(f32(r, b, m, k)), d.input(f32(r, b, k, n))], transpose_b=False)
+    y = d.op("transpose", [y], dims=(1, 0, 2))
+    y = d.op("reshape", [y], dims=(m, b * n))
+    d.mark_output(y)
+    name, _ = run_single_group(d, backend, P("reshape", P("transpose", P("batch_matmul", W, W))))
+    assert name.endswith("_merge") or "_merge_" in name, name
+
+
+def test_permuted_store_refuses_other_layouts():
+    r = rng_for(16)
+    d = wl.GraphDesc("dense_bad_split")
+    y = d.op("dense", [d.input(f32(r, 8, 64)), d.const(f32(r, 64, 64))])
+    y = d.op("bias_add", [y, d.const(f32(r, 64))], axis=-1)
+    y = d.op("reshape", [y], dims=(8, 4, 16))
+    y = d.op("transpose", [y], dims=(0, 2, 1))
+    d.mark_output(y)
+    s = clg.Session(d, [("igemm_s", P("transpose", P("reshape", P("bias_add", P("dense", W, W), W))))], device=0)
+    assert len(s.match()) == 1
+    assert B.clg_profile_match(s.ctx, s.graph, 0) >= B.COST_INF
+    s.close()
+
+
 def test_dense_bias_relu_reshape():
     r = rng_for(8)
     d = wl.GraphDesc("dense_rs")

@@ -103,6 +103,9 @@ def default_registry(variants=("igemm",)):
                                ("bias_add", "relu", "reshape")]))
         add(be, [P("batch_matmul", W, W),
                  P("mul_scalar", P("batch_matmul", W, W))])
+        # results stored permuted: projection split into heads, heads merged
+        add(be, [P("transpose", P("reshape", P("bias_add", dense, W))),
+                 P("reshape", P("transpose", P("batch_matmul", W, W)))])
         convt = P("conv2d_transpose", W, W)
         add(be, _tails(convt, [(), ("bias_add",), ("bias_add", "relu"),
                                ("bias_add", "tanh")]))
