@@ -123,6 +123,80 @@ __global__ __launch_bounds__(256) void rowwise_kernel(RowwiseArgs a) {
     }
 }
 
+// One workgroup (four waves) per row: for few, long rows (layer norm over 128 x 768,
+// the 1 x 1000 softmax of a classifier) a wave per row leaves most of the chip
+// idle and strings ITEMS dependent loads and exponentials behind each other.
+// Each reduction is a wave reduction plus four partial values through LDS, added
+// in wave order.  gamma / beta are fetched before the reductions.
+template <int ITEMS>
+__global__ __launch_bounds__(256) void rowwise_block_kernel(RowwiseArgs a) {
+    __shared__ float part[2][4];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int row = blockIdx.x;
+    const float *xr = a.x + (int64_t)row * a.len;
+    float *yr = a.y + (int64_t)row * a.len;
+    float v[ITEMS], ga[ITEMS], be[ITEMS];
+#pragma unroll
+    for (int t = 0; t < ITEMS; ++t) {
+        const int c = tid + 256 * t;
+        v[t] = 0.f;
+        ga[t] = 0.f;
+        be[t] = 0.f;
+        if (c < a.len) {
+            v[t] = apply_steps(a.pro, xr[c], (int64_t)row * a.len + c, c);
+            if (a.mode == 1) {
+                ga[t] = a.gamma[c];
+                be[t] = a.beta[c];
+            }
+        }
+    }
+    auto block_sum = [&](float x, int slot) {
+        x = wave_sum(x);
+        if (lane == 0) part[slot][wave] = x;
+        __syncthreads();
+        return (part[slot][0] + part[slot][1]) + (part[slot][2] + part[slot][3]);
+    };
+    if (a.mode == 0) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < ITEMS; ++t)
+            if (tid + 256 * t < a.len) mx = fmaxf(mx, v[t]);
+        mx = wave_max(mx);
+        if (lane == 0) part[0][wave] = mx;
+        __syncthreads();
+        mx = fmaxf(fmaxf(part[0][0], part[0][1]), fmaxf(part[0][2], part[0][3]));
+        float sum = 0.f;
+#pragma unroll
+        for (int t = 0; t < ITEMS; ++t) {
+            v[t] = (tid + 256 * t < a.len) ? expf(v[t] - mx) : 0.f;
+            sum += v[t];
+        }
+        const float inv = 1.0f / block_sum(sum, 1);
+#pragma unroll
+        for (int t = 0; t < ITEMS; ++t)
+            if (tid + 256 * t < a.len) yr[tid + 256 * t] = v[t] * inv;
+    } else {
+        float sum = 0.f;
+#pragma unroll
+        for (int t = 0; t < ITEMS; ++t) sum += v[t];          // padding lanes hold 0
+        const float mean = block_sum(sum, 0) / (float)a.len;
+        float sq = 0.f;
+#pragma unroll
+        for (int t = 0; t < ITEMS; ++t) {
+            const float d = (tid + 256 * t < a.len) ? v[t] - mean : 0.f;
+            v[t] = d;
+            sq += d * d;
+        }
+        const float var = block_sum(sq, 1) / (float)a.len;
+        const float inv = 1.0f / sqrtf(var + a.eps);
+#pragma unroll
+        for (int t = 0; t < ITEMS; ++t) {
+            const int c = tid + 256 * t;
+            if (c < a.len) yr[c] = v[t] * inv * ga[t] + be[t];
+        }
+    }
+}
+
 // Rows longer than 64 * 32: same arithmetic, the row is re-read per pass.
 __global__ __launch_bounds__(256) void rowwise_long_kernel(RowwiseArgs a) {
     const int lane = threadIdx.x & (kWave - 1);
@@ -159,6 +233,13 @@ int launch_rowwise(const RowwiseArgs &a, void *stream) {
     const dim3 grid((a.rows + rows_per_block - 1) / rows_per_block);
     const int items = (a.len + kWave - 1) / kWave;
     hipStream_t s = (hipStream_t)stream;
+    if (a.len > 256 && a.len <= 2048 && a.rows <= 1024) {          // few long rows: a workgroup per row
+        const int bi = (a.len + 255) / 256;
+        if (bi <= 2) hipLaunchKernelGGL(rowwise_block_kernel<2>, dim3(a.rows), dim3(256), 0, s, a);
+        else if (bi <= 4) hipLaunchKernelGGL(rowwise_block_kernel<4>, dim3(a.rows), dim3(256), 0, s, a);
+        else hipLaunchKernelGGL(rowwise_block_kernel<8>, dim3(a.rows), dim3(256), 0, s, a);
+        return (int)hipGetLastError();
+    }
     if (items <= 1) hipLaunchKernelGGL(rowwise_kernel<1>, grid, dim3(block), 0, s, a);
     else if (items <= 2) hipLaunchKernelGGL(rowwise_kernel<2>, grid, dim3(block), 0, s, a);
     else if (items <= 4) hipLaunchKernelGGL(rowwise_kernel<4>, grid, dim3(block), 0, s, a);

@@ -274,7 +274,7 @@ def test_batch_matmul(case, backend):
 
 
 # --------------------------------------------------------------- row-wise
-@pytest.mark.parametrize("shape", [(12, 128, 128), (1, 1000), (1, 10), (3, 7, 65), (2, 2100), (5, 300)])
+@pytest.mark.parametrize("shape", [(12, 128, 128), (1, 1000), (1, 10), (3, 7, 65), (2, 2100), (5, 300), (2, 2048), (3, 700)])
 def test_softmax(shape):
     r = rng_for(7, *shape)
     d = wl.GraphDesc("softmax_case")
@@ -286,7 +286,7 @@ def test_softmax(shape):
     run_single_group(d, "rowwise", P("softmax", P("mul_scalar", W)), tol=1e-5)
 
 
-@pytest.mark.parametrize("shape", [(128, 768), (4, 48), (3, 2100), (1, 64), (7, 65)])
+@pytest.mark.parametrize("shape", [(128, 768), (4, 48), (3, 2100), (1, 64), (7, 65), (2, 2048), (9, 700), (5, 257)])
 def test_layer_norm(shape):
     r = rng_for(9, *shape)
     L = shape[-1]
