@@ -66,6 +66,21 @@ int launch_rfd_wgk(const GemmArgs &a, hipStream_t s) {
     }
 }
 
+// K-waves per workgroup: enough to give every wave one chunk.  With `cap_grid`
+// (dense, and the per-MFMA tap path, whose chunks are short) no more than keeps
+// the whole grid at about four waves per SIMD (1024 SIMDs): a tile whose K is
+// cut into many short pieces pays the fixed cost of a wave once per piece.  The
+// 1x1 / 3x3 convolution paths measured best with one chunk per wave throughout.
+int pick_waves(int chunks, int64_t tiles, int forced, bool cap_grid) {
+    if (forced == 1 || forced == 2 || forced == 4 || forced == 8 || forced == 16) return forced;
+    int wgk = 1;
+    while (wgk < 16 && wgk < chunks) wgk *= 2;
+    if (!cap_grid) return wgk;
+    int cap = 1;
+    while (cap < 16 && (int64_t)cap * 2 * tiles <= 4096) cap *= 2;
+    return wgk < cap ? wgk : cap;
+}
+
 int chunk_mfmas(int tapk) { return tapk == 1 ? 16 : (tapk == 9 ? 36 : 4); }
 int chunk_groups(int tapk) { return tapk == 1 ? 4 : (tapk == 9 ? 9 : 1); }
 
@@ -87,9 +102,7 @@ bool rf_resolve_dense(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves) 
     if (a->cs_len && a->cs_len % ts) return false;           // a tile's columns must stay within one block of the split
     const int ng = a->K / (4 * nslot);                       // weight groups (4 MFMAs each)
     const int nc = (ng + 3) / 4;                             // chunks per tile
-    int wgk = 1;
-    if (waves == 1 || waves == 2 || waves == 4 || waves == 8 || waves == 16) wgk = waves;
-    else while (wgk < 16 && wgk < nc) wgk *= 2;
+    const int wgk = pick_waves(nc, (int64_t)((a->M + ts - 1) / ts) * ((a->N + ts - 1) / ts), waves, true);
     a->rf_ts = ts;
     a->rf_tapk = -1;
     a->rf_wgk = wgk;
@@ -130,9 +143,7 @@ bool rf_resolve(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves) {
     }
     const int nm = ncq * taps;
     const int nc = (nm + chunk_mfmas(tapk) - 1) / chunk_mfmas(tapk);   // chunks per tile
-    int wgk = 1;
-    if (waves == 1 || waves == 2 || waves == 4 || waves == 8 || waves == 16) wgk = waves;
-    else while (wgk < 16 && wgk < nc) wgk *= 2;
+    const int wgk = pick_waves(nc, (int64_t)((a->Cout + ts - 1) / ts) * ((npix + ts - 1) / ts) * a->Nimg, waves, tapk == 0);
     a->rf_ts = ts;
     a->rf_tapk = tapk;
     a->rf_wgk = wgk;
