@@ -67,16 +67,20 @@ struct RfMfma<16> {
     static __device__ __forceinline__ int row(int g, int s) { return 4 * s + g; }
 };
 
-// TAPK: 1 = 1x1 filter without padding, 9 = 3x3 filter, 0 = any filter (tap
-// geometry computed per MFMA).  TAPK 1 and 9 need Cin % NSLOT == 0.
+// TAPK: 1 = 1x1 filter without padding, 9 = 3x3 filter, 4 = 2x2 filter, 0 = any
+// filter (tap geometry computed per MFMA).  TAPK 1, 9 and 4 need Cin % NSLOT == 0.
 // Work units per wave ("chunks"): 16 MFMAs (TAPK 1), 36 MFMAs = all taps of
-// four channel groups (TAPK 9), 4 MFMAs (TAPK 0).
-template <int TAPK>
-struct RfChunk {
-    static constexpr int GROUPS = TAPK == 1 ? 4 : (TAPK == 9 ? 9 : 1);
-};
+// four channel groups (TAPK 9), 16 MFMAs likewise (TAPK 4), 4 MFMAs (TAPK 0).
+//
+// Transposed convolution (DCGAN, paper Sec. 5.1) with stride s: the output pixels
+// with (oh % s, ow % s) = (a, b) form a "phase" that only meets the taps
+// kh = (a + pad) % s + s*u.  Written with u' = KH/s - 1 - u, a phase is an
+// ordinary stride-1 convolution over the (HO/s x WO/s) grid of its pixels, with
+// KH/s x KW/s taps and padding KH/s - 1 - (a + pad) / s; one grid.z slice per
+// phase, each with its own packed (tap-flipped) weights.  k4 s2 p1 gives four
+// 2x2 phases.
 
-template <int TS, int TAPK, int WGK>
+template <int TS, int TAPK, int WGK, bool CONVT>
 __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
     using MF = RfMfma<TS>;
     typedef typename MF::acc_t acc_t;
@@ -91,7 +95,23 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
     const int w = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int r = lane % TS, s = lane / TS;
 
-    const int npix = p.HO * p.WO;
+    // effective geometry: the convolution itself, or one phase of a transposed convolution
+    int KHe = p.KH, KWe = p.KW, she = p.sh, swe = p.sw, phe = p.ph, pwe = p.pw, HOe = p.HO, WOe = p.WO;
+    int a_h = 0, a_w = 0, phase = 0, ks = blockIdx.z;
+    if constexpr (CONVT) {
+        phase = blockIdx.z;
+        ks = 0;
+        a_h = phase / p.sw;
+        a_w = phase - a_h * p.sw;
+        KHe = p.KH / p.sh;
+        KWe = p.KW / p.sw;
+        phe = KHe - 1 - (a_h + p.ph) / p.sh;
+        pwe = KWe - 1 - (a_w + p.pw) / p.sw;
+        she = swe = 1;
+        HOe = p.HO / p.sh;
+        WOe = p.WO / p.sw;
+    }
+    const int npix = HOe * WOe;
     const int tiles_n = (npix + TS - 1) / TS;
     const int tiles_m = (p.Cout + TS - 1) / TS;
     const int tile = xcd_remap(blockIdx.x, gridDim.x);
@@ -100,17 +120,16 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
     const int nt = p.rf_jmajor ? tile / tiles_m : tile % tiles_n;
     const int i0 = mt * TS, j0 = nt * TS;
     const int img = blockIdx.y;
-    const int ks = blockIdx.z;
 
     const int jp = min(j0 + r, npix - 1);
     const int oh = (int)(((uint64_t)(uint32_t)jp * p.rf_wo_magic) >> 32);
-    const int ow = jp - oh * p.WO;
-    const int ih0 = oh * p.sh - p.ph, iw0 = ow * p.sw - p.pw;
+    const int ow = jp - oh * WOe;
+    const int ih0 = oh * she - phe, iw0 = ow * swe - pwe;
     const int HW = p.H * p.W;
     const int cbase = p.rf_groups > 1 ? (i0 / p.rf_cpg_out) * p.rf_cpg_in : 0;
     const int cin = min(p.rf_cin_tile, p.Cin - cbase);       // input channels this m-tile contracts
     const float *const x_img = p.B + ((int64_t)img * p.Cin + cbase) * HW;
-    const f32x4 *const Ap = reinterpret_cast<const f32x4 *>(p.A) + (int64_t)mt * p.rf_ngtot * kWave + lane;
+    const f32x4 *const Ap = reinterpret_cast<const f32x4 *>(p.A) + ((int64_t)phase * tiles_m + mt) * p.rf_ngtot * kWave + lane;
     const int nch = p.rf_nch;                                // chunks per wave
     const int c0 = (ks * WGK + w) * nch;                     // this wave's first chunk
     const int cq_last = (cin + NSLOT - 1) / NSLOT - 1;
@@ -124,6 +143,10 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
         const int l = e % kWave, g = e / kWave;
         const int i = i0 + MF::row(g, l / TS), j = j0 + l % TS;
         e_off[t] = (e < PER_WAVE && i < p.Cout && j < npix) ? ((int64_t)img * p.Cout + i) * npix + j : -1;
+        if (CONVT && e_off[t] >= 0) {                 // the phase's pixel (oh', ow') is output pixel (a_h + s oh', a_w + s ow')
+            const int ohh = (int)(((uint64_t)(uint32_t)j * p.rf_wo_magic) >> 32), oww = j - ohh * WOe;
+            e_off[t] = (((int64_t)img * p.Cout + i) * p.HO + a_h + p.sh * ohh) * p.WO + a_w + p.sw * oww;
+        }
         e_bias[t] = 0.f;
         e_add[t] = 0.f;
         if (p.splitk == 1 && e_off[t] >= 0) {
@@ -200,13 +223,53 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
 #pragma unroll
             for (int u = 0; u < 36; ++u) acc = MF::mma(a[u / 4][u % 4], b[u], acc);
         }
+    } else if constexpr (TAPK == 4) {
+        // ---- 2x2 (a phase of a k4 s2 transposed convolution): like 3x3, a chunk is four
+        // channel groups x four taps
+        int voff[4];
+        bool ok[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int ih = ih0 + t / 2, iw = iw0 + t % 2;
+            ok[t] = ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
+            voff[t] = s * HW + (ok[t] ? ih * p.W + iw : 0);
+        }
+        const int64_t cq_step = (int64_t)NSLOT * HW;
+        f32x4 a[2][4];
+        float b[2][16];
+#define CLG_RF_LOAD(set, c)                                                                   \
+    do {                                                                                      \
+        const int ch_ = min((c), nch - 1) + c0;                                               \
+        _Pragma("unroll") for (int u = 0; u < 4; ++u) a[set][u] = Ap[(int64_t)(ch_ * 4 + u) * kWave]; \
+        _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                       \
+            const float *xc_ = x_img + min(ch_ * 4 + q, cq_last) * cq_step;                   \
+            _Pragma("unroll") for (int t = 0; t < 4; ++t) b[set][q * 4 + t] = xc_[voff[t]];   \
+        }                                                                                     \
+        __builtin_amdgcn_sched_barrier(0);                                                    \
+    } while (0)
+#define CLG_RF_MMA(set)                                                                       \
+    do {                                                                                      \
+        _Pragma("unroll") for (int u = 0; u < 16; ++u)                                        \
+            acc = MF::mma(a[set][u / 4][u % 4], ok[u % 4] ? b[set][u] : 0.f, acc);            \
+    } while (0)
+        CLG_RF_LOAD(0, 0);
+        int c = 0;
+        for (; c + 1 < nch; c += 2) {
+            CLG_RF_LOAD(1, c + 1);
+            CLG_RF_MMA(0);
+            CLG_RF_LOAD(0, c + 2);
+            CLG_RF_MMA(1);
+        }
+        if (c < nch) CLG_RF_MMA(0);
+#undef CLG_RF_LOAD
+#undef CLG_RF_MMA
     } else {
         // ---- any filter: tap geometry per MFMA; (cq, kh, kw) advance with n
-        const int taps = p.KH * p.KW;
+        const int taps = KHe * KWe;
         const int nm = p.rf_nm;
         int n = c0 * 4;
         int cq = n / taps, t = n - cq * taps;
-        int kh = t / p.KW, kw = t - kh * p.KW;
+        int kh = t / KWe, kw = t - kh * KWe;
         for (int c = 0; c < nch; ++c) {
             const f32x4 a = Ap[(int64_t)(c0 + c) * kWave];
             float b[4];
@@ -218,9 +281,9 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
                 const float v = x_img[ok ? (int64_t)ch * HW + ih * p.W + iw : 0];
                 b[q] = ok ? v : 0.f;
                 ++n;
-                if (++kw == p.KW) {
+                if (++kw == KWe) {
                     kw = 0;
-                    if (++kh == p.KH) {
+                    if (++kh == KHe) {
                         kh = 0;
                         ++cq;
                     }
@@ -391,16 +454,25 @@ __global__ void rf_pack_kernel(const float *w, float *dst, GemmArgs p, int64_t t
     constexpr int NSLOT = RfMfma<TS>::NSLOT;
     const int64_t d = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (d >= total) return;
-    const int taps = p.KH * p.KW;
+    const int KHe = p.rf_convt ? p.KH / p.sh : p.KH, KWe = p.rf_convt ? p.KW / p.sw : p.KW;
+    const int taps = KHe * KWe;
+    const int tiles_m = (p.Cout + TS - 1) / TS;
     const int q = (int)(d & 3), lane = (int)((d >> 2) & 63);
     const int64_t gg = d >> 8;
-    const int g = (int)(gg % p.rf_ngtot), mt = (int)(gg / p.rf_ngtot);
+    const int g = (int)(gg % p.rf_ngtot);
+    const int mt = (int)((gg / p.rf_ngtot) % tiles_m), phase = (int)(gg / p.rf_ngtot / tiles_m);
     const int n = 4 * g + q;
     const int cq = n / taps, t = n - cq * taps;
     const int i = mt * TS + lane % TS, cl = cq * NSLOT + lane / TS;      // output channel, channel within the tile's span
     float v = 0.f;
     if (n < p.rf_nm && i < p.Cout && cl < p.rf_cin_tile) {
-        if (p.rf_groups > 1) {
+        if (p.rf_convt) {
+            // w is [Cin][Cout][KH][KW]; tap u' of the phase is kernel tap r + s * (KH/s - 1 - u')
+            const int a_h = phase / p.sw, a_w = phase - a_h * p.sw;
+            const int uh = t / KWe, uw = t - uh * KWe;
+            const int kh = (a_h + p.ph) % p.sh + p.sh * (KHe - 1 - uh), kw = (a_w + p.pw) % p.sw + p.sw * (KWe - 1 - uw);
+            v = w[(((int64_t)cl * p.Cout + i) * p.KH + kh) * p.KW + kw];
+        } else if (p.rf_groups > 1) {
             const int ch = (mt * TS / p.rf_cpg_out) * p.rf_cpg_in + cl;  // input channel
             const int grp = i / p.rf_cpg_out;
             if (ch / p.rf_cpg_in == grp) v = w[((int64_t)i * p.rf_cpg_in + (ch - grp * p.rf_cpg_in)) * taps + t];

@@ -7,13 +7,24 @@ namespace clg {
 
 namespace {
 
-template <int TS, int TAPK, int WGK>
-int launch_rf_one(const GemmArgs &a, hipStream_t s) {
-    const int npix = a.HO * a.WO;
+template <int TS, int TAPK, int WGK, bool CONVT>
+int launch_rf_one_t(const GemmArgs &a, hipStream_t s) {
+    const int npix = a.rf_convt ? (a.HO / a.sh) * (a.WO / a.sw) : a.HO * a.WO;
     const int tiles = ((a.Cout + TS - 1) / TS) * ((npix + TS - 1) / TS);
     const size_t lds = WGK > 1 ? (size_t)WGK * RfMfma<TS>::NACC * kWave * sizeof(float) : 0;
-    hipLaunchKernelGGL((conv_rf_kernel<TS, TAPK, WGK>), dim3(tiles, a.Nimg, a.splitk), dim3(WGK * kWave), lds, s, a);
+    const int gz = a.rf_convt ? a.sh * a.sw : a.splitk;      // sub-pixel phases, or K splits
+    hipLaunchKernelGGL((conv_rf_kernel<TS, TAPK, WGK, CONVT>), dim3(tiles, a.Nimg, gz), dim3(WGK * kWave), lds, s, a);
     return (int)hipGetLastError();
+}
+
+// transposed convolutions run the 2x2 and the any-filter paths only
+template <int TS, int TAPK, int WGK>
+int launch_rf_one(const GemmArgs &a, hipStream_t s) {
+    if constexpr (TAPK == 4 || TAPK == 0) {
+        if (a.rf_convt) return launch_rf_one_t<TS, TAPK, WGK, true>(a, s);
+    }
+    if (a.rf_convt) return (int)hipErrorInvalidValue;
+    return launch_rf_one_t<TS, TAPK, WGK, false>(a, s);
 }
 
 template <int TS, int TAPK>
@@ -33,6 +44,7 @@ int launch_rf_tap(const GemmArgs &a, hipStream_t s) {
     switch (a.rf_tapk) {
     case 1: return launch_rf_wgk<TS, 1>(a, s);
     case 9: return launch_rf_wgk<TS, 9>(a, s);
+    case 4: return launch_rf_wgk<TS, 4>(a, s);
     default: return launch_rf_wgk<TS, 0>(a, s);
     }
 }
@@ -81,8 +93,8 @@ int pick_waves(int chunks, int64_t tiles, int forced, bool cap_grid) {
     return wgk < cap ? wgk : cap;
 }
 
-int chunk_mfmas(int tapk) { return tapk == 1 ? 16 : (tapk == 9 ? 36 : 4); }
-int chunk_groups(int tapk) { return tapk == 1 ? 4 : (tapk == 9 ? 9 : 1); }
+int chunk_mfmas(int tapk) { return tapk == 1 || tapk == 4 ? 16 : (tapk == 9 ? 36 : 4); }
+int chunk_groups(int tapk) { return tapk == 1 || tapk == 4 ? 4 : (tapk == 9 ? 9 : 1); }
 
 }  // namespace
 
@@ -156,10 +168,46 @@ bool rf_resolve(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves) {
     return true;
 }
 
+bool rf_resolve_convt(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves) {
+    (void)n_cus;
+    if (a->mode != GM_CONVT || (epi_flags & EF_GENERIC)) return false;
+    if (a->sh < 1 || a->sw < 1 || a->KH % a->sh || a->KW % a->sw || a->HO % a->sh || a->WO % a->sw) return false;
+    const int khe = a->KH / a->sh, kwe = a->KW / a->sw, hoe = a->HO / a->sh, woe = a->WO / a->sw;
+    // every phase's padding must be non-negative (it is for pad <= kernel / stride - 1 ... checked directly)
+    for (int ph = 0; ph < a->sh; ++ph)
+        if (khe - 1 - (ph + a->ph) / a->sh < 0) return false;
+    for (int pw = 0; pw < a->sw; ++pw)
+        if (kwe - 1 - (pw + a->pw) / a->sw < 0) return false;
+    const int nslot = ts == 32 ? 2 : 4;
+    const int64_t npix = (int64_t)hoe * woe;
+    if (npix * woe >= ((int64_t)1 << 32)) return false;
+    if ((int64_t)a->Cin * a->H * a->W >= ((int64_t)1 << 30)) return false;
+    const int taps = khe * kwe;
+    const int ncq = (a->Cin + nslot - 1) / nslot;
+    const int tapk = (khe == 2 && kwe == 2 && a->Cin % nslot == 0) ? 4 : 0;
+    const int nm = ncq * taps;
+    const int nc = (nm + chunk_mfmas(tapk) - 1) / chunk_mfmas(tapk);
+    const int64_t tiles = (int64_t)((a->Cout + ts - 1) / ts) * ((npix + ts - 1) / ts) * a->Nimg * a->sh * a->sw;
+    const int wgk = pick_waves(nc, tiles, waves, true);
+    a->rf_ts = ts;
+    a->rf_tapk = tapk;
+    a->rf_wgk = wgk;
+    a->rf_nch = (nc + wgk - 1) / wgk;
+    a->splitk = 1;
+    a->rf_ngtot = wgk * a->rf_nch * chunk_groups(tapk);
+    a->rf_nm = nm;
+    a->rf_groups = 1;
+    a->rf_cin_tile = a->Cin;
+    a->rf_convt = 1;
+    a->rf_jmajor = (int64_t)a->Cin * a->H * a->W > (int64_t)a->Cout * a->Cin * taps ? 1 : 0;
+    a->rf_wo_magic = (((uint64_t)1 << 32) / (uint64_t)woe) + 1;
+    return true;
+}
+
 size_t rf_pack_bytes(const GemmArgs &a) {
     if (!a.rf_ts) return 0;
     const size_t tiles_m = (size_t)((a.rf_tapk == -1 ? a.N : a.Cout) + a.rf_ts - 1) / a.rf_ts;
-    return tiles_m * (size_t)a.rf_ngtot * 256 * sizeof(float);
+    return (a.rf_convt ? (size_t)a.sh * a.sw : 1) * tiles_m * (size_t)a.rf_ngtot * 256 * sizeof(float);
 }
 
 int launch_rf_pack(const GemmArgs &a, const float *w, float *dst, void *stream) {

@@ -86,10 +86,11 @@ struct GemmArgs {
     int32_t bias_on_row;                   // 1: channel = i (conv), 0: channel = j (dense)
     int32_t patch_sz;                      // 3x3 kernel: floats per channel of the LDS input patch
     // register-fed convolution (gemm_rf.h); rf_ts = 0: not used.  A then points at the packed weights.
-    int32_t rf_ts, rf_tapk, rf_wgk;        // tile edge 32|16, tap mode 1|9|0 (-1: dense), K-waves per workgroup
+    int32_t rf_ts, rf_tapk, rf_wgk;        // tile edge 32|16, tap mode 1|9|4|0 (-1: dense), K-waves per workgroup
     int32_t rf_nch, rf_ngtot, rf_nm;       // chunks per wave, packed groups per m-tile, MFMAs per tile
     int32_t rf_jmajor, rf_groups;          // rf_groups > 1: grouped convolution (Cin, Cout are totals)
-    int32_t rf_cin_tile, rf_cpg_in, rf_cpg_out, rf_pad_;   // channels contracted per m-tile; channels per group
+    int32_t rf_cin_tile, rf_cpg_in, rf_cpg_out;            // channels contracted per m-tile; channels per group
+    int32_t rf_convt;                      // 1: transposed convolution, one sub-pixel phase per grid.z slice
     uint64_t rf_wo_magic;                  // floor(2^32 / WO) + 1: pixel / WO by multiply-high
     // dense only: output column n goes to (n / cs_len) * cs_stride + n % cs_len within its row block
     // (cs_len = 0: plain row-major).  This is how reshape + transpose of the result is fused (head split).
@@ -173,6 +174,8 @@ size_t gemm_scratch_bytes(const GemmArgs &a);
 bool rf_resolve(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves = 0);
 // The same for GM_NT dense (A = activations [M,K], B = weights [N,K], no batch).
 bool rf_resolve_dense(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves = 0);
+// The same for GM_CONVT (kernel and output sizes divisible by the stride).
+bool rf_resolve_convt(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves = 0);
 size_t rf_pack_bytes(const GemmArgs &a);
 // Packs conv weights w [Cout][Cin][KH][KW] into dst (rf_pack_bytes) for the kernel.
 int launch_rf_pack(const GemmArgs &a, const float *w, float *dst, void *stream);

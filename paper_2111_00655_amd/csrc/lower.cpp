@@ -372,6 +372,9 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
                 a.bias_on_row = 1;
                 c.gemm_swap = true;
                 c.name = "convt_igemm";
+                if (want_rf && g.nodes[wb].kind == NODE_CONST)
+                    rf = rf_resolve_convt(&a, a.tile == TILE_R32 ? 32 : 16, epi_fast_flags(epi), ctx.n_cus);
+                if (rf) c.pack_bytes = rf_pack_bytes(a);
             }
             macs = (double)a.batch * a.M * a.N * a.K;
             if (rf && a.rf_groups > 1) macs /= a.rf_groups;
@@ -381,7 +384,8 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
             if (rf) {
                 c.scratch_bytes = gemm_scratch_bytes(a);
                 c.name = (a.rf_tapk == -1 ? "dense_rf" + std::to_string(a.rf_ts)
-                                          : "conv_rf" + std::to_string(a.rf_ts) + "_t" + std::to_string(a.rf_tapk)) +
+                                          : std::string(a.rf_convt ? "convt_rf" : "conv_rf") + std::to_string(a.rf_ts) + "_t" +
+                                                std::to_string(a.rf_tapk)) +
                          "_w" + std::to_string(a.rf_wgk) + (a.cs_len ? "_split" : "");
             } else {
                 if (want_rf) a.tile = TILE_S8;           // what the register-fed kernels do not run goes to the LDS-tiled ones

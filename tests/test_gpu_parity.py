@@ -153,20 +153,39 @@ def test_grouped_conv_is_refused_by_igemm():
 
 
 # ------------------------------------------------------- transposed convolution
-@pytest.mark.parametrize("backend", IGEMM)
-@pytest.mark.parametrize("case", [(1, 64, 32, 4, ("bias_add", "relu")), (2, 32, 16, 8, ("bias_add", "relu")),
-                                  (3, 16, 3, 16, ("bias_add", "tanh")), (1, 24, 40, 5, ())])
-def test_conv2d_transpose_fused(case, backend):
+def convt_desc(case, k=4, stride=2, pad=1):
     batch, cin, cout, h, tail = case
-    r = rng_for(3, cin, cout, h)
+    r = rng_for(3, cin, cout, h, k)
     d = wl.GraphDesc("convt_case")
     x = d.input(f32(r, batch, cin, h, h))
-    wt = d.const(f32(r, cin, cout, 4, 4, scale=0.05))
-    y = d.op("conv2d_transpose", [x, wt], stride=(2, 2), pad=(1, 1))
+    wt = d.const(f32(r, cin, cout, k, k, scale=0.05))
+    y = d.op("conv2d_transpose", [x, wt], stride=(stride, stride), pad=(pad, pad))
     for op in tail:
         y = d.op("bias_add", [y, d.const(f32(r, cout))], axis=1) if op == "bias_add" else d.op(op, [y])
     d.mark_output(y)
-    run_single_group(d, backend, tail_pattern(P("conv2d_transpose", W, W), tail))
+    return d, tail_pattern(P("conv2d_transpose", W, W), tail)
+
+
+@pytest.mark.parametrize("backend", IGEMM + RF)
+@pytest.mark.parametrize("case", [(1, 64, 32, 4, ("bias_add", "relu")), (2, 32, 16, 8, ("bias_add", "relu")),
+                                  (3, 16, 3, 16, ("bias_add", "tanh")), (1, 24, 40, 5, ()),
+                                  (2, 7, 5, 6, ("bias_add", "relu"))])
+def test_conv2d_transpose_fused(case, backend):
+    d, pat = convt_desc(case)
+    name, _ = run_single_group(d, backend, pat)
+    if backend in RF:
+        assert name.startswith("convt_rf"), name
+
+
+@pytest.mark.parametrize("backend", RF)
+@pytest.mark.parametrize("geom", [(6, 3, 0), (2, 2, 0), (3, 1, 1), (4, 1, 0)])
+def test_conv2d_transpose_other_geometries(geom, backend):
+    """Kernel sizes, strides and paddings other than k4 s2 p1: three phases per axis,
+    2x2 without overlap, stride 1 (a single phase with flipped taps)."""
+    k, s, p = geom
+    d, pat = convt_desc((2, 8, 12, 5, ("bias_add", "relu")), k=k, stride=s, pad=p)
+    name, _ = run_single_group(d, backend, pat)
+    assert name.startswith("convt_rf"), name
 
 
 # ------------------------------------------------------------- dense / bmm
