@@ -112,12 +112,13 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
         WOe = p.WO / p.sw;
     }
     const int npix = HOe * WOe;
-    const int tiles_n = (npix + TS - 1) / TS;
     const int tiles_m = (p.Cout + TS - 1) / TS;
     const int tile = xcd_remap(blockIdx.x, gridDim.x);
-    // neighbouring workgroups share the larger operand: weights rows (i-major) or pixels (j-major)
-    const int mt = p.rf_jmajor ? tile % tiles_m : tile / tiles_n;
-    const int nt = p.rf_jmajor ? tile / tiles_m : tile % tiles_n;
+    // neighbouring workgroups share the larger operand: weights rows (i-major) or pixels (j-major);
+    // tile / rf_tile_div by multiply-high (an integer division costs some thirty instructions)
+    const int t_hi = (int)(((uint64_t)(uint32_t)tile * p.rf_tile_magic) >> 32), t_lo = tile - t_hi * p.rf_tile_div;
+    const int mt = p.rf_jmajor ? t_lo : t_hi;
+    const int nt = p.rf_jmajor ? t_hi : t_lo;
     const int i0 = mt * TS, j0 = nt * TS;
     const int img = blockIdx.y;
 
@@ -357,11 +358,10 @@ __global__ __launch_bounds__(WGK *kWave) void dense_rf_kernel(GemmArgs p) {
     const int w = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int r = lane % TS, s = lane / TS;
 
-    const int tiles_j = (p.M + TS - 1) / TS;
-    const int tiles_i = (p.N + TS - 1) / TS;
     const int tile = xcd_remap(blockIdx.x, gridDim.x);
-    const int mt = p.rf_jmajor ? tile % tiles_i : tile / tiles_j;     // weight-row tile
-    const int nt = p.rf_jmajor ? tile / tiles_i : tile % tiles_j;     // activation-row tile
+    const int t_hi = (int)(((uint64_t)(uint32_t)tile * p.rf_tile_magic) >> 32), t_lo = tile - t_hi * p.rf_tile_div;
+    const int mt = p.rf_jmajor ? t_lo : t_hi;     // weight-row tile
+    const int nt = p.rf_jmajor ? t_hi : t_lo;     // activation-row tile
     const int i0 = mt * TS, j0 = nt * TS;
     const int ks = blockIdx.z;
 

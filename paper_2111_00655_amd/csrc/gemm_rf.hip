@@ -93,6 +93,13 @@ int pick_waves(int chunks, int64_t tiles, int forced, bool cap_grid) {
     return wgk < cap ? wgk : cap;
 }
 
+// Tile order: tile = hi * div + lo with lo running over the m-tiles (j-major) or the n-tiles.
+bool set_tile_order(GemmArgs *a, int tiles_m, int tiles_n) {
+    a->rf_tile_div = a->rf_jmajor ? tiles_m : tiles_n;
+    a->rf_tile_magic = (((uint64_t)1 << 32) / (uint64_t)a->rf_tile_div) + 1;
+    return (int64_t)tiles_m * tiles_n * a->rf_tile_div < ((int64_t)1 << 32);      // range in which the multiply-high is exact
+}
+
 int chunk_mfmas(int tapk) { return tapk == 1 || tapk == 4 ? 16 : (tapk == 9 ? 36 : 4); }
 int chunk_groups(int tapk) { return tapk == 1 || tapk == 4 ? 4 : (tapk == 9 ? 9 : 1); }
 
@@ -123,7 +130,9 @@ bool rf_resolve_dense(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves) 
     a->rf_ngtot = wgk * a->splitk * a->rf_nch * 4;
     a->rf_nm = ng * 4;
     a->rf_jmajor = a->M > a->N ? 1 : 0;
-    return true;
+    if (set_tile_order(a, (a->N + ts - 1) / ts, (a->M + ts - 1) / ts)) return true;
+    a->rf_ts = 0;
+    return false;
 }
 
 bool rf_resolve(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves) {
@@ -165,7 +174,10 @@ bool rf_resolve(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves) {
     a->rf_nm = nm;
     a->rf_jmajor = (int64_t)a->Cin * a->H * a->W > (int64_t)a->Cout * a->K ? 1 : 0;
     a->rf_wo_magic = (((uint64_t)1 << 32) / (uint64_t)a->WO) + 1;
-    return true;
+    if (set_tile_order(a, (a->Cout + ts - 1) / ts, (int)((npix + ts - 1) / ts))) return true;
+    a->rf_ts = 0;
+    a->rf_convt = 0;
+    return false;
 }
 
 bool rf_resolve_convt(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves) {
@@ -201,7 +213,10 @@ bool rf_resolve_convt(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves) 
     a->rf_convt = 1;
     a->rf_jmajor = (int64_t)a->Cin * a->H * a->W > (int64_t)a->Cout * a->Cin * taps ? 1 : 0;
     a->rf_wo_magic = (((uint64_t)1 << 32) / (uint64_t)woe) + 1;
-    return true;
+    if (set_tile_order(a, (a->Cout + ts - 1) / ts, (int)((npix + ts - 1) / ts))) return true;
+    a->rf_ts = 0;
+    a->rf_convt = 0;
+    return false;
 }
 
 size_t rf_pack_bytes(const GemmArgs &a) {

@@ -92,6 +92,8 @@ struct GemmArgs {
     int32_t rf_cin_tile, rf_cpg_in, rf_cpg_out;            // channels contracted per m-tile; channels per group
     int32_t rf_convt;                      // 1: transposed convolution, one sub-pixel phase per grid.z slice
     uint64_t rf_wo_magic;                  // floor(2^32 / WO) + 1: pixel / WO by multiply-high
+    uint64_t rf_tile_magic;                // the same for rf_tile_div
+    int32_t rf_tile_div, rf_pad2_;         // tiles along the fast axis of the tile order (m-tiles if rf_jmajor)
     // dense only: output column n goes to (n / cs_len) * cs_stride + n % cs_len within its row block
     // (cs_len = 0: plain row-major).  This is how reshape + transpose of the result is fused (head split).
     int32_t cs_len, cs_pad_;
