@@ -130,7 +130,9 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
     const int cbase = p.rf_groups > 1 ? (i0 / p.rf_cpg_out) * p.rf_cpg_in : 0;
     const int cin = min(p.rf_cin_tile, p.Cin - cbase);       // input channels this m-tile contracts
     const float *const x_img = p.B + ((int64_t)img * p.Cin + cbase) * HW;
-    const f32x4 *const Ap = reinterpret_cast<const f32x4 *>(p.A) + ((int64_t)phase * tiles_m + mt) * p.rf_ngtot * kWave + lane;
+    // packed weights of this m-tile; a wave's load is base + uniform group offset + lane
+    const f32x4 *const Ab = reinterpret_cast<const f32x4 *>(p.A) + ((int64_t)phase * tiles_m + mt) * p.rf_ngtot * kWave;
+    const uint32_t lane_u = (uint32_t)lane;
     const int nch = p.rf_nch;                                // chunks per wave
     const int c0 = (ks * WGK + w) * nch;                     // this wave's first chunk
     const int cq_last = (cin + NSLOT - 1) / NSLOT - 1;
@@ -162,17 +164,19 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
 
     if constexpr (TAPK == 1) {
         // ---- 1x1: MFMA n contracts channels n*NSLOT .. n*NSLOT+NSLOT-1 at this lane's pixel
-        const int lane_off = s * HW + ih0 * p.W + iw0;
-        const int64_t cq_step = (int64_t)NSLOT * HW;
+        // addresses are "uniform base + 32-bit lane offset": one scalar multiply and no 64-bit
+        // vector arithmetic per load (offsets within an image fit 32 bits: checked on the host)
+        const uint32_t lane_off = (uint32_t)(s * HW + ih0 * p.W + iw0);
+        const uint32_t cq_step = (uint32_t)(NSLOT * HW);
         f32x4 a[2][4];
         float b[2][16];
 #define CLG_RF_LOAD(set, c)                                                                   \
     do {                                                                                      \
         const int ch_ = min((c), nch - 1) + c0;                                               \
-        _Pragma("unroll") for (int u = 0; u < 4; ++u) a[set][u] = Ap[(int64_t)(ch_ * 4 + u) * kWave]; \
+        _Pragma("unroll") for (int u = 0; u < 4; ++u) a[set][u] = (Ab + (uint32_t)(ch_ * 4 + u) * kWave)[lane_u]; \
         _Pragma("unroll") for (int u = 0; u < 16; ++u) {                                      \
             const int cq_ = min(ch_ * 16 + u, cq_last);                                       \
-            b[set][u] = x_img[cq_ * cq_step + lane_off];                                      \
+            b[set][u] = (x_img + (uint32_t)cq_ * cq_step)[lane_off];                          \
         }                                                                                     \
         __builtin_amdgcn_sched_barrier(0);   /* all loads of a chunk go out before its MFMAs */ \
     } while (0)
@@ -194,24 +198,24 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
     } else if constexpr (TAPK == 9) {
         // ---- 3x3: the nine tap offsets of this lane's pixel are fixed; a chunk is
         // four channel groups x nine taps
-        int voff[9];
+        uint32_t voff[9];
         bool ok[9];
 #pragma unroll
         for (int t = 0; t < 9; ++t) {
             const int ih = ih0 + t / 3, iw = iw0 + t % 3;
             ok[t] = ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
-            voff[t] = s * HW + (ok[t] ? ih * p.W + iw : 0);
+            voff[t] = (uint32_t)(s * HW + (ok[t] ? ih * p.W + iw : 0));
         }
-        const int64_t cq_step = (int64_t)NSLOT * HW;
+        const uint32_t cq_step = (uint32_t)(NSLOT * HW);
         for (int c = 0; c < nch; ++c) {
             const int ch = c0 + c;
             f32x4 a[9];
             float b[36];
 #pragma unroll
-            for (int u = 0; u < 9; ++u) a[u] = Ap[(int64_t)(ch * 9 + u) * kWave];
+            for (int u = 0; u < 9; ++u) a[u] = (Ab + (uint32_t)(ch * 9 + u) * kWave)[lane_u];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const float *xc = x_img + min(ch * 4 + q, cq_last) * cq_step;
+                const float *xc = x_img + (uint32_t)min(ch * 4 + q, cq_last) * cq_step;
 #pragma unroll
                 for (int t = 0; t < 9; ++t) {
                     const float v = xc[voff[t]];
@@ -227,23 +231,23 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
     } else if constexpr (TAPK == 4) {
         // ---- 2x2 (a phase of a k4 s2 transposed convolution): like 3x3, a chunk is four
         // channel groups x four taps
-        int voff[4];
+        uint32_t voff[4];
         bool ok[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const int ih = ih0 + t / 2, iw = iw0 + t % 2;
             ok[t] = ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
-            voff[t] = s * HW + (ok[t] ? ih * p.W + iw : 0);
+            voff[t] = (uint32_t)(s * HW + (ok[t] ? ih * p.W + iw : 0));
         }
-        const int64_t cq_step = (int64_t)NSLOT * HW;
+        const uint32_t cq_step = (uint32_t)(NSLOT * HW);
         f32x4 a[2][4];
         float b[2][16];
 #define CLG_RF_LOAD(set, c)                                                                   \
     do {                                                                                      \
         const int ch_ = min((c), nch - 1) + c0;                                               \
-        _Pragma("unroll") for (int u = 0; u < 4; ++u) a[set][u] = Ap[(int64_t)(ch_ * 4 + u) * kWave]; \
+        _Pragma("unroll") for (int u = 0; u < 4; ++u) a[set][u] = (Ab + (uint32_t)(ch_ * 4 + u) * kWave)[lane_u]; \
         _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                       \
-            const float *xc_ = x_img + min(ch_ * 4 + q, cq_last) * cq_step;                   \
+            const float *xc_ = x_img + (uint32_t)min(ch_ * 4 + q, cq_last) * cq_step;         \
             _Pragma("unroll") for (int t = 0; t < 4; ++t) b[set][q * 4 + t] = xc_[voff[t]];   \
         }                                                                                     \
         __builtin_amdgcn_sched_barrier(0);                                                    \
@@ -272,7 +276,7 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
         int cq = n / taps, t = n - cq * taps;
         int kh = t / KWe, kw = t - kh * KWe;
         for (int c = 0; c < nch; ++c) {
-            const f32x4 a = Ap[(int64_t)(c0 + c) * kWave];
+            const f32x4 a = (Ab + (uint32_t)(c0 + c) * kWave)[lane_u];
             float b[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
@@ -365,8 +369,11 @@ __global__ __launch_bounds__(WGK *kWave) void dense_rf_kernel(GemmArgs p) {
     const int i0 = mt * TS, j0 = nt * TS;
     const int ks = blockIdx.z;
 
-    const f32x4 *const Ap = reinterpret_cast<const f32x4 *>(p.B) + (int64_t)mt * p.rf_ngtot * kWave + lane;
-    const f32x4 *const Xp = reinterpret_cast<const f32x4 *>(p.A + (int64_t)min(j0 + r, p.M - 1) * p.lda) + s;
+    // addresses are "uniform base + 32-bit lane offset" (no 64-bit vector arithmetic per load)
+    const f32x4 *const Ab = reinterpret_cast<const f32x4 *>(p.B) + (int64_t)mt * p.rf_ngtot * kWave;
+    const f32x4 *const Xb = reinterpret_cast<const f32x4 *>(p.A);
+    const uint32_t lane_u = (uint32_t)lane;
+    const uint32_t x_lane = (uint32_t)(min(j0 + r, p.M - 1) * (p.lda / 4) + s);      // in 16-byte units
     const int nch = p.rf_nch;
     const int c0 = (ks * WGK + w) * nch;
     const int g_last = p.K / (4 * NSLOT) - 1;
@@ -399,8 +406,8 @@ __global__ __launch_bounds__(WGK *kWave) void dense_rf_kernel(GemmArgs p) {
 #define CLG_RFD_LOAD(set, c)                                                                  \
     do {                                                                                      \
         const int ch_ = min((c), nch - 1) + c0;                                               \
-        _Pragma("unroll") for (int u = 0; u < 4; ++u) a[set][u] = Ap[(int64_t)(ch_ * 4 + u) * kWave]; \
-        _Pragma("unroll") for (int u = 0; u < 4; ++u) b[set][u] = Xp[min(ch_ * 4 + u, g_last) * NSLOT]; \
+        _Pragma("unroll") for (int u = 0; u < 4; ++u) a[set][u] = (Ab + (uint32_t)(ch_ * 4 + u) * kWave)[lane_u]; \
+        _Pragma("unroll") for (int u = 0; u < 4; ++u) b[set][u] = (Xb + (uint32_t)min(ch_ * 4 + u, g_last) * NSLOT)[x_lane]; \
         __builtin_amdgcn_sched_barrier(0);                                                    \
     } while (0)
 #define CLG_RFD_MMA(set)                                                                      \

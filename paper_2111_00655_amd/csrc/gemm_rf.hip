@@ -118,6 +118,7 @@ bool rf_resolve_dense(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves) 
     if (a->mode != GM_NT || a->batch != 1 || (epi_flags & EF_GENERIC)) return false;
     const int nslot = ts == 32 ? 2 : 4;
     if (a->K % (4 * nslot) || a->lda % 4) return false;
+    if ((int64_t)a->M * a->lda >= ((int64_t)1 << 31)) return false;     // 32-bit lane offsets
     if (a->cs_len && a->cs_len % ts) return false;           // a tile's columns must stay within one block of the split
     const int ng = a->K / (4 * nslot);                       // weight groups (4 MFMAs each)
     const int nc = (ng + 3) / 4;                             // chunks per tile
