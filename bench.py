@@ -25,6 +25,9 @@ if ROOT not in sys.path:
 
 PEAK_MFMA_F32_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
 PEAK_HBM_GBPS = 8000.0            # MI355X HBM3E
+# the MFMA kernel variants registered as separate backends; the search picks one per fused subgraph
+VARIANTS = ("igemm", "igemm_s", "igemm_s8", "igemm_s16", "igemm_m", "igemm_l", "igemm_s_nk", "igemm_s8_nk",
+            "igemm_s16_nk", "igemm_r32", "igemm_r16")
 
 
 def optimise(desc, reg, opts, cost_log=""):
@@ -63,6 +66,74 @@ def time_steps(plan, steps, warmup):
         plan.execute()
     torch.cuda.synchronize()
     return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def graph_replay_ms(plan, steps, warmup):
+    """The same kernel sequence captured once into a HIP graph and replayed.
+    The replayed outputs are checked against the eager ones (bitwise) before timing."""
+    import torch
+    plan.execute()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in plan._out]
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        plan.execute()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=st):
+            plan.execute()
+    torch.cuda.synchronize()
+    for rep in range(3):                       # several replays with eager work between them
+        for t in plan._out:
+            t.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        if not all(torch.equal(a, b) for a, b in zip(ref, plan._out)):
+            return None
+    for _ in range(warmup):
+        g.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        g.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def cold_cache_ms(plan, steps=20):
+    """One pass at a time with the caches scrubbed in between (a 512 MB buffer is
+    rewritten before each pass), timed with an event pair around the pass."""
+    import torch
+    scrub = torch.empty(512 * 1024 * 1024 // 4, dtype=torch.float32, device="cuda")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    tot = 0.0
+    for i in range(steps):
+        scrub.fill_(float(i))
+        e0.record()
+        plan.execute()
+        e1.record()
+        torch.cuda.synchronize()
+        tot += e0.elapsed_time(e1)
+    return tot / steps
+
+
+def ablation(desc, variants, opts, cost_log, steps, warmup):
+    """Latency of the placement found when the MFMA kernels are restricted to a
+    single variant, next to the search over all of them (paper Sec. 5.5 studies
+    the same question for its backends)."""
+    import workloads as wl
+    out = {}
+    for v in variants:
+        reg = wl.default_registry((v,))
+        try:
+            s, plan, _, _, t = optimise(desc, reg, opts, cost_log)
+        except Exception as e:                 # a variant alone may not cover the graph (grouped conv)
+            out[v] = None
+            continue
+        out[v] = round(time_steps(plan, steps, warmup), 4)
+        plan.destroy()
+        s.close()
+    return out
 
 
 def kernel_table(plan, reps=20):
@@ -106,7 +177,7 @@ def roofline_of(rows, step_ns=None):
 
 
 def cpu_baseline(desc):
-    """The oracle as it stands, one full forward pass on the host cores."""
+    """The oracle as it stands, one full forward pass on the host cores (and one on a single thread)."""
     from oracle.graph import Graph
     from oracle import ops
     g = Graph(desc)
@@ -114,8 +185,15 @@ def cpu_baseline(desc):
     t0 = time.perf_counter()
     g.run()
     dt = time.perf_counter() - t0
-    return dict(value=round(dt * 1e3, 2), unit="ms", cores=ops.max_threads(), kind="oracle",
-                sample="one full batch-1 forward pass of the same graph (all layers), second of two runs")
+    n = ops.max_threads()
+    ops.set_threads(1)
+    t0 = time.perf_counter()
+    g.run()
+    dt1 = time.perf_counter() - t0
+    ops.set_threads(n)
+    return dict(value=round(dt * 1e3, 2), unit="ms", cores=n, kind="oracle",
+                sample="one full batch-1 forward pass of the same graph (all layers), second of two runs",
+                single_thread_ms=round(dt1 * 1e3, 2))
 
 
 def main():
@@ -128,6 +206,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--dump", default="", help="write the per-kernel table to this JSON file")
     ap.add_argument("--cost-log", default="", help="cost-log file: reuse measured subgraph costs from it, add new ones")
+    ap.add_argument("--ablation", action="store_true", help="also time the placement under each single MFMA kernel variant")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: batch-1 inference of one graph is a dependency chain and "
@@ -141,8 +220,7 @@ def main():
     import workloads as wl
     from paper_2111_00655_amd import binding as B
 
-    reg = wl.default_registry(("igemm", "igemm_s", "igemm_s8", "igemm_s16", "igemm_m", "igemm_l", "igemm_s_nk", "igemm_s8_nk", "igemm_s16_nk",
-                               "igemm_r32", "igemm_r16"))
+    reg = wl.default_registry(VARIANTS)
     opts = B.ProfileOpts(warmup=10, batches=5, min_batch_us=200, max_launches=500)
 
     desc = wl.MODEL_BUILDERS[args.model](0)
@@ -152,6 +230,9 @@ def main():
     roof = roofline_of(rows, ms_per_step * 1e6)
     kernel_only_ms = sum(r["ns"] for r in rows) / 1e6
     empty_ns = B.clg_profile_empty(s.ctx)
+    graph_ms = graph_replay_ms(plan, args.steps, args.warmup)
+    cold_ms = cold_cache_ms(plan)
+    abl = ablation(desc, VARIANTS, opts, args.cost_log, max(20, args.steps // 2), args.warmup) if args.ablation else None
 
     extra = {}
     if not args.no_extra:
@@ -195,6 +276,9 @@ def main():
         "roofline": roof,
         "cpu_baseline": cpu,
         "kernel_only_ms": round(kernel_only_ms, 4),
+        "graph_replay_ms": None if graph_ms is None else round(graph_ms, 4),
+        "cold_cache_ms": round(cold_ms, 4),
+        "ablation_ms": abl,
         "empty_launch_ns": int(empty_ns),
         "optimise": {k: (round(v, 4) if isinstance(v, float) else v) for k, v in timing.items()},
         "other_workloads": extra,
