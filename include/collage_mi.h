@@ -215,6 +215,13 @@ int32_t clg_graph_node_shape(const clg_graph *g, int32_t node, int32_t *dtype,
  *              128x128 (kernel variants for the search to place per layer)
  *   "igemm_s_nk", "igemm_s8_nk", "igemm_s16_nk"   those tiles, never splitting
  *              K across workgroups (no second reduction kernel)
+ *   "igemm_r32", "igemm_r16"   register-fed MFMA kernels with 32x32 / 16x16
+ *              output tiles for conv2d (any groups), conv2d_transpose and dense
+ *              whose weights are constants: the weights are re-packed once per
+ *              plan and read straight into MFMA operands, K is split across the
+ *              waves of a workgroup.  What they do not run (batch_matmul,
+ *              non-constant weights, tails outside scale/bias/add/activation)
+ *              falls back to the "igemm_s8" kernels.
  *   "direct"   direct convolution (any groups) and pooling
  *   "rowwise"  softmax and layer norm with fused elementwise prologue
  *   "eltwise"  elementwise chains, embedding gather, layout copies
@@ -294,7 +301,12 @@ int32_t clg_search_stats(const clg_graph *g, int64_t stats[5]);
  * search's).  Validates disjointness and cover (OVERLAP, NOT_A_COVER,
  * UNKNOWN_ID), orders the groups topologically, lowers each to one kernel
  * (NO_KERNEL if a backend cannot run its match) and plans the intermediate
- * tensors in one workspace; tensors pass between kernels by pointer. */
+ * tensors in one workspace; tensors pass between kernels by pointer.
+ * Kernels that read packed weights get their copy here: the plan allocates
+ * device memory for it (OUT_OF_MEMORY on failure), fills it on the null
+ * stream and waits for that; the constants' device pointers must therefore
+ * be valid at this call.  clg_plan_destroy frees those copies; the plan must
+ * not be destroyed while one of its executions is still running. */
 int32_t clg_compile(clg_ctx *ctx, clg_graph *g, const int32_t *matches,
                     size_t n, clg_plan **out);
 int32_t clg_plan_destroy(clg_plan *plan);
