@@ -30,6 +30,24 @@ VARIANTS = ("igemm", "igemm_s", "igemm_s8", "igemm_s16", "igemm_m", "igemm_l", "
             "igemm_s16_nk", "igemm_r32", "igemm_r16")
 
 
+# HBM-side traffic of the fp32 MFMA kernels of one ResNet-50 step, from two rocprofv3 --pmc runs of this file
+# (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch, summed over the 57 such dispatches of a step and averaged over
+# the steps of the run).  Scale factors from the 256 MiB plain device copy of --calib-copy in the same runs:
+# WRITE_SIZE read 262144.0 KiB for it (factor 1.000), FETCH_SIZE 131083.5 KiB (factor 2.000).  The figures hold
+# for the kernel sources they were taken with; after any change to them `traffic` is reported as null.
+TRAFFIC = {"resnet50": {"sources": "07001b72b803bf22", "fetch_bytes": 304.48e6, "write_bytes": 46.87e6}}
+
+
+def kernel_sources_fingerprint():
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2111_00655_amd", "csrc", "*"))):
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
 def optimise(desc, reg, opts, cost_log=""):
     """register -> match -> profile -> search -> compile; returns pieces + timings.
     With a cost log file, measured costs are reused from / added to it."""
@@ -207,6 +225,9 @@ def main():
     ap.add_argument("--dump", default="", help="write the per-kernel table to this JSON file")
     ap.add_argument("--cost-log", default="", help="cost-log file: reuse measured subgraph costs from it, add new ones")
     ap.add_argument("--ablation", action="store_true", help="also time the placement under each single MFMA kernel variant")
+    ap.add_argument("--calib-copy", type=int, default=0, metavar="MIB",
+                    help="also run three plain device copies of MIB MiB (read MIB, write MIB): the known-size kernel "
+                         "against which hardware byte counters of a profiled run are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: batch-1 inference of one graph is a dependency chain and "
@@ -228,6 +249,10 @@ def main():
     ms_per_step = time_steps(plan, args.steps, args.warmup)
     rows = kernel_table(plan)
     roof = roofline_of(rows, ms_per_step * 1e6)
+    roof["algorithmic_bytes"] = int(sum(r["bytes"] for r in rows if r["bound"] == "mfma"))
+    tr = TRAFFIC.get(args.model)
+    if tr and tr["sources"] == kernel_sources_fingerprint():
+        roof["traffic"] = int(tr["fetch_bytes"] + tr["write_bytes"])      # bytes per step, same launches as `achieved`
     kernel_only_ms = sum(r["ns"] for r in rows) / 1e6
     empty_ns = B.clg_profile_empty(s.ctx)
     graph_ms = graph_replay_ms(plan, args.steps, args.warmup)
@@ -251,6 +276,14 @@ def main():
             s2.close()
 
     cpu = None if args.no_cpu else cpu_baseline(desc)
+
+    if args.calib_copy:
+        n = args.calib_copy * 1024 * 1024 // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     if args.dump:
         os.makedirs(os.path.dirname(os.path.abspath(args.dump)), exist_ok=True)
