@@ -35,14 +35,17 @@ VARIANTS = ("igemm", "igemm_s", "igemm_s8", "igemm_s16", "igemm_m", "igemm_l", "
 # the steps of the run).  Scale factors from the 256 MiB plain device copy of --calib-copy in the same runs:
 # WRITE_SIZE read 262144.0 KiB for it (factor 1.000), FETCH_SIZE 131083.5 KiB (factor 2.000).  The figures hold
 # for the kernel sources they were taken with; after any change to them `traffic` is reported as null.
-TRAFFIC = {"resnet50": {"sources": "07001b72b803bf22", "fetch_bytes": 304.48e6, "write_bytes": 46.87e6}}
+TRAFFIC = {"resnet50": {"sources": "b9752c02da947a4a", "fetch_bytes": 304.48e6, "write_bytes": 46.87e6}}
 
 
 def kernel_sources_fingerprint():
     import glob
     import hashlib
     h = hashlib.sha256()
-    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2111_00655_amd", "csrc", "*"))):
+    d = os.path.join(ROOT, "paper_2111_00655_amd", "csrc")
+    files = glob.glob(os.path.join(d, "*.hip")) + glob.glob(os.path.join(d, "gemm_*.h"))
+    files += [os.path.join(d, "device_common.h"), os.path.join(d, "kernels.h")]
+    for f in sorted(files):                     # the device code: kernels, their headers and argument blocks
         with open(f, "rb") as fh:
             h.update(fh.read())
     return h.hexdigest()[:16]

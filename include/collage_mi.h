@@ -314,6 +314,23 @@ int32_t clg_plan_workspace_bytes(const clg_plan *plan, size_t *bytes);
 int32_t clg_plan_num_kernels(const clg_plan *plan, size_t *n);
 int32_t clg_plan_kernel_info(const clg_plan *plan, size_t index,
                              clg_kernel_info *info);
+/* Lanes (Sec. 4.1: the groups of a placement form a DAG, not a chain).  An
+ * execution enqueues kernels of independent branches on up to `lanes` HIP
+ * streams: lane 0 is the caller's stream, the others belong to the plan
+ * (created at its first execution, default priority, released by
+ * clg_plan_destroy).  Lanes are forked from and joined back into the caller's
+ * stream with events inside every clg_execute, so for the caller the call
+ * behaves like work on its own stream, also under HIP graph capture.
+ * Dependencies: data flow between kernels plus every reuse of a workspace
+ * region.  lanes = 1 (the default) runs everything on the caller's stream; at
+ * most 4.  On MI355X a dependency between two hardware queues costs several
+ * times a small kernel, so at batch 1 more than one lane measured slower
+ * (ResNet-50: 0.55 ms against 0.38 ms); the option is for placements whose
+ * branches hold long kernels.  Not to be called while the plan executes (it waits for the
+ * plan's own streams).  Executions of one plan must not overlap each other.
+ * clg_plan_num_lanes: lanes the current schedule uses (1 for a chain). */
+int32_t clg_plan_set_lanes(clg_plan *plan, int32_t lanes);
+int32_t clg_plan_num_lanes(const clg_plan *plan, int32_t *lanes);
 /* inputs: host array of device pointers, one per graph input in creation
  * order; outputs: host array of device pointers, one per marked output, each
  * large enough for its tensor; workspace: device memory of at least

@@ -106,6 +106,8 @@ SYMBOLS = {
     "clg_plan_workspace_bytes": (C.c_int32, [_P, _szp]),
     "clg_plan_num_kernels": (C.c_int32, [_P, _szp]),
     "clg_plan_kernel_info": (C.c_int32, [_P, C.c_size_t, C.POINTER(KernelInfo)]),
+    "clg_plan_set_lanes": (C.c_int32, [_P, C.c_int32]),
+    "clg_plan_num_lanes": (C.c_int32, [_P, _i32p]),
     "clg_execute": (C.c_int32, [_P, C.POINTER(_P), C.POINTER(_P), _P, C.c_size_t, _P]),
     "clg_execute_timed": (C.c_int32, [_P, C.POINTER(_P), C.POINTER(_P), _P, C.c_size_t, _P, _i64p, C.c_size_t]),
 }
@@ -365,6 +367,16 @@ def clg_plan_workspace_bytes(plan):
 def clg_plan_num_kernels(plan):
     n = C.c_size_t()
     _check(lib().clg_plan_num_kernels(plan, C.byref(n)))
+    return n.value
+
+
+def clg_plan_set_lanes(plan, lanes):
+    _check(lib().clg_plan_set_lanes(plan, int(lanes)))
+
+
+def clg_plan_num_lanes(plan):
+    n = C.c_int32()
+    _check(lib().clg_plan_num_lanes(plan, C.byref(n)))
     return n.value
 
 

@@ -361,6 +361,20 @@ int32_t clg_plan_num_kernels(const clg_plan *plan, size_t *n) {
     return CLG_OK;
 }
 
+int32_t clg_plan_set_lanes(clg_plan *plan, int32_t lanes) {
+    CLG_TRY
+    NEED(plan);
+    if (lanes < 1 || lanes > 4) return fail(CLG_INVALID_ARG, "lanes must be 1..4 (got %d)", lanes);
+    return set_plan_lanes(plan->p, lanes);
+    CLG_CATCH
+}
+
+int32_t clg_plan_num_lanes(const clg_plan *plan, int32_t *lanes) {
+    NEED(plan); NEED(lanes);
+    *lanes = plan->p.n_lanes;
+    return CLG_OK;
+}
+
 int32_t clg_plan_kernel_info(const clg_plan *plan, size_t index, clg_kernel_info *info) {
     NEED(plan); NEED(info);
     if (index >= plan->p.calls.size()) return fail(CLG_UNKNOWN_ID, "kernel index %zu", index);

@@ -159,6 +159,16 @@ struct Plan {
     std::vector<int64_t> scratch_offset;   // call -> workspace byte offset of its scratch
     std::vector<void *> packed;            // call -> re-packed weights (device memory owned by the plan) or null
     size_t workspace_bytes = 0;
+    // concurrent lanes: kernels of independent branches go to different HIP streams
+    int32_t max_lanes = 1;                 // 1 = everything on the caller's stream (default: see clg_plan_set_lanes)
+    int32_t n_lanes = 1;                   // lanes the schedule uses
+    std::vector<int32_t> lane;             // call -> lane (0 = the caller's stream)
+    std::vector<std::vector<int32_t>> waits;   // call -> earlier calls on other lanes it must wait for
+    std::vector<char> signals;             // call -> some later call on another lane waits for it
+    std::vector<void *> side_streams;      // hipStream_t of lanes 1.., created at the first execution
+    std::vector<void *> events;            // hipEvent_t per call (null unless it signals)
+    void *ev_begin = nullptr;
+    std::vector<void *> ev_end;            // per side lane
     Plan() = default;
     Plan(const Plan &) = delete;
     Plan &operator=(const Plan &) = delete;
@@ -179,6 +189,10 @@ const char *op_name(int32_t kind);
 
 int32_t match_all(Context &ctx, Graph &g);
 int32_t compile_plan(Context &ctx, Graph &g, const int32_t *ids, size_t n, Plan *plan);
+// (Re)computes the lane schedule of a compiled plan for at most plan->max_lanes lanes.
+void schedule_lanes(Plan *plan);
+// Changes the lane limit: waits for the plan's own streams, releases them and their events, reschedules.
+int32_t set_plan_lanes(Plan &p, int32_t lanes);
 int32_t execute_plan(Plan &p, const void *const *inputs, void *const *outputs, void *workspace,
                      size_t ws_bytes, void *stream, int64_t *kernel_ns);
 int32_t profile_match(Context &ctx, Graph &g, int32_t match, const clg_profile_opts *opts, int64_t *cost_ns);

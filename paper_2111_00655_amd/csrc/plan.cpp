@@ -124,6 +124,7 @@ int32_t compile_plan(Context &ctx, Graph &g, const int32_t *ids, size_t n, Plan 
             arena.release(plan->value_offset[c.out_node]);     // value nobody reads
     }
     plan->workspace_bytes = (size_t)arena.peak;
+    schedule_lanes(plan);
 
     // kernels that read their weights in a packed order get a private copy,
     // written once here and owned by the plan
@@ -153,6 +154,121 @@ int32_t compile_plan(Context &ctx, Graph &g, const int32_t *ids, size_t n, Plan 
 Plan::~Plan() {
     for (void *p : packed)
         if (p) (void)hipFree(p);
+    for (void *e : events)
+        if (e) (void)hipEventDestroy((hipEvent_t)e);
+    for (void *e : ev_end)
+        if (e) (void)hipEventDestroy((hipEvent_t)e);
+    if (ev_begin) (void)hipEventDestroy((hipEvent_t)ev_begin);
+    for (void *s : side_streams)
+        if (s) (void)hipStreamDestroy((hipStream_t)s);
+}
+
+int32_t set_plan_lanes(Plan &p, int32_t lanes) {
+    for (void *s : p.side_streams)
+        if (s && hipStreamSynchronize((hipStream_t)s) != hipSuccess)
+            return fail(CLG_HIP_ERROR, "synchronising a lane failed: %s", hipGetErrorString(hipGetLastError()));
+    for (void *e : p.events)
+        if (e) (void)hipEventDestroy((hipEvent_t)e);
+    for (void *e : p.ev_end)
+        if (e) (void)hipEventDestroy((hipEvent_t)e);
+    if (p.ev_begin) (void)hipEventDestroy((hipEvent_t)p.ev_begin);
+    for (void *s : p.side_streams)
+        if (s) (void)hipStreamDestroy((hipStream_t)s);
+    p.events.clear();
+    p.ev_end.clear();
+    p.ev_begin = nullptr;
+    p.side_streams.clear();
+    p.max_lanes = lanes;
+    schedule_lanes(&p);
+    return CLG_OK;
+}
+
+// Lane schedule.  A placement's quotient graph has independent branches (the
+// projection shortcut next to the main path of a residual block; the query, key
+// and value projections of an attention layer), and at batch 1 one kernel rarely
+// fills the chip, so such branches run on different HIP streams.  Dependencies
+// are the data dependencies between kernels plus every reuse of a workspace
+// region (the workspace was planned for the sequential order).  Kernels are
+// still enqueued in plan order; a kernel stays on the lane of its latest
+// dependency when everything queued there is among its (transitive)
+// dependencies, and otherwise moves to another lane, waiting on events for what
+// it needs from elsewhere.
+void schedule_lanes(Plan *plan) {
+    const Graph &g = *plan->graph;
+    const size_t nc = plan->calls.size();
+    plan->lane.assign(nc, 0);
+    plan->waits.assign(nc, {});
+    plan->signals.assign(nc, 0);
+    plan->n_lanes = 1;
+    if (plan->max_lanes <= 1 || nc < 3) return;
+
+    struct Region { int64_t lo, hi; };
+    auto overlap = [](const std::vector<Region> &a, const std::vector<Region> &b) {
+        for (const Region &x : a)
+            for (const Region &y : b)
+                if (x.lo < y.hi && y.lo < x.hi) return true;
+        return false;
+    };
+    std::vector<std::vector<Region>> rd(nc), wr(nc);
+    std::vector<int32_t> produced_at(g.nodes.size(), -1);
+    for (size_t i = 0; i < nc; ++i) {
+        const KernelCall &c = plan->calls[i];
+        for (int32_t v : operands_of(c))
+            if (plan->value_offset[v] >= 0)
+                rd[i].push_back({plan->value_offset[v], plan->value_offset[v] + round_up(4 * g.nodes[v].shape.numel())});
+        if (plan->value_offset[c.out_node] >= 0)
+            wr[i].push_back({plan->value_offset[c.out_node],
+                             plan->value_offset[c.out_node] + round_up(4 * g.nodes[c.out_node].shape.numel())});
+        if (plan->scratch_offset[i] >= 0)
+            wr[i].push_back({plan->scratch_offset[i], plan->scratch_offset[i] + round_up((int64_t)c.scratch_bytes)});
+        produced_at[c.out_node] = (int32_t)i;
+    }
+    // direct dependencies and their transitive closure (bit sets over calls)
+    const size_t words = (nc + 63) / 64;
+    std::vector<std::vector<int32_t>> deps(nc);
+    std::vector<std::vector<uint64_t>> reach(nc, std::vector<uint64_t>(words, 0));
+    for (size_t j = 0; j < nc; ++j) {
+        for (int32_t v : operands_of(plan->calls[j])) {
+            const int32_t i = g.nodes[v].is_op() ? produced_at[v] : -1;
+            if (i >= 0 && (size_t)i < j) deps[j].push_back(i);
+        }
+        for (size_t i = 0; i < j; ++i)
+            if (overlap(wr[j], rd[i]) || overlap(wr[j], wr[i]) || overlap(rd[j], wr[i])) deps[j].push_back((int32_t)i);
+        std::sort(deps[j].begin(), deps[j].end());
+        deps[j].erase(std::unique(deps[j].begin(), deps[j].end()), deps[j].end());
+        for (int32_t i : deps[j]) {
+            reach[j][(size_t)i / 64] |= (uint64_t)1 << (i % 64);
+            for (size_t w = 0; w < words; ++w) reach[j][w] |= reach[i][w];
+        }
+    }
+    auto depends = [&](size_t j, int32_t i) { return i < 0 || ((reach[j][(size_t)i / 64] >> (i % 64)) & 1) != 0; };
+
+    const int lanes = std::min<int>(plan->max_lanes, 4);
+    std::vector<int32_t> last(lanes, -1);            // last call queued on each lane
+    for (size_t j = 0; j < nc; ++j) {
+        int pick = -1;
+        const int home = deps[j].empty() ? 0 : plan->lane[deps[j].back()];
+        if (depends(j, last[home])) pick = home;
+        for (int l = 0; l < lanes && pick < 0; ++l)
+            if (depends(j, last[l])) pick = l;         // a lane whose queue this call follows anyway (or an idle one)
+        if (pick < 0) {                                // every lane holds unrelated work: join the least recently used
+            pick = 0;
+            for (int l = 1; l < lanes; ++l)
+                if (last[l] < last[pick]) pick = l;
+        }
+        plan->lane[j] = pick;
+        last[pick] = (int32_t)j;
+        plan->n_lanes = std::max(plan->n_lanes, pick + 1);
+        // wait for the latest direct dependency on every other lane (a lane runs in order)
+        std::vector<int32_t> latest(lanes, -1);
+        for (int32_t i : deps[j])
+            if (plan->lane[i] != pick) latest[plan->lane[i]] = std::max(latest[plan->lane[i]], i);
+        for (int l = 0; l < lanes; ++l)
+            if (latest[l] >= 0) {
+                plan->waits[j].push_back(latest[l]);
+                plan->signals[latest[l]] = 1;
+            }
+    }
 }
 
 int32_t pack_weights(const KernelCall &c, const void *w, void *dst, void *stream) {
@@ -255,6 +371,36 @@ int32_t execute_plan(Plan &p, const void *const *inputs, void *const *outputs, v
         for (auto &e : ev)
             if (hipEventCreate(&e) != hipSuccess) return fail(CLG_HIP_ERROR, "hipEventCreate failed");
     }
+    // lanes: per-kernel timing runs everything on the caller's stream
+    const bool lanes = !kernel_ns && p.n_lanes > 1;
+    hipError_t he = hipSuccess;
+    if (lanes) {
+        if (p.side_streams.empty()) {                  // first execution: the plan's own streams and events
+            p.side_streams.assign((size_t)p.n_lanes - 1, nullptr);
+            p.ev_end.assign((size_t)p.n_lanes - 1, nullptr);
+            p.events.assign(p.calls.size(), nullptr);
+            for (auto &s : p.side_streams)
+                if (he == hipSuccess) he = hipStreamCreateWithFlags((hipStream_t *)&s, hipStreamNonBlocking);
+            for (auto &e : p.ev_end)
+                if (he == hipSuccess) he = hipEventCreateWithFlags((hipEvent_t *)&e, hipEventDisableTiming);
+            if (he == hipSuccess) he = hipEventCreateWithFlags((hipEvent_t *)&p.ev_begin, hipEventDisableTiming);
+            for (size_t i = 0; i < p.calls.size(); ++i)
+                if (p.signals[i] && he == hipSuccess)
+                    he = hipEventCreateWithFlags((hipEvent_t *)&p.events[i], hipEventDisableTiming);
+            if (he != hipSuccess) {
+                p.n_lanes = 1;                         // the partly built set is released with the plan
+                return fail(CLG_HIP_ERROR, "creating the plan's streams and events failed: %s", hipGetErrorString(he));
+            }
+        }
+        // the side lanes start after everything already queued on the caller's stream
+        he = hipEventRecord((hipEvent_t)p.ev_begin, (hipStream_t)stream);
+        for (void *s : p.side_streams)
+            if (he == hipSuccess) he = hipStreamWaitEvent((hipStream_t)s, (hipEvent_t)p.ev_begin, 0);
+        if (he != hipSuccess) return fail(CLG_HIP_ERROR, "lane fork failed: %s", hipGetErrorString(he));
+    }
+    auto stream_of = [&](size_t i) -> void * {
+        return (lanes && p.lane[i] > 0) ? p.side_streams[(size_t)p.lane[i] - 1] : stream;
+    };
     int32_t rc = CLG_OK;
     for (size_t i = 0; i < p.calls.size() && rc == CLG_OK; ++i) {
         const KernelCall &c = p.calls[i];
@@ -264,10 +410,27 @@ int32_t execute_plan(Plan &p, const void *const *inputs, void *const *outputs, v
             if (v >= 0 && !ptr_of(v)) rc = fail(CLG_INVALID_ARG, "constant node %d has no device pointer", v);
         if (rc != CLG_OK) break;
         void *scratch = p.scratch_offset[i] >= 0 ? (char *)workspace + p.scratch_offset[i] : nullptr;
+        void *st = stream_of(i);
+        if (lanes)
+            for (int32_t w : p.waits[i])
+                if (hipStreamWaitEvent((hipStream_t)st, (hipEvent_t)p.events[w], 0) != hipSuccess)
+                    rc = fail(CLG_HIP_ERROR, "hipStreamWaitEvent failed");
+        if (rc != CLG_OK) break;
         if (kernel_ns) (void)hipEventRecord(ev[2 * i], (hipStream_t)stream);
         rc = launch_call(c, ptr_of(c.a_node), ptr_of(c.b_node), ptr_of(c.c_node),
-                         const_cast<void *>(ptr_of(c.out_node)), epi, scratch, p.packed[i], stream);
+                         const_cast<void *>(ptr_of(c.out_node)), epi, scratch, p.packed[i], st);
         if (kernel_ns) (void)hipEventRecord(ev[2 * i + 1], (hipStream_t)stream);
+        if (lanes && p.signals[i] && rc == CLG_OK && hipEventRecord((hipEvent_t)p.events[i], (hipStream_t)st) != hipSuccess)
+            rc = fail(CLG_HIP_ERROR, "hipEventRecord failed");
+    }
+    if (lanes) {
+        // join: the caller's stream continues after every side lane (also after a failed launch, so that
+        // nothing the plan queued is left running behind the caller's back)
+        for (size_t l = 0; l < p.side_streams.size(); ++l) {
+            he = hipEventRecord((hipEvent_t)p.ev_end[l], (hipStream_t)p.side_streams[l]);
+            if (he == hipSuccess) he = hipStreamWaitEvent((hipStream_t)stream, (hipEvent_t)p.ev_end[l], 0);
+            if (he != hipSuccess && rc == CLG_OK) rc = fail(CLG_HIP_ERROR, "lane join failed: %s", hipGetErrorString(he));
+        }
     }
     if (kernel_ns) {
         if (rc == CLG_OK && hipStreamSynchronize((hipStream_t)stream) != hipSuccess)

@@ -93,6 +93,14 @@ class Plan:
     def kernels(self):
         return [B.clg_plan_kernel_info(self.h, i) for i in range(self.n_kernels)]
 
+    def set_lanes(self, lanes):
+        B.clg_plan_set_lanes(self.h, lanes)
+        return self
+
+    @property
+    def n_lanes(self):
+        return B.clg_plan_num_lanes(self.h)
+
     def bind(self, feeds=None):
         """Allocates workspace, inputs and outputs on the device (torch)."""
         s = self.s

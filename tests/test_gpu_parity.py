@@ -487,3 +487,34 @@ def test_execute_argument_errors():
     assert len(ns) == plan.n_kernels and np.all(ns > 0)
     plan.destroy()
     s.close()
+
+
+# ------------------------------------------------------------------- lanes
+@pytest.mark.parametrize("name", ["resnet50", "bert_base", "tiny_cnn"])
+def test_lanes_give_the_same_result_as_one_stream(name):
+    """Independent branches of a placement run on several HIP streams; the outputs
+    must equal, bit for bit, those of the same plan on the caller's stream alone,
+    on repeated executions and after switching back and forth."""
+    desc = wl.MODEL_BUILDERS[name](0)
+    reg = wl.default_registry(("igemm_s8", "igemm_r16"))
+    s = clg.Session(desc, reg, device=0)
+    s.match()
+    costs = s.profile(B.ProfileOpts(warmup=5, batches=2, min_batch_us=50, max_launches=100))
+    _, ids = s.search(costs, 0)
+    plan = s.compile(ids).bind()
+    assert plan.n_lanes == 1                    # the default
+    plan.set_lanes(3)
+    if name != "tiny_cnn":
+        assert plan.n_lanes > 1, "the model has parallel branches"
+    multi = [plan.run() for _ in range(3)]
+    plan.set_lanes(1)
+    assert plan.n_lanes == 1
+    single = plan.run()
+    plan.set_lanes(3)
+    again = plan.run()
+    for outs in multi + [again]:
+        assert all(np.array_equal(a, b) for a, b in zip(outs, single))
+    ref = Graph(desc).run()
+    assert max(norm_err(a, b) for a, b in zip(single, ref)) <= NET_TOL
+    plan.destroy()
+    s.close()
