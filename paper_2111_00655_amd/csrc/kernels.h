@@ -84,6 +84,7 @@ struct GemmArgs {
     // convolution geometry (GM_CONV, GM_CONVT)
     int32_t Nimg, Cin, H, W, Cout, KH, KW, sh, sw, ph, pw, HO, WO;
     int32_t bias_on_row;                   // 1: channel = i (conv), 0: channel = j (dense)
+    int32_t gemv;                          // 1: GM_NT with at most 8 rows runs the matrix-vector kernel (a wave per column)
     int32_t patch_sz;                      // 3x3 kernel: floats per channel of the LDS input patch
     // register-fed convolution (gemm_rf.h); rf_ts = 0: not used.  A then points at the packed weights.
     int32_t rf_ts, rf_tapk, rf_wgk;        // tile edge 32|16, tap mode 1|9|4|0 (-1: dense), K-waves per workgroup
@@ -184,5 +185,7 @@ int launch_rf_pack(const GemmArgs &a, const float *w, float *dst, void *stream);
 int epi_fast_flags(const Epilogue &e);
 // Whether the lean matrix-product kernel takes these sizes (pointer alignment aside).
 bool lean_mm_shape_ok(const GemmArgs &a, int epi_flags);
+// Whether the matrix-vector kernel takes these sizes (pointer alignment aside).
+bool gemv_shape_ok(const GemmArgs &a, int epi_flags);
 
 }  // namespace clg

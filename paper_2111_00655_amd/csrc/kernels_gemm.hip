@@ -369,11 +369,68 @@ static EpiFast make_epi_fast(const Epilogue &e) {
 
 int epi_fast_flags(const Epilogue &e) { return make_epi_fast(e).flags; }
 
+// ---- matrix-vector product: dense with a handful of rows (a classifier at batch 1) --------------
+// y[m][n] = sum_k x[m][k] * w[n][k], M <= 8.  The weights are read exactly once and
+// bound the kernel (HBM), so one wave owns one column n: it streams the 4K-byte
+// class row of w with 16-byte loads, all issued before the first use, multiplies it
+// with every row of x, and reduces across its lanes.
+constexpr int kGemvRows = 8;
+
+__global__ __launch_bounds__(256) void gemv_nt_kernel(GemmArgs p) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int n = blockIdx.x * (256 / kWave) + threadIdx.x / kWave;
+    if (n >= p.N) return;
+    const f32x4 *wrow = reinterpret_cast<const f32x4 *>(p.B + (int64_t)n * p.ldb);
+    const int k4 = p.K / 4;
+    float acc[kGemvRows];
+#pragma unroll
+    for (int m = 0; m < kGemvRows; ++m) acc[m] = 0.f;
+    for (int c0 = 0; c0 < k4; c0 += 8 * kWave) {
+        f32x4 w[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) w[u] = wrow[min(c0 + u * kWave + lane, k4 - 1)];
+#pragma unroll
+        for (int m = 0; m < kGemvRows; ++m) {
+            if (m >= p.M) break;
+            const f32x4 *xrow = reinterpret_cast<const f32x4 *>(p.A + (int64_t)m * p.lda);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int c = c0 + u * kWave + lane;
+                const f32x4 x = xrow[min(c, k4 - 1)];
+                const float d = w[u][0] * x[0] + w[u][1] * x[1] + w[u][2] * x[2] + w[u][3] * x[3];
+                acc[m] += c < k4 ? d : 0.f;
+            }
+        }
+    }
+#pragma unroll
+    for (int m = 0; m < kGemvRows; ++m) acc[m] = wave_sum(acc[m]);
+    float mine = 0.f;
+#pragma unroll
+    for (int m = 0; m < kGemvRows; ++m) mine = lane == m ? acc[m] : mine;      // lane m finishes row m
+    if (lane < p.M) {
+        const int64_t off = (int64_t)lane * p.ldc + n;
+        const float bv = (p.ef.flags & EF_BIAS) ? p.ef.bias[n] : 0.f;
+        const float av = (p.ef.flags & EF_ADD) ? p.ef.add[off] : 0.f;
+        p.C[off] = finish_value(p, mine, bv, av);
+    }
+}
+
+bool gemv_shape_ok(const GemmArgs &a, int epi_flags) {
+    // rows shorter than two 16-byte loads per lane leave most of a wave idle: those stay with the tiled kernels
+    return a.mode == GM_NT && a.batch == 1 && a.M >= 1 && a.M <= kGemvRows && a.K % 4 == 0 && a.K >= 512 && a.lda % 4 == 0 &&
+           a.ldb % 4 == 0 && a.cs_len == 0 && !(epi_flags & EF_GENERIC);
+}
+
 int launch_gemm(const GemmArgs &a_in, void *stream) {
     hipStream_t s = (hipStream_t)stream;
     GemmArgs a = a_in;
     a.ef = make_epi_fast(a.epi);
     if (a.rf_ts) return launch_rf_conv(a, s);
+    if (a.gemv) {
+        if (!al16(a.A) || !al16(a.B)) return (int)hipErrorInvalidValue;       // rows are read 16 bytes at a time
+        hipLaunchKernelGGL(gemv_nt_kernel, dim3((unsigned)((a.N + 3) / 4)), dim3(256), 0, s, a);
+        return (int)hipGetLastError();
+    }
     int err;
     const bool a_vec = a.K % 4 == 0 && a.lda % 4 == 0 && a.strideA % 4 == 0 && al16(a.A);
     switch (a.mode) {

@@ -391,6 +391,12 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
                 if (want_rf) a.tile = TILE_S8;           // what the register-fed kernels do not run goes to the LDS-tiled ones
                 gemm_resolve(&a, ctx.n_cus);
                 if (be.no_split) a.splitk = 1;
+                if (k0 == CLG_OP_DENSE && gemv_shape_ok(a, epi_fast_flags(epi))) {
+                    a.gemv = 1;                          // a handful of rows: the weights are streamed once, a wave per column
+                    a.splitk = 1;
+                    c.bound = 1;
+                    c.name = "gemv_nt";
+                }
                 if (a.cs_len) {
                     // only the lean kernel's K-wave tiles place columns block by block, and the
                     // split-K reduction derives a bias channel from the plain offset
@@ -401,7 +407,7 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
                 }
                 c.scratch_bytes = gemm_scratch_bytes(a);
                 static const char *tn[] = {"auto", "s", "m", "l", "s8", "s16"};
-                c.name += std::string("_") + tn[a.tile] + (a.splitk > 1 ? "_k" + std::to_string(a.splitk) : "");
+                if (!a.gemv) c.name += std::string("_") + tn[a.tile] + (a.splitk > 1 ? "_k" + std::to_string(a.splitk) : "");
             }
         }
         c.a_node = xa;

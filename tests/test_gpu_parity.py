@@ -192,9 +192,10 @@ def test_conv2d_transpose_other_geometries(geom, backend):
 DENSE_CASES = [(128, 768, 768, ("bias_add",)), (128, 768, 3072, ("bias_add", "gelu")),
                (128, 3072, 768, ("bias_add", "add")), (1, 2048, 1000, ("bias_add",)),
                (1, 32, 10, ("bias_add",)), (5, 100, 130, ("bias_add", "relu")), (130, 27, 70, ()),
-               (70, 4096, 50, ("bias_add", "relu")), (33, 48, 40, ("bias_add", "tanh"))]
+               (70, 4096, 50, ("bias_add", "relu")), (33, 48, 40, ("bias_add", "tanh")),
+               (8, 2100, 37, ("bias_add", "add")), (3, 100, 8192, ("bias_add", "relu"))]
 # which of them the register-fed dense kernel takes (K a multiple of 16); the others fall back to the LDS-tiled kernel
-DENSE_RF = {0, 1, 2, 3, 4, 7, 8}
+DENSE_RF = {0, 1, 2, 3, 4, 7, 8}          # (K = 2100 and K = 100 are not multiples of 8 / 16)
 
 
 @pytest.mark.parametrize("backend", IGEMM + RF)
@@ -216,6 +217,8 @@ def test_dense_fused(ci, backend):
     name, _ = run_single_group(d, backend, tail_pattern(P("dense", W, W), tail))
     if backend in RF:
         assert name.startswith("dense_rf") == (ci in DENSE_RF), name
+    else:
+        assert (name == "gemv_nt") == (m <= 8 and k % 4 == 0 and k >= 512), name
 
 
 @pytest.mark.parametrize("backend", ("igemm", "igemm_s", "igemm_s8", "igemm_s16") + RF)
