@@ -51,13 +51,13 @@ def kernel_sources_fingerprint():
     return h.hexdigest()[:16]
 
 
-def optimise(desc, reg, opts, cost_log=""):
+def optimise(desc, reg, opts, cost_log="", rules=()):
     """register -> match -> profile -> search -> compile; returns pieces + timings.
     With a cost log file, measured costs are reused from / added to it."""
     import paper_2111_00655_amd as clg
     from paper_2111_00655_amd import binding as B
     t0 = time.perf_counter()
-    s = clg.Session(desc, reg, device=0)
+    s = clg.Session(desc, reg, device=0, rules=rules)
     if cost_log and os.path.exists(cost_log):
         B.clg_cost_log_load(s.ctx, cost_log)
     t1 = time.perf_counter()
@@ -228,6 +228,8 @@ def main():
     ap.add_argument("--dump", default="", help="write the per-kernel table to this JSON file")
     ap.add_argument("--cost-log", default="", help="cost-log file: reuse measured subgraph costs from it, add new ones")
     ap.add_argument("--ablation", action="store_true", help="also time the placement under each single MFMA kernel variant")
+    ap.add_argument("--rules", action="store_true",
+                    help="build the registry with the pattern generator from pattern rules instead of the listed patterns")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MIB",
                     help="also run three plain device copies of MIB MiB (read MIB, write MIB): the known-size kernel "
                          "against which hardware byte counters of a profiled run are scaled")
@@ -247,8 +249,13 @@ def main():
     reg = wl.default_registry(VARIANTS)
     opts = B.ProfileOpts(warmup=10, batches=5, min_batch_us=200, max_launches=500)
 
+    rules = ()
+    if args.rules:
+        from workloads import patterns as wp
+        reg, rules = wp.rule_registry(VARIANTS)
     desc = wl.MODEL_BUILDERS[args.model](0)
-    s, plan, costs, ids, timing = optimise(desc, reg, opts, args.cost_log)
+    s, plan, costs, ids, timing = optimise(desc, reg, opts, args.cost_log, rules)
+    timing["n_patterns"] = B.clg_num_patterns(s.ctx)
     ms_per_step = time_steps(plan, args.steps, args.warmup)
     rows = kernel_table(plan)
     roof = roofline_of(rows, ms_per_step * 1e6)
@@ -268,7 +275,7 @@ def main():
             if name == args.model:
                 continue
             d2 = wl.MODEL_BUILDERS[name](0)
-            s2, p2, _, _, t2 = optimise(d2, reg, opts)
+            s2, p2, _, _, t2 = optimise(d2, reg, opts, "", rules)
             ms2 = time_steps(p2, max(20, args.steps // 2), args.warmup)
             r2 = kernel_table(p2, reps=5)
             extra[name] = dict(ms_per_step=round(ms2, 4), kernels=p2.n_kernels,

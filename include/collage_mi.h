@@ -237,6 +237,42 @@ int32_t clg_register_pattern(clg_ctx *ctx, int32_t backend,
                              const clg_pattern_node *nodes, int32_t n,
                              int32_t *pattern);
 int32_t clg_num_patterns(const clg_ctx *ctx, int32_t *n);
+/* Reads a registered pattern back: its backend and its nodes (post-order, as
+ * given to clg_register_pattern).  nodes: host array of cap entries, may be
+ * NULL when cap = 0 (count only); *n receives the node count.  UNKNOWN_ID,
+ * INVALID_ARG if cap is too small. */
+int32_t clg_get_pattern(const clg_ctx *ctx, int32_t pattern, int32_t *backend,
+                        clg_pattern_node *nodes, int32_t cap, int32_t *n);
+
+/* ---- pattern rules (Sec. 3: "pattern rule", automatic pattern generator) --- */
+/* The second way to describe a backend: instead of listing patterns, say which
+ * operators the backend runs and what it fuses; the generator then finds every
+ * legitimate pattern on a given graph and adds it to the registry.
+ * op_class[kind]: CLG_RULE_NONE (not run), CLG_RULE_FUSABLE (may seed a group
+ * that absorbs the element-wise operators after it: convolutions, matrix
+ * products) or CLG_RULE_ELEMWISE (may be absorbed; seeds a group of its own,
+ * which grows only if grow_from_elemwise is set).  max_ops bounds a group
+ * (1 .. CLG_MAX_MATCH_NODES). */
+#define CLG_RULE_NONE 0
+#define CLG_RULE_FUSABLE 1
+#define CLG_RULE_ELEMWISE 2
+typedef struct clg_pattern_rule {
+    int32_t op_class[CLG_OP_COUNT];
+    int32_t max_ops;
+    int32_t grow_from_elemwise;
+} clg_pattern_rule;
+/* Visits the operators of g in node order.  For an operator the rule runs, its
+ * own pattern (all operands wildcards) is registered for `backend`; then the
+ * group is widened one operator at a time - the sink's only consumer, if it is
+ * element-wise, uses the sink once, and the sink is not a graph output (a
+ * group becomes one kernel with a single exit) - registering the chain pattern
+ * after every step (other operands: wildcards).  Patterns this backend already
+ * has are not registered twice; patterns the backend's kernel family cannot
+ * run are skipped.  New patterns are appended to the registry in the order
+ * found; *n_added (may be NULL) receives their number.  Matches of g have to
+ * be enumerated again afterwards. */
+int32_t clg_generate_patterns(clg_ctx *ctx, clg_graph *g, int32_t backend,
+                              const clg_pattern_rule *rule, int32_t *n_added);
 
 /* ---- matches (Alg. 1: "find a subgraph g rooted at v_s that matches b_i") - */
 /* Enumerates every legal match of every registered pattern.  Legal: pattern

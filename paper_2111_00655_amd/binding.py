@@ -51,6 +51,13 @@ class AttrConstraint(C.Structure):
     _fields_ = [("attr", C.c_int32), ("lo", C.c_int64), ("hi", C.c_int64)]
 
 
+class PatternRule(C.Structure):
+    _fields_ = [("op_class", C.c_int32 * 17), ("max_ops", C.c_int32), ("grow_from_elemwise", C.c_int32)]
+
+
+RULE_NONE, RULE_FUSABLE, RULE_ELEMWISE = 0, 1, 2
+
+
 class PatternNode(C.Structure):
     _fields_ = [("op", C.c_int32), ("n_args", C.c_int32), ("args", C.c_int32 * MAX_PATTERN_ARGS),
                 ("n_constraints", C.c_int32), ("constraints", AttrConstraint * MAX_CONSTRAINTS)]
@@ -91,6 +98,8 @@ SYMBOLS = {
     "clg_register_backend": (C.c_int32, [_P, C.c_char_p, _i32p]),
     "clg_register_pattern": (C.c_int32, [_P, C.c_int32, C.POINTER(PatternNode), C.c_int32, _i32p]),
     "clg_num_patterns": (C.c_int32, [_P, _i32p]),
+    "clg_get_pattern": (C.c_int32, [_P, C.c_int32, _i32p, C.POINTER(PatternNode), C.c_int32, _i32p]),
+    "clg_generate_patterns": (C.c_int32, [_P, _P, C.c_int32, C.POINTER(PatternRule), _i32p]),
     "clg_match_all": (C.c_int32, [_P, _P, C.POINTER(Match), C.c_size_t, _szp]),
     "clg_profile_match": (C.c_int32, [_P, _P, C.c_int32, C.POINTER(ProfileOpts), _i64p]),
     "clg_profile_all": (C.c_int32, [_P, _P, C.POINTER(ProfileOpts), _i64p, C.c_size_t]),
@@ -277,6 +286,41 @@ def clg_register_pattern(ctx, backend, pattern):
 def clg_num_patterns(ctx):
     n = C.c_int32()
     _check(lib().clg_num_patterns(ctx, C.byref(n)))
+    return n.value
+
+
+def clg_get_pattern(ctx, pattern):
+    """(backend id, nested pattern (op, args, constraints)) of a registered pattern."""
+    n, be = C.c_int32(), C.c_int32()
+    _check(lib().clg_get_pattern(ctx, int(pattern), C.byref(be), None, 0, C.byref(n)))
+    arr = (PatternNode * n.value)()
+    _check(lib().clg_get_pattern(ctx, int(pattern), C.byref(be), arr, n.value, C.byref(n)))
+    attr_names = {v: k for k, v in ATTR_ID.items()}
+
+    def rec(i):
+        nd = arr[i]
+        if nd.op == WILDCARD:
+            return "*"
+        cons = tuple(sorted((attr_names[nd.constraints[k].attr], (int(nd.constraints[k].lo), int(nd.constraints[k].hi)))
+                            for k in range(nd.n_constraints)))
+        return (OP_KINDS[nd.op], tuple(rec(nd.args[k]) for k in range(nd.n_args)), cons)
+
+    return be.value, rec(n.value - 1)
+
+
+def make_rule(op_class, max_ops, grow_from_elemwise):
+    """op_class: operator kind name -> RULE_NONE / RULE_FUSABLE / RULE_ELEMWISE (missing kinds: none)."""
+    r = PatternRule()
+    for k, name in enumerate(OP_KINDS):
+        r.op_class[k] = int(op_class.get(name, RULE_NONE))
+    r.max_ops = int(max_ops)
+    r.grow_from_elemwise = 1 if grow_from_elemwise else 0
+    return r
+
+
+def clg_generate_patterns(ctx, g, backend, rule):
+    n = C.c_int32()
+    _check(lib().clg_generate_patterns(ctx, g, int(backend), C.byref(rule), C.byref(n)))
     return n.value
 
 

@@ -211,6 +211,29 @@ int32_t clg_num_patterns(const clg_ctx *ctx, int32_t *n) {
     return CLG_OK;
 }
 
+int32_t clg_get_pattern(const clg_ctx *ctx, int32_t pattern, int32_t *backend, clg_pattern_node *nodes, int32_t cap,
+                        int32_t *n) {
+    NEED(ctx); NEED(n);
+    if (pattern < 0 || pattern >= (int32_t)ctx->c.patterns.size()) return fail(CLG_UNKNOWN_ID, "pattern id %d", pattern);
+    const Pattern &p = ctx->c.patterns[pattern];
+    *n = (int32_t)p.nodes.size();
+    if (backend) *backend = p.backend;
+    if (cap == 0) return CLG_OK;
+    NEED(nodes);
+    if (cap < *n) return fail(CLG_INVALID_ARG, "pattern has %d nodes, room for %d", *n, cap);
+    std::copy(p.nodes.begin(), p.nodes.end(), nodes);
+    return CLG_OK;
+}
+
+int32_t clg_generate_patterns(clg_ctx *ctx, clg_graph *g, int32_t backend, const clg_pattern_rule *rule,
+                              int32_t *n_added) {
+    CLG_TRY
+    NEED(ctx); NEED(g); NEED(rule);
+    if (g->g.ctx != &ctx->c) return fail(CLG_INVALID_ARG, "graph belongs to another context");
+    return generate_patterns(ctx->c, g->g, backend, *rule, n_added);
+    CLG_CATCH
+}
+
 int32_t clg_match_all(clg_ctx *ctx, clg_graph *g, clg_match *out, size_t cap, size_t *n) {
     CLG_TRY
     NEED(ctx); NEED(g); NEED(n);

@@ -148,6 +148,8 @@ struct KernelCall {
 int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, KernelCall *out);
 // Structure check at registration time.
 int32_t check_pattern(const Context &ctx, Pattern *p);
+// Pattern generator (rules.cpp).
+int32_t generate_patterns(Context &ctx, Graph &g, int32_t backend, const clg_pattern_rule &rule, int32_t *n_added);
 
 // ---- plan -----------------------------------------------------------------------------
 struct Plan {

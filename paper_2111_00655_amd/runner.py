@@ -13,7 +13,11 @@ from . import binding as B
 
 
 class Session:
-    def __init__(self, desc, registry, device=0):
+    def __init__(self, desc, registry, device=0, rules=()):
+        """registry: (backend name, pattern) pairs, registered in order.  rules:
+        (backend name, op_class dict, max_ops, grow_from_elemwise) tuples; the
+        library's pattern generator adds their patterns for this graph after
+        the listed ones (see full_registry())."""
         self.desc = desc
         self.registry = list(registry)
         self.device = device
@@ -55,6 +59,22 @@ class Session:
         for o in desc.outputs:
             B.clg_graph_mark_output(self.graph, o)
         self.out_shapes = [B.clg_graph_node_shape(self.graph, o)[1] for o in desc.outputs]
+        self.generated = 0
+        for backend, op_class, max_ops, grow in rules:
+            bid = B.clg_register_backend(self.ctx, backend)
+            self.generated += B.clg_generate_patterns(self.ctx, self.graph, bid, B.make_rule(op_class, max_ops, grow))
+        self._backend_names = {}
+        for backend in [b for b, _ in self.registry] + [r[0] for r in rules]:
+            self._backend_names[B.clg_register_backend(self.ctx, backend)] = backend
+
+    def full_registry(self):
+        """The whole registry B in registration order, generated patterns included,
+        as (backend name, pattern) pairs read back from the library."""
+        out = []
+        for pid in range(B.clg_num_patterns(self.ctx)):
+            be, pat = B.clg_get_pattern(self.ctx, pid)
+            out.append((self._backend_names[be], pat))
+        return out
 
     # ---- steps of the path -----------------------------------------------------
     def match(self):

@@ -452,6 +452,34 @@ def test_model_under_searched_placement(name):
     s.close()
 
 
+@pytest.mark.parametrize("name", ["tiny_cnn", "resnet50", "bert_base", "dcgan_b1"])
+def test_model_under_a_rule_generated_registry(name):
+    """The registry comes from pattern rules (the generator walks this graph) plus the
+    few patterns no rule covers; matches and placement equal the oracle's over the
+    same registry, the outputs equal the oracle's."""
+    from workloads import patterns as wp
+    desc = wl.MODEL_BUILDERS[name](0)
+    explicit, rules = wp.rule_registry(("igemm_s8", "igemm_r16"))
+    s = clg.Session(desc, explicit, device=0, rules=rules)
+    assert s.generated > 0
+    reg = s.full_registry()
+    g = Graph(desc)
+    oms = enumerate_matches(g, reg)
+    lms = s.match()
+    assert [(m.pattern, m.first) for m in lms] == [(m.pattern, m.first) for m in oms]
+    costs = s.profile(B.ProfileOpts(warmup=3, batches=3, min_batch_us=50, max_launches=50))
+    got_search = s.search(costs, 0)
+    assert got_search == search.dp(g, reg, oms, costs, 0)
+    plan = s.compile(got_search[1])
+    got = plan.run()
+    ref = g.run()
+    errs = [norm_err(a, b) for a, b in zip(got, ref)]
+    print(name, "generated patterns", s.generated, "kernels", plan.n_kernels, "errors", errs)
+    assert max(errs) <= NET_TOL, errs
+    plan.destroy()
+    s.close()
+
+
 def test_profiler_is_repeatable_and_cached():
     desc = wl.resnet50(0, image=64, blocks=(1,))
     reg = wl.default_registry()

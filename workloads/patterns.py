@@ -131,3 +131,41 @@ def small_registry():
             ("A", P("mul_scalar", P("tanh", W))),
             ("A", P("add", P("mul_scalar", W), W))]
     return reg
+
+
+# ---- pattern rules (data only) ---------------------------------------------------
+RULE_NONE, RULE_FUSABLE, RULE_ELEMWISE = 0, 1, 2
+FUSABLE_OPS = ("conv2d", "conv2d_transpose", "dense", "batch_matmul")
+ELEMWISE_OPS = ("bias_add", "add", "mul_scalar", "relu", "gelu", "tanh")
+
+
+def listing_rule_classes():
+    """Operator classes of the rule sketched in the paper's registration
+    listing: convolutions and matrix products are fusable, the pointwise
+    operators element-wise, everything else is not run."""
+    cls = {k: RULE_FUSABLE for k in FUSABLE_OPS}
+    cls.update({k: RULE_ELEMWISE for k in ELEMWISE_OPS})
+    return cls
+
+
+def rule_registry(variants=("igemm",)):
+    """A registry described mostly by rules: (explicit pairs, rules).  Each MFMA
+    variant gets the fusable-seeded rule (a contraction plus its element-wise
+    tail, up to nine operators), the element-wise kernel family the
+    element-wise-seeded one; what no rule covers (row-wise reductions, pools,
+    gather, layout copies) is listed explicitly."""
+    fus = {k: RULE_FUSABLE for k in FUSABLE_OPS}
+    fus.update({k: RULE_ELEMWISE for k in ELEMWISE_OPS})
+    elt = {k: RULE_ELEMWISE for k in ELEMWISE_OPS}
+    # an MFMA backend runs groups seeded by a contraction only (the generator drops what its kernels do not
+    # run); the element-wise family gets the element-wise operators as seeds of growing groups
+    rules = [(be, dict(fus), 9, False) for be in variants]
+    rules.append(("eltwise", elt, 8, True))
+    explicit = [("eltwise", p) for p in (P("take", W, W), P("reshape", W), P("transpose", W),
+                                         P("add", P("add", P("take", W, W), W), W),
+                                         P("transpose", P("reshape", W)), P("reshape", P("transpose", W)))]
+    explicit += [("rowwise", p) for p in (P("softmax", W), P("layer_norm", W, W, W),
+                                          P("softmax", P("mul_scalar", W)),
+                                          P("layer_norm", P("add", W, W), W, W))]
+    explicit += [("direct", p) for p in (P("max_pool2d", W), P("global_avg_pool2d", W))]
+    return explicit, rules
