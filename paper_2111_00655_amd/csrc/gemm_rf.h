@@ -373,7 +373,12 @@ __global__ __launch_bounds__(WGK *kWave) void dense_rf_kernel(GemmArgs p) {
     const f32x4 *const Ab = reinterpret_cast<const f32x4 *>(p.B) + (int64_t)mt * p.rf_ngtot * kWave;
     const f32x4 *const Xb = reinterpret_cast<const f32x4 *>(p.A);
     const uint32_t lane_u = (uint32_t)lane;
-    const uint32_t x_lane = (uint32_t)(min(j0 + r, p.M - 1) * (p.lda / 4) + s);      // in 16-byte units
+    // The 16 bytes lane (slot s, column r) needs lie at row r, k-part s.  Loaded by that lane itself, neighbouring
+    // lanes would touch different rows; instead lane l loads row l / NSLOT, part l % NSLOT (neighbouring lanes
+    // read neighbouring addresses) and the values change lanes afterwards (ds_bpermute: no memory access).
+    const int lrow = lane / NSLOT, lpart = lane % NSLOT;
+    const uint32_t x_lane = (uint32_t)(min(j0 + lrow, p.M - 1) * (p.lda / 4) + lpart);      // in 16-byte units
+    const int src_lane4 = (r * NSLOT + s) * 4;                                            // byte address for ds_bpermute
     const int nch = p.rf_nch;
     const int c0 = (ks * WGK + w) * nch;
     const int g_last = p.K / (4 * NSLOT) - 1;
@@ -412,7 +417,11 @@ __global__ __launch_bounds__(WGK *kWave) void dense_rf_kernel(GemmArgs p) {
     } while (0)
 #define CLG_RFD_MMA(set)                                                                      \
     do {                                                                                      \
-        _Pragma("unroll") for (int u = 0; u < 16; ++u) acc = MF::mma(a[set][u / 4][u % 4], b[set][u / 4][u % 4], acc); \
+        _Pragma("unroll") for (int u = 0; u < 16; ++u) {                                      \
+            const float own_ = b[set][u / 4][u % 4];      /* (a copy: not the vector element itself) */ \
+            const float bv_ = __int_as_float(__builtin_amdgcn_ds_bpermute(src_lane4, __float_as_int(own_))); \
+            acc = MF::mma(a[set][u / 4][u % 4], bv_, acc);                                    \
+        }                                                                                     \
     } while (0)
     CLG_RFD_LOAD(0, 0);
     int c = 0;
