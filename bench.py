@@ -228,6 +228,8 @@ def main():
     ap.add_argument("--dump", default="", help="write the per-kernel table to this JSON file")
     ap.add_argument("--cost-log", default="", help="cost-log file: reuse measured subgraph costs from it, add new ones")
     ap.add_argument("--ablation", action="store_true", help="also time the placement under each single MFMA kernel variant")
+    ap.add_argument("--batch-sweep", default="", metavar="B1,B2,...",
+                    help="also time ResNeXt-50 at these batch sizes (the paper's Fig. 8 varies the batch for this model)")
     ap.add_argument("--rules", action="store_true",
                     help="build the registry with the pattern generator from pattern rules instead of the listed patterns")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MIB",
@@ -285,6 +287,17 @@ def main():
             p2.destroy()
             s2.close()
 
+    sweep = None
+    if args.batch_sweep:
+        sweep = {}
+        for b in [int(x) for x in args.batch_sweep.split(",")]:
+            d2 = wl.resnext50(0, batch=b)
+            s2, p2, _, _, t2 = optimise(d2, reg, opts, "", rules)
+            ms2 = time_steps(p2, max(20, args.steps // 4), args.warmup)
+            sweep[str(b)] = dict(ms_per_step=round(ms2, 4), images_per_s=round(b / ms2 * 1e3, 1), kernels=p2.n_kernels)
+            p2.destroy()
+            s2.close()
+
     cpu = None if args.no_cpu else cpu_baseline(desc)
 
     if args.calib_copy:
@@ -322,6 +335,7 @@ def main():
         "graph_replay_ms": None if graph_ms is None else round(graph_ms, 4),
         "cold_cache_ms": round(cold_ms, 4),
         "ablation_ms": abl,
+        "resnext50_batch_sweep": sweep,
         "empty_launch_ns": int(empty_ns),
         "optimise": {k: (round(v, 4) if isinstance(v, float) else v) for k, v in timing.items()},
         "other_workloads": extra,

@@ -480,6 +480,25 @@ def test_model_under_a_rule_generated_registry(name):
     s.close()
 
 
+@pytest.mark.parametrize("batch", [2, 5])
+def test_resnext_at_larger_batch(batch):
+    """The paper also varies the batch size (its Fig. 8, ResNeXt-50): the whole path at
+    batch > 1 on a reduced ResNeXt (grouped 3x3, strided projection, residual adds)."""
+    desc = wl.resnext50(0, image=64, width=32, blocks=(2, 1), groups=8, classes=20, batch=batch)
+    reg = wl.default_registry(("igemm_s8", "igemm_r32", "igemm_r16"))
+    s, g, oms = _session_and_oracle(desc, reg)
+    costs = s.profile(B.ProfileOpts(warmup=3, batches=3, min_batch_us=50, max_launches=50))
+    got_search = s.search(costs, 0)
+    assert got_search == search.dp(g, reg, oms, costs, 0)
+    plan = s.compile(got_search[1])
+    got = plan.run()
+    ref = g.run()
+    assert got[0].shape == (batch, 20)
+    assert max(norm_err(a, b) for a, b in zip(got, ref)) <= NET_TOL
+    plan.destroy()
+    s.close()
+
+
 def test_profiler_is_repeatable_and_cached():
     desc = wl.resnet50(0, image=64, blocks=(1,))
     reg = wl.default_registry()

@@ -79,14 +79,14 @@ def tiny_cnn(seed: int = 0, image: int = 32) -> GraphDesc:
 # --------------------------------------------------------------------------
 def resnet50(seed: int = 0, image: int = 224, width: int = 64,
              blocks=(3, 4, 6, 3), groups: int = 1, group_width_mult: int = 1,
-             classes: int = 1000, name: str = "resnet50") -> GraphDesc:
+             classes: int = 1000, name: str = "resnet50", batch: int = 1) -> GraphDesc:
     """v1.5: the stride-2 convolution of a down-sampling bottleneck is its
     3x3 one; the first block of every stage has a 1x1 projection shortcut.
     `group_width_mult` widens the inner (3x3) channels: 2 with groups=32
     gives the 32x4d ResNeXt layout (128/256/512/1024 inner channels)."""
     g = GraphDesc(name)
     rw, rx = _Rng(seed), _Rng(seed + 1000003)
-    x = g.input(rx.normal((1, 3, image, image)), "x")
+    x = g.input(rx.normal((batch, 3, image, image)), "x")
     y = _conv(g, rw, x, 3, width, 7, 2, 3, name="stem")
     y = g.op("max_pool2d", [y], "pool", kernel=(3, 3), stride=(2, 2),
              pad=(1, 1))
@@ -121,9 +121,9 @@ def resnet50(seed: int = 0, image: int = 224, width: int = 64,
 
 def resnext50(seed: int = 0, image: int = 224, width: int = 64,
               blocks=(3, 4, 6, 3), groups: int = 32,
-              classes: int = 1000) -> GraphDesc:
+              classes: int = 1000, batch: int = 1) -> GraphDesc:
     return resnet50(seed, image, width, blocks, groups=groups,
-                    group_width_mult=2, classes=classes, name="resnext50")
+                    group_width_mult=2, classes=classes, name="resnext50", batch=batch)
 
 
 # --------------------------------------------------------------------------
