@@ -1,0 +1,136 @@
+"""Graph-level placement (paper Sec. 4.2): the evolutionary search over digit strings.
+
+The oracle's search is pinned by a generation worked by hand and by what must hold for any
+fitness; the library's search must then equal the oracle's draw for draw."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from oracle import evolve as oe
+
+HERE = os.path.dirname(__file__)
+
+
+def worked_example():
+    out = {}
+    for line in open(os.path.join(HERE, "golden", "evolve_worked_example.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        k, *v = line.split()
+        out[k] = v
+    return out
+
+
+def example_cost(b):
+    return 10 - 3 * b[0] - 2 * b[2] + 4 * b[0] * b[2] + b[1]
+
+
+EXAMPLE_OPTS = dict(population=2, generations=1, tournament=2, p_init=0.5, p_mutate=0.5, p_flip=0.5, p_cross=1.0)
+
+
+def u32(fracs):
+    return [int(float(f) * 4294967296.0) for f in fracs]
+
+
+def random_cost_table(n, seed):
+    """A cost per string with pairwise terms, so that it is not a sum over digits."""
+    r = np.random.default_rng(seed)
+    lin = r.uniform(-1, 1, n)
+    pair = np.triu(r.uniform(-1, 1, (n, n)), 1)
+
+    def cost(b):
+        v = np.asarray(b, dtype=np.float64)
+        return float(10 + lin @ v + v @ pair @ v)
+    return cost
+
+
+def draws(seed, count=20000):
+    return np.random.default_rng(seed).integers(0, 2 ** 32, count, dtype=np.uint64).tolist()
+
+
+# ---- the oracle against facts that do not come from it ---------------------------------------------
+def test_oracle_reproduces_the_generation_worked_by_hand():
+    ex = worked_example()
+    best, cost, evals, hist = oe.evolve(4, example_cost, u32(ex["draws"]), **EXAMPLE_OPTS)
+    assert best == [int(x) for x in ex["best"]]
+    assert cost == float(ex["best_cost"][0])
+    assert evals == int(ex["evaluations"][0])
+    assert hist == [float(x) for x in ex["history"]]
+    # the hand derivation also says this is the minimum over all strings
+    assert cost == min(example_cost(b) for b in itertools.product((0, 1), repeat=4))
+
+
+def test_oracle_uses_exactly_the_draws_of_the_worked_example():
+    ex = worked_example()
+    r = u32(ex["draws"])
+    with pytest.raises(ValueError):
+        oe.evolve(4, example_cost, r[:-1], **EXAMPLE_OPTS)
+    oe.evolve(4, example_cost, r, **EXAMPLE_OPTS)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_oracle_invariants_for_any_cost(seed):
+    n = 7
+    cost = random_cost_table(n, seed)
+    seen = []
+
+    def f(b):
+        seen.append(tuple(b))
+        return cost(b)
+    best, c, evals, hist = oe.evolve(n, f, draws(seed), population=6, generations=12, tournament=3,
+                                     p_init=0.3, p_mutate=0.6, p_flip=0.2, p_cross=0.7)
+    assert len(seen) == len(set(seen)) == evals               # a string is measured once
+    assert seen[0] == (0,) * n                                # the operator-level placement is a seed
+    assert c == cost(best) == min(cost(b) for b in seen)      # best ever evaluated
+    assert c <= cost([0] * n)                                 # never worse than the seed
+    assert all(a >= b for a, b in zip(hist, hist[1:])) and hist[-1] == c and len(hist) == 13
+
+
+def test_oracle_finds_the_exhaustive_minimum_on_small_strings():
+    n = 6
+    for seed in range(4):
+        cost = random_cost_table(n, 100 + seed)
+        _, c, evals, _ = oe.evolve(n, cost, draws(seed, 200000), population=16, generations=80, tournament=3,
+                                   p_init=0.5, p_mutate=0.8, p_flip=0.25, p_cross=0.7)
+        assert c == min(cost(b) for b in itertools.product((0, 1), repeat=n))
+        assert evals <= 2 ** n
+
+
+def test_oracle_without_mutation_and_crossover_only_selects():
+    n = 8
+    cost = random_cost_table(n, 5)
+    seen = []
+
+    def f(b):
+        seen.append(tuple(b))
+        return cost(b)
+    _, c, evals, hist = oe.evolve(n, f, draws(3), population=8, generations=5, p_init=0.5, p_mutate=0.0, p_cross=0.0)
+    assert evals == len(set(seen)) <= 8 and hist == [c] * 6
+
+
+def test_oracle_crossover_keeps_every_position_s_digits():
+    # p_mutate = 0: whatever crossover does, the multiset of digits at each position of the two
+    # strings is unchanged, so with a population of 2 and both strings surviving selection
+    # (tournament of 1 = a copy of a random member) position-wise sums never exceed the initial ones
+    n = 10
+    seen = []
+
+    def f(b):
+        seen.append(tuple(b))
+        return float(sum(b))
+    oe.evolve(n, f, draws(11), population=2, generations=20, tournament=1, p_init=0.5, p_mutate=0.0, p_cross=1.0)
+    first = seen[1]                                           # the random member; the seed is all zeros
+    for s in seen:
+        assert all(x <= y for x, y in zip(s, first))          # a 1 can only come from the random member
+
+
+def test_oracle_patience_stops_early():
+    calls = []
+
+    def f(b):
+        calls.append(1)
+        return 1.0                                            # nothing ever improves
+    _, _, _, hist = oe.evolve(5, f, draws(1), population=4, generations=50, patience=3)
+    assert len(hist) == 4
