@@ -230,6 +230,8 @@ def main():
     ap.add_argument("--ablation", action="store_true", help="also time the placement under each single MFMA kernel variant")
     ap.add_argument("--batch-sweep", default="", metavar="B1,B2,...",
                     help="also time ResNeXt-50 at these batch sizes (the paper's Fig. 8 varies the batch for this model)")
+    ap.add_argument("--graph-level", default="", metavar="MODEL,...",
+                    help="also run the graph-level evolutionary search (paper Sec. 4.2) on these workloads' op-level plans")
     ap.add_argument("--rules", action="store_true",
                     help="build the registry with the pattern generator from pattern rules instead of the listed patterns")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MIB",
@@ -298,6 +300,25 @@ def main():
             p2.destroy()
             s2.close()
 
+    graph_level = None
+    if args.graph_level:
+        import numpy as np
+        graph_level = {}
+        for name in args.graph_level.split(","):
+            d2 = wl.MODEL_BUILDERS[name](0)
+            s2, p2, _, _, _ = optimise(d2, reg, opts, "", rules)
+            p2.bind()
+            rand = np.random.default_rng(0).integers(0, 2 ** 32, 1 << 20, dtype=np.uint64).tolist()
+            t0 = time.perf_counter()
+            best, best_ns, seed_ns, evals, hist = p2.search_graph_level(
+                B.make_es_opts(population=8, generations=6, tournament=3, p_init=0.1, p_mutate=0.5, p_flip=0.05, p_cross=0.5),
+                rand, lanes=2, warmup=3, batches=3, reps=20)
+            graph_level[name] = dict(op_level_ms=round(seed_ns / 1e6, 4), graph_level_ms=round(best_ns / 1e6, 4),
+                                     kernels=p2.n_kernels, handed_over=int(sum(best)), strings_measured=evals,
+                                     history_ms=[round(h / 1e6, 4) for h in hist], search_s=round(time.perf_counter() - t0, 2))
+            p2.destroy()
+            s2.close()
+
     cpu = None if args.no_cpu else cpu_baseline(desc)
 
     if args.calib_copy:
@@ -336,6 +357,7 @@ def main():
         "cold_cache_ms": round(cold_ms, 4),
         "ablation_ms": abl,
         "resnext50_batch_sweep": sweep,
+        "graph_level_search": graph_level,
         "empty_launch_ns": int(empty_ns),
         "optimise": {k: (round(v, 4) if isinstance(v, float) else v) for k, v in timing.items()},
         "other_workloads": extra,

@@ -327,6 +327,85 @@ int32_t clg_match_key(clg_ctx *ctx, clg_graph *g, int32_t match, char *buf,
 int32_t clg_search_dp(clg_ctx *ctx, clg_graph *g, const int64_t *cost_ns,
                       size_t n_costs, int64_t eps_ns, int32_t *chosen,
                       size_t cap, size_t *n_chosen, int64_t *total_ns);
+/* ---- graph-level placement search (Sec. 4.2) ------------------------------ */
+/* Evolutionary search over strings of n digits.  Digit i = 0 keeps the
+ * op-level decision for item i, 1 hands item i to the graph-level backend;
+ * what an item is and what the handing-over does is the fitness function's
+ * business (clg_search_graph_level below supplies the library's own).  fitness
+ * returns the cost of a string measured on the whole graph (lower is better;
+ * NaN aborts the search with INVALID_ARG); it is called once per distinct
+ * string, from the calling thread.
+ * The population is the all-zero string plus population-1 strings whose
+ * digits are 1 with probability p_init.  One generation: every string mutates
+ * with probability p_mutate (each digit then flips with probability p_flip);
+ * `population` tournaments of `tournament` entrants drawn with replacement
+ * choose the next population (an entrant wins only when strictly cheaper);
+ * neighbours (0,1), (2,3).. swap, with probability p_cross, the digits between
+ * two cut points drawn from 0..n; the new strings are measured.  The search
+ * ends after `generations` generations, or after `patience` (> 0) generations
+ * in a row without a new best.  The result is the cheapest string ever
+ * measured (the earliest among equals), so it never costs more than the seed.
+ * Randomness: rand is a host array of n_rand 32-bit draws consumed in order;
+ * probability p happens when draw / 2^32 < p, an index below m is
+ * (draw * m) >> 32.  Equal draws and an equal fitness function give equal
+ * results.  INVALID_ARG when the draws run out (a generation uses at most
+ * population * (n + 1 + tournament) + 3 * (population / 2) of them, the initial
+ * population (population - 1) * n).
+ * best: host, n bytes.  history (may be null): host, generations + 1 doubles,
+ * history[g] = best cost after g generations.  evaluations, generations_run
+ * (may be null): distinct strings measured, generations done. */
+typedef double (*clg_fitness_fn)(const uint8_t *digits, size_t n, void *user);
+typedef struct clg_es_opts {
+    int32_t population;      /* >= 2                                  */
+    int32_t generations;     /* >= 0                                  */
+    int32_t tournament;      /* >= 1                                  */
+    int32_t patience;        /* 0 = run all generations               */
+    double p_init, p_mutate, p_flip, p_cross;   /* each in [0, 1]     */
+} clg_es_opts;
+int32_t clg_evolve(size_t n, const clg_es_opts *opts, const uint32_t *rand,
+                   size_t n_rand, clg_fitness_fn fitness, void *user,
+                   uint8_t *best, double *best_cost, int64_t *evaluations,
+                   double *history, int32_t *generations_run);
+
+/* The library's own graph-level backend is the plan's lane scheduler (see
+ * clg_plan_set_lanes): an item is one kernel of the compiled op-level
+ * placement, digit 1 hands it to the scheduler, which may then run it on
+ * another HIP stream beside independent kernels, digit 0 keeps it in its place
+ * on the caller's stream.  What a handed-over kernel gains or loses depends
+ * on which of its neighbours are handed over as well, so strings are priced
+ * by timing the whole sequence.
+ * clg_plan_set_handover: digits: host, n = clg_plan_num_kernels bytes (0/1);
+ * lanes: 2..4 streams for the scheduler.  All zeros = the op-level plan.
+ * Waits for the plan's streams; not to be called while the plan executes.
+ * clg_plan_measure: time of one clg_execute in ns: opts->warmup executions,
+ * then opts->batches (>= 1) batches of opts->reps (>= 1) executions between
+ * two events on `stream`; the smallest batch mean.  Arguments as clg_execute;
+ * blocks until done.
+ * clg_search_graph_level: clg_evolve over the plan's kernels with that
+ * measurement as the fitness; every distinct string is set, timed and kept.
+ * best: host, clg_plan_num_kernels bytes; *best_ns its time; *seed_ns (may be
+ * null) the time of the all-zero string, i.e. of the op-level placement, so
+ * *best_ns <= *seed_ns.  On return the plan is set to `best`.  evaluations,
+ * history, generations_run as in clg_evolve (history in ns). */
+typedef struct clg_measure_opts {
+    int32_t warmup, batches, reps;
+} clg_measure_opts;
+int32_t clg_plan_set_handover(clg_plan *plan, const uint8_t *digits, size_t n,
+                              int32_t lanes);
+int32_t clg_plan_measure(clg_plan *plan, const void *const *inputs,
+                         void *const *outputs, void *workspace,
+                         size_t workspace_bytes, void *stream,
+                         const clg_measure_opts *opts, int64_t *ns);
+int32_t clg_search_graph_level(clg_plan *plan, const void *const *inputs,
+                               void *const *outputs, void *workspace,
+                               size_t workspace_bytes, void *stream,
+                               int32_t lanes, const clg_es_opts *opts,
+                               const uint32_t *rand, size_t n_rand,
+                               const clg_measure_opts *measure, uint8_t *best,
+                               int64_t *best_ns, int64_t *seed_ns,
+                               int64_t *evaluations, double *history,
+                               int32_t *generations_run);
+
 /* Sizes of the last search on this graph: operators N, most matches at one
  * frontier P, most new frontiers from one match F, largest relaxed set S, and
  * the number of stored sub-placements. */

@@ -69,6 +69,24 @@ class Match(C.Structure):
                 ("binding", C.c_int32 * MAX_MATCH_NODES)]
 
 
+class EsOpts(C.Structure):
+    _fields_ = [("population", C.c_int32), ("generations", C.c_int32), ("tournament", C.c_int32),
+                ("patience", C.c_int32), ("p_init", C.c_double), ("p_mutate", C.c_double),
+                ("p_flip", C.c_double), ("p_cross", C.c_double)]
+
+
+FITNESS_FN = C.CFUNCTYPE(C.c_double, C.POINTER(C.c_uint8), C.c_size_t, C.c_void_p)
+
+
+def make_es_opts(population=8, generations=10, tournament=3, patience=0,
+                 p_init=0.25, p_mutate=0.5, p_flip=0.1, p_cross=0.5):
+    return EsOpts(population, generations, tournament, patience, p_init, p_mutate, p_flip, p_cross)
+
+
+class MeasureOpts(C.Structure):
+    _fields_ = [("warmup", C.c_int32), ("batches", C.c_int32), ("reps", C.c_int32)]
+
+
 class ProfileOpts(C.Structure):
     _fields_ = [("warmup", C.c_int32), ("batches", C.c_int32), ("min_batch_us", C.c_int32),
                 ("max_launches", C.c_int32), ("seed", C.c_uint64), ("no_cache", C.c_int32)]
@@ -117,6 +135,16 @@ SYMBOLS = {
     "clg_plan_kernel_info": (C.c_int32, [_P, C.c_size_t, C.POINTER(KernelInfo)]),
     "clg_plan_set_lanes": (C.c_int32, [_P, C.c_int32]),
     "clg_plan_num_lanes": (C.c_int32, [_P, _i32p]),
+    "clg_plan_set_handover": (C.c_int32, [_P, C.POINTER(C.c_uint8), C.c_size_t, C.c_int32]),
+    "clg_plan_measure": (C.c_int32, [_P, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_void_p, C.c_size_t,
+                                     C.c_void_p, C.POINTER(MeasureOpts), _i64p]),
+    "clg_search_graph_level": (C.c_int32, [_P, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_void_p, C.c_size_t,
+                                           C.c_void_p, C.c_int32, C.POINTER(EsOpts), C.POINTER(C.c_uint32), C.c_size_t,
+                                           C.POINTER(MeasureOpts), C.POINTER(C.c_uint8), _i64p, _i64p, _i64p,
+                                           C.POINTER(C.c_double), _i32p]),
+    "clg_evolve": (C.c_int32, [C.c_size_t, C.POINTER(EsOpts), C.POINTER(C.c_uint32), C.c_size_t, FITNESS_FN,
+                               C.c_void_p, C.POINTER(C.c_uint8), C.POINTER(C.c_double), C.POINTER(C.c_int64),
+                               C.POINTER(C.c_double), _i32p]),
     "clg_execute": (C.c_int32, [_P, C.POINTER(_P), C.POINTER(_P), _P, C.c_size_t, _P]),
     "clg_execute_timed": (C.c_int32, [_P, C.POINTER(_P), C.POINTER(_P), _P, C.c_size_t, _P, _i64p, C.c_size_t]),
 }
@@ -324,6 +352,30 @@ def clg_generate_patterns(ctx, g, backend, rule):
     return n.value
 
 
+# ---- graph-level search ---------------------------------------------------------------
+def clg_evolve(n, opts, rand, fitness):
+    """fitness: Python callable on a list of digits.  Returns (best digits, best cost,
+    evaluations, history up to the generations run)."""
+    raised = []
+
+    def call(digits, count, _user):
+        try:
+            return float(fitness([digits[i] for i in range(count)]))
+        except BaseException as e:            # must not unwind through the C frames
+            raised.append(e)
+            return float("nan")
+    r = (C.c_uint32 * max(len(rand), 1))(*[int(x) for x in rand])
+    best = (C.c_uint8 * max(n, 1))()
+    cost, evals, gens = C.c_double(), C.c_int64(), C.c_int32()
+    hist = (C.c_double * (opts.generations + 1))()
+    rc = lib().clg_evolve(n, C.byref(opts), r, len(rand), FITNESS_FN(call), None, best, C.byref(cost),
+                          C.byref(evals), hist, C.byref(gens))
+    if raised:
+        raise raised[0]
+    _check(rc)
+    return [best[i] for i in range(n)], cost.value, evals.value, [hist[i] for i in range(gens.value + 1)]
+
+
 # ---- matches ------------------------------------------------------------------------
 def clg_match_all(ctx, g):
     n = C.c_size_t()
@@ -447,3 +499,32 @@ def clg_execute_timed(plan, inputs, outputs, workspace, ws_bytes, stream=0):
     _check(lib().clg_execute_timed(plan, _ptr_array(inputs), _ptr_array(outputs), _P(int(workspace) or None),
                                    int(ws_bytes), _P(int(stream) or None), ns.ctypes.data_as(_i64p), ns.size))
     return ns[:n]
+
+
+def clg_plan_set_handover(plan, digits, lanes=2):
+    d = (C.c_uint8 * max(len(digits), 1))(*[int(x) for x in digits])
+    _check(lib().clg_plan_set_handover(plan, d, len(digits), int(lanes)))
+
+
+def clg_plan_measure(plan, inputs, outputs, workspace, ws_bytes, stream=0, warmup=5, batches=5, reps=20):
+    ns = C.c_int64()
+    m = MeasureOpts(warmup, batches, reps)
+    _check(lib().clg_plan_measure(plan, _ptr_array(inputs), _ptr_array(outputs), _P(int(workspace) or None),
+                                  int(ws_bytes), _P(int(stream) or None), C.byref(m), C.byref(ns)))
+    return ns.value
+
+
+def clg_search_graph_level(plan, inputs, outputs, workspace, ws_bytes, stream, lanes, opts, rand,
+                           warmup=3, batches=3, reps=20):
+    """Returns (best digits, best ns, seed ns, evaluations, history)."""
+    n = clg_plan_num_kernels(plan)
+    r = (C.c_uint32 * max(len(rand), 1))(*[int(x) for x in rand])
+    best = (C.c_uint8 * max(n, 1))()
+    best_ns, seed_ns, evals, gens = C.c_int64(), C.c_int64(), C.c_int64(), C.c_int32()
+    hist = (C.c_double * (opts.generations + 1))()
+    m = MeasureOpts(warmup, batches, reps)
+    _check(lib().clg_search_graph_level(plan, _ptr_array(inputs), _ptr_array(outputs), _P(int(workspace) or None),
+                                        int(ws_bytes), _P(int(stream) or None), int(lanes), C.byref(opts), r, len(rand),
+                                        C.byref(m), best, C.byref(best_ns), C.byref(seed_ns), C.byref(evals), hist,
+                                        C.byref(gens)))
+    return [best[i] for i in range(n)], best_ns.value, seed_ns.value, evals.value, [hist[i] for i in range(gens.value + 1)]

@@ -19,7 +19,7 @@ BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libcollage_mi.so")
 
 SOURCES = ["graph.cpp", "matcher.cpp", "search.cpp", "lower.cpp", "plan.cpp",
-           "profiler.cpp", "rules.cpp", "capi.cpp", "kernels_gemm.hip", "gemm_fast_mm.hip", "gemm_fast_conv.hip",
+           "profiler.cpp", "rules.cpp", "evolve.cpp", "capi.cpp", "kernels_gemm.hip", "gemm_fast_mm.hip", "gemm_fast_conv.hip",
            "gemm_lean_mm.hip", "gemm_lean_conv.hip", "gemm_rf.hip",
            "kernels_misc.hip"]
 

@@ -1,6 +1,7 @@
 // The C ABI (include/collage_mi.h): argument checking and marshalling only.
 #include <cstdio>
 #include <new>
+#include <string>
 
 #include <hip/hip_runtime_api.h>
 
@@ -384,10 +385,119 @@ int32_t clg_plan_num_kernels(const clg_plan *plan, size_t *n) {
     return CLG_OK;
 }
 
+static int32_t check_es_opts(const clg_es_opts *o) {
+    if (o->population < 2 || o->population > 4096) return fail(CLG_INVALID_ARG, "population must be 2..4096 (got %d)", o->population);
+    if (o->generations < 0) return fail(CLG_INVALID_ARG, "generations %d", o->generations);
+    if (o->tournament < 1 || o->tournament > 4096) return fail(CLG_INVALID_ARG, "tournament must be 1..4096 (got %d)", o->tournament);
+    if (o->patience < 0) return fail(CLG_INVALID_ARG, "patience %d", o->patience);
+    for (double p : {o->p_init, o->p_mutate, o->p_flip, o->p_cross})
+        if (!(p >= 0.0 && p <= 1.0)) return fail(CLG_INVALID_ARG, "a probability is outside [0, 1]");
+    return CLG_OK;
+}
+
+int32_t clg_evolve(size_t n, const clg_es_opts *opts, const uint32_t *rand, size_t n_rand, clg_fitness_fn fitness,
+                   void *user, uint8_t *best, double *best_cost, int64_t *evaluations, double *history,
+                   int32_t *generations_run) {
+    CLG_TRY
+    NEED(opts); NEED(fitness); NEED(best_cost);
+    if (n && !best) return fail(CLG_INVALID_ARG, "clg_evolve: best is null");
+    if (n_rand && !rand) return fail(CLG_INVALID_ARG, "clg_evolve: rand is null");
+    if (n > (1u << 20)) return fail(CLG_INVALID_ARG, "%zu digits", n);
+    const int32_t rc = check_es_opts(opts);
+    if (rc != CLG_OK) return rc;
+    return evolve(n, *opts, rand, n_rand, fitness, user, best, best_cost, evaluations, history, generations_run);
+    CLG_CATCH
+}
+
+static int32_t check_measure_opts(const clg_measure_opts *m) {
+    if (m->warmup < 0 || m->batches < 1 || m->reps < 1 || m->batches > 1000 || m->reps > 100000)
+        return fail(CLG_INVALID_ARG, "measure options: warmup %d batches %d reps %d", m->warmup, m->batches, m->reps);
+    return CLG_OK;
+}
+
+int32_t clg_plan_set_handover(clg_plan *plan, const uint8_t *digits, size_t n, int32_t lanes) {
+    CLG_TRY
+    NEED(plan);
+    if (n != plan->p.calls.size()) return fail(CLG_INVALID_ARG, "%zu digits for a plan of %zu kernels", n, plan->p.calls.size());
+    if (n && !digits) return fail(CLG_INVALID_ARG, "clg_plan_set_handover: digits is null");
+    if (lanes < 2 || lanes > 4) return fail(CLG_INVALID_ARG, "lanes must be 2..4 (got %d)", lanes);
+    for (size_t i = 0; i < n; ++i)
+        if (digits[i] > 1) return fail(CLG_INVALID_ARG, "digit %zu is %d", i, (int)digits[i]);
+    plan->p.handed.assign(digits, digits + n);
+    return set_plan_lanes(plan->p, lanes);
+    CLG_CATCH
+}
+
+int32_t clg_plan_measure(clg_plan *plan, const void *const *inputs, void *const *outputs, void *workspace,
+                         size_t workspace_bytes, void *stream, const clg_measure_opts *opts, int64_t *ns) {
+    CLG_TRY
+    NEED(plan); NEED(opts); NEED(ns);
+    const int32_t rc = check_measure_opts(opts);
+    if (rc != CLG_OK) return rc;
+    return measure_plan(plan->p, inputs, outputs, workspace, workspace_bytes, stream, *opts, ns);
+    CLG_CATCH
+}
+
+namespace {
+struct GraphLevelJob {
+    clg_plan *plan;
+    const void *const *inputs;
+    void *const *outputs;
+    void *workspace;
+    size_t ws_bytes;
+    void *stream;
+    int32_t lanes;
+    clg_measure_opts m;
+    int32_t rc = CLG_OK;
+    std::string message;
+    int64_t seed_ns = -1;
+};
+
+// fitness of the evolutionary search: set the string, time the whole sequence
+double graph_level_cost(const uint8_t *digits, size_t n, void *user) {
+    GraphLevelJob &j = *(GraphLevelJob *)user;
+    if (j.rc != CLG_OK) return 0.0 / 0.0;
+    int64_t ns = 0;
+    j.rc = clg_plan_set_handover(j.plan, digits, n, j.lanes);
+    if (j.rc == CLG_OK) j.rc = measure_plan(j.plan->p, j.inputs, j.outputs, j.workspace, j.ws_bytes, j.stream, j.m, &ns);
+    if (j.rc != CLG_OK) {
+        j.message = last_error();
+        return 0.0 / 0.0;
+    }
+    if (j.seed_ns < 0) j.seed_ns = ns;                 // the first string measured is the all-zero seed
+    return (double)ns;
+}
+}  // namespace
+
+int32_t clg_search_graph_level(clg_plan *plan, const void *const *inputs, void *const *outputs, void *workspace,
+                               size_t workspace_bytes, void *stream, int32_t lanes, const clg_es_opts *opts,
+                               const uint32_t *rand, size_t n_rand, const clg_measure_opts *measure, uint8_t *best,
+                               int64_t *best_ns, int64_t *seed_ns, int64_t *evaluations, double *history,
+                               int32_t *generations_run) {
+    CLG_TRY
+    NEED(plan); NEED(opts); NEED(measure); NEED(best); NEED(best_ns);
+    if (n_rand && !rand) return fail(CLG_INVALID_ARG, "clg_search_graph_level: rand is null");
+    if (lanes < 2 || lanes > 4) return fail(CLG_INVALID_ARG, "lanes must be 2..4 (got %d)", lanes);
+    int32_t rc = check_es_opts(opts);
+    if (rc == CLG_OK) rc = check_measure_opts(measure);
+    if (rc != CLG_OK) return rc;
+    GraphLevelJob job{plan, inputs, outputs, workspace, workspace_bytes, stream, lanes, *measure, CLG_OK, {}, -1};
+    const size_t n = plan->p.calls.size();
+    double cost = 0;
+    rc = evolve(n, *opts, rand, n_rand, graph_level_cost, &job, best, &cost, evaluations, history, generations_run);
+    if (job.rc != CLG_OK) return fail(job.rc, "%s", job.message.c_str());     // the measurement's own error
+    if (rc != CLG_OK) return rc;
+    *best_ns = (int64_t)cost;
+    if (seed_ns) *seed_ns = job.seed_ns;
+    return clg_plan_set_handover(plan, best, n, lanes);
+    CLG_CATCH
+}
+
 int32_t clg_plan_set_lanes(clg_plan *plan, int32_t lanes) {
     CLG_TRY
     NEED(plan);
     if (lanes < 1 || lanes > 4) return fail(CLG_INVALID_ARG, "lanes must be 1..4 (got %d)", lanes);
+    plan->p.handed.clear();                            // every kernel may move
     return set_plan_lanes(plan->p, lanes);
     CLG_CATCH
 }

@@ -164,6 +164,7 @@ struct Plan {
     // concurrent lanes: kernels of independent branches go to different HIP streams
     int32_t max_lanes = 1;                 // 1 = everything on the caller's stream (default: see clg_plan_set_lanes)
     int32_t n_lanes = 1;                   // lanes the schedule uses
+    std::vector<char> handed;              // call -> the lane scheduler may move it off the caller's stream (empty: all)
     std::vector<int32_t> lane;             // call -> lane (0 = the caller's stream)
     std::vector<std::vector<int32_t>> waits;   // call -> earlier calls on other lanes it must wait for
     std::vector<char> signals;             // call -> some later call on another lane waits for it
@@ -189,12 +190,20 @@ int32_t infer_shape(const Graph &g, int32_t kind, const std::vector<int32_t> &in
 int64_t attr_value(const Graph &g, int32_t node, int32_t attr, bool *ok);
 const char *op_name(int32_t kind);
 
+// Evolutionary search over digit strings (evolve.cpp); arguments as clg_evolve.
+int32_t evolve(size_t n, const clg_es_opts &o, const uint32_t *rand, size_t n_rand, clg_fitness_fn fn, void *user,
+               uint8_t *best, double *best_cost, int64_t *evaluations, double *history, int32_t *generations_run);
+
 int32_t match_all(Context &ctx, Graph &g);
 int32_t compile_plan(Context &ctx, Graph &g, const int32_t *ids, size_t n, Plan *plan);
 // (Re)computes the lane schedule of a compiled plan for at most plan->max_lanes lanes.
 void schedule_lanes(Plan *plan);
 // Changes the lane limit: waits for the plan's own streams, releases them and their events, reschedules.
 int32_t set_plan_lanes(Plan &p, int32_t lanes);
+// Whole-sequence time: `warmup` executions, then `batches` batches of `reps` executions between two
+// events on `stream`; *ns = the smallest batch mean.
+int32_t measure_plan(Plan &p, const void *const *inputs, void *const *outputs, void *workspace, size_t ws_bytes,
+                     void *stream, const clg_measure_opts &o, int64_t *ns);
 int32_t execute_plan(Plan &p, const void *const *inputs, void *const *outputs, void *workspace,
                      size_t ws_bytes, void *stream, int64_t *kernel_ns);
 int32_t profile_match(Context &ctx, Graph &g, int32_t match, const clg_profile_opts *opts, int64_t *cost_ns);

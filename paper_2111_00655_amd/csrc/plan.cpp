@@ -246,9 +246,9 @@ void schedule_lanes(Plan *plan) {
     const int lanes = std::min<int>(plan->max_lanes, 4);
     std::vector<int32_t> last(lanes, -1);            // last call queued on each lane
     for (size_t j = 0; j < nc; ++j) {
-        int pick = -1;
+        int pick = (!plan->handed.empty() && !plan->handed[j]) ? 0 : -1;   // not handed over: the caller's stream
         const int home = deps[j].empty() ? 0 : plan->lane[deps[j].back()];
-        if (depends(j, last[home])) pick = home;
+        if (pick < 0 && depends(j, last[home])) pick = home;
         for (int l = 0; l < lanes && pick < 0; ++l)
             if (depends(j, last[l])) pick = l;         // a lane whose queue this call follows anyway (or an idle one)
         if (pick < 0) {                                // every lane holds unrelated work: join the least recently used
@@ -269,6 +269,37 @@ void schedule_lanes(Plan *plan) {
                 plan->signals[latest[l]] = 1;
             }
     }
+}
+
+int32_t measure_plan(Plan &p, const void *const *inputs, void *const *outputs, void *workspace, size_t ws_bytes,
+                     void *stream, const clg_measure_opts &o, int64_t *ns) {
+    if (p.ctx->device < 0) return fail(CLG_HIP_ERROR, "host-only context: no device to execute on");
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
+        if (e0) (void)hipEventDestroy(e0);
+        return fail(CLG_HIP_ERROR, "hipEventCreate failed");
+    }
+    int32_t rc = CLG_OK;
+    double best = -1;
+    for (int32_t i = 0; i < o.warmup && rc == CLG_OK; ++i)
+        rc = execute_plan(p, inputs, outputs, workspace, ws_bytes, stream, nullptr);
+    for (int32_t b = 0; b < o.batches && rc == CLG_OK; ++b) {
+        (void)hipEventRecord(e0, (hipStream_t)stream);
+        for (int32_t i = 0; i < o.reps && rc == CLG_OK; ++i)
+            rc = execute_plan(p, inputs, outputs, workspace, ws_bytes, stream, nullptr);
+        (void)hipEventRecord(e1, (hipStream_t)stream);
+        if (hipEventSynchronize(e1) != hipSuccess && rc == CLG_OK)
+            rc = fail(CLG_HIP_ERROR, "waiting for a timed batch failed: %s", hipGetErrorString(hipGetLastError()));
+        float ms = 0.f;
+        if (rc == CLG_OK && hipEventElapsedTime(&ms, e0, e1) != hipSuccess) rc = fail(CLG_HIP_ERROR, "hipEventElapsedTime failed");
+        const double per = (double)ms * 1.0e6 / o.reps;
+        if (best < 0 || per < best) best = per;
+    }
+    if (rc != CLG_OK) (void)hipStreamSynchronize((hipStream_t)stream);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc == CLG_OK) *ns = (int64_t)(best + 0.5);
+    return rc;
 }
 
 int32_t pack_weights(const KernelCall &c, const void *w, void *dst, void *stream) {

@@ -117,6 +117,18 @@ class Plan:
         B.clg_plan_set_lanes(self.h, lanes)
         return self
 
+    def set_handover(self, digits, lanes=2):
+        B.clg_plan_set_handover(self.h, digits, lanes)
+        return self
+
+    def measure(self, warmup=5, batches=5, reps=20):
+        """Nanoseconds of one execution of the whole sequence (smallest batch mean)."""
+        return B.clg_plan_measure(self.h, *self._args(), warmup=warmup, batches=batches, reps=reps)
+
+    def search_graph_level(self, opts, rand, lanes=2, warmup=3, batches=3, reps=20):
+        """Sec. 4.2 on this plan: (best digits, best ns, seed ns, evaluations, history); leaves the plan set to best."""
+        return B.clg_search_graph_level(self.h, *self._args(), lanes, opts, rand, warmup=warmup, batches=batches, reps=reps)
+
     @property
     def n_lanes(self):
         return B.clg_plan_num_lanes(self.h)

@@ -539,6 +539,72 @@ def test_execute_argument_errors():
     s.close()
 
 
+# ------------------------------------------------------------------- graph-level search
+def _rand_u32(seed, n=200000):
+    return np.random.default_rng(seed).integers(0, 2 ** 32, n, dtype=np.uint64).tolist()
+
+
+@pytest.mark.parametrize("name", ["resnet_small", "tiny_cnn"])
+def test_graph_level_search_keeps_outputs_and_never_loses_to_the_seed(name):
+    """Sec. 4.2: digit strings over the kernels of the op-level plan, priced by timing the whole
+    sequence.  Whatever string wins, the plan must compute the same values as the op-level plan
+    (bit for bit: the same kernels, another schedule), equal the oracle, and its measured time is
+    by construction at most the all-zero seed's."""
+    if name == "tiny_cnn":
+        desc = wl.tiny_cnn(0)
+    else:
+        desc = wl.resnet50(0, image=64, width=16, blocks=(2, 2), classes=10)
+    reg = wl.default_registry(("igemm_s8", "igemm_r16"))
+    s, g, oms = _session_and_oracle(desc, reg)
+    costs = s.profile(B.ProfileOpts(warmup=3, batches=2, min_batch_us=50, max_launches=50))
+    _, ids = s.search(costs, 0)
+    plan = s.compile(ids).bind()
+    base = plan.run()
+    opts = B.make_es_opts(population=6, generations=4, tournament=3, p_init=0.3, p_mutate=0.6, p_flip=0.15, p_cross=0.6)
+    best, best_ns, seed_ns, evals, hist = plan.search_graph_level(opts, _rand_u32(5), lanes=3, warmup=2, batches=2, reps=10)
+    assert len(best) == plan.n_kernels and set(best) <= {0, 1}
+    assert 0 < best_ns <= seed_ns and hist[0] <= seed_ns and hist[-1] == best_ns
+    assert all(a >= b for a, b in zip(hist, hist[1:])) and 1 <= evals <= 6 * 5 * 2
+    got = plan.run()                            # the plan is left set to the best string
+    assert all(np.array_equal(a, b) for a, b in zip(got, base))
+    assert max(norm_err(a, b) for a, b in zip(got, g.run())) <= NET_TOL
+    # every string gives the same values: all ones, alternating, and back to the seed
+    n = plan.n_kernels
+    for digits in ([1] * n, [i % 2 for i in range(n)], [0] * n):
+        plan.set_handover(digits, lanes=2)
+        assert all(np.array_equal(a, b) for a, b in zip(plan.run(), base))
+    assert plan.n_lanes == 1                    # all zeros is the op-level plan on the caller's stream
+    assert plan.measure(warmup=2, batches=2, reps=5) > 0
+    plan.destroy()
+    s.close()
+
+
+def test_graph_level_search_equals_the_oracle_s_on_the_same_costs():
+    """The library's search drives set_handover + measure; with the measured costs recorded per
+    string, the oracle's search replayed on that table must walk the same strings and end at the
+    same one (the search itself is deterministic given the draws)."""
+    desc = wl.tiny_cnn(0)
+    reg = wl.default_registry(("igemm_s8",))
+    s, g, oms = _session_and_oracle(desc, reg)
+    costs = s.profile(B.ProfileOpts(warmup=3, batches=2, min_batch_us=50, max_launches=50))
+    _, ids = s.search(costs, 0)
+    plan = s.compile(ids).bind()
+    table = {}
+
+    def measured(d):
+        plan.set_handover(d, lanes=2)
+        table[tuple(d)] = float(plan.measure(warmup=1, batches=1, reps=5))
+        return table[tuple(d)]
+    kw = dict(population=4, generations=3, tournament=2, p_init=0.5, p_mutate=0.5, p_flip=0.2, p_cross=0.5)
+    rand = _rand_u32(7, 5000)
+    got = B.clg_evolve(plan.n_kernels, B.make_es_opts(**kw), rand, measured)
+    from oracle import evolve as oe
+    want = oe.evolve(plan.n_kernels, lambda d: table[tuple(d)], rand, **kw)
+    assert got[0] == want[0] and got[1] == want[1] and got[2] == want[2] == len(table) and got[3] == want[3]
+    plan.destroy()
+    s.close()
+
+
 # ------------------------------------------------------------------- lanes
 @pytest.mark.parametrize("name", ["resnet50", "bert_base", "tiny_cnn"])
 def test_lanes_give_the_same_result_as_one_stream(name):

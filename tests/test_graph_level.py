@@ -134,3 +134,83 @@ def test_oracle_patience_stops_early():
         return 1.0                                            # nothing ever improves
     _, _, _, hist = oe.evolve(5, f, draws(1), population=4, generations=50, patience=3)
     assert len(hist) == 4
+
+
+# ---- the library's search equals the oracle's, draw for draw --------------------------------------------
+from paper_2111_00655_amd import binding as B  # noqa: E402
+
+
+def test_library_reproduces_the_generation_worked_by_hand():
+    ex = worked_example()
+    best, cost, evals, hist = B.clg_evolve(4, B.make_es_opts(patience=0, **EXAMPLE_OPTS), u32(ex["draws"]), example_cost)
+    assert best == [int(x) for x in ex["best"]] and cost == 7.0 and evals == 5 and hist == [8.0, 7.0]
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_library_equals_oracle(seed):
+    r = np.random.default_rng(1000 + seed)
+    n = int(r.integers(1, 40))
+    opts = dict(population=int(r.integers(2, 12)), generations=int(r.integers(0, 15)), tournament=int(r.integers(1, 5)),
+                patience=int(r.integers(0, 4)), p_init=float(r.uniform(0, 1)), p_mutate=float(r.uniform(0, 1)),
+                p_flip=float(r.uniform(0, 0.5)), p_cross=float(r.uniform(0, 1)))
+    cost = random_cost_table(n, seed)
+    rand = draws(seed, 40000)
+    want = oe.evolve(n, cost, rand, **opts)
+    got = B.clg_evolve(n, B.make_es_opts(**opts), rand, cost)
+    assert got[0] == want[0] and got[1] == want[1] and got[2] == want[2] and got[3] == want[3]
+
+
+def test_library_measures_a_string_once_and_in_the_oracle_s_order():
+    n = 9
+    cost = random_cost_table(n, 2)
+    a, b = [], []
+    opts = dict(population=6, generations=8, tournament=2, p_init=0.4, p_mutate=0.7, p_flip=0.3, p_cross=0.6)
+    oe.evolve(n, lambda d: (a.append(tuple(d)), cost(d))[1], draws(9), **opts)
+    B.clg_evolve(n, B.make_es_opts(**opts), draws(9), lambda d: (b.append(tuple(d)), cost(d))[1])
+    assert a == b and len(set(b)) == len(b)
+
+
+def test_library_search_errors():
+    ok = B.make_es_opts(population=4, generations=3)
+    with pytest.raises(B.ClgError, match="draws"):
+        B.clg_evolve(8, ok, [1, 2, 3], lambda d: 1.0)
+    with pytest.raises(B.ClgError, match="population"):
+        B.clg_evolve(8, B.make_es_opts(population=1), draws(0), lambda d: 1.0)
+    with pytest.raises(B.ClgError, match="probability"):
+        B.clg_evolve(8, B.make_es_opts(p_flip=1.5), draws(0), lambda d: 1.0)
+    with pytest.raises(B.ClgError, match="NaN"):
+        B.clg_evolve(8, ok, draws(0), lambda d: float("nan"))
+    with pytest.raises(ZeroDivisionError):
+        B.clg_evolve(8, ok, draws(0), lambda d: 1 / 0)
+    # no digits: the seed is the only string
+    best, cost, evals, hist = B.clg_evolve(0, ok, draws(0), lambda d: 3.0)
+    assert best == [] and cost == 3.0 and evals == 1 and hist == [3.0] * 4
+
+
+# ---- the plan's digits (host-only: the schedule is computed without a device) ----------------------------
+def test_handover_digits_on_a_plan():
+    import workloads as wl
+    import paper_2111_00655_amd as clg
+    d = wl.resnet50(0, image=32, width=8, blocks=(2, 2), classes=10)
+    s = clg.Session(d, wl.default_registry(("igemm_s8",)), device=None)
+    ms = s.match()
+    _, ids = s.search(wl.synthetic_costs(len(ms), 0), 0)
+    plan = s.compile(ids)
+    n = plan.n_kernels
+    plan.set_handover([0] * n, lanes=3)
+    assert plan.n_lanes == 1                                  # all zeros: the operator-level plan as it is
+    plan.set_handover([1] * n, lanes=3)
+    assert plan.n_lanes > 1                                   # the projection shortcut can leave the main path
+    with pytest.raises(clg.ClgError, match="digits"):
+        plan.set_handover([0] * (n - 1))
+    with pytest.raises(clg.ClgError, match="digit"):
+        plan.set_handover([2] + [0] * (n - 1))
+    with pytest.raises(clg.ClgError, match="lanes"):
+        plan.set_handover([0] * n, lanes=1)
+    with pytest.raises(clg.ClgError) as e:                    # no device: nothing to time
+        B.clg_plan_measure(plan.h, [256], [256, 256], 256, plan.ws_bytes)
+    assert e.value.status == "HIP_ERROR"
+    plan.set_lanes(3)                                         # the plain lane option hands every kernel over
+    assert plan.n_lanes > 1
+    plan.destroy()
+    s.close()
