@@ -88,7 +88,7 @@ typedef enum clg_op_kind {
 
 #define CLG_MAX_DIMS 6
 
-/* Operator attributes ("attributes such as layout and kernel size", Sec. 3).
+/* Operator attributes (Sec. 3: patterns may constrain attributes such as kernel size).
  * Fields an operator does not use are ignored.  Zero-initialise, then set. */
 typedef struct clg_attrs {
     int32_t stride[2];      /* conv2d, conv2d_transpose, max_pool2d           */
@@ -305,7 +305,7 @@ int32_t clg_profile_all(clg_ctx *ctx, clg_graph *g,
  * dispatch floor (the context-switch cost eps of Eq. 2, for reference). */
 int32_t clg_profile_empty(clg_ctx *ctx, const clg_profile_opts *opts,
                           int64_t *cost_ns);
-/* Cost log as a text file ("cached to the log for future usage", Sec. 4.2):
+/* Cost log as a text file (Sec. 4.2: measured costs are kept in a log and reused):
  * one "key<TAB>nanoseconds" line per entry.  load merges into the context's
  * log (file entries win); save writes the whole log. */
 int32_t clg_cost_log_load(clg_ctx *ctx, const char *path);
