@@ -83,7 +83,10 @@ typedef enum clg_op_kind {
     CLG_OP_TAKE = 14,               /* (table[V,H], ids[L] int32) -> [L,H]        */
     CLG_OP_RESHAPE = 15,            /* (x); dims = new shape                      */
     CLG_OP_TRANSPOSE = 16,          /* (x); dims = permutation                    */
-    CLG_OP_COUNT = 17
+    CLG_OP_AVG_POOL2D = 17,         /* (x); kernel stride pad; mean over the window's
+                                       pixels inside the image (padding not counted) */
+    CLG_OP_CONCAT = 18,             /* (x0, x1, ...), 2..8 operands; axis         */
+    CLG_OP_COUNT = 19
 } clg_op_kind;
 
 #define CLG_MAX_DIMS 6
@@ -91,11 +94,12 @@ typedef enum clg_op_kind {
 /* Operator attributes (Sec. 3: patterns may constrain attributes such as kernel size).
  * Fields an operator does not use are ignored.  Zero-initialise, then set. */
 typedef struct clg_attrs {
-    int32_t stride[2];      /* conv2d, conv2d_transpose, max_pool2d           */
+    int32_t stride[2];      /* conv2d, conv2d_transpose, max/avg_pool2d       */
     int32_t pad[2];         /* same                                           */
-    int32_t kernel[2];      /* max_pool2d window                              */
+    int32_t kernel[2];      /* max/avg_pool2d window                          */
     int32_t groups;         /* conv2d; 0 is read as 1                         */
-    int32_t axis;           /* bias_add: 1 (channel of NCHW) or -1 / last     */
+    int32_t axis;           /* bias_add: 1 (channel of NCHW) or -1 / last;
+                               concat: the axis joined (negative: from the end) */
     int32_t transpose_b;    /* batch_matmul: 1 = b is [B,N,K]                 */
     int32_t ndims;          /* reshape / transpose: entries used in dims      */
     int64_t dims[CLG_MAX_DIMS];
@@ -117,7 +121,7 @@ typedef struct clg_attr_constraint {
     int64_t lo, hi;
 } clg_attr_constraint;
 
-#define CLG_MAX_PATTERN_ARGS 3
+#define CLG_MAX_PATTERN_ARGS 8
 #define CLG_MAX_CONSTRAINTS 4
 #define CLG_MAX_PATTERN_NODES 32
 #define CLG_MAX_MATCH_NODES 16
@@ -222,9 +226,14 @@ int32_t clg_graph_node_shape(const clg_graph *g, int32_t node, int32_t *dtype,
  *              waves of a workgroup.  What they do not run (batch_matmul,
  *              non-constant weights, tails outside scale/bias/add/activation)
  *              falls back to the "igemm_s8" kernels.
- *   "direct"   direct convolution (any groups) and pooling
+ *   "sepconv"  separable convolution in one kernel: [relu] -> depthwise
+ *              conv2d -> 1x1 conv2d -> elementwise tail, or relu -> 1x1 conv2d
+ *              (any stride) -> tail; both weights constants, the depthwise
+ *              result stays in LDS, the 1x1 weights are re-packed per plan
+ *   "direct"   direct convolution (any groups), max / average pooling (window
+ *              pools also with an elementwise tail), global average pooling
  *   "rowwise"  softmax and layer norm with fused elementwise prologue
- *   "eltwise"  elementwise chains, embedding gather, layout copies
+ *   "eltwise"  elementwise chains, embedding gather, layout copies, concat
  * Returns UNKNOWN_ID for any other name.  Registering a name twice returns
  * the same id.  Registration order of patterns is significant: it is the
  * iteration order of B in Alg. 1 and breaks ties in the search. */

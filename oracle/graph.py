@@ -74,6 +74,10 @@ class Graph:
             return ops.layer_norm(x[0], x[1], x[2], a.get("eps", 1e-12))
         if k == "max_pool2d":
             return ops.max_pool2d(x[0], a["kernel"], a["stride"], a["pad"])
+        if k == "avg_pool2d":
+            return ops.avg_pool2d(x[0], a["kernel"], a["stride"], a["pad"])
+        if k == "concat":
+            return ops.concat(x, a.get("axis", 1))
         if k == "global_avg_pool2d":
             return ops.global_avg_pool2d(x[0])
         if k == "take":

@@ -245,6 +245,32 @@ void orc_max_pool2d(const float *x, float *y, int N, int C, int H, int W,
             }
 }
 
+/* mean over the part of the window that lies inside the image (padding is
+ * not counted, neither in the sum nor in the divisor) */
+void orc_avg_pool2d(const float *x, float *y, int N, int C, int H, int W,
+                    int KH, int KW, int sh, int sw, int ph, int pw)
+{
+    const int HO = (H + 2 * ph - KH) / sh + 1;
+    const int WO = (W + 2 * pw - KW) / sw + 1;
+    for (int nc = 0; nc < N * C; ++nc)
+        for (int oh = 0; oh < HO; ++oh)
+            for (int ow = 0; ow < WO; ++ow) {
+                double acc = 0.0;
+                int cnt = 0;
+                for (int kh = 0; kh < KH; ++kh) {
+                    const int ih = oh * sh - ph + kh;
+                    if (ih < 0 || ih >= H) continue;
+                    for (int kw = 0; kw < KW; ++kw) {
+                        const int iw = ow * sw - pw + kw;
+                        if (iw < 0 || iw >= W) continue;
+                        acc += x[((size_t)nc * H + ih) * W + iw];
+                        ++cnt;
+                    }
+                }
+                y[((size_t)nc * HO + oh) * WO + ow] = cnt ? (float)(acc / (double)cnt) : 0.0f;
+            }
+}
+
 /* mean over H*W; output [N, C] */
 void orc_global_avg_pool2d(const float *x, float *y, int NC, int HW)
 {

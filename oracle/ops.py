@@ -45,6 +45,7 @@ _tanh = _sig("orc_tanh", [_f, _f, C.c_int64])
 _softmax = _sig("orc_softmax", [_f, _f, C.c_int64, C.c_int64])
 _ln = _sig("orc_layer_norm", [_f, _f, _f, _f, C.c_int64, C.c_int64, C.c_double])
 _maxpool = _sig("orc_max_pool2d", [_f, _f] + [C.c_int] * 10)
+_avgpool = _sig("orc_avg_pool2d", [_f, _f] + [C.c_int] * 10)
 _gap = _sig("orc_global_avg_pool2d", [_f, _f, C.c_int, C.c_int])
 _take = _sig("orc_take", [_f, _i, _f, C.c_int64, C.c_int64, C.c_int64], C.c_int)
 _set_threads = _sig("orc_set_threads", [C.c_int])
@@ -205,6 +206,38 @@ def max_pool2d(x, kernel=(3, 3), stride=(2, 2), pad=(1, 1)):
     ho, wo = (h + 2 * ph - kh) // sh + 1, (w + 2 * pw - kw) // sw + 1
     y = np.empty((n, c, ho, wo), np.float32)
     _maxpool(_p(x), _p(y), n, c, h, w, kh, kw, sh, sw, ph, pw)
+    return y
+
+
+def avg_pool2d(x, kernel=(3, 3), stride=(1, 1), pad=(1, 1)):
+    """Mean over the window's pixels inside the image (padding not counted)."""
+    x = _f32(x)
+    (kh, kw), (sh, sw), (ph, pw) = _pair(kernel), _pair(stride), _pair(pad)
+    n, c, h, w = x.shape
+    ho, wo = (h + 2 * ph - kh) // sh + 1, (w + 2 * pw - kw) // sw + 1
+    y = np.empty((n, c, ho, wo), np.float32)
+    _avgpool(_p(x), _p(y), n, c, h, w, kh, kw, sh, sw, ph, pw)
+    return y
+
+
+def concat(xs, axis=1):
+    """Tensors joined along `axis`; every other extent equal."""
+    xs = [_f32(x) for x in xs]
+    nd = xs[0].ndim
+    ax = axis + nd if axis < 0 else axis
+    for x in xs:
+        if x.ndim != nd or any(x.shape[d] != xs[0].shape[d] for d in range(nd) if d != ax):
+            raise ValueError("concat: shapes differ outside the axis")
+    outer = int(np.prod(xs[0].shape[:ax], dtype=np.int64))
+    shape = list(xs[0].shape)
+    shape[ax] = sum(x.shape[ax] for x in xs)
+    y = np.empty(shape, np.float32)
+    yf = y.reshape(outer, -1)
+    at = 0
+    for x in xs:                      # plain copies, block by block
+        xf = x.reshape(outer, -1)
+        yf[:, at:at + xf.shape[1]] = xf
+        at += xf.shape[1]
     return y
 
 

@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libcollage_mi.so")
 
 MAX_DIMS = 6
-MAX_PATTERN_ARGS = 3
+MAX_PATTERN_ARGS = 8
 MAX_CONSTRAINTS = 4
 MAX_MATCH_NODES = 16
 COST_INF = 1 << 60
@@ -23,7 +23,7 @@ WILDCARD = -1
 
 OP_KINDS = ("conv2d", "conv2d_transpose", "dense", "batch_matmul", "bias_add", "add",
             "mul_scalar", "relu", "gelu", "tanh", "softmax", "layer_norm", "max_pool2d",
-            "global_avg_pool2d", "take", "reshape", "transpose")
+            "global_avg_pool2d", "take", "reshape", "transpose", "avg_pool2d", "concat")
 OP_ID = {k: i for i, k in enumerate(OP_KINDS)}
 ATTR_ID = {k: i for i, k in enumerate(("groups", "kernel_h", "kernel_w", "stride_h", "stride_w",
                                        "pad_h", "pad_w", "transpose_b", "axis"))}
@@ -52,7 +52,7 @@ class AttrConstraint(C.Structure):
 
 
 class PatternRule(C.Structure):
-    _fields_ = [("op_class", C.c_int32 * 17), ("max_ops", C.c_int32), ("grow_from_elemwise", C.c_int32)]
+    _fields_ = [("op_class", C.c_int32 * len(OP_KINDS)), ("max_ops", C.c_int32), ("grow_from_elemwise", C.c_int32)]
 
 
 RULE_NONE, RULE_FUSABLE, RULE_ELEMWISE = 0, 1, 2

@@ -114,7 +114,7 @@ int32_t clg_graph_op(clg_graph *g, int32_t op_kind, int32_t n_in, const int32_t 
                      int32_t *node) {
     CLG_TRY
     NEED(g); NEED(node);
-    if (n_in < 1 || n_in > 3) return fail(CLG_INVALID_ARG, "n_in %d", n_in);
+    if (n_in < 1 || n_in > CLG_MAX_PATTERN_ARGS) return fail(CLG_INVALID_ARG, "n_in %d", n_in);
     NEED(in_nodes);
     Node nd;
     nd.kind = op_kind;
@@ -172,7 +172,7 @@ int32_t clg_register_backend(clg_ctx *ctx, const char *name, int32_t *backend) {
         {"igemm_l", FAM_IGEMM, TILE_L, 0}, {"igemm_s8", FAM_IGEMM, TILE_S8, 0}, {"igemm_s16", FAM_IGEMM, TILE_S16, 0},
         {"igemm_r32", FAM_IGEMM, TILE_R32, 1}, {"igemm_r16", FAM_IGEMM, TILE_R16, 1},
         {"igemm_s_nk", FAM_IGEMM, TILE_S, 1}, {"igemm_s8_nk", FAM_IGEMM, TILE_S8, 1}, {"igemm_s16_nk", FAM_IGEMM, TILE_S16, 1},
-        {"direct", FAM_DIRECT, 0, 0}, {"rowwise", FAM_ROWWISE, 0, 0}, {"eltwise", FAM_ELTWISE, 0, 0}};
+        {"sepconv", FAM_SEPCONV, 0, 0}, {"direct", FAM_DIRECT, 0, 0}, {"rowwise", FAM_ROWWISE, 0, 0}, {"eltwise", FAM_ELTWISE, 0, 0}};
     const std::string s(name);
     for (size_t i = 0; i < ctx->c.backends.size(); ++i)
         if (ctx->c.backends[i].name == s) {

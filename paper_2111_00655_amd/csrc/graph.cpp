@@ -26,7 +26,7 @@ const char *last_error() { return g_err; }
 static const char *kOpNames[CLG_OP_COUNT] = {
     "conv2d", "conv2d_transpose", "dense", "batch_matmul", "bias_add", "add",
     "mul_scalar", "relu", "gelu", "tanh", "softmax", "layer_norm", "max_pool2d",
-    "global_avg_pool2d", "take", "reshape", "transpose"};
+    "global_avg_pool2d", "take", "reshape", "transpose", "avg_pool2d", "concat"};
 
 const char *op_name(int32_t kind) {
     if (kind >= 0 && kind < CLG_OP_COUNT) return kOpNames[kind];
@@ -59,9 +59,13 @@ static int n_operands(int32_t kind) {
 int32_t infer_shape(const Graph &g, int32_t kind, const std::vector<int32_t> &in,
                     const clg_attrs &a, Shape *out, int32_t *dtype) {
     if (kind < 0 || kind >= CLG_OP_COUNT) return fail(CLG_INVALID_ARG, "unknown op kind %d", kind);
-    if ((int)in.size() != n_operands(kind))
+    if (kind == CLG_OP_CONCAT) {
+        if (in.size() < 2 || in.size() > CLG_MAX_PATTERN_ARGS)
+            return fail(CLG_INVALID_ARG, "concat takes 2..%d operands, got %zu", CLG_MAX_PATTERN_ARGS, in.size());
+    } else if ((int)in.size() != n_operands(kind)) {
         return fail(CLG_INVALID_ARG, "%s takes %d operands, got %zu", op_name(kind),
                     n_operands(kind), in.size());
+    }
     const Shape &x = g.nodes[in[0]].shape;
     *dtype = CLG_F32;
     auto f32 = [&](int i) { return g.nodes[in[i]].dtype == CLG_F32; };
@@ -140,6 +144,20 @@ int32_t infer_shape(const Graph &g, int32_t kind, const std::vector<int32_t> &in
         y = x;
         break;
     }
+    case CLG_OP_CONCAT: {
+        const int ax = a.axis < 0 ? a.axis + x.ndim : a.axis;
+        if (ax < 0 || ax >= x.ndim) return bad("axis");
+        y = x;
+        for (size_t i = 1; i < in.size(); ++i) {
+            const Shape &s = g.nodes[in[i]].shape;
+            if (!f32((int)i) || s.ndim != x.ndim) return bad("operands must be fp32 tensors of one rank");
+            for (int d = 0; d < x.ndim; ++d)
+                if (d != ax && s.d[d] != x.d[d]) return bad("extents differ outside the axis");
+            y.d[ax] += s.d[ax];
+        }
+        break;
+    }
+    case CLG_OP_AVG_POOL2D:
     case CLG_OP_MAX_POOL2D: {
         if (x.ndim != 4) return bad("needs x[N,C,H,W]");
         if (a.kernel[0] < 1 || a.kernel[1] < 1 || a.stride[0] < 1 || a.stride[1] < 1 ||
@@ -196,14 +214,14 @@ int64_t attr_value(const Graph &g, int32_t node, int32_t attr, bool *ok) {
     const Node &nd = g.nodes[node];
     *ok = true;
     auto weight_dim = [&](int d) -> int64_t {
-        if (nd.kind == CLG_OP_MAX_POOL2D) return nd.attrs.kernel[d - 2];
+        if (nd.kind == CLG_OP_MAX_POOL2D || nd.kind == CLG_OP_AVG_POOL2D) return nd.attrs.kernel[d - 2];
         if ((nd.kind == CLG_OP_CONV2D || nd.kind == CLG_OP_CONV2D_TRANSPOSE) && nd.in.size() > 1)
             return g.nodes[nd.in[1]].shape.d[d];
         *ok = false;
         return 0;
     };
     const bool spatial = nd.kind == CLG_OP_CONV2D || nd.kind == CLG_OP_CONV2D_TRANSPOSE ||
-                         nd.kind == CLG_OP_MAX_POOL2D;
+                         nd.kind == CLG_OP_MAX_POOL2D || nd.kind == CLG_OP_AVG_POOL2D;
     switch (attr) {
     case CLG_ATTR_GROUPS: return nd.attrs.groups > 0 ? nd.attrs.groups : 1;
     case CLG_ATTR_KERNEL_H: return weight_dim(2);

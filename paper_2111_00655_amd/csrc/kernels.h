@@ -115,8 +115,39 @@ struct DirectConvArgs {
 struct PoolArgs {
     const float *x;
     float *y;
-    int32_t mode;                          // 0 max pool, 1 global average
+    int32_t mode;                          // 0 max pool, 1 global average, 2 average pool (padding not counted)
     int32_t NC, H, W, KH, KW, sh, sw, ph, pw, HO, WO;
+    Epilogue epi;                          // fused elementwise tail of a window pool
+};
+
+// ---- separable convolution in one kernel (sepconv.hip) -----------------------------------------
+// y = tail(Wp * dw(relu?(x))) with dw a depthwise KH x KW convolution (stride, pad) or, when wd is
+// null, the plain stride-sh/sw sub-sampling of a 1x1 convolution (KH = KW = 1, pad 0).
+struct SepConvArgs {
+    const float *x;                        // [N][C][H][W]
+    const float *wd;                       // depthwise weights [C][KH*KW], or null
+    const float *wp;                       // packed 1x1 weights (sepconv_pack_bytes)
+    float *y;                              // [N][Cout][HO][WO]
+    int32_t N, C, H, W, Cout, KH, KW, sh, sw, ph, pw, HO, WO;
+    int32_t pro_relu;                      // relu on x first
+    int32_t has_dw;                        // a depthwise stage precedes the 1x1 convolution (wd is set at launch)
+    int32_t ngroups, m_tiles, n_tiles, mt_per_wg, nwaves;   // set by sepconv_resolve
+    Epilogue epi;
+};
+void sepconv_resolve(SepConvArgs *a);
+size_t sepconv_pack_bytes(const SepConvArgs &a);
+size_t sepconv_lds_bytes(const SepConvArgs &a);
+int launch_sepconv_pack(const SepConvArgs &a, const float *w, float *dst, void *stream);
+int launch_sepconv(const SepConvArgs &a, void *stream);
+
+// ---- concat: y[r][...] = x_0[r][...] x_1[r][...] ..., r < outer ---------------------------------
+struct ConcatArgs {
+    int32_t n;                             // operands, at most 8
+    int64_t outer;                         // product of the extents before the axis
+    int64_t row;                           // output elements per outer index = sum of chunk[]
+    int64_t chunk[8];                      // operand elements per outer index
+    const float *src[8];
+    float *y;
 };
 
 // ---- row-wise reductions ------------------------------------------------------------------
@@ -160,6 +191,7 @@ int launch_pool(const PoolArgs &a, void *stream);
 int launch_rowwise(const RowwiseArgs &a, void *stream);
 int launch_eltwise(const EltwiseArgs &a, void *stream);
 int launch_layout(const LayoutArgs &a, void *stream);
+int launch_concat(const ConcatArgs &a, void *stream);
 // Scratch-operand fill for the measurer: uniform values in [-1, 1) from a
 // counter hash of (seed, index); ids: zeros.
 int launch_fill(float *p, int64_t n, uint64_t seed, void *stream);

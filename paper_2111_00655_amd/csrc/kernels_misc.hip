@@ -308,24 +308,30 @@ int launch_direct_conv(const DirectConvArgs &a, void *stream) {
 }
 
 // ------------------------------------------------------------------------ pooling
-__global__ __launch_bounds__(256) void max_pool_kernel(PoolArgs a) {
+// One output pixel per thread.  AVG: mean over the window's pixels inside the image.
+template <bool AVG>
+__global__ __launch_bounds__(256) void window_pool_kernel(PoolArgs a) {
     const int64_t total = (int64_t)a.NC * a.HO * a.WO;
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= total) return;
     const int ow = (int)(i % a.WO), oh = (int)((i / a.WO) % a.HO);
     const int64_t nc = i / ((int64_t)a.WO * a.HO);
     const float *xp = a.x + nc * a.H * a.W;
-    float best = -INFINITY;
+    float acc = AVG ? 0.f : -INFINITY;
+    int cnt = 0;
     for (int kh = 0; kh < a.KH; ++kh) {
         const int ih = oh * a.sh - a.ph + kh;
         if (ih < 0 || ih >= a.H) continue;
         for (int kw = 0; kw < a.KW; ++kw) {
             const int iw = ow * a.sw - a.pw + kw;
             if (iw < 0 || iw >= a.W) continue;
-            best = fmaxf(best, xp[(int64_t)ih * a.W + iw]);
+            const float v = xp[(int64_t)ih * a.W + iw];
+            acc = AVG ? acc + v : fmaxf(acc, v);
+            ++cnt;
         }
     }
-    a.y[i] = best;
+    if (AVG) acc = cnt ? acc / (float)cnt : 0.f;
+    a.y[i] = apply_steps(a.epi, acc, i, chan_of(a.epi, i));
 }
 
 // one wave per (n, c) plane
@@ -343,9 +349,11 @@ __global__ __launch_bounds__(256) void global_avg_pool_kernel(PoolArgs a) {
 
 int launch_pool(const PoolArgs &a, void *stream) {
     hipStream_t s = (hipStream_t)stream;
-    if (a.mode == 0) {
+    if (a.mode == 0 || a.mode == 2) {
         const int64_t total = (int64_t)a.NC * a.HO * a.WO;
-        hipLaunchKernelGGL(max_pool_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, a);
+        const dim3 grid((unsigned)((total + 255) / 256));
+        if (a.mode == 0) hipLaunchKernelGGL(window_pool_kernel<false>, grid, dim3(256), 0, s, a);
+        else hipLaunchKernelGGL(window_pool_kernel<true>, grid, dim3(256), 0, s, a);
     } else {
         hipLaunchKernelGGL(global_avg_pool_kernel, dim3((a.NC + 3) / 4), dim3(256), 0, s, a);
     }
@@ -369,6 +377,34 @@ __global__ __launch_bounds__(256) void layout_kernel(LayoutArgs a) {
 int launch_layout(const LayoutArgs &a, void *stream) {
     const int grid = (int)std::min<int64_t>((a.numel + 255) / 256, 256 * 16);
     hipLaunchKernelGGL(layout_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, a);
+    return (int)hipGetLastError();
+}
+
+// ------------------------------------------------------------------------- concat
+// Output element o = (r, col): the operand whose column range holds col supplies it.
+template <int VEC>
+__global__ __launch_bounds__(256) void concat_kernel(ConcatArgs a) {
+    const int64_t n = a.outer * a.row / VEC;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const int64_t o = i * VEC;
+        const int64_t r = o / a.row;
+        int64_t col = o - r * a.row;
+        int s = 0;
+        while (s < a.n - 1 && col >= a.chunk[s]) col -= a.chunk[s++];
+        const float *src = a.src[s] + r * a.chunk[s] + col;
+        if constexpr (VEC == 4) *reinterpret_cast<float4 *>(a.y + o) = *reinterpret_cast<const float4 *>(src);
+        else a.y[o] = *src;
+    }
+}
+
+int launch_concat(const ConcatArgs &a, void *stream) {
+    bool vec = aligned16(a.y);
+    for (int s = 0; s < a.n; ++s) vec = vec && a.chunk[s] % 4 == 0 && aligned16(a.src[s]);
+    const int64_t items = a.outer * a.row / (vec ? 4 : 1);
+    const int grid = (int)std::min<int64_t>((items + 255) / 256, 256 * 16);
+    if (vec) hipLaunchKernelGGL(concat_kernel<4>, dim3(grid), dim3(256), 0, (hipStream_t)stream, a);
+    else hipLaunchKernelGGL(concat_kernel<1>, dim3(grid), dim3(256), 0, (hipStream_t)stream, a);
     return (int)hipGetLastError();
 }
 

@@ -110,9 +110,25 @@ int32_t check_pattern(const Context &ctx, Pattern *p) {
             for (int t = 1; t < len - 2; ++t) ok = ok && kind(t) != CLG_OP_RESHAPE;
         }
         break;
+    case FAM_SEPCONV: {
+        // [relu] conv2d [conv2d] tail: a depthwise + 1x1 pair, or a 1x1 convolution behind a relu;
+        // which convolution is which is checked per match
+        int t = 0;
+        const bool pro = k0 == CLG_OP_RELU;
+        if (pro) ++t;
+        int convs = 0;
+        while (t < len && kind(t) == CLG_OP_CONV2D && convs < 2) {
+            if (t > 0 && p->main_arg[t] != 0) break;
+            ++t;
+            ++convs;
+        }
+        ok = convs >= 1 && (pro || convs == 2) && tail_ok(t, len) && kl != CLG_OP_RESHAPE;
+        break;
+    }
     case FAM_DIRECT:
-        ok = (k0 == CLG_OP_CONV2D && tail_ok(1, len)) ||
-             (len == 1 && (k0 == CLG_OP_MAX_POOL2D || k0 == CLG_OP_GLOBAL_AVG_POOL2D));
+        ok = ((k0 == CLG_OP_CONV2D || k0 == CLG_OP_MAX_POOL2D || k0 == CLG_OP_AVG_POOL2D) && tail_ok(1, len) &&
+              kl != CLG_OP_RESHAPE) ||
+             (len == 1 && k0 == CLG_OP_GLOBAL_AVG_POOL2D);
         break;
     case FAM_ROWWISE:
         ok = is_rowwise(kl) && (len == 1 || (p->main_arg[len - 1] == 0 && is_elementwise(k0) &&
@@ -127,6 +143,8 @@ int32_t check_pattern(const Context &ctx, Pattern *p) {
                 n_tr += kind(t) == CLG_OP_TRANSPOSE;
             }
             ok = ok && n_tr <= 1;
+        } else if (k0 == CLG_OP_CONCAT) {
+            ok = len == 1;
         } else {
             ok = (is_elementwise(k0) || k0 == CLG_OP_TAKE) && tail_ok(1, len) &&
                  kl != CLG_OP_RESHAPE;
@@ -235,8 +253,67 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
 
     Epilogue epi{};
     int32_t rc = CLG_OK;
-
-    if (is_contraction(k0)) {
+    if (be.family == FAM_SEPCONV) {
+        int t = 0;
+        SepConvArgs &a = c.sep;
+        a.pro_relu = k0 == CLG_OP_RELU ? 1 : 0;
+        if (a.pro_relu) ++t;
+        const int32_t xa = cv.arg(0, 0);
+        const Shape &xs = g.nodes[xa].shape;
+        const int t_first = t;
+        int t_pw = t;
+        if (t + 1 < len && cv.op(t + 1) == CLG_OP_CONV2D) t_pw = t + 1;
+        const Node &pwn = g.nodes[cv.node(t_pw)];
+        const int32_t wp = cv.arg(t_pw, 1);
+        const Shape &wps = g.nodes[wp].shape;
+        if (xs.ndim != 4) return fail(CLG_NO_KERNEL, "sepconv needs x[N,C,H,W]");
+        a.N = (int)xs.d[0]; a.C = (int)xs.d[1]; a.H = (int)xs.d[2]; a.W = (int)xs.d[3];
+        const Node &first = g.nodes[cv.node(t_first)];
+        a.sh = first.attrs.stride[0]; a.sw = first.attrs.stride[1];
+        a.ph = first.attrs.pad[0]; a.pw = first.attrs.pad[1];
+        a.KH = a.KW = 1;
+        double macs = 0;
+        if (t_pw != t_first) {                             // depthwise stage
+            const int32_t wd = cv.arg(t_first, 1);
+            const Shape &wds = g.nodes[wd].shape;
+            const int G = first.attrs.groups > 0 ? first.attrs.groups : 1;
+            if (G != a.C || wds.d[0] != a.C || wds.d[1] != 1 || g.nodes[wd].kind != NODE_CONST)
+                return fail(CLG_NO_KERNEL, "the first convolution of a separable pair must be depthwise with constant weights");
+            a.KH = (int)wds.d[2]; a.KW = (int)wds.d[3];
+            a.has_dw = 1;
+            if (pwn.attrs.stride[0] != 1 || pwn.attrs.stride[1] != 1)
+                return fail(CLG_NO_KERNEL, "the 1x1 convolution of a separable pair must have stride 1");
+            c.c_node = wd;
+            use(wd);
+            macs += (double)first.shape.numel() * a.KH * a.KW;
+        }
+        const int Gp = pwn.attrs.groups > 0 ? pwn.attrs.groups : 1;
+        if (Gp != 1 || wps.d[2] != 1 || wps.d[3] != 1 || pwn.attrs.pad[0] != 0 || pwn.attrs.pad[1] != 0 ||
+            wps.d[1] != a.C || g.nodes[wp].kind != NODE_CONST)
+            return fail(CLG_NO_KERNEL, "sepconv ends in an ungrouped 1x1 convolution without padding and with constant weights");
+        a.Cout = (int)wps.d[0];
+        a.HO = (int)pwn.shape.d[2]; a.WO = (int)pwn.shape.d[3];
+        if ((int64_t)a.N * a.HO * a.WO > ((int64_t)1 << 30)) return fail(CLG_NO_KERNEL, "sepconv: too many pixels");
+        for (int u = t_pw + 1; u < len; ++u)
+            if ((rc = add_step(cv, u, false, &epi, c.epi_nodes)) != CLG_OK) return rc;
+        if (epi.bias_c && (epi.bias_inner != (int64_t)a.HO * a.WO || epi.bias_c != a.Cout))
+            return fail(CLG_NO_KERNEL, "bias_add axis does not match the kernel's channel dimension");
+        for (int s = 0; s < epi.n; ++s) use(c.epi_nodes[s]);
+        a.epi = epi;
+        sepconv_resolve(&a);
+        if (sepconv_lds_bytes(a) > 160 * 1024) return fail(CLG_NO_KERNEL, "sepconv: %d input channels do not fit in LDS", a.C);
+        c.pack_bytes = sepconv_pack_bytes(a);
+        c.kind = CALL_SEPCONV;
+        c.a_node = xa;
+        c.b_node = wp;
+        use(xa);
+        use(wp);
+        macs += (double)pwn.shape.numel() * a.C;
+        c.flops = 2.0 * macs;
+        c.bound = 0;
+        c.name = std::string(a.pro_relu ? "relu_" : "") + (c.c_node >= 0 ? "sepconv" + std::to_string(a.KH) : std::string("pwconv")) +
+                 "_w" + std::to_string(a.nwaves) + "m" + std::to_string(a.mt_per_wg) + (epi.n ? "_epi" + std::to_string(epi.n) : std::string());
+    } else if (is_contraction(k0)) {
         const int32_t xa = cv.arg(0, 0), wb = cv.arg(0, 1);
         const Shape &xs = g.nodes[xa].shape, &ws = g.nodes[wb].shape, &ys = anchor.shape;
         use(xa);
@@ -413,19 +490,40 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
         c.a_node = xa;
         c.b_node = wb;
         c.flops = 2.0 * macs;
-    } else if (k0 == CLG_OP_MAX_POOL2D || k0 == CLG_OP_GLOBAL_AVG_POOL2D) {
+    } else if (k0 == CLG_OP_CONCAT) {
+        // the operands go into the call's eight pointer slots for fused-step operands
+        ConcatArgs &a = c.cat;
+        const int ax = anchor.attrs.axis < 0 ? anchor.attrs.axis + out_shape.ndim : anchor.attrs.axis;
+        a.n = (int32_t)anchor.in.size();
+        a.outer = 1;
+        for (int d = 0; d < ax; ++d) a.outer *= out_shape.d[d];
+        a.row = out_shape.numel() / a.outer;
+        for (int i = 0; i < a.n; ++i) {
+            const int32_t v = cv.arg(0, i);
+            a.chunk[i] = g.nodes[v].shape.numel() / a.outer;
+            c.epi_nodes[i] = v;
+            use(v);
+        }
+        c.kind = CALL_CONCAT;
+        c.name = "concat" + std::to_string(a.n);
+        c.a_node = cv.arg(0, 0);
+    } else if (k0 == CLG_OP_MAX_POOL2D || k0 == CLG_OP_AVG_POOL2D || k0 == CLG_OP_GLOBAL_AVG_POOL2D) {
         const int32_t xa = cv.arg(0, 0);
         const Shape &xs = g.nodes[xa].shape;
         use(xa);
         PoolArgs &a = c.pool;
         a.NC = (int)(xs.d[0] * xs.d[1]); a.H = (int)xs.d[2]; a.W = (int)xs.d[3];
-        if (k0 == CLG_OP_MAX_POOL2D) {
-            a.mode = 0;
+        if (k0 != CLG_OP_GLOBAL_AVG_POOL2D) {
+            a.mode = k0 == CLG_OP_MAX_POOL2D ? 0 : 2;
             a.KH = anchor.attrs.kernel[0]; a.KW = anchor.attrs.kernel[1];
             a.sh = anchor.attrs.stride[0]; a.sw = anchor.attrs.stride[1];
             a.ph = anchor.attrs.pad[0]; a.pw = anchor.attrs.pad[1];
             a.HO = (int)anchor.shape.d[2]; a.WO = (int)anchor.shape.d[3];
-            c.name = "max_pool";
+            for (int t = 1; t < len; ++t)
+                if ((rc = add_step(cv, t, false, &epi, c.epi_nodes)) != CLG_OK) return rc;
+            for (int s = 0; s < epi.n; ++s) use(c.epi_nodes[s]);
+            a.epi = epi;
+            c.name = (a.mode == 0 ? "max_pool" : "avg_pool") + (epi.n ? "_epi" + std::to_string(epi.n) : std::string());
         } else {
             a.mode = 1;
             a.HO = a.WO = 1;

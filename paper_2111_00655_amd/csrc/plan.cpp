@@ -303,7 +303,8 @@ int32_t measure_plan(Plan &p, const void *const *inputs, void *const *outputs, v
 }
 
 int32_t pack_weights(const KernelCall &c, const void *w, void *dst, void *stream) {
-    const int err = launch_rf_pack(c.gemm, (const float *)w, (float *)dst, stream);
+    const int err = c.kind == CALL_SEPCONV ? launch_sepconv_pack(c.sep, (const float *)w, (float *)dst, stream)
+                                           : launch_rf_pack(c.gemm, (const float *)w, (float *)dst, stream);
     if (err != 0) return fail(CLG_HIP_ERROR, "weight packing launch failed: %s", hipGetErrorString((hipError_t)err));
     return CLG_OK;
 }
@@ -342,6 +343,7 @@ int32_t launch_call(const KernelCall &c, const void *a, const void *b, const voi
     case CALL_POOL: {
         PoolArgs k = c.pool;
         k.x = (const float *)a; k.y = (float *)out;
+        k.epi = bind(c.pool.epi);
         err = launch_pool(k, stream);
         break;
     }
@@ -363,6 +365,21 @@ int32_t launch_call(const KernelCall &c, const void *a, const void *b, const voi
         LayoutArgs k = c.layout;
         k.x = (const float *)a; k.y = (float *)out;
         err = launch_layout(k, stream);
+        break;
+    }
+    case CALL_SEPCONV: {
+        if (!packed) return fail(CLG_INVALID_ARG, "%s needs packed weights, none were prepared", c.name.c_str());
+        SepConvArgs k = c.sep;
+        k.x = (const float *)a; k.wp = (const float *)packed; k.wd = (const float *)c3; k.y = (float *)out;
+        k.epi = bind(c.sep.epi);
+        err = launch_sepconv(k, stream);
+        break;
+    }
+    case CALL_CONCAT: {
+        ConcatArgs k = c.cat;
+        for (int s = 0; s < k.n; ++s) k.src[s] = (const float *)epi_ptrs[s];
+        k.y = (float *)out;
+        err = launch_concat(k, stream);
         break;
     }
     default:

@@ -140,6 +140,79 @@ def test_grouped_conv_register_fed(case, backend):
     assert name.startswith("conv_rf"), name
 
 
+@pytest.mark.parametrize("backend", ("direct",) + RF)
+@pytest.mark.parametrize("case", [(44, 44, 28, 28, 3, 1, 1, 44), (44, 44, 28, 28, 5, 2, 2, 44), (22, 22, 15, 15, 7, 2, 3, 22),
+                                  (176, 176, 7, 7, 5, 1, 2, 176), (11, 11, 56, 56, 7, 2, 3, 11)])
+def test_depthwise_conv(case, backend):
+    """One input channel per group (the depthwise half of a separable convolution), NasNet-A's sizes."""
+    cin, cout, h, w, k, s, p, g = case
+    d, pat = conv_desc((cin, cout, h, w, k, s, p, ()), 8, groups=g)
+    run_single_group(d, backend, pat)
+
+
+SEP_CASES = [
+    # batch, c, cout, h, w, k (0 = no depthwise stage), stride, pre-relu, tail
+    (1, 44, 44, 28, 28, 3, 1, True, ("bias_add",)),
+    (1, 44, 44, 28, 28, 5, 2, True, ("bias_add", "relu")),
+    (1, 22, 22, 15, 13, 7, 2, True, ("bias_add", "add")),
+    (1, 176, 176, 7, 7, 5, 1, True, ("bias_add", "add", "relu")),
+    (1, 11, 11, 56, 56, 7, 2, False, ("bias_add",)),
+    (2, 88, 88, 14, 14, 3, 1, True, ()),
+    (3, 20, 50, 9, 9, 3, 1, False, ("bias_add",)),            # Cout != C, ragged everything, batch 3
+    (1, 1056, 176, 7, 7, 0, 1, True, ("bias_add",)),          # relu + 1x1 over 1056 channels (LDS > 64 KB)
+    (1, 264, 88, 28, 28, 0, 2, True, ("bias_add",)),          # relu + strided 1x1
+    (1, 32, 11, 112, 112, 0, 1, True, ("bias_add", "relu")),  # many pixels, one m-tile
+    (2, 7, 5, 6, 5, 0, 1, True, ()),
+]
+
+
+@pytest.mark.parametrize("case", SEP_CASES)
+def test_separable_conv_in_one_kernel(case):
+    """[relu] -> depthwise -> 1x1 -> tail (or relu -> 1x1 -> tail) as one kernel against the oracle's
+    operator-by-operator result."""
+    batch, c, cout, h, w, k, s, pre, tail = case
+    r = rng_for(21, c, cout, h, k)
+    d = wl.GraphDesc("sep_case")
+    x = d.input(f32(r, batch, c, h, w))
+    y = d.op("relu", [x]) if pre else x
+    pat = P("relu", W) if pre else W
+    if k:
+        wd = d.const(f32(r, c, 1, k, k, scale=1.0 / k))
+        y = d.op("conv2d", [y, wd], stride=(s, s), pad=(k // 2, k // 2), groups=c)
+        pat = P("conv2d", pat, W)
+    wp = d.const(f32(r, cout, c, 1, 1, scale=1.0 / np.sqrt(c)))
+    y = d.op("conv2d", [y, wp], stride=(1, 1) if k else (s, s), pad=(0, 0), groups=1)
+    pat = P("conv2d", pat, W)
+    for op in tail:
+        if op == "bias_add":
+            y = d.op("bias_add", [y, d.const(f32(r, cout))], axis=1)
+        elif op == "add":
+            ho, wo = ((h + 2 * (k // 2) - k) // s + 1, (w + 2 * (k // 2) - k) // s + 1) if k else ((h - 1) // s + 1, (w - 1) // s + 1)
+            y = d.op("add", [y, d.input(f32(r, batch, cout, ho, wo))])
+        else:
+            y = d.op(op, [y])
+    d.mark_output(y)
+    name, _ = run_single_group(d, "sepconv", tail_pattern(pat, tail))
+    assert ("sepconv" in name) == bool(k) and name.startswith("relu_") == pre, name
+
+
+def test_sepconv_refuses_what_it_cannot_run():
+    r = rng_for(22)
+    d = wl.GraphDesc("not_sep")
+    x = d.input(f32(r, 1, 8, 6, 6))
+    y = d.op("conv2d", [d.op("relu", [x]), d.const(f32(r, 8, 8, 3, 3))], stride=(1, 1), pad=(1, 1), groups=1)
+    d.mark_output(y)
+    s = clg.Session(d, [("sepconv", P("conv2d", P("relu", W), W))], device=0)
+    assert len(s.match()) == 1
+    assert B.clg_profile_match(s.ctx, s.graph, 0) >= B.COST_INF      # a 3x3 convolution is not the 1x1 stage
+    with pytest.raises(clg.ClgError) as e:
+        s.compile([0])
+    assert e.value.status == "NO_KERNEL"
+    s.close()
+    with pytest.raises(clg.ClgError):                                  # a lone convolution is not this family's
+        clg.Session(d, [("sepconv", P("conv2d", W, W))], device=0)
+
+
 def test_grouped_conv_is_refused_by_igemm():
     d, pat = conv_desc((8, 8, 6, 6, 3, 1, 1, ()), 5, groups=2)
     s = clg.Session(d, [("igemm", pat)], device=0)
@@ -388,6 +461,34 @@ def test_pools():
     run_single_group(d, "direct", P("global_avg_pool2d", W), tol=1e-6)
 
 
+@pytest.mark.parametrize("k,s,p,shape", [(3, 1, 1, (2, 5, 15, 13)), (3, 2, 1, (1, 44, 28, 28)), (2, 2, 0, (3, 7, 8, 10)),
+                                         (5, 1, 2, (1, 3, 9, 9))])
+def test_avg_pool_and_pools_with_a_fused_add(k, s, p, shape):
+    r = rng_for(15)
+    d = wl.GraphDesc("avgpool")
+    d.mark_output(d.op("avg_pool2d", [d.input(f32(r, *shape))], kernel=(k, k), stride=(s, s), pad=(p, p)))
+    run_single_group(d, "direct", P("avg_pool2d", W), tol=1e-6)
+    for kind in ("avg_pool2d", "max_pool2d"):
+        d = wl.GraphDesc(kind + "_add")
+        x = d.input(f32(r, *shape))
+        y = d.op(kind, [x], kernel=(k, k), stride=(s, s), pad=(p, p))
+        ho, wo = (shape[2] + 2 * p - k) // s + 1, (shape[3] + 2 * p - k) // s + 1
+        other = d.input(f32(r, shape[0], shape[1], ho, wo))
+        # the pool may be either operand of the add
+        d.mark_output(d.op("add", [other, y] if kind == "max_pool2d" else [y, other]))
+        run_single_group(d, "direct", P("add", P(kind, W), W), tol=1e-6)
+
+
+@pytest.mark.parametrize("shapes,axis", [([(1, 44, 7, 7)] * 6, 1), ([(2, 3, 5, 4), (2, 1, 5, 4), (2, 6, 5, 4)], 1),
+                                         ([(3, 5), (3, 2)], -1), ([(2, 4, 3), (5, 4, 3), (1, 4, 3), (1, 4, 3)], 0),
+                                         ([(1, 8, 4, 4)] * 8, 1)])
+def test_concat(shapes, axis):
+    r = rng_for(16)
+    d = wl.GraphDesc("concat")
+    d.mark_output(d.op("concat", [d.input(f32(r, *s)) for s in shapes], axis=axis))
+    run_single_group(d, "eltwise", P("concat", *([W] * len(shapes))), tol=0.0)
+
+
 # ---------------------------------------------------------- whole graphs
 def _session_and_oracle(desc, reg):
     s = clg.Session(desc, reg, device=0)
@@ -496,6 +597,35 @@ def test_resnext_at_larger_batch(batch):
     assert got[0].shape == (batch, 20)
     assert max(norm_err(a, b) for a, b in zip(got, ref)) <= NET_TOL
     plan.destroy()
+    s.close()
+
+
+def test_nasnet_cells_whole_path():
+    """NasNet-A (paper Sec. 5.1) at reduced size: separable convolutions (depthwise + 1x1), average and
+    max pools, identities, adds and six-way concats in many parallel branches; channel counts that
+    are no multiple of a tile (2, 4, 8 channels; 48-channel concats)."""
+    desc = wl.nasnet_a(0, image=32, stem=8, filters=8, cells=1, classes=10)
+    reg = wl.default_registry(("igemm_s8", "igemm_r16"), sepconv=True)
+    s, g, oms = _session_and_oracle(desc, reg)
+    costs = s.profile(B.ProfileOpts(warmup=2, batches=2, min_batch_us=30, max_launches=30))
+    got_search = s.search(costs, 0)
+    assert got_search == search.dp(g, reg, oms, costs, 0)
+    plan = s.compile(got_search[1])
+    assert any("sepconv" in k["name"] for k in plan.kernels())    # the fused separable kernel wins somewhere
+    got = plan.run()
+    ref = g.run()
+    assert max(norm_err(a, b) for a, b in zip(got, ref)) <= NET_TOL
+    # a second placement: every operator alone, on whatever backend lists it first
+    first = {}
+    for i, m in enumerate(oms):
+        if len(m.nodes) == 1 and costs[i] < B.COST_INF:
+            first.setdefault(m.nodes[0], i)
+    plan2 = s.compile(sorted(first.values()))
+    assert plan2.n_kernels == len(g.op_ids)
+    got2 = plan2.run()
+    assert max(norm_err(a, b) for a, b in zip(got2, ref)) <= NET_TOL
+    plan.destroy()
+    plan2.destroy()
     s.close()
 
 

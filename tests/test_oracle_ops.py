@@ -267,6 +267,35 @@ def test_max_pool_vs_torch_and_padding_is_minus_inf():
     assert np.all(ops.max_pool2d(neg, (3, 3), (2, 2), (1, 1)) < 0)
 
 
+@pytest.mark.parametrize("k,s,p", [(3, 1, 1), (3, 2, 1), (2, 2, 0), (5, 1, 2), (1, 2, 0)])
+def test_avg_pool_vs_torch_padding_not_counted(k, s, p):
+    x = rnd(2, 3, 9, 8)
+    y = ops.avg_pool2d(x, (k, k), (s, s), (p, p))
+    ref = F.avg_pool2d(t64(x), k, s, p, count_include_pad=False).numpy()
+    close(y, ref, rtol=1e-6)
+    # a constant image stays constant up to the border (it would not if padding were counted)
+    assert np.all(ops.avg_pool2d(np.full((1, 2, 6, 7), 2.5, np.float32), (k, k), (s, s), (p, p)) == 2.5)
+
+
+def test_avg_pool_corner_divisor_by_hand():
+    # 3x3 window, pad 1, on a 3x3 ramp 0..8: the corner window holds 0 1 3 4 (mean 2),
+    # the top edge window 0 1 2 3 4 5 (mean 2.5), the centre all nine (mean 4)
+    x = np.arange(9, dtype=np.float32).reshape(1, 1, 3, 3)
+    y = ops.avg_pool2d(x, (3, 3), (1, 1), (1, 1))
+    assert y[0, 0, 0, 0] == 2.0 and y[0, 0, 0, 1] == 2.5 and y[0, 0, 1, 1] == 4.0 and y[0, 0, 2, 2] == 6.0
+
+
+def test_concat_vs_torch_and_by_hand():
+    a, b, c = rnd(2, 3, 4, 5), rnd(2, 1, 4, 5), rnd(2, 6, 4, 5)
+    assert np.array_equal(ops.concat([a, b, c], 1), torch.cat([torch.from_numpy(t) for t in (a, b, c)], 1).numpy())
+    u, v = rnd(3, 4), rnd(3, 2)
+    assert np.array_equal(ops.concat([u, v], -1), np.concatenate([u, v], 1))
+    y = ops.concat([np.zeros((1, 1, 2, 2), np.float32), np.ones((1, 2, 2, 2), np.float32)], 1)
+    assert y.shape == (1, 3, 2, 2) and y[0, 0].sum() == 0 and y[0, 1:].sum() == 8
+    with pytest.raises(ValueError):
+        ops.concat([a, rnd(2, 3, 4, 6)], 1)
+
+
 def test_global_avg_pool():
     x = rnd(2, 5, 3, 4)
     close(ops.global_avg_pool2d(x), x.astype(np.float64).mean((2, 3)))

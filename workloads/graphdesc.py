@@ -27,6 +27,8 @@ OP_KINDS = (
     "take",               # (table[V,H], ids[L] int32) -> [L,H]
     "reshape",            # (x) dims
     "transpose",          # (x) dims = permutation
+    "avg_pool2d",         # (x) kernel, stride, pad; padding is not counted
+    "concat",             # (x0, x1, ...) axis; 2 to 8 operands
 )
 
 

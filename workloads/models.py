@@ -289,6 +289,100 @@ def random_dag(seed: int, n_ops: int = 10, ch: int = 4, image: int = 6
     return g
 
 
+# --------------------------------------------------------------------------
+# NasNet-A (one of the paper's Sec. 5.1 workloads): cells of separable
+# convolutions, poolings and identities joined by adds and a channel concat
+# --------------------------------------------------------------------------
+def nasnet_a(seed: int = 0, image: int = 224, stem: int = 32, filters: int = 44,
+             cells: int = 4, classes: int = 1000, batch: int = 1) -> GraphDesc:
+    """The mobile layout (4 normal cells per stage, 44 filters, 1056 features)
+    by default.  Cell wiring after the published NASNet-A diagram (Zoph et al.
+    2018): five two-branch blocks per cell, unused states concatenated.
+    BatchNorm is folded into the preceding 1x1 convolution as a bias.  A
+    separable convolution is relu -> depthwise k x k -> 1x1 -> bias, applied
+    twice (the stride sits in the first depthwise).  Simplifications of this
+    stand-in: 'same' padding everywhere (224 -> 112 -> 56 -> 28 -> 14 -> 7), and
+    a previous state of twice the resolution is brought down by relu -> 1x1
+    convolution of stride 2 instead of the two-path factorised reduction."""
+    g = GraphDesc("nasnet_a")
+    rw, rx = _Rng(seed), _Rng(seed + 1000003)
+    x = g.input(rx.normal((batch, 3, image, image)), "x")
+
+    def pw(t, cin, cout, stride, nm):                       # relu -> 1x1 -> bias
+        t = g.op("relu", [t], nm + ".relu")
+        return _conv(g, rw, t, cin, cout, 1, stride, 0, act=None, name=nm)
+
+    def sep(t, c, k, stride, nm):
+        for i, s in enumerate((stride, 1)):
+            t = g.op("relu", [t], f"{nm}.{i}.relu")
+            w = g.const(_he(rw, (c, 1, k, k), k * k), f"{nm}.{i}.dw.w")
+            t = g.op("conv2d", [t, w], f"{nm}.{i}.dw", stride=(s, s), pad=(k // 2, k // 2), groups=c)
+            t = _conv(g, rw, t, c, c, 1, 1, 0, act=None, name=f"{nm}.{i}.pw")
+        return t
+
+    def pool(kind, t, stride, nm):
+        return g.op(kind, [t], nm, kernel=(3, 3), stride=(stride, stride), pad=(1, 1))
+
+    def add(a, b, nm):
+        return g.op("add", [a, b], nm)
+
+    def adjust(h, hp, shape_h, shape_p, f, nm):
+        """Both states to `f` channels at the current state's resolution."""
+        (ch, sh), (cp, sp) = shape_h, shape_p
+        hp = pw(hp, cp, f, 1 if sp == sh else 2, nm + ".prev")
+        h = pw(h, ch, f, 1, nm + ".cur")
+        return h, hp
+
+    def normal(h, hp, shape_h, shape_p, f, nm):
+        h, hp = adjust(h, hp, shape_h, shape_p, f, nm)
+        y1 = add(sep(h, f, 3, 1, nm + ".b1l"), h, nm + ".b1")
+        y2 = add(sep(hp, f, 3, 1, nm + ".b2l"), sep(h, f, 5, 1, nm + ".b2r"), nm + ".b2")
+        y3 = add(pool("avg_pool2d", h, 1, nm + ".b3l"), hp, nm + ".b3")
+        y4 = add(pool("avg_pool2d", hp, 1, nm + ".b4l"), pool("avg_pool2d", hp, 1, nm + ".b4r"), nm + ".b4")
+        y5 = add(sep(hp, f, 5, 1, nm + ".b5l"), sep(hp, f, 3, 1, nm + ".b5r"), nm + ".b5")
+        out = g.op("concat", [hp, y1, y2, y3, y4, y5], nm + ".cat", axis=1)
+        return out, (6 * f, shape_h[1])
+
+    def reduction(h, hp, shape_h, shape_p, f, nm):
+        h, hp = adjust(h, hp, shape_h, shape_p, f, nm)
+        y1 = add(sep(hp, f, 7, 2, nm + ".b1l"), sep(h, f, 5, 2, nm + ".b1r"), nm + ".b1")
+        y2 = add(pool("max_pool2d", h, 2, nm + ".b2l"), sep(hp, f, 7, 2, nm + ".b2r"), nm + ".b2")
+        y3 = add(pool("avg_pool2d", h, 2, nm + ".b3l"), sep(hp, f, 5, 2, nm + ".b3r"), nm + ".b3")
+        y4 = add(pool("max_pool2d", h, 2, nm + ".b4l"), sep(y1, f, 3, 1, nm + ".b4r"), nm + ".b4")
+        y5 = add(pool("avg_pool2d", y1, 1, nm + ".b5l"), y2, nm + ".b5")
+        out = g.op("concat", [y2, y3, y4, y5], nm + ".cat", axis=1)
+        return out, (4 * f, (shape_h[1] + 1) // 2)
+
+    size = (image + 1) // 2
+    h = _conv(g, rw, x, 3, stem, 3, 2, 1, act=None, name="stem")
+    states = [(h, (stem, size)), (h, (stem, size))]          # (previous, current)
+
+    def step(cell, f, nm):
+        (hp, sp), (hc, sc) = states
+        out, so = cell(hc, hp, sc, sp, f, nm)
+        states[0], states[1] = (hc, sc), (out, so)
+
+    step(reduction, filters // 4, "stem1")
+    step(reduction, filters // 2, "stem2")
+    for stage in range(3):
+        f = filters * (2 ** stage)
+        if stage:
+            step(reduction, f, f"r{stage}")
+        for c in range(cells):
+            step(normal, f, f"s{stage}c{c}")
+    y, (cin, _) = states[1]
+    y = g.op("relu", [y], "head.relu")
+    p = g.op("global_avg_pool2d", [y], "gap")
+    w = g.const(_he(rw, (classes, cin), cin), "fc.w")
+    b = g.const(rw.uniform((classes,), -0.1, 0.1), "fc.b")
+    d = g.op("dense", [p, w], "fc")
+    logits = g.op("bias_add", [d, b], "fc.bias", axis=-1)
+    prob = g.op("softmax", [logits], "softmax")
+    g.mark_output(logits)
+    g.mark_output(prob)
+    return g
+
+
 MODEL_BUILDERS = {
     "tiny_cnn": tiny_cnn,
     "resnet50": resnet50,
@@ -296,4 +390,5 @@ MODEL_BUILDERS = {
     "bert_base": bert_base,
     "dcgan_b1": lambda seed=0: dcgan(seed, batch=1),
     "dcgan_b64": lambda seed=0: dcgan(seed, batch=64),
+    "nasnet_a": nasnet_a,
 }

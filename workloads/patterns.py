@@ -52,11 +52,12 @@ def _tails(anchor, tails):
     return out
 
 
-def default_registry(variants=("igemm",)):
+def default_registry(variants=("igemm",), sepconv=False):
     """The registry the benchmarks and the GPU parity tests use.  `variants`
     lists the MFMA implicit-GEMM kernel variants to register as separate
     backends (same patterns each), so that the search can pick a tile
-    configuration per layer."""
+    configuration per layer.  `sepconv` adds the one-kernel separable
+    convolution family (NasNet-A's building block)."""
     reg = []
 
     def add(backend, pats):
@@ -76,6 +77,7 @@ def default_registry(variants=("igemm",)):
                 P("transpose", P("reshape", W)),
                 P("reshape", P("transpose", W))]
     add("eltwise", ew_single + ew_fused)
+    add("eltwise", [P("concat", *([W] * n)) for n in range(2, 9)])
 
     # --- row-wise reductions
     add("rowwise", [P("softmax", W), P("layer_norm", W, W, W),
@@ -89,6 +91,14 @@ def default_registry(variants=("igemm",)):
                                     ("bias_add", "add"),
                                     ("bias_add", "add", "relu")]))
     add("direct", [P("max_pool2d", W), P("global_avg_pool2d", W)])
+    add("direct", [P("avg_pool2d", W), P("add", P("avg_pool2d", W), W), P("add", P("max_pool2d", W), W)])
+
+    # --- separable convolution in one kernel: [relu] depthwise 1x1 tail, or relu 1x1 tail
+    sep_anchors = [P("conv2d", P("conv2d", P("relu", W), W), W), P("conv2d", P("conv2d", W, W), W),
+                   P("conv2d", P("relu", W), W)]
+    for anchor in sep_anchors if sepconv else ():
+        add("sepconv", _tails(anchor, [(), ("bias_add",), ("bias_add", "relu"), ("bias_add", "add"),
+                                       ("bias_add", "add", "relu")]))
 
     # --- MFMA implicit GEMM / GEMM variants
     for be in variants:
