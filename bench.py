@@ -250,7 +250,7 @@ def main():
     import workloads as wl
     from paper_2111_00655_amd import binding as B
 
-    reg = wl.default_registry(VARIANTS)
+    reg = wl.default_registry(VARIANTS, sepconv=True)
     opts = B.ProfileOpts(warmup=10, batches=5, min_batch_us=200, max_launches=500)
 
     rules = ()
@@ -275,7 +275,7 @@ def main():
 
     extra = {}
     if not args.no_extra:
-        for name in ("bert_base", "resnext50", "dcgan_b1", "dcgan_b64", "tiny_cnn", "resnet50"):
+        for name in ("bert_base", "resnext50", "dcgan_b1", "dcgan_b64", "tiny_cnn", "nasnet_a", "resnet50"):
             if name == args.model:
                 continue
             d2 = wl.MODEL_BUILDERS[name](0)

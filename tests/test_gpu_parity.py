@@ -553,6 +553,27 @@ def test_model_under_searched_placement(name):
     s.close()
 
 
+@pytest.mark.parametrize("name", ["resnet50", "nasnet_a"])
+def test_model_in_the_benchmark_s_configuration(name):
+    """Full size, the registry and measurer options bench.py uses (all kernel variants and the
+    one-kernel separable convolution family)."""
+    import bench
+    desc = wl.MODEL_BUILDERS[name](0)
+    reg = wl.default_registry(bench.VARIANTS, sepconv=True)
+    s, g, oms = _session_and_oracle(desc, reg)
+    costs = s.profile(B.ProfileOpts(warmup=10, batches=5, min_batch_us=200, max_launches=500))
+    got_search = s.search(costs, 0)
+    assert got_search == search.dp(g, reg, oms, costs, 0)
+    plan = s.compile(got_search[1])
+    got = plan.run()
+    ref = g.run()
+    errs = [norm_err(a, b) for a, b in zip(got, ref)]
+    print(name, "kernels", plan.n_kernels, "errors", errs)
+    assert max(errs) <= NET_TOL, errs
+    plan.destroy()
+    s.close()
+
+
 @pytest.mark.parametrize("name", ["tiny_cnn", "resnet50", "bert_base", "dcgan_b1"])
 def test_model_under_a_rule_generated_registry(name):
     """The registry comes from pattern rules (the generator walks this graph) plus the
