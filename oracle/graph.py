@@ -50,6 +50,12 @@ class Graph:
         k = nd["kind"]
         if k == "conv2d":
             return ops.conv2d(x[0], x[1], a["stride"], a["pad"], a.get("groups", 1))
+        if k == "conv3d":
+            return ops.conv3d(x[0], x[1], a["stride"], a["pad"])
+        if k == "max_pool3d":
+            return ops.max_pool3d(x[0], a["kernel"], a["stride"], a["pad"])
+        if k == "global_avg_pool3d":
+            return ops.global_avg_pool3d(x[0])
         if k == "conv2d_transpose":
             return ops.conv2d_transpose(x[0], x[1], a["stride"], a["pad"])
         if k == "dense":

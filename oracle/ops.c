@@ -76,6 +76,73 @@ void orc_conv2d(const float *x, const float *w, float *y,
         }
 }
 
+/* 3-D convolution (3D-ResNet50, paper Sec. 5.1): x[N,C,D,H,W], w[O,C,KD,KH,KW];
+ * y[n,co,od,oh,ow] = sum_{ci,kd,kh,kw} x[n,ci,od*sd-pd+kd,oh*sh-ph+kh,ow*sw-pw+kw] * w[co,ci,kd,kh,kw],
+ * zero padding. */
+void orc_conv3d(const float *x, const float *w, float *y,
+                int N, int C, int D, int H, int W, int O, int KD, int KH, int KW,
+                int sd, int sh, int sw, int pd, int ph, int pw)
+{
+    const int DO = (D + 2 * pd - KD) / sd + 1;
+    const int HO = (H + 2 * ph - KH) / sh + 1;
+    const int WO = (W + 2 * pw - KW) / sw + 1;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int co = 0; co < O; ++co)
+            for (int od = 0; od < DO; ++od)
+                for (int oh = 0; oh < HO; ++oh)
+                    for (int ow = 0; ow < WO; ++ow) {
+                        double acc = 0.0;
+                        for (int ci = 0; ci < C; ++ci)
+                            for (int kd = 0; kd < KD; ++kd) {
+                                const int id = od * sd - pd + kd;
+                                if (id < 0 || id >= D) continue;
+                                for (int kh = 0; kh < KH; ++kh) {
+                                    const int ih = oh * sh - ph + kh;
+                                    if (ih < 0 || ih >= H) continue;
+                                    for (int kw = 0; kw < KW; ++kw) {
+                                        const int iw = ow * sw - pw + kw;
+                                        if (iw < 0 || iw >= W) continue;
+                                        const double xv = x[((((size_t)n * C + ci) * D + id) * H + ih) * W + iw];
+                                        const double wv = w[((((size_t)co * C + ci) * KD + kd) * KH + kh) * KW + kw];
+                                        acc += xv * wv;
+                                    }
+                                }
+                            }
+                        y[((((size_t)n * O + co) * DO + od) * HO + oh) * WO + ow] = (float)acc;
+                    }
+}
+
+/* max over the 3-D window; padding counts as -infinity */
+void orc_max_pool3d(const float *x, float *y, int NC, int D, int H, int W,
+                    int KD, int KH, int KW, int sd, int sh, int sw, int pd, int ph, int pw)
+{
+    const int DO = (D + 2 * pd - KD) / sd + 1;
+    const int HO = (H + 2 * ph - KH) / sh + 1;
+    const int WO = (W + 2 * pw - KW) / sw + 1;
+    for (int nc = 0; nc < NC; ++nc)
+        for (int od = 0; od < DO; ++od)
+            for (int oh = 0; oh < HO; ++oh)
+                for (int ow = 0; ow < WO; ++ow) {
+                    float best = -INFINITY;
+                    for (int kd = 0; kd < KD; ++kd) {
+                        const int id = od * sd - pd + kd;
+                        if (id < 0 || id >= D) continue;
+                        for (int kh = 0; kh < KH; ++kh) {
+                            const int ih = oh * sh - ph + kh;
+                            if (ih < 0 || ih >= H) continue;
+                            for (int kw = 0; kw < KW; ++kw) {
+                                const int iw = ow * sw - pw + kw;
+                                if (iw < 0 || iw >= W) continue;
+                                const float v = x[(((size_t)nc * D + id) * H + ih) * W + iw];
+                                if (v > best) best = v;
+                            }
+                        }
+                    }
+                    y[(((size_t)nc * DO + od) * HO + oh) * WO + ow] = best;
+                }
+}
+
 /* y[n,co,oh,ow] = sum over (ci,ih,iw,kh,kw) with oh = ih*s-p+kh, ow = iw*s-p+kw
  * of x[n,ci,ih,iw] * w[ci,co,kh,kw];  HO = (H-1)*s - 2p + KH. */
 void orc_conv2d_transpose(const float *x, const float *w, float *y,

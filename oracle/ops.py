@@ -33,6 +33,8 @@ def _sig(name, argtypes, restype=None):
 
 
 _conv2d = _sig("orc_conv2d", [_f, _f, _f] + [C.c_int] * 12)
+_conv3d = _sig("orc_conv3d", [_f, _f, _f] + [C.c_int] * 15)
+_maxpool3d = _sig("orc_max_pool3d", [_f, _f] + [C.c_int] * 13)
 _convt = _sig("orc_conv2d_transpose", [_f, _f, _f] + [C.c_int] * 11)
 _dense = _sig("orc_dense", [_f, _f, _f] + [C.c_int] * 3)
 _bmm = _sig("orc_batch_matmul", [_f, _f, _f] + [C.c_int] * 5)
@@ -101,6 +103,44 @@ def conv2d(x, w, stride=(1, 1), pad=(0, 0), groups=1):
     n, c, h, wd = x.shape
     _conv2d(_p(x), _p(w), _p(y), n, c, h, wd, w.shape[0], w.shape[2],
             w.shape[3], sh, sw, ph, pw, int(groups))
+    return y
+
+
+def _triple(v):
+    return (int(v[0]), int(v[1]), int(v[2]))
+
+
+def conv3d(x, w, stride=(1, 1, 1), pad=(0, 0, 0)):
+    x, w = _f32(x), _f32(w)
+    n, c, d, h, wd = x.shape
+    o, ci, kd, kh, kw = w.shape
+    if ci != c:
+        raise ValueError("conv3d: channels")
+    (sd, sh, sw), (pd, ph, pw) = _triple(stride), _triple(pad)
+    do, ho, wo = (d + 2 * pd - kd) // sd + 1, (h + 2 * ph - kh) // sh + 1, (wd + 2 * pw - kw) // sw + 1
+    if min(do, ho, wo) <= 0:
+        raise ValueError("conv3d: empty output")
+    y = np.empty((n, o, do, ho, wo), np.float32)
+    _conv3d(_p(x), _p(w), _p(y), n, c, d, h, wd, o, kd, kh, kw, sd, sh, sw, pd, ph, pw)
+    return y
+
+
+def max_pool3d(x, kernel=(3, 3, 3), stride=(2, 2, 2), pad=(1, 1, 1)):
+    x = _f32(x)
+    n, c, d, h, w = x.shape
+    (kd, kh, kw), (sd, sh, sw), (pd, ph, pw) = _triple(kernel), _triple(stride), _triple(pad)
+    do, ho, wo = (d + 2 * pd - kd) // sd + 1, (h + 2 * ph - kh) // sh + 1, (w + 2 * pw - kw) // sw + 1
+    y = np.empty((n, c, do, ho, wo), np.float32)
+    _maxpool3d(_p(x), _p(y), n * c, d, h, w, kd, kh, kw, sd, sh, sw, pd, ph, pw)
+    return y
+
+
+def global_avg_pool3d(x):
+    """Mean over D, H and W; output [N, C]."""
+    x = _f32(x)
+    n, c, d, h, w = x.shape
+    y = np.empty((n, c), np.float32)
+    _gap(_p(x), _p(y), n * c, d * h * w)
     return y
 
 

@@ -296,6 +296,39 @@ def test_concat_vs_torch_and_by_hand():
         ops.concat([a, rnd(2, 3, 4, 6)], 1)
 
 
+@pytest.mark.parametrize("k,s,p", [((3, 3, 3), (1, 1, 1), (1, 1, 1)), ((3, 3, 3), (2, 2, 2), (1, 1, 1)),
+                                   ((7, 7, 7), (1, 2, 2), (3, 3, 3)), ((1, 1, 1), (2, 2, 2), (0, 0, 0)),
+                                   ((3, 1, 2), (1, 2, 1), (0, 0, 1))])
+def test_conv3d_vs_torch(k, s, p):
+    x, w = rnd(2, 3, 6, 9, 8), rnd(5, 3, *k)
+    ref = F.conv3d(t64(x), t64(w), stride=s, padding=p).numpy()
+    close(ops.conv3d(x, w, s, p), ref, rtol=1e-5)
+
+
+def test_conv3d_closed_forms():
+    # all-ones kernel on an all-ones volume counts the taps inside: 27 in the middle, 8 in a corner
+    y = ops.conv3d(np.ones((1, 2, 4, 4, 4), np.float32), np.ones((1, 2, 3, 3, 3), np.float32), (1, 1, 1), (1, 1, 1))
+    assert y[0, 0, 1, 1, 1] == 54 and y[0, 0, 0, 0, 0] == 16 and y[0, 0, 0, 1, 1] == 36
+    # a delta at tap (kd, kh, kw) = (2, 0, 1) reads x at (d + 1, h - 1, w): the three axes are not interchangeable
+    x = rnd(1, 1, 5, 5, 5)
+    w = np.zeros((1, 1, 3, 3, 3), np.float32)
+    w[0, 0, 2, 0, 1] = 1
+    y = ops.conv3d(x, w, (1, 1, 1), (1, 1, 1))
+    assert np.array_equal(y[0, 0, 1:4, 1:5, :], x[0, 0, 2:5, 0:4, :]) and np.all(y[0, 0, 4] == 0) and np.all(y[0, 0, :, 0] == 0)
+    # depth 1, kernel depth 1: the 2-D convolution
+    x2, w2 = rnd(2, 3, 7, 6), rnd(4, 3, 3, 3)
+    y3 = ops.conv3d(x2[:, :, None], w2[:, :, None], (1, 2, 1), (0, 1, 1))
+    assert np.array_equal(y3[:, :, 0], ops.conv2d(x2, w2, (2, 1), (1, 1)))
+
+
+def test_max_pool3d_and_global_avg_pool3d():
+    x = rnd(2, 3, 6, 9, 8)
+    assert np.array_equal(ops.max_pool3d(x, (3, 3, 3), (2, 2, 2), (1, 1, 1)), F.max_pool3d(torch.from_numpy(x), 3, 2, 1).numpy())
+    assert np.array_equal(ops.max_pool3d(x, (1, 3, 2), (1, 2, 2), (0, 1, 0)),
+                          F.max_pool3d(torch.from_numpy(x), (1, 3, 2), (1, 2, 2), (0, 1, 0)).numpy())
+    close(ops.global_avg_pool3d(x), x.astype(np.float64).mean((2, 3, 4)))
+
+
 def test_global_avg_pool():
     x = rnd(2, 5, 3, 4)
     close(ops.global_avg_pool2d(x), x.astype(np.float64).mean((2, 3)))

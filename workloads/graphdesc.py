@@ -29,6 +29,9 @@ OP_KINDS = (
     "transpose",          # (x) dims = permutation
     "avg_pool2d",         # (x) kernel, stride, pad; padding is not counted
     "concat",             # (x0, x1, ...) axis; 2 to 8 operands
+    "conv3d",             # (x[N,C,D,H,W], w[O,C,kd,kh,kw]) stride, pad: 3 entries each (d, h, w)
+    "max_pool3d",         # (x[N,C,D,H,W]) kernel, stride, pad: 3 entries each
+    "global_avg_pool3d",  # (x[N,C,D,H,W]) -> [N,C]
 )
 
 
