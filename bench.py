@@ -275,7 +275,7 @@ def main():
 
     extra = {}
     if not args.no_extra:
-        for name in ("bert_base", "resnext50", "dcgan_b1", "dcgan_b64", "tiny_cnn", "nasnet_a", "resnet50"):
+        for name in ("bert_base", "resnext50", "dcgan_b1", "dcgan_b64", "tiny_cnn", "nasnet_a", "resnet3d_50", "resnet50"):
             if name == args.model:
                 continue
             d2 = wl.MODEL_BUILDERS[name](0)

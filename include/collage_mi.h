@@ -86,7 +86,12 @@ typedef enum clg_op_kind {
     CLG_OP_AVG_POOL2D = 17,         /* (x); kernel stride pad; mean over the window's
                                        pixels inside the image (padding not counted) */
     CLG_OP_CONCAT = 18,             /* (x0, x1, ...), 2..8 operands; axis         */
-    CLG_OP_COUNT = 19
+    CLG_OP_CONV3D = 19,             /* (x[N,C,D,H,W], w[O,C,kd,kh,kw]); stride pad, with
+                                       stride_d pad_d for the depth axis             */
+    CLG_OP_MAX_POOL3D = 20,         /* (x[N,C,D,H,W]); kernel stride pad + kernel_d
+                                       stride_d pad_d; padding = -inf                */
+    CLG_OP_GLOBAL_AVG_POOL3D = 21,  /* (x[N,C,D,H,W]) -> [N,C]                      */
+    CLG_OP_COUNT = 22
 } clg_op_kind;
 
 #define CLG_MAX_DIMS 6
@@ -105,6 +110,10 @@ typedef struct clg_attrs {
     int64_t dims[CLG_MAX_DIMS];
     double scalar;          /* mul_scalar                                     */
     double eps;             /* layer_norm                                     */
+    int32_t stride_d;       /* conv3d, max_pool3d: the depth axis (stride, pad */
+    int32_t pad_d;          /* and kernel hold the H and W entries)            */
+    int32_t kernel_d;       /* max_pool3d window depth                         */
+    int32_t reserved_;
 } clg_attrs;
 
 /* Attribute constraints of a pattern node (the has_attr of the paper's

@@ -23,7 +23,8 @@ WILDCARD = -1
 
 OP_KINDS = ("conv2d", "conv2d_transpose", "dense", "batch_matmul", "bias_add", "add",
             "mul_scalar", "relu", "gelu", "tanh", "softmax", "layer_norm", "max_pool2d",
-            "global_avg_pool2d", "take", "reshape", "transpose", "avg_pool2d", "concat")
+            "global_avg_pool2d", "take", "reshape", "transpose", "avg_pool2d", "concat",
+            "conv3d", "max_pool3d", "global_avg_pool3d")
 OP_ID = {k: i for i, k in enumerate(OP_KINDS)}
 ATTR_ID = {k: i for i, k in enumerate(("groups", "kernel_h", "kernel_w", "stride_h", "stride_w",
                                        "pad_h", "pad_w", "transpose_b", "axis"))}
@@ -44,7 +45,8 @@ class Attrs(C.Structure):
     _fields_ = [("stride", C.c_int32 * 2), ("pad", C.c_int32 * 2), ("kernel", C.c_int32 * 2),
                 ("groups", C.c_int32), ("axis", C.c_int32), ("transpose_b", C.c_int32),
                 ("ndims", C.c_int32), ("dims", C.c_int64 * MAX_DIMS), ("scalar", C.c_double),
-                ("eps", C.c_double)]
+                ("eps", C.c_double), ("stride_d", C.c_int32), ("pad_d", C.c_int32), ("kernel_d", C.c_int32),
+                ("reserved_", C.c_int32)]
 
 
 class AttrConstraint(C.Structure):
@@ -226,9 +228,13 @@ def clg_graph_const(g, dtype, shape, dev_ptr):
 
 def make_attrs(**kw):
     a = Attrs()
+    a.stride_d, a.pad_d, a.kernel_d = 1, 0, 1
     for k in ("stride", "pad", "kernel"):
         if k in kw:
             v = kw[k]
+            if len(v) == 3:                  # (depth, height, width) of the 3-D operators
+                setattr(a, k + "_d", int(v[0]))
+                v = v[1:]
             getattr(a, k)[0], getattr(a, k)[1] = int(v[0]), int(v[1])
     a.groups = int(kw.get("groups", 1))
     a.axis = int(kw.get("axis", 1))

@@ -80,7 +80,9 @@ struct RfMfma<16> {
 // phase, each with its own packed (tap-flipped) weights.  k4 s2 p1 gives four
 // 2x2 phases.
 
-template <int TS, int TAPK, int WGK, bool CONVT>
+// GEO: 0 = convolution (2-D, or 3-D with a single depth tap), 1 = transposed convolution,
+// 2 = 3-D convolution with the depth taps folded into the channel index.
+template <int TS, int TAPK, int WGK, int GEO>
 __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
     using MF = RfMfma<TS>;
     typedef typename MF::acc_t acc_t;
@@ -89,6 +91,8 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
     constexpr int PER_WAVE = NACC * kWave;                  // outputs of a tile
     constexpr int EPT = (PER_WAVE + NT - 1) / NT;           // outputs finished per thread
     extern __shared__ float red[];
+    constexpr bool CONVT = GEO == 1;
+    constexpr bool FOLD = GEO == 2;
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -120,16 +124,25 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
     const int mt = p.rf_jmajor ? t_lo : t_hi;
     const int nt = p.rf_jmajor ? t_hi : t_lo;
     const int i0 = mt * TS, j0 = nt * TS;
-    const int img = blockIdx.y;
+    // grid.y: the image, or (image, output depth) of a 3-D convolution
+    int img = blockIdx.y, od = 0;
+    const int DOe = p.DO > 1 ? p.DO : 1;
+    if (p.DO > 1) {
+        img = blockIdx.y / p.DO;
+        od = blockIdx.y - img * p.DO;
+    }
+    const int id0 = od * p.sd - p.pd;                        // input depth of depth tap 0
 
     const int jp = min(j0 + r, npix - 1);
     const int oh = (int)(((uint64_t)(uint32_t)jp * p.rf_wo_magic) >> 32);
     const int ow = jp - oh * WOe;
     const int ih0 = oh * she - phe, iw0 = ow * swe - pwe;
     const int HW = p.H * p.W;
+    const int CS = p.rf_cs;                                  // elements between channels: HW, or D * HW
     const int cbase = p.rf_groups > 1 ? (i0 / p.rf_cpg_out) * p.rf_cpg_in : 0;
     const int cin = min(p.rf_cin_tile, p.Cin - cbase);       // input channels this m-tile contracts
-    const float *const x_img = p.B + ((int64_t)img * p.Cin + cbase) * HW;
+    // without folded depth taps the single depth tap's plane is part of the base address
+    const float *const x_img = p.B + (int64_t)img * p.rf_img_stride + (int64_t)cbase * CS + (FOLD ? 0 : (int64_t)id0 * HW);
     // packed weights of this m-tile; a wave's load is base + uniform group offset + lane
     const f32x4 *const Ab = reinterpret_cast<const f32x4 *>(p.A) + ((int64_t)phase * tiles_m + mt) * p.rf_ngtot * kWave;
     const uint32_t lane_u = (uint32_t)lane;
@@ -145,7 +158,7 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
         const int e = tid + t * NT;
         const int l = e % kWave, g = e / kWave;
         const int i = i0 + MF::row(g, l / TS), j = j0 + l % TS;
-        e_off[t] = (e < PER_WAVE && i < p.Cout && j < npix) ? ((int64_t)img * p.Cout + i) * npix + j : -1;
+        e_off[t] = (e < PER_WAVE && i < p.Cout && j < npix) ? (((int64_t)img * p.Cout + i) * DOe + od) * npix + j : -1;
         if (CONVT && e_off[t] >= 0) {                 // the phase's pixel (oh', ow') is output pixel (a_h + s oh', a_w + s ow')
             const int ohh = (int)(((uint64_t)(uint32_t)j * p.rf_wo_magic) >> 32), oww = j - ohh * WOe;
             e_off[t] = (((int64_t)img * p.Cout + i) * p.HO + a_h + p.sh * ohh) * p.WO + a_w + p.sw * oww;
@@ -166,8 +179,8 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
         // ---- 1x1: MFMA n contracts channels n*NSLOT .. n*NSLOT+NSLOT-1 at this lane's pixel
         // addresses are "uniform base + 32-bit lane offset": one scalar multiply and no 64-bit
         // vector arithmetic per load (offsets within an image fit 32 bits: checked on the host)
-        const uint32_t lane_off = (uint32_t)(s * HW + ih0 * p.W + iw0);
-        const uint32_t cq_step = (uint32_t)(NSLOT * HW);
+        const uint32_t lane_off = (uint32_t)(s * CS + ih0 * p.W + iw0);
+        const uint32_t cq_step = (uint32_t)(NSLOT * CS);
         f32x4 a[2][4];
         float b[2][16];
 #define CLG_RF_LOAD(set, c)                                                                   \
@@ -204,18 +217,29 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
         for (int t = 0; t < 9; ++t) {
             const int ih = ih0 + t / 3, iw = iw0 + t % 3;
             ok[t] = ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
-            voff[t] = (uint32_t)(s * HW + (ok[t] ? ih * p.W + iw : 0));
+            voff[t] = (uint32_t)((FOLD ? 0 : s * CS) + (ok[t] ? ih * p.W + iw : 0));
         }
-        const uint32_t cq_step = (uint32_t)(NSLOT * HW);
+        const uint32_t cq_step = (uint32_t)(NSLOT * CS);
         for (int c = 0; c < nch; ++c) {
             const int ch = c0 + c;
             f32x4 a[9];
             float b[36];
+            bool okd[4] = {true, true, true, true};
 #pragma unroll
             for (int u = 0; u < 9; ++u) a[u] = (Ab + (uint32_t)(ch * 9 + u) * kWave)[lane_u];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const float *xc = x_img + (uint32_t)min(ch * 4 + q, cq_last) * cq_step;
+                const float *xc;
+                if constexpr (FOLD) {
+                    // this lane's folded channel c * KD + kd: plane (c, id0 + kd) of the volume
+                    const uint32_t chq = (uint32_t)(min(ch * 4 + q, cq_last) * NSLOT + s);
+                    const uint32_t cc = (uint32_t)(((uint64_t)chq * p.rf_kd_magic) >> 32);
+                    const int idd = id0 + (int)(chq - cc * (uint32_t)p.KD);
+                    okd[q] = idd >= 0 && idd < p.D;
+                    xc = x_img + (cc * (uint32_t)p.D + (uint32_t)(okd[q] ? idd : 0)) * (uint32_t)HW;
+                } else {
+                    xc = x_img + (uint32_t)min(ch * 4 + q, cq_last) * cq_step;
+                }
 #pragma unroll
                 for (int t = 0; t < 9; ++t) {
                     const float v = xc[voff[t]];
@@ -224,7 +248,7 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
             }
             __builtin_amdgcn_sched_barrier(0);       // all 45 loads go out before the first MFMA waits
 #pragma unroll
-            for (int u = 0; u < 36; ++u) b[u] = ok[u % 9] ? b[u] : 0.f;
+            for (int u = 0; u < 36; ++u) b[u] = (ok[u % 9] && okd[u / 9]) ? b[u] : 0.f;
 #pragma unroll
             for (int u = 0; u < 36; ++u) acc = MF::mma(a[u / 4][u % 4], b[u], acc);
         }
@@ -237,9 +261,9 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
         for (int t = 0; t < 4; ++t) {
             const int ih = ih0 + t / 2, iw = iw0 + t % 2;
             ok[t] = ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
-            voff[t] = (uint32_t)(s * HW + (ok[t] ? ih * p.W + iw : 0));
+            voff[t] = (uint32_t)(s * CS + (ok[t] ? ih * p.W + iw : 0));
         }
-        const uint32_t cq_step = (uint32_t)(NSLOT * HW);
+        const uint32_t cq_step = (uint32_t)(NSLOT * CS);
         f32x4 a[2][4];
         float b[2][16];
 #define CLG_RF_LOAD(set, c)                                                                   \
@@ -282,8 +306,15 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
             for (int q = 0; q < 4; ++q) {
                 const int ch = cq * NSLOT + s;
                 const int ih = ih0 + kh, iw = iw0 + kw;
-                const bool ok = n < nm && ch < cin && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
-                const float v = x_img[ok ? (int64_t)ch * HW + ih * p.W + iw : 0];
+                bool ok = n < nm && ch < cin && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
+                int64_t plane = (int64_t)ch * CS;
+                if constexpr (FOLD) {
+                    const uint32_t cc = (uint32_t)(((uint64_t)(uint32_t)ch * p.rf_kd_magic) >> 32);
+                    const int idd = id0 + (ch - (int)cc * p.KD);
+                    ok = ok && idd >= 0 && idd < p.D;
+                    plane = ((int64_t)cc * p.D + idd) * HW;
+                }
+                const float v = x_img[ok ? plane + ih * p.W + iw : 0];
                 b[q] = ok ? v : 0.f;
                 ++n;
                 if (++kw == KWe) {

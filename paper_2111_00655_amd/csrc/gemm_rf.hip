@@ -7,24 +7,30 @@ namespace clg {
 
 namespace {
 
-template <int TS, int TAPK, int WGK, bool CONVT>
+template <int TS, int TAPK, int WGK, int GEO>
 int launch_rf_one_t(const GemmArgs &a, hipStream_t s) {
     const int npix = a.rf_convt ? (a.HO / a.sh) * (a.WO / a.sw) : a.HO * a.WO;
     const int tiles = ((a.Cout + TS - 1) / TS) * ((npix + TS - 1) / TS);
     const size_t lds = WGK > 1 ? (size_t)WGK * RfMfma<TS>::NACC * kWave * sizeof(float) : 0;
     const int gz = a.rf_convt ? a.sh * a.sw : a.splitk;      // sub-pixel phases, or K splits
-    hipLaunchKernelGGL((conv_rf_kernel<TS, TAPK, WGK, CONVT>), dim3(tiles, a.Nimg, gz), dim3(WGK * kWave), lds, s, a);
+    const int gy = a.Nimg * (a.DO > 1 ? a.DO : 1);           // images, or (image, output depth) pairs
+    if (gy > 65535) return (int)hipErrorInvalidValue;
+    hipLaunchKernelGGL((conv_rf_kernel<TS, TAPK, WGK, GEO>), dim3(tiles, gy, gz), dim3(WGK * kWave), lds, s, a);
     return (int)hipGetLastError();
 }
 
-// transposed convolutions run the 2x2 and the any-filter paths only
+// transposed convolutions run the 2x2 and the any-filter paths only, folded depth taps the 3x3 and the
+// any-filter paths
 template <int TS, int TAPK, int WGK>
 int launch_rf_one(const GemmArgs &a, hipStream_t s) {
     if constexpr (TAPK == 4 || TAPK == 0) {
-        if (a.rf_convt) return launch_rf_one_t<TS, TAPK, WGK, true>(a, s);
+        if (a.rf_convt) return launch_rf_one_t<TS, TAPK, WGK, 1>(a, s);
     }
-    if (a.rf_convt) return (int)hipErrorInvalidValue;
-    return launch_rf_one_t<TS, TAPK, WGK, false>(a, s);
+    if constexpr (TAPK == 9 || TAPK == 0) {
+        if (a.rf_fold && !a.rf_convt) return launch_rf_one_t<TS, TAPK, WGK, 2>(a, s);
+    }
+    if (a.rf_convt || a.rf_fold) return (int)hipErrorInvalidValue;
+    return launch_rf_one_t<TS, TAPK, WGK, 0>(a, s);
 }
 
 template <int TS, int TAPK>
@@ -142,10 +148,22 @@ bool rf_resolve(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves) {
     const int nslot = ts == 32 ? 2 : 4;
     const int64_t npix = (int64_t)a->HO * a->WO;
     if (npix * a->WO >= ((int64_t)1 << 32)) return false;             // multiply-high division range
-    if ((int64_t)a->Cin * a->H * a->W >= ((int64_t)1 << 30)) return false;   // 32-bit lane offsets
+    // depth geometry: a 2-D convolution has depth 1 everywhere; with KD > 1 the depth taps are folded into
+    // the channel index, and Cin counts folded channels (the weights [Cout][Cin][KD][KH*KW] are then
+    // [Cout][Cin * KD][KH*KW] as they lie)
+    if (a->D < 1) { a->D = 1; a->KD = 1; a->sd = 1; a->pd = 0; a->DO = 1; }
+    const int cin_real = a->Cin;
+    a->rf_fold = a->KD > 1 ? 1 : 0;
+    a->rf_cs = a->D * a->H * a->W;
+    a->rf_img_stride = (int64_t)cin_real * a->rf_cs;
+    a->rf_kd_magic = (((uint64_t)1 << 32) / (uint64_t)a->KD) + 1;
+    if (a->rf_img_stride >= ((int64_t)1 << 30)) return false;         // 32-bit lane offsets
+    if (!a->rf_fold && a->pd != 0) return false;                      // a single depth tap must lie inside
+    const int groups = a->rf_groups > 1 ? a->rf_groups : 1;
+    if (a->rf_fold && groups > 1) return false;
+    a->Cin = cin_real * a->KD;
     const int taps = a->KH * a->KW;
     // grouped: an m-tile contracts the channels of the groups its rows belong to
-    const int groups = a->rf_groups > 1 ? a->rf_groups : 1;
     int cin_tile = a->Cin;
     if (groups > 1) {
         if (a->Cin % groups || a->Cout % groups) return false;
@@ -160,12 +178,12 @@ bool rf_resolve(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves) {
     const int ncq = (cin_tile + nslot - 1) / nslot;
     int tapk = 0;
     if (cin_tile % nslot == 0 && (groups == 1 || a->rf_cpg_in % nslot == 0)) {
-        if (taps == 1 && a->ph == 0 && a->pw == 0) tapk = 1;
+        if (taps == 1 && a->ph == 0 && a->pw == 0 && !a->rf_fold) tapk = 1;
         else if (a->KH == 3 && a->KW == 3) tapk = 9;
     }
     const int nm = ncq * taps;
     const int nc = (nm + chunk_mfmas(tapk) - 1) / chunk_mfmas(tapk);   // chunks per tile
-    const int wgk = pick_waves(nc, (int64_t)((a->Cout + ts - 1) / ts) * ((npix + ts - 1) / ts) * a->Nimg, waves, tapk == 0);
+    const int wgk = pick_waves(nc, (int64_t)((a->Cout + ts - 1) / ts) * ((npix + ts - 1) / ts) * a->Nimg * a->DO, waves, tapk == 0);
     a->rf_ts = ts;
     a->rf_tapk = tapk;
     a->rf_wgk = wgk;
@@ -178,6 +196,8 @@ bool rf_resolve(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves) {
     if (set_tile_order(a, (a->Cout + ts - 1) / ts, (int)((npix + ts - 1) / ts))) return true;
     a->rf_ts = 0;
     a->rf_convt = 0;
+    a->rf_fold = 0;
+    a->Cin = cin_real;
     return false;
 }
 
@@ -212,6 +232,12 @@ bool rf_resolve_convt(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves) 
     a->rf_groups = 1;
     a->rf_cin_tile = a->Cin;
     a->rf_convt = 1;
+    a->D = a->KD = a->sd = a->DO = 1;
+    a->pd = 0;
+    a->rf_fold = 0;
+    a->rf_cs = a->H * a->W;
+    a->rf_img_stride = (int64_t)a->Cin * a->rf_cs;
+    a->rf_kd_magic = 0;
     a->rf_jmajor = (int64_t)a->Cin * a->H * a->W > (int64_t)a->Cout * a->Cin * taps ? 1 : 0;
     a->rf_wo_magic = (((uint64_t)1 << 32) / (uint64_t)woe) + 1;
     if (set_tile_order(a, (a->Cout + ts - 1) / ts, (int)((npix + ts - 1) / ts))) return true;

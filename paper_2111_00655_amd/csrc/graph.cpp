@@ -26,7 +26,8 @@ const char *last_error() { return g_err; }
 static const char *kOpNames[CLG_OP_COUNT] = {
     "conv2d", "conv2d_transpose", "dense", "batch_matmul", "bias_add", "add",
     "mul_scalar", "relu", "gelu", "tanh", "softmax", "layer_norm", "max_pool2d",
-    "global_avg_pool2d", "take", "reshape", "transpose", "avg_pool2d", "concat"};
+    "global_avg_pool2d", "take", "reshape", "transpose", "avg_pool2d", "concat", "conv3d", "max_pool3d",
+    "global_avg_pool3d"};
 
 const char *op_name(int32_t kind) {
     if (kind >= 0 && kind < CLG_OP_COUNT) return kOpNames[kind];
@@ -47,7 +48,7 @@ std::string Shape::str() const {
 static int n_operands(int32_t kind) {
     switch (kind) {
     case CLG_OP_CONV2D: case CLG_OP_CONV2D_TRANSPOSE: case CLG_OP_DENSE:
-    case CLG_OP_BATCH_MATMUL: case CLG_OP_BIAS_ADD: case CLG_OP_ADD: case CLG_OP_TAKE:
+    case CLG_OP_BATCH_MATMUL: case CLG_OP_BIAS_ADD: case CLG_OP_ADD: case CLG_OP_TAKE: case CLG_OP_CONV3D:
         return 2;
     case CLG_OP_LAYER_NORM:
         return 3;
@@ -92,6 +93,36 @@ int32_t infer_shape(const Graph &g, int32_t kind, const std::vector<int32_t> &in
         y.ndim = 4; y.d[0] = x.d[0]; y.d[1] = w.d[0]; y.d[2] = ho; y.d[3] = wo;
         break;
     }
+    case CLG_OP_CONV3D: {
+        const Shape &w = g.nodes[in[1]].shape;
+        if (x.ndim != 5 || w.ndim != 5 || !f32(1)) return bad("needs x[N,C,D,H,W], w[O,C,kd,kh,kw]");
+        if (a.stride_d < 1 || a.stride[0] < 1 || a.stride[1] < 1 || a.pad_d < 0 || a.pad[0] < 0 || a.pad[1] < 0)
+            return bad("stride/pad");
+        if (a.groups > 1 || w.d[1] != x.d[1]) return bad("channels (groups must be 1)");
+        const int64_t st[3] = {a.stride_d, a.stride[0], a.stride[1]}, pd[3] = {a.pad_d, a.pad[0], a.pad[1]};
+        y.ndim = 5; y.d[0] = x.d[0]; y.d[1] = w.d[0];
+        for (int d = 0; d < 3; ++d) {
+            if (x.d[2 + d] + 2 * pd[d] < w.d[2 + d]) return bad("empty output");
+            y.d[2 + d] = (x.d[2 + d] + 2 * pd[d] - w.d[2 + d]) / st[d] + 1;
+        }
+        break;
+    }
+    case CLG_OP_MAX_POOL3D: {
+        if (x.ndim != 5) return bad("needs x[N,C,D,H,W]");
+        const int64_t k[3] = {a.kernel_d, a.kernel[0], a.kernel[1]}, st[3] = {a.stride_d, a.stride[0], a.stride[1]},
+                      pd[3] = {a.pad_d, a.pad[0], a.pad[1]};
+        y.ndim = 5; y.d[0] = x.d[0]; y.d[1] = x.d[1];
+        for (int d = 0; d < 3; ++d) {
+            if (k[d] < 1 || st[d] < 1 || pd[d] < 0 || 2 * pd[d] > k[d]) return bad("kernel/stride/pad");
+            if (x.d[2 + d] + 2 * pd[d] < k[d]) return bad("empty output");
+            y.d[2 + d] = (x.d[2 + d] + 2 * pd[d] - k[d]) / st[d] + 1;
+        }
+        break;
+    }
+    case CLG_OP_GLOBAL_AVG_POOL3D:
+        if (x.ndim != 5) return bad("needs x[N,C,D,H,W]");
+        y.ndim = 2; y.d[0] = x.d[0]; y.d[1] = x.d[1];
+        break;
     case CLG_OP_CONV2D_TRANSPOSE: {
         const Shape &w = g.nodes[in[1]].shape;
         if (x.ndim != 4 || w.ndim != 4 || !f32(1)) return bad("needs x[N,C,H,W], w[C,O,kh,kw]");

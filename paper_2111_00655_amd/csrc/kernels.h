@@ -92,6 +92,13 @@ struct GemmArgs {
     int32_t rf_jmajor, rf_groups;          // rf_groups > 1: grouped convolution (Cin, Cout are totals)
     int32_t rf_cin_tile, rf_cpg_in, rf_cpg_out;            // channels contracted per m-tile; channels per group
     int32_t rf_convt;                      // 1: transposed convolution, one sub-pixel phase per grid.z slice
+    // 3-D convolution on the register-fed kernels: one grid.y slice per (image, output depth);
+    // the depth taps are folded into the channel index (channel' = c * KD + kd, Cin holds Cin * KD)
+    int32_t D, KD, sd, pd, DO;             // input depth, depth taps, depth stride / padding, output depth (1, 1, 1, 0, 1 for 2-D)
+    int32_t rf_fold;                       // 1: KD > 1
+    int32_t rf_cs;                         // elements between two input channels (D * H * W)
+    int64_t rf_img_stride;                 // elements between two images of x
+    uint64_t rf_kd_magic;                  // floor(2^32 / KD) + 1
     uint64_t rf_wo_magic;                  // floor(2^32 / WO) + 1: pixel / WO by multiply-high
     uint64_t rf_tile_magic;                // the same for rf_tile_div
     int32_t rf_tile_div, rf_pad2_;         // tiles along the fast axis of the tile order (m-tiles if rf_jmajor)
@@ -117,6 +124,7 @@ struct PoolArgs {
     float *y;
     int32_t mode;                          // 0 max pool, 1 global average, 2 average pool (padding not counted)
     int32_t NC, H, W, KH, KW, sh, sw, ph, pw, HO, WO;
+    int32_t D, KD, sd, pd, DO;             // depth axis of a 3-D window pool (1, 1, 1, 0, 1 for 2-D)
     Epilogue epi;                          // fused elementwise tail of a window pool
 };
 

@@ -311,23 +311,28 @@ int launch_direct_conv(const DirectConvArgs &a, void *stream) {
 // One output pixel per thread.  AVG: mean over the window's pixels inside the image.
 template <bool AVG>
 __global__ __launch_bounds__(256) void window_pool_kernel(PoolArgs a) {
-    const int64_t total = (int64_t)a.NC * a.HO * a.WO;
+    const int64_t total = (int64_t)a.NC * a.DO * a.HO * a.WO;
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= total) return;
     const int ow = (int)(i % a.WO), oh = (int)((i / a.WO) % a.HO);
-    const int64_t nc = i / ((int64_t)a.WO * a.HO);
-    const float *xp = a.x + nc * a.H * a.W;
+    const int od = (int)((i / ((int64_t)a.WO * a.HO)) % a.DO);
+    const int64_t nc = i / ((int64_t)a.WO * a.HO * a.DO);
+    const float *xp = a.x + nc * a.D * a.H * a.W;
     float acc = AVG ? 0.f : -INFINITY;
     int cnt = 0;
-    for (int kh = 0; kh < a.KH; ++kh) {
-        const int ih = oh * a.sh - a.ph + kh;
-        if (ih < 0 || ih >= a.H) continue;
-        for (int kw = 0; kw < a.KW; ++kw) {
-            const int iw = ow * a.sw - a.pw + kw;
-            if (iw < 0 || iw >= a.W) continue;
-            const float v = xp[(int64_t)ih * a.W + iw];
-            acc = AVG ? acc + v : fmaxf(acc, v);
-            ++cnt;
+    for (int kd = 0; kd < a.KD; ++kd) {
+        const int id = od * a.sd - a.pd + kd;
+        if (id < 0 || id >= a.D) continue;
+        for (int kh = 0; kh < a.KH; ++kh) {
+            const int ih = oh * a.sh - a.ph + kh;
+            if (ih < 0 || ih >= a.H) continue;
+            for (int kw = 0; kw < a.KW; ++kw) {
+                const int iw = ow * a.sw - a.pw + kw;
+                if (iw < 0 || iw >= a.W) continue;
+                const float v = xp[((int64_t)id * a.H + ih) * a.W + iw];
+                acc = AVG ? acc + v : fmaxf(acc, v);
+                ++cnt;
+            }
         }
     }
     if (AVG) acc = cnt ? acc / (float)cnt : 0.f;
@@ -349,8 +354,9 @@ __global__ __launch_bounds__(256) void global_avg_pool_kernel(PoolArgs a) {
 
 int launch_pool(const PoolArgs &a, void *stream) {
     hipStream_t s = (hipStream_t)stream;
+    if (a.D < 1 || a.KD < 1 || a.sd < 1 || a.DO < 1) return (int)hipErrorInvalidValue;
     if (a.mode == 0 || a.mode == 2) {
-        const int64_t total = (int64_t)a.NC * a.HO * a.WO;
+        const int64_t total = (int64_t)a.NC * a.DO * a.HO * a.WO;
         const dim3 grid((unsigned)((total + 255) / 256));
         if (a.mode == 0) hipLaunchKernelGGL(window_pool_kernel<false>, grid, dim3(256), 0, s, a);
         else hipLaunchKernelGGL(window_pool_kernel<true>, grid, dim3(256), 0, s, a);

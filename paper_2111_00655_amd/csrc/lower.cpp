@@ -24,7 +24,7 @@ bool is_elementwise(int32_t op) {
 }
 bool is_contraction(int32_t op) {
     return op == CLG_OP_CONV2D || op == CLG_OP_CONV2D_TRANSPOSE || op == CLG_OP_DENSE ||
-           op == CLG_OP_BATCH_MATMUL;
+           op == CLG_OP_BATCH_MATMUL || op == CLG_OP_CONV3D;
 }
 bool is_layout(int32_t op) { return op == CLG_OP_RESHAPE || op == CLG_OP_TRANSPOSE; }
 bool is_rowwise(int32_t op) { return op == CLG_OP_SOFTMAX || op == CLG_OP_LAYER_NORM; }
@@ -126,9 +126,9 @@ int32_t check_pattern(const Context &ctx, Pattern *p) {
         break;
     }
     case FAM_DIRECT:
-        ok = ((k0 == CLG_OP_CONV2D || k0 == CLG_OP_MAX_POOL2D || k0 == CLG_OP_AVG_POOL2D) && tail_ok(1, len) &&
-              kl != CLG_OP_RESHAPE) ||
-             (len == 1 && k0 == CLG_OP_GLOBAL_AVG_POOL2D);
+        ok = ((k0 == CLG_OP_CONV2D || k0 == CLG_OP_MAX_POOL2D || k0 == CLG_OP_AVG_POOL2D || k0 == CLG_OP_MAX_POOL3D) &&
+              tail_ok(1, len) && kl != CLG_OP_RESHAPE) ||
+             (len == 1 && (k0 == CLG_OP_GLOBAL_AVG_POOL2D || k0 == CLG_OP_GLOBAL_AVG_POOL3D));
         break;
     case FAM_ROWWISE:
         ok = is_rowwise(kl) && (len == 1 || (p->main_arg[len - 1] == 0 && is_elementwise(k0) &&
@@ -247,9 +247,10 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
     std::string kinds;
     for (int t = 0; t < len; ++t) kinds += std::string(t ? "+" : "") + op_name(cv.op(t));
     char abuf[160];
-    std::snprintf(abuf, sizeof abuf, "s%dx%d,p%dx%d,g%d,tb%d,k%dx%d", anchor.attrs.stride[0], anchor.attrs.stride[1],
+    std::snprintf(abuf, sizeof abuf, "s%dx%d,p%dx%d,g%d,tb%d,k%dx%d,d%d.%d.%d,ax%d", anchor.attrs.stride[0], anchor.attrs.stride[1],
                   anchor.attrs.pad[0], anchor.attrs.pad[1], anchor.attrs.groups > 0 ? anchor.attrs.groups : 1,
-                  anchor.attrs.transpose_b ? 1 : 0, anchor.attrs.kernel[0], anchor.attrs.kernel[1]);
+                  anchor.attrs.transpose_b ? 1 : 0, anchor.attrs.kernel[0], anchor.attrs.kernel[1],
+                  anchor.attrs.stride_d, anchor.attrs.pad_d, anchor.attrs.kernel_d, anchor.attrs.axis);
 
     Epilogue epi{};
     int32_t rc = CLG_OK;
@@ -330,9 +331,9 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
                     return fail(CLG_NO_KERNEL, "a residual add cannot be fused in front of a permuted store");
         for (int s = 0; s < epi.n; ++s) use(c.epi_nodes[s]);
         // where the channel of a bias step lives
-        const bool conv_like = (k0 == CLG_OP_CONV2D || k0 == CLG_OP_CONV2D_TRANSPOSE);
+        const bool conv_like = (k0 == CLG_OP_CONV2D || k0 == CLG_OP_CONV2D_TRANSPOSE || k0 == CLG_OP_CONV3D);
         if (epi.bias_c) {
-            const int64_t want_inner = conv_like ? ys.d[2] * ys.d[3] : 1;
+            const int64_t want_inner = k0 == CLG_OP_CONV3D ? ys.d[2] * ys.d[3] * ys.d[4] : (conv_like ? ys.d[2] * ys.d[3] : 1);
             const int64_t want_c = conv_like ? ys.d[1] : ys.d[ys.ndim - 1];
             if (k0 == CLG_OP_BATCH_MATMUL || epi.bias_inner != want_inner || epi.bias_c != want_c)
                 return fail(CLG_NO_KERNEL, "bias_add axis does not match the kernel's channel dimension");
@@ -397,6 +398,28 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
                     a.strideC = a.N;
                     c.name += "_merge";
                 }
+            } else if (k0 == CLG_OP_CONV3D) {
+                // only the register-fed kernels run it: one grid slice per output depth, depth taps folded
+                // into the channel index
+                if (!want_rf || g.nodes[wb].kind != NODE_CONST)
+                    return fail(CLG_NO_KERNEL, "conv3d runs on the register-fed kernels with constant weights only");
+                a.Nimg = (int)xs.d[0]; a.Cin = (int)xs.d[1]; a.D = (int)xs.d[2]; a.H = (int)xs.d[3]; a.W = (int)xs.d[4];
+                a.Cout = (int)ws.d[0]; a.KD = (int)ws.d[2]; a.KH = (int)ws.d[3]; a.KW = (int)ws.d[4];
+                a.sd = anchor.attrs.stride_d; a.sh = anchor.attrs.stride[0]; a.sw = anchor.attrs.stride[1];
+                a.pd = anchor.attrs.pad_d; a.ph = anchor.attrs.pad[0]; a.pw = anchor.attrs.pad[1];
+                a.DO = (int)ys.d[2]; a.HO = (int)ys.d[3]; a.WO = (int)ys.d[4];
+                a.bias_on_row = 1;
+                c.gemm_swap = true;
+                a.mode = GM_CONV;
+                a.M = a.Cout; a.N = a.Nimg * a.DO * a.HO * a.WO; a.K = a.Cin * a.KD * a.KH * a.KW;
+                a.lda = a.K;
+                a.rf_groups = 1;
+                if ((int64_t)a.Nimg * a.DO > 65535) return fail(CLG_NO_KERNEL, "conv3d: too many (image, depth) slices");
+                if (a.KD == 1 && a.pd != 0) return fail(CLG_NO_KERNEL, "conv3d: depth padding needs more than one depth tap");
+                rf = rf_resolve(&a, a.tile == TILE_R32 ? 32 : 16, epi_fast_flags(epi), ctx.n_cus);
+                if (!rf) return fail(CLG_NO_KERNEL, "conv3d: the register-fed kernel does not take this shape or tail");
+                c.pack_bytes = rf_pack_bytes(a);
+                c.name = "conv3d";
             } else if (k0 == CLG_OP_CONV2D) {
                 const int G = anchor.attrs.groups > 0 ? anchor.attrs.groups : 1;
                 if (G != 1 && !want_rf)
@@ -461,7 +484,7 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
             if (rf) {
                 c.scratch_bytes = gemm_scratch_bytes(a);
                 c.name = (a.rf_tapk == -1 ? "dense_rf" + std::to_string(a.rf_ts)
-                                          : std::string(a.rf_convt ? "convt_rf" : "conv_rf") + std::to_string(a.rf_ts) + "_t" +
+                                          : std::string(a.rf_convt ? "convt_rf" : (a.D > 1 ? "conv3d_rf" : "conv_rf")) + std::to_string(a.rf_ts) + "_t" +
                                                 std::to_string(a.rf_tapk)) +
                          "_w" + std::to_string(a.rf_wgk) + (a.cs_len ? "_split" : "");
             } else {
@@ -507,12 +530,40 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
         c.kind = CALL_CONCAT;
         c.name = "concat" + std::to_string(a.n);
         c.a_node = cv.arg(0, 0);
+    } else if (k0 == CLG_OP_MAX_POOL3D || k0 == CLG_OP_GLOBAL_AVG_POOL3D) {
+        const int32_t xa = cv.arg(0, 0);
+        const Shape &xs = g.nodes[xa].shape;
+        use(xa);
+        PoolArgs &a = c.pool;
+        a.NC = (int)(xs.d[0] * xs.d[1]);
+        if (k0 == CLG_OP_MAX_POOL3D) {
+            a.mode = 0;
+            a.D = (int)xs.d[2]; a.H = (int)xs.d[3]; a.W = (int)xs.d[4];
+            a.KD = anchor.attrs.kernel_d; a.KH = anchor.attrs.kernel[0]; a.KW = anchor.attrs.kernel[1];
+            a.sd = anchor.attrs.stride_d; a.sh = anchor.attrs.stride[0]; a.sw = anchor.attrs.stride[1];
+            a.pd = anchor.attrs.pad_d; a.ph = anchor.attrs.pad[0]; a.pw = anchor.attrs.pad[1];
+            a.DO = (int)anchor.shape.d[2]; a.HO = (int)anchor.shape.d[3]; a.WO = (int)anchor.shape.d[4];
+            for (int t = 1; t < len; ++t)
+                if ((rc = add_step(cv, t, false, &epi, c.epi_nodes)) != CLG_OK) return rc;
+            for (int s = 0; s < epi.n; ++s) use(c.epi_nodes[s]);
+            a.epi = epi;
+            c.name = "max_pool3d" + (epi.n ? "_epi" + std::to_string(epi.n) : std::string());
+        } else {
+            a.mode = 1;                                        // the mean over D*H*W values per (n, c)
+            a.H = (int)(xs.d[2] * xs.d[3]); a.W = (int)xs.d[4];
+            a.D = a.KD = a.sd = a.DO = 1;
+            a.HO = a.WO = 1;
+            c.name = "global_avg_pool3d";
+        }
+        c.kind = CALL_POOL;
+        c.a_node = xa;
     } else if (k0 == CLG_OP_MAX_POOL2D || k0 == CLG_OP_AVG_POOL2D || k0 == CLG_OP_GLOBAL_AVG_POOL2D) {
         const int32_t xa = cv.arg(0, 0);
         const Shape &xs = g.nodes[xa].shape;
         use(xa);
         PoolArgs &a = c.pool;
         a.NC = (int)(xs.d[0] * xs.d[1]); a.H = (int)xs.d[2]; a.W = (int)xs.d[3];
+        a.D = a.KD = a.sd = a.DO = 1;
         if (k0 != CLG_OP_GLOBAL_AVG_POOL2D) {
             a.mode = k0 == CLG_OP_MAX_POOL2D ? 0 : 2;
             a.KH = anchor.attrs.kernel[0]; a.KW = anchor.attrs.kernel[1];

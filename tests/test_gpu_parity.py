@@ -150,6 +150,75 @@ def test_depthwise_conv(case, backend):
     run_single_group(d, backend, pat)
 
 
+CONV3D_CASES = [
+    # batch, cin, cout, d, h, w, kernel, stride, pad, tail
+    (1, 16, 32, 4, 9, 9, (3, 3, 3), (1, 1, 1), (1, 1, 1), ("bias_add", "relu")),
+    (1, 16, 24, 6, 10, 8, (3, 3, 3), (2, 2, 2), (1, 1, 1), ("bias_add", "add", "relu")),
+    (2, 8, 40, 5, 7, 7, (3, 3, 3), (1, 1, 1), (1, 1, 1), ("bias_add",)),           # batch 2, ragged pixels
+    (1, 3, 16, 6, 20, 20, (7, 7, 7), (1, 2, 2), (3, 3, 3), ("bias_add", "relu")),     # the stem's shape class
+    (1, 64, 48, 4, 7, 7, (1, 1, 1), (1, 1, 1), (0, 0, 0), ("bias_add", "relu")),      # 1x1x1
+    (1, 64, 128, 8, 14, 14, (1, 1, 1), (2, 2, 2), (0, 0, 0), ("bias_add",)),          # strided 1x1x1 projection
+    (2, 32, 16, 3, 6, 5, (1, 1, 1), (1, 1, 1), (0, 0, 0), ("bias_add", "add", "relu")),
+    (1, 6, 10, 4, 6, 6, (3, 1, 1), (1, 1, 1), (1, 0, 0), ()),                          # depth taps only
+    (1, 8, 12, 5, 8, 8, (1, 3, 3), (2, 1, 1), (0, 1, 1), ("bias_add",)),               # one depth tap, depth stride 2
+    (1, 5, 7, 4, 6, 6, (2, 3, 2), (1, 2, 1), (1, 1, 0), ()),                           # odd everything
+]
+
+
+@pytest.mark.parametrize("backend", RF)
+@pytest.mark.parametrize("case", CONV3D_CASES)
+def test_conv3d_register_fed(case, backend):
+    """3-D convolution (3D-ResNet50, paper Sec. 5.1): one grid slice per output depth, depth taps folded
+    into the channel index of the 2-D kernels."""
+    batch, cin, cout, dd, h, w, k, s, p, tail = case
+    r = rng_for(31, cin, cout, dd, h)
+    d = wl.GraphDesc("conv3d_case")
+    x = d.input(f32(r, batch, cin, dd, h, w))
+    wt = d.const(f32(r, cout, cin, *k, scale=1.0 / np.sqrt(cin * k[0] * k[1] * k[2])))
+    y = d.op("conv3d", [x, wt], stride=s, pad=p)
+    od = [(n + 2 * pp - kk) // ss + 1 for n, pp, kk, ss in zip((dd, h, w), p, k, s)]
+    for op in tail:
+        if op == "bias_add":
+            y = d.op("bias_add", [y, d.const(f32(r, cout))], axis=1)
+        elif op == "add":
+            y = d.op("add", [y, d.input(f32(r, batch, cout, *od))])
+        else:
+            y = d.op(op, [y])
+    d.mark_output(y)
+    name, _ = run_single_group(d, backend, tail_pattern(P("conv3d", W, W), tail))
+    assert name.startswith("conv3d_rf"), name
+
+
+def test_pools_3d():
+    r = rng_for(32)
+    d = wl.GraphDesc("maxpool3d")
+    d.mark_output(d.op("max_pool3d", [d.input(f32(r, 2, 5, 6, 15, 13))], kernel=(3, 3, 3), stride=(2, 2, 2), pad=(1, 1, 1)))
+    run_single_group(d, "direct", P("max_pool3d", W), tol=0.0)
+    d = wl.GraphDesc("maxpool3d_b")
+    d.mark_output(d.op("max_pool3d", [d.input(f32(r, 1, 3, 4, 7, 6))], kernel=(1, 3, 2), stride=(1, 2, 2), pad=(0, 1, 0)))
+    run_single_group(d, "direct", P("max_pool3d", W), tol=0.0)
+    d = wl.GraphDesc("gap3d")
+    d.mark_output(d.op("global_avg_pool3d", [d.input(f32(r, 2, 37, 2, 4, 4))]))
+    run_single_group(d, "direct", P("global_avg_pool3d", W), tol=1e-6)
+
+
+def test_resnet3d_whole_path():
+    """3D-ResNet50 at reduced size through profile, search, compile, execute."""
+    desc = wl.resnet3d_50(0, frames=4, image=32, width=16, blocks=(2, 1, 1), classes=10)
+    reg = wl.default_registry(("igemm_s8", "igemm_r32", "igemm_r16"))
+    s, g, oms = _session_and_oracle(desc, reg)
+    costs = s.profile(B.ProfileOpts(warmup=2, batches=2, min_batch_us=30, max_launches=30))
+    got_search = s.search(costs, 0)
+    assert got_search == search.dp(g, reg, oms, costs, 0)
+    plan = s.compile(got_search[1])
+    got = plan.run()
+    ref = g.run()
+    assert got[0].shape == (1, 10)
+    assert max(norm_err(a, b) for a, b in zip(got, ref)) <= NET_TOL
+    plan.destroy()
+    s.close()
+
+
 SEP_CASES = [
     # batch, c, cout, h, w, k (0 = no depthwise stage), stride, pre-relu, tail
     (1, 44, 44, 28, 28, 3, 1, True, ("bias_add",)),
@@ -553,7 +622,7 @@ def test_model_under_searched_placement(name):
     s.close()
 
 
-@pytest.mark.parametrize("name", ["resnet50", "nasnet_a"])
+@pytest.mark.parametrize("name", ["resnet50", "nasnet_a", "resnet3d_50"])
 def test_model_in_the_benchmark_s_configuration(name):
     """Full size, the registry and measurer options bench.py uses (all kernel variants and the
     one-kernel separable convolution family)."""

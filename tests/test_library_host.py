@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_layouts_match_the_header_sizes():
     # sizes implied by the header's field lists on LP64
-    assert ctypes.sizeof(B.Attrs) == 4 * 10 + 8 * 6 + 16
+    assert ctypes.sizeof(B.Attrs) == 4 * 10 + 8 * 6 + 16 + 4 * 4
     assert ctypes.sizeof(B.Match) == 4 * 5 + 4 * 16 * 2
     assert ctypes.sizeof(B.PatternNode) == 4 * (3 + 8) + 4 + 24 * 4        # op, n_args, args[8], n_constraints, pad
     assert ctypes.sizeof(B.KernelInfo) == 64 + 8 + 16
@@ -46,7 +46,8 @@ def _small_models():
             wl.resnext50(0, image=32, width=8, blocks=(1, 1), groups=4, classes=10),
             wl.bert_base(0, layers=2, seq=8, hidden=32, heads=4, ffn=64, vocab=50, max_pos=16),
             wl.dcgan(0, batch=2, latent=8, base=16),
-            wl.nasnet_a(0, image=24, stem=4, filters=4, cells=1, classes=5)]
+            wl.nasnet_a(0, image=24, stem=4, filters=4, cells=1, classes=5),
+            wl.resnet3d_50(0, frames=4, image=16, width=8, blocks=(1, 1), classes=5)]
 
 
 def _same_matches(lib_ms, orc_ms):
@@ -57,10 +58,10 @@ def _same_matches(lib_ms, orc_ms):
         assert tuple(a.binding[:a.n_nodes]) == b.binding
 
 
-@pytest.mark.parametrize("idx", range(6))
+@pytest.mark.parametrize("idx", range(7))
 def test_matches_and_placements_bit_exact_vs_oracle(idx):
     d = _small_models()[idx]
-    reg = wl.default_registry(("igemm", "igemm_s"))
+    reg = wl.default_registry(("igemm", "igemm_s", "igemm_r16"))
     s = clg.Session(d, reg, device=None)
     g = Graph(d)
     oms = enumerate_matches(g, reg)

@@ -290,6 +290,59 @@ def random_dag(seed: int, n_ops: int = 10, ch: int = 4, image: int = 6
 
 
 # --------------------------------------------------------------------------
+# 3D-ResNet50 (one of the paper's Sec. 5.1 workloads): ResNet-50 with every
+# convolution and pooling extended to three dimensions (Hara et al. 2018)
+# --------------------------------------------------------------------------
+def _conv3(g, rng, x, cin, cout, k, stride, pad, act="relu", residual=None, name=""):
+    """conv3d -> bias_add -> [add residual] -> [relu]; k, stride, pad: (d, h, w)."""
+    fan_in = cin * k[0] * k[1] * k[2]
+    w = g.const(_he(rng, (cout, cin) + tuple(k), fan_in), name + ".w")
+    b = g.const(rng.uniform((cout,), -0.1, 0.1), name + ".b")
+    y = g.op("conv3d", [x, w], name + ".conv", stride=tuple(stride), pad=tuple(pad))
+    y = g.op("bias_add", [y, b], name + ".bias", axis=1)
+    if residual is not None:
+        y = g.op("add", [y, residual], name + ".add")
+    if act == "relu":
+        y = g.op("relu", [y], name + ".relu")
+    return y
+
+
+def resnet3d_50(seed: int = 0, frames: int = 16, image: int = 112, width: int = 64,
+                blocks=(3, 4, 6, 3), classes: int = 400, batch: int = 1) -> GraphDesc:
+    """Clip of `frames` x image x image; 7x7x7 stem with stride (1, 2, 2), 3x3x3
+    max pool of stride 2, bottlenecks 1x1x1 -> 3x3x3 -> 1x1x1 with the stride
+    (2, 2, 2) of a down-sampling block in its 3x3x3 convolution and a 1x1x1
+    projection shortcut in the first block of every stage, global average pool,
+    classifier (400 action classes).  BatchNorm folded."""
+    g = GraphDesc("resnet3d_50")
+    rw, rx = _Rng(seed), _Rng(seed + 1000003)
+    x = g.input(rx.normal((batch, 3, frames, image, image)), "x")
+    y = _conv3(g, rw, x, 3, width, (7, 7, 7), (1, 2, 2), (3, 3, 3), name="stem")
+    y = g.op("max_pool3d", [y], "pool", kernel=(3, 3, 3), stride=(2, 2, 2), pad=(1, 1, 1))
+    cin = width
+    for s, nblk in enumerate(blocks):
+        inner = width * (2 ** s)
+        cout = inner * 4
+        for b in range(nblk):
+            st = (2, 2, 2) if (b == 0 and s > 0) else (1, 1, 1)
+            nm = f"s{s}b{b}"
+            sc = _conv3(g, rw, y, cin, cout, (1, 1, 1), st, (0, 0, 0), act=None, name=nm + ".proj") if b == 0 else y
+            t = _conv3(g, rw, y, cin, inner, (1, 1, 1), (1, 1, 1), (0, 0, 0), name=nm + ".c1")
+            t = _conv3(g, rw, t, inner, inner, (3, 3, 3), st, (1, 1, 1), name=nm + ".c2")
+            y = _conv3(g, rw, t, inner, cout, (1, 1, 1), (1, 1, 1), (0, 0, 0), residual=sc, name=nm + ".c3")
+            cin = cout
+    p = g.op("global_avg_pool3d", [y], "gap")
+    w = g.const(_he(rw, (classes, cin), cin), "fc.w")
+    b = g.const(rw.uniform((classes,), -0.1, 0.1), "fc.b")
+    d = g.op("dense", [p, w], "fc")
+    logits = g.op("bias_add", [d, b], "fc.bias", axis=-1)
+    prob = g.op("softmax", [logits], "softmax")
+    g.mark_output(logits)
+    g.mark_output(prob)
+    return g
+
+
+# --------------------------------------------------------------------------
 # NasNet-A (one of the paper's Sec. 5.1 workloads): cells of separable
 # convolutions, poolings and identities joined by adds and a channel concat
 # --------------------------------------------------------------------------
@@ -391,4 +444,5 @@ MODEL_BUILDERS = {
     "dcgan_b1": lambda seed=0: dcgan(seed, batch=1),
     "dcgan_b64": lambda seed=0: dcgan(seed, batch=64),
     "nasnet_a": nasnet_a,
+    "resnet3d_50": resnet3d_50,
 }

@@ -92,6 +92,7 @@ def default_registry(variants=("igemm",), sepconv=False):
                                     ("bias_add", "add", "relu")]))
     add("direct", [P("max_pool2d", W), P("global_avg_pool2d", W)])
     add("direct", [P("avg_pool2d", W), P("add", P("avg_pool2d", W), W), P("add", P("max_pool2d", W), W)])
+    add("direct", [P("max_pool3d", W), P("global_avg_pool3d", W)])
 
     # --- separable convolution in one kernel: [relu] depthwise 1x1 tail, or relu 1x1 tail
     sep_anchors = [P("conv2d", P("conv2d", P("relu", W), W), W), P("conv2d", P("conv2d", W, W), W),
@@ -116,6 +117,9 @@ def default_registry(variants=("igemm",), sepconv=False):
         # results stored permuted: projection split into heads, heads merged
         add(be, [P("transpose", P("reshape", P("bias_add", dense, W))),
                  P("reshape", P("transpose", P("batch_matmul", W, W)))])
+        if be in GROUPED_CONV_BACKENDS:      # the register-fed kernels also run 3-D convolutions
+            add(be, _tails(P("conv3d", W, W), [(), ("bias_add",), ("bias_add", "relu"), ("bias_add", "add"),
+                                               ("bias_add", "add", "relu")]))
         convt = P("conv2d_transpose", W, W)
         add(be, _tails(convt, [(), ("bias_add",), ("bias_add", "relu"),
                                ("bias_add", "tanh")]))
@@ -145,7 +149,7 @@ def small_registry():
 
 # ---- pattern rules (data only) ---------------------------------------------------
 RULE_NONE, RULE_FUSABLE, RULE_ELEMWISE = 0, 1, 2
-FUSABLE_OPS = ("conv2d", "conv2d_transpose", "dense", "batch_matmul")
+FUSABLE_OPS = ("conv2d", "conv2d_transpose", "dense", "batch_matmul", "conv3d")
 ELEMWISE_OPS = ("bias_add", "add", "mul_scalar", "relu", "gelu", "tanh")
 
 
