@@ -80,8 +80,10 @@ struct RfMfma<16> {
 // phase, each with its own packed (tap-flipped) weights.  k4 s2 p1 gives four
 // 2x2 phases.
 
-// GEO: 0 = convolution (2-D, or 3-D with a single depth tap), 1 = transposed convolution,
-// 2 = 3-D convolution with the depth taps folded into the channel index.
+// GEO: 0 = 2-D convolution, 1 = transposed convolution, 2 = 3-D convolution with the depth taps
+// folded into the channel index, 3 = 3-D convolution with a single depth tap.  The depth code is
+// compiled into GEO 2 and 3 only: a few more kernel arguments and one division are a measurable
+// part of a four-microsecond kernel.
 template <int TS, int TAPK, int WGK, int GEO>
 __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
     using MF = RfMfma<TS>;
@@ -93,6 +95,7 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
     extern __shared__ float red[];
     constexpr bool CONVT = GEO == 1;
     constexpr bool FOLD = GEO == 2;
+    constexpr bool DEPTH = GEO >= 2;
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -125,24 +128,25 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
     const int nt = p.rf_jmajor ? t_hi : t_lo;
     const int i0 = mt * TS, j0 = nt * TS;
     // grid.y: the image, or (image, output depth) of a 3-D convolution
-    int img = blockIdx.y, od = 0;
-    const int DOe = p.DO > 1 ? p.DO : 1;
-    if (p.DO > 1) {
+    int img = blockIdx.y, od = 0, DOe = 1;
+    if constexpr (DEPTH) {
+        DOe = p.DO;
         img = blockIdx.y / p.DO;
         od = blockIdx.y - img * p.DO;
     }
-    const int id0 = od * p.sd - p.pd;                        // input depth of depth tap 0
+    const int id0 = DEPTH ? od * p.sd - p.pd : 0;            // input depth of depth tap 0
 
     const int jp = min(j0 + r, npix - 1);
     const int oh = (int)(((uint64_t)(uint32_t)jp * p.rf_wo_magic) >> 32);
     const int ow = jp - oh * WOe;
     const int ih0 = oh * she - phe, iw0 = ow * swe - pwe;
     const int HW = p.H * p.W;
-    const int CS = p.rf_cs;                                  // elements between channels: HW, or D * HW
+    const int CS = DEPTH ? p.rf_cs : HW;                     // elements between channels: HW, or D * HW
     const int cbase = p.rf_groups > 1 ? (i0 / p.rf_cpg_out) * p.rf_cpg_in : 0;
     const int cin = min(p.rf_cin_tile, p.Cin - cbase);       // input channels this m-tile contracts
     // without folded depth taps the single depth tap's plane is part of the base address
-    const float *const x_img = p.B + (int64_t)img * p.rf_img_stride + (int64_t)cbase * CS + (FOLD ? 0 : (int64_t)id0 * HW);
+    const float *const x_img = DEPTH ? p.B + (int64_t)img * p.rf_img_stride + (FOLD ? 0 : (int64_t)id0 * HW)
+                                     : p.B + ((int64_t)img * p.Cin + cbase) * HW;
     // packed weights of this m-tile; a wave's load is base + uniform group offset + lane
     const f32x4 *const Ab = reinterpret_cast<const f32x4 *>(p.A) + ((int64_t)phase * tiles_m + mt) * p.rf_ngtot * kWave;
     const uint32_t lane_u = (uint32_t)lane;

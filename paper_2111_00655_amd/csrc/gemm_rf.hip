@@ -30,6 +30,10 @@ int launch_rf_one(const GemmArgs &a, hipStream_t s) {
         if (a.rf_fold && !a.rf_convt) return launch_rf_one_t<TS, TAPK, WGK, 2>(a, s);
     }
     if (a.rf_convt || a.rf_fold) return (int)hipErrorInvalidValue;
+    if constexpr (TAPK != 4) {
+        if (a.D > 1) return launch_rf_one_t<TS, TAPK, WGK, 3>(a, s);
+    }
+    if (a.D > 1 || a.DO > 1) return (int)hipErrorInvalidValue;
     return launch_rf_one_t<TS, TAPK, WGK, 0>(a, s);
 }
 
@@ -160,7 +164,7 @@ bool rf_resolve(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves) {
     if (a->rf_img_stride >= ((int64_t)1 << 30)) return false;         // 32-bit lane offsets
     if (!a->rf_fold && a->pd != 0) return false;                      // a single depth tap must lie inside
     const int groups = a->rf_groups > 1 ? a->rf_groups : 1;
-    if (a->rf_fold && groups > 1) return false;
+    if ((a->rf_fold || a->D > 1) && groups > 1) return false;      // the depth variants take ungrouped convolutions
     a->Cin = cin_real * a->KD;
     const int taps = a->KH * a->KW;
     // grouped: an m-tile contracts the channels of the groups its rows belong to

@@ -92,13 +92,6 @@ struct GemmArgs {
     int32_t rf_jmajor, rf_groups;          // rf_groups > 1: grouped convolution (Cin, Cout are totals)
     int32_t rf_cin_tile, rf_cpg_in, rf_cpg_out;            // channels contracted per m-tile; channels per group
     int32_t rf_convt;                      // 1: transposed convolution, one sub-pixel phase per grid.z slice
-    // 3-D convolution on the register-fed kernels: one grid.y slice per (image, output depth);
-    // the depth taps are folded into the channel index (channel' = c * KD + kd, Cin holds Cin * KD)
-    int32_t D, KD, sd, pd, DO;             // input depth, depth taps, depth stride / padding, output depth (1, 1, 1, 0, 1 for 2-D)
-    int32_t rf_fold;                       // 1: KD > 1
-    int32_t rf_cs;                         // elements between two input channels (D * H * W)
-    int64_t rf_img_stride;                 // elements between two images of x
-    uint64_t rf_kd_magic;                  // floor(2^32 / KD) + 1
     uint64_t rf_wo_magic;                  // floor(2^32 / WO) + 1: pixel / WO by multiply-high
     uint64_t rf_tile_magic;                // the same for rf_tile_div
     int32_t rf_tile_div, rf_pad2_;         // tiles along the fast axis of the tile order (m-tiles if rf_jmajor)
@@ -106,8 +99,18 @@ struct GemmArgs {
     // (cs_len = 0: plain row-major).  This is how reshape + transpose of the result is fused (head split).
     int32_t cs_len, cs_pad_;
     int64_t cs_stride;
+    EpiFast ef;                            // filled by launch_gemm from epi; in front of the step list, next to the
+                                           // other fields the register-fed kernels read
     Epilogue epi;
-    EpiFast ef;                            // filled by launch_gemm from epi
+    // (kept behind everything the 2-D kernels read)
+    // 3-D convolution on the register-fed kernels: one grid.y slice per (image, output depth);
+    // the depth taps are folded into the channel index (channel' = c * KD + kd, Cin holds Cin * KD)
+    int32_t D, KD, sd, pd, DO;             // input depth, depth taps, depth stride / padding, output depth (1, 1, 1, 0, 1 for 2-D)
+    int32_t rf_fold;                       // 1: KD > 1
+    int32_t rf_cs;                         // elements between two input channels (D * H * W)
+    int64_t rf_img_stride;                 // elements between two images of x
+    uint64_t rf_kd_magic;                  // floor(2^32 / KD) + 1
+    int32_t rf_pad3_;
 };
 
 // ---- direct convolution (any groups) -----------------------------------------------------
