@@ -72,45 +72,52 @@ enum GemmTile : int32_t {
 };
 
 struct GemmArgs {
-    int32_t mode, tile, splitk, batch;
-    int32_t M, N, K;
-    int32_t lda, ldb, ldc;
-    int64_t strideA, strideB, strideC;     // per batch, in elements
+    // The order is by who reads what: a kernel fetches its arguments with scalar loads, one cache
+    // line of 64 bytes at a time, before it can do anything else, and the register-fed kernels are
+    // a few microseconds long.  What they read comes first (three lines); moving the fast epilogue
+    // from behind the step list to the front measured 3 % of ResNet-50's kernel time.
+    // -- line 0
     const float *A;
     const float *B;
     float *C;
     float *partial;                        // split-K partial sums [splitk][numel(C)]
     int64_t c_numel;
+    uint64_t rf_wo_magic;                  // floor(2^32 / WO) + 1: pixel / WO by multiply-high
+    uint64_t rf_tile_magic;                // the same for rf_tile_div
+    int32_t splitk, rf_tile_div;           // rf_tile_div: tiles along the fast axis of the tile order (m-tiles if rf_jmajor)
+    // -- line 1
+    EpiFast ef;                            // filled by launch_gemm from epi
     // convolution geometry (GM_CONV, GM_CONVT)
-    int32_t Nimg, Cin, H, W, Cout, KH, KW, sh, sw, ph, pw, HO, WO;
-    int32_t bias_on_row;                   // 1: channel = i (conv), 0: channel = j (dense)
-    int32_t gemv;                          // 1: GM_NT with at most 8 rows runs the matrix-vector kernel (a wave per column)
-    int32_t patch_sz;                      // 3x3 kernel: floats per channel of the LDS input patch
+    int32_t Nimg, Cin, H, W, Cout, KH, KW, sh, sw, ph;
+    // -- line 2
+    int32_t pw, HO, WO;
     // register-fed convolution (gemm_rf.h); rf_ts = 0: not used.  A then points at the packed weights.
-    int32_t rf_ts, rf_tapk, rf_wgk;        // tile edge 32|16, tap mode 1|9|4|0 (-1: dense), K-waves per workgroup
     int32_t rf_nch, rf_ngtot, rf_nm;       // chunks per wave, packed groups per m-tile, MFMAs per tile
     int32_t rf_jmajor, rf_groups;          // rf_groups > 1: grouped convolution (Cin, Cout are totals)
     int32_t rf_cin_tile, rf_cpg_in, rf_cpg_out;            // channels contracted per m-tile; channels per group
-    int32_t rf_convt;                      // 1: transposed convolution, one sub-pixel phase per grid.z slice
-    uint64_t rf_wo_magic;                  // floor(2^32 / WO) + 1: pixel / WO by multiply-high
-    uint64_t rf_tile_magic;                // the same for rf_tile_div
-    int32_t rf_tile_div, rf_pad2_;         // tiles along the fast axis of the tile order (m-tiles if rf_jmajor)
+    int32_t M, N, K;
+    int32_t lda, ldc;
+    // -- line 3: dense on the register-fed kernel also reads these
     // dense only: output column n goes to (n / cs_len) * cs_stride + n % cs_len within its row block
     // (cs_len = 0: plain row-major).  This is how reshape + transpose of the result is fused (head split).
-    int32_t cs_len, cs_pad_;
     int64_t cs_stride;
-    EpiFast ef;                            // filled by launch_gemm from epi; in front of the step list, next to the
-                                           // other fields the register-fed kernels read
+    int32_t cs_len, ldb;
+    int32_t mode, tile, batch;
+    int32_t rf_ts, rf_tapk, rf_wgk;        // tile edge 32|16, tap mode 1|9|4|0 (-1: dense), K-waves per workgroup
+    int32_t rf_convt;                      // 1: transposed convolution, one sub-pixel phase per grid.z slice
+    int32_t bias_on_row;                   // 1: channel = i (conv), 0: channel = j (dense)
+    int32_t gemv;                          // 1: GM_NT with at most 8 rows runs the matrix-vector kernel (a wave per column)
+    int32_t patch_sz;                      // 3x3 kernel: floats per channel of the LDS input patch
+    int64_t strideA, strideB, strideC;     // per batch, in elements
     Epilogue epi;
-    // (kept behind everything the 2-D kernels read)
     // 3-D convolution on the register-fed kernels: one grid.y slice per (image, output depth);
     // the depth taps are folded into the channel index (channel' = c * KD + kd, Cin holds Cin * KD)
     int32_t D, KD, sd, pd, DO;             // input depth, depth taps, depth stride / padding, output depth (1, 1, 1, 0, 1 for 2-D)
     int32_t rf_fold;                       // 1: KD > 1
     int32_t rf_cs;                         // elements between two input channels (D * H * W)
+    int32_t rf_pad3_;
     int64_t rf_img_stride;                 // elements between two images of x
     uint64_t rf_kd_magic;                  // floor(2^32 / KD) + 1
-    int32_t rf_pad3_;
 };
 
 // ---- direct convolution (any groups) -----------------------------------------------------
