@@ -226,6 +226,9 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--dump", default="", help="write the per-kernel table to this JSON file")
+    ap.add_argument("--table", default="", metavar="FILE",
+                    help="write a text table of every fused kernel of a step: time, achieved TFLOP/s or GB/s, fraction of "
+                         "the fp32 MFMA peak or of the HBM bandwidth")
     ap.add_argument("--cost-log", default="", help="cost-log file: reuse measured subgraph costs from it, add new ones")
     ap.add_argument("--ablation", action="store_true", help="also time the placement under each single MFMA kernel variant")
     ap.add_argument("--batch-sweep", default="", metavar="B1,B2,...",
@@ -328,6 +331,25 @@ def main():
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
+
+    if args.table:
+        scale = ms_per_step * 1e6 / sum(r["ns"] for r in rows)
+        lines = [f"{args.model} batch 1 fp32, one MI355X: the {len(rows)} fused kernels of one step in execution order.",
+                 f"Durations: HIP event pair around every launch, scaled by {scale:.3f} so that they add up to the step time "
+                 f"measured without the events ({ms_per_step * 1e3:.1f} us).",
+                 f"Peaks: fp32 MFMA {PEAK_MFMA_F32_TFLOPS} TFLOP/s, HBM {PEAK_HBM_GBPS} GB/s.  flops / bytes are the operator's own "
+                 "(no padding or tile waste; every operand and the output once).",
+                 "",
+                 f"{'#':>3s} {'kernel':34s} {'bound':5s} {'us':>7s} {'MFLOP':>9s} {'KB':>9s} {'TFLOP/s':>8s} {'GB/s':>8s} {'of peak':>8s}"]
+        for i, r in enumerate(rows):
+            t = r["ns"] * scale
+            tf, gb = r["flops"] / t / 1e3, r["bytes"] / t
+            frac = tf / PEAK_MFMA_F32_TFLOPS if r["bound"] == "mfma" else gb / PEAK_HBM_GBPS
+            lines.append(f"{i:3d} {r['name'][:34]:34s} {r['bound']:5s} {t / 1e3:7.2f} {r['flops'] / 1e6:9.1f} "
+                         f"{r['bytes'] / 1e3:9.1f} {tf:8.2f} {gb:8.1f} {frac:8.4f}")
+        os.makedirs(os.path.dirname(os.path.abspath(args.table)), exist_ok=True)
+        with open(args.table, "w") as f:
+            f.write("\n".join(lines) + "\n")
 
     if args.dump:
         os.makedirs(os.path.dirname(os.path.abspath(args.dump)), exist_ok=True)
