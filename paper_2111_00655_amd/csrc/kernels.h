@@ -150,8 +150,11 @@ struct SepConvArgs {
     int32_t pro_relu;                      // relu on x first
     int32_t has_dw;                        // a depthwise stage precedes the 1x1 convolution (wd is set at launch)
     int32_t ngroups, m_tiles, n_tiles, mt_per_wg, nwaves;   // set by sepconv_resolve
+    EpiFast ef;                            // filled by launch_sepconv from epi; EF_GENERIC: the step list is interpreted
     Epilogue epi;
 };
+// The common form of a fused tail (see EpiFast) with the step operands as bound in `e`.
+EpiFast make_epi_fast(const Epilogue &e);
 void sepconv_resolve(SepConvArgs *a);
 size_t sepconv_pack_bytes(const SepConvArgs &a);
 size_t sepconv_lds_bytes(const SepConvArgs &a);

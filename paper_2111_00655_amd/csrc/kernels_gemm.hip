@@ -351,7 +351,7 @@ size_t gemm_scratch_bytes(const GemmArgs &a) {
 static bool al16(const void *p) { return ((uintptr_t)p & 15) == 0; }
 
 // Recognises the common form [scale] [bias] [add] [activation] of a fused tail.
-static EpiFast make_epi_fast(const Epilogue &e) {
+EpiFast make_epi_fast(const Epilogue &e) {
     EpiFast f{0, 1.f, nullptr, nullptr};
     int stage = 0;      // 0 scale, 1 bias, 2 add, 3 activation, 4 done
     for (int i = 0; i < e.n; ++i) {

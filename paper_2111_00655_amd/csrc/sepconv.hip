@@ -64,10 +64,16 @@ __global__ __launch_bounds__(NW * 64) void sepconv_kernel(SepConvArgs a) {
     const int hwo = a.HO * a.WO;
     const int total_pix = a.N * hwo;
 
-    // depthwise weights -> LDS (coalesced; every thread of a 16-lane group reads the same ones later)
+    // depthwise weights -> LDS (coalesced; every thread of a 16-lane group reads the same ones later).
+    // The first four per thread are only loaded here and written to LDS after every other load of
+    // the prologue has been issued: a store to LDS waits for its data, and nothing behind it would
+    // go out meanwhile.
+    constexpr int kWdEarly = 4;
+    float wd_reg[kWdEarly];
+    const int nwd = KS > 0 ? a.C * KS * KS : 0;
     if constexpr (KS > 0) {
-        const int nwd = a.C * KS * KS;
-        for (int i = tid; i < nwd; i += nt) wl[i] = a.wd[i];
+#pragma unroll
+        for (int u = 0; u < kWdEarly; ++u) wd_reg[u] = a.wd[min(tid + u * nt, nwd - 1)];
     }
 
     // this wave's part of phase 2, and its first A operands (in flight during phase 1)
@@ -84,13 +90,11 @@ __global__ __launch_bounds__(NW * 64) void sepconv_kernel(SepConvArgs a) {
         if (have_tile && g0 + u < g1) a_pre[u] = ap[(int64_t)(g0 + u) * 64];
     }
 
-    // operands of the first bias and the first residual-add step for the outputs this lane will
-    // finish (accumulator r: channel mt*16 + 4*(lane/16) + r, pixel lane%16), fetched now
-    int s_bias = -1, s_add = -1;
-    for (int s = a.epi.n - 1; s >= 0; --s) {
-        if (a.epi.s[s].op == EPI_BIAS) s_bias = s;
-        if (a.epi.s[s].op == EPI_ADD) s_add = s;
-    }
+    // operands of the bias and the residual-add step for the outputs this lane will finish
+    // (accumulator r: channel mt*16 + 4*(lane/16) + r, pixel lane%16), fetched now.  A tail outside
+    // the common form (EF_GENERIC) is interpreted step by step at the end instead.
+    const int ef = a.ef.flags;
+    const bool fast = !(ef & EF_GENERIC);
     float e_bias[4] = {0.f, 0.f, 0.f, 0.f}, e_add[4] = {0.f, 0.f, 0.f, 0.f};
     int64_t e_off[4] = {-1, -1, -1, -1};
     if (have_tile && kw == 0) {
@@ -102,8 +106,8 @@ __global__ __launch_bounds__(NW * 64) void sepconv_kernel(SepConvArgs a) {
                 const int co = mt * kRows + 4 * (lane >> 4) + r;
                 if (co >= a.Cout) continue;
                 e_off[r] = ((int64_t)n_img * a.Cout + co) * hwo + rem;
-                if (s_bias >= 0) e_bias[r] = a.epi.s[s_bias].ptr[co];
-                if (s_add >= 0) e_add[r] = a.epi.s[s_add].ptr[e_off[r]];
+                if (fast && (ef & EF_BIAS)) e_bias[r] = a.ef.bias[co];
+                if (fast && (ef & EF_ADD)) e_add[r] = a.ef.add[e_off[r]];
             }
         }
     }
@@ -148,7 +152,13 @@ __global__ __launch_bounds__(NW * 64) void sepconv_kernel(SepConvArgs a) {
 #pragma unroll
                         for (int kx = 0; kx < KS; ++kx) xv[u][kh * KS + kx] = xc[ro[kh] + co[kx]];
                 }
-                if (it == 0) __syncthreads();            // the first round's loads are on their way: now the staged weights
+                if (it == 0) {                             // the first round's loads are on their way: now the weights
+#pragma unroll
+                    for (int u = 0; u < kWdEarly; ++u)
+                        if (tid + u * nt < nwd) wl[tid + u * nt] = wd_reg[u];
+                    for (int i = tid + kWdEarly * nt; i < nwd; i += nt) wl[i] = a.wd[i];
+                    __syncthreads();
+                }
 #pragma unroll
                 for (int u = 0; u < CU; ++u) {
                     const int c = c0 + u * cstep;
@@ -239,15 +249,15 @@ __global__ __launch_bounds__(NW * 64) void sepconv_kernel(SepConvArgs a) {
     for (int r = 0; r < 4; ++r) {
         if (e_off[r] < 0) continue;
         float v = acc[r];
-#pragma unroll 1
-        for (int s = 0; s < a.epi.n; ++s) {
-            const int op = a.epi.s[s].op;
-            if (op == EPI_BIAS) v += s == s_bias ? e_bias[r] : a.epi.s[s].ptr[mt * kRows + 4 * (lane >> 4) + r];
-            else if (op == EPI_ADD) v += s == s_add ? e_add[r] : a.epi.s[s].ptr[e_off[r]];
-            else if (op == EPI_RELU) v = v > 0.f ? v : 0.f;
-            else if (op == EPI_GELU) v = gelu_erf(v);
-            else if (op == EPI_TANH) v = tanhf(v);
-            else if (op == EPI_SCALE) v *= a.epi.s[s].scalar;
+        if (fast) {
+            if (ef & EF_SCALE) v *= a.ef.scale;
+            v += e_bias[r];
+            v += e_add[r];
+            if (ef & EF_RELU) v = v > 0.f ? v : 0.f;
+            else if (ef & EF_GELU) v = gelu_erf(v);
+            else if (ef & EF_TANH) v = tanhf(v);
+        } else {
+            v = apply_steps(a.epi, v, e_off[r], mt * kRows + 4 * (lane >> 4) + r);
         }
         a.y[e_off[r]] = v;
     }
@@ -294,7 +304,9 @@ int launch_sepconv_pack(const SepConvArgs &a, const float *w, float *dst, void *
     return (int)hipGetLastError();
 }
 
-int launch_sepconv(const SepConvArgs &a, void *stream) {
+int launch_sepconv(const SepConvArgs &a_in, void *stream) {
+    SepConvArgs a = a_in;
+    a.ef = make_epi_fast(a.epi);
     const dim3 grid((unsigned)a.n_tiles, (unsigned)((a.m_tiles + a.mt_per_wg - 1) / a.mt_per_wg));
     const size_t lds = sepconv_lds_bytes(a);
     if (lds > 160 * 1024) return (int)hipErrorInvalidValue;
