@@ -311,13 +311,19 @@ int launch_direct_conv(const DirectConvArgs &a, void *stream) {
 // One output pixel per thread.  AVG: mean over the window's pixels inside the image.
 template <bool AVG>
 __global__ __launch_bounds__(256) void window_pool_kernel(PoolArgs a) {
-    const int64_t total = (int64_t)a.NC * a.DO * a.HO * a.WO;
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    // 32-bit index arithmetic (the launcher checks the sizes): a 64-bit division is a long routine
+    const uint32_t total = (uint32_t)(a.NC * a.DO * a.HO * a.WO);
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= total) return;
-    const int ow = (int)(i % a.WO), oh = (int)((i / a.WO) % a.HO);
-    const int od = (int)((i / ((int64_t)a.WO * a.HO)) % a.DO);
-    const int64_t nc = i / ((int64_t)a.WO * a.HO * a.DO);
-    const float *xp = a.x + nc * a.D * a.H * a.W;
+    const uint32_t q1 = i / (uint32_t)a.WO, q2 = q1 / (uint32_t)a.HO;
+    const int ow = (int)(i - q1 * a.WO), oh = (int)(q1 - q2 * a.HO);
+    int od = 0;
+    uint32_t nc = q2;
+    if (a.DO > 1) {
+        nc = q2 / (uint32_t)a.DO;
+        od = (int)(q2 - nc * a.DO);
+    }
+    const float *xp = a.x + (int64_t)nc * a.D * a.H * a.W;
     float acc = AVG ? 0.f : -INFINITY;
     int cnt = 0;
     for (int kd = 0; kd < a.KD; ++kd) {
@@ -329,14 +335,15 @@ __global__ __launch_bounds__(256) void window_pool_kernel(PoolArgs a) {
             for (int kw = 0; kw < a.KW; ++kw) {
                 const int iw = ow * a.sw - a.pw + kw;
                 if (iw < 0 || iw >= a.W) continue;
-                const float v = xp[((int64_t)id * a.H + ih) * a.W + iw];
+                const float v = xp[(id * a.H + ih) * a.W + iw];
                 acc = AVG ? acc + v : fmaxf(acc, v);
                 ++cnt;
             }
         }
     }
     if (AVG) acc = cnt ? acc / (float)cnt : 0.f;
-    a.y[i] = apply_steps(a.epi, acc, i, chan_of(a.epi, i));
+    if (a.epi.n) acc = apply_steps(a.epi, acc, i, a.epi.bias_c ? (int)((i / (uint32_t)a.epi.bias_inner) % (uint32_t)a.epi.bias_c) : 0);
+    a.y[i] = acc;
 }
 
 // one wave per (n, c) plane
@@ -355,6 +362,8 @@ __global__ __launch_bounds__(256) void global_avg_pool_kernel(PoolArgs a) {
 int launch_pool(const PoolArgs &a, void *stream) {
     hipStream_t s = (hipStream_t)stream;
     if (a.D < 1 || a.KD < 1 || a.sd < 1 || a.DO < 1) return (int)hipErrorInvalidValue;
+    if ((int64_t)a.NC * a.DO * a.HO * a.WO >= ((int64_t)1 << 31) || (int64_t)a.D * a.H * a.W >= ((int64_t)1 << 31))
+        return (int)hipErrorInvalidValue;                      // the window kernels index with 32 bits
     if (a.mode == 0 || a.mode == 2) {
         const int64_t total = (int64_t)a.NC * a.DO * a.HO * a.WO;
         const dim3 grid((unsigned)((total + 255) / 256));
