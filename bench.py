@@ -31,11 +31,11 @@ VARIANTS = ("igemm", "igemm_s", "igemm_s8", "igemm_s16", "igemm_m", "igemm_l", "
 
 
 # HBM-side traffic of the fp32 MFMA kernels of one ResNet-50 step, from two rocprofv3 --pmc runs of this file
-# (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch, summed over the 57 such dispatches of a step and averaged over
+# (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch, summed over the 56 such dispatches of a step (53 fused convolutions, 3 split-K reductions) and averaged over
 # the steps of the run).  Scale factors from the 256 MiB plain device copy of --calib-copy in the same runs:
 # WRITE_SIZE read 262144.0 KiB for it (factor 1.000), FETCH_SIZE 131083.5 KiB (factor 2.000).  The figures hold
 # for the kernel sources they were taken with; after any change to them `traffic` is reported as null.
-TRAFFIC = {"resnet50": {"sources": "b9752c02da947a4a", "fetch_bytes": 304.48e6, "write_bytes": 46.87e6}}
+TRAFFIC = {"resnet50": {"sources": "d67029f8fea3912a", "fetch_bytes": 296.64e6, "write_bytes": 46.86e6}}
 
 
 def kernel_sources_fingerprint():
