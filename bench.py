@@ -253,7 +253,7 @@ def main():
     import workloads as wl
     from paper_2111_00655_amd import binding as B
 
-    reg = wl.default_registry(VARIANTS, sepconv=True)
+    reg = wl.default_registry(VARIANTS, sepconv=True, attention=True)
     opts = B.ProfileOpts(warmup=10, batches=5, min_batch_us=200, max_launches=500)
 
     rules = ()

@@ -239,6 +239,10 @@ int32_t clg_graph_node_shape(const clg_graph *g, int32_t node, int32_t *dtype,
  *              conv2d -> 1x1 conv2d -> elementwise tail, or relu -> 1x1 conv2d
  *              (any stride) -> tail; both weights constants, the depthwise
  *              result stays in LDS, the 1x1 weights are re-packed per plan
+ *   "attention"  softmax(scale q k^T) v per head in one kernel: batch_matmul
+ *              -> [mul_scalar] -> softmax -> batch_matmul [-> transpose ->
+ *              reshape that puts the heads side by side]; head sizes 32, 64,
+ *              128, up to 512 keys; the scores never leave the chip
  *   "direct"   direct convolution (any groups), max / average pooling (window
  *              pools also with an elementwise tail), global average pooling
  *   "rowwise"  softmax and layer norm with fused elementwise prologue

@@ -172,7 +172,7 @@ int32_t clg_register_backend(clg_ctx *ctx, const char *name, int32_t *backend) {
         {"igemm_l", FAM_IGEMM, TILE_L, 0}, {"igemm_s8", FAM_IGEMM, TILE_S8, 0}, {"igemm_s16", FAM_IGEMM, TILE_S16, 0},
         {"igemm_r32", FAM_IGEMM, TILE_R32, 1}, {"igemm_r16", FAM_IGEMM, TILE_R16, 1},
         {"igemm_s_nk", FAM_IGEMM, TILE_S, 1}, {"igemm_s8_nk", FAM_IGEMM, TILE_S8, 1}, {"igemm_s16_nk", FAM_IGEMM, TILE_S16, 1},
-        {"sepconv", FAM_SEPCONV, 0, 0}, {"direct", FAM_DIRECT, 0, 0}, {"rowwise", FAM_ROWWISE, 0, 0}, {"eltwise", FAM_ELTWISE, 0, 0}};
+        {"sepconv", FAM_SEPCONV, 0, 0}, {"attention", FAM_ATTENTION, 0, 0}, {"direct", FAM_DIRECT, 0, 0}, {"rowwise", FAM_ROWWISE, 0, 0}, {"eltwise", FAM_ELTWISE, 0, 0}};
     const std::string s(name);
     for (size_t i = 0; i < ctx->c.backends.size(); ++i)
         if (ctx->c.backends[i].name == s) {

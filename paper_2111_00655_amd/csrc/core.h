@@ -80,7 +80,8 @@ struct Graph {
 };
 
 // ---- registry ------------------------------------------------------------------------
-enum Family : int32_t { FAM_IGEMM = 0, FAM_DIRECT = 1, FAM_ROWWISE = 2, FAM_ELTWISE = 3, FAM_SEPCONV = 4 };
+enum Family : int32_t { FAM_IGEMM = 0, FAM_DIRECT = 1, FAM_ROWWISE = 2, FAM_ELTWISE = 3, FAM_SEPCONV = 4,
+                        FAM_ATTENTION = 5 };
 
 struct Backend {
     std::string name;
@@ -116,7 +117,7 @@ struct Operand {
 
 enum CallKind : int32_t {
     CALL_GEMM = 0, CALL_DIRECT_CONV, CALL_POOL, CALL_GAP, CALL_ROWWISE,
-    CALL_ELTWISE, CALL_LAYOUT, CALL_CONCAT, CALL_SEPCONV
+    CALL_ELTWISE, CALL_LAYOUT, CALL_CONCAT, CALL_SEPCONV, CALL_ATTENTION
 };
 
 struct KernelCall {
@@ -141,6 +142,7 @@ struct KernelCall {
     EltwiseArgs elt{};
     LayoutArgs layout{};
     ConcatArgs cat{};                                  // operands in epi_nodes[0..n)
+    AttentionArgs att{};                               // a = q, b = k, c = v
     SepConvArgs sep{};                                 // a = x, b = 1x1 weights (packed by the plan), c = depthwise weights
     KernelCall() { for (auto &e : epi_nodes) e = -1; }
 };

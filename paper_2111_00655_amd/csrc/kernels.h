@@ -161,6 +161,21 @@ size_t sepconv_lds_bytes(const SepConvArgs &a);
 int launch_sepconv_pack(const SepConvArgs &a, const float *w, float *dst, void *stream);
 int launch_sepconv(const SepConvArgs &a, void *stream);
 
+// ---- scaled-dot-product attention in one kernel (attention.hip) -----------------------------
+// y[h] = softmax(scale * q[h] k[h]^T) v[h]; q [B][Sq][d], k and v [B][Sk][d]; y [B][Sq][d], or with
+// merge = 1 the heads side by side: [Sq][B*d].
+struct AttentionArgs {
+    const float *q;
+    const float *k;
+    const float *v;
+    float *y;
+    int32_t B, Sq, Sk, d;
+    float scale;
+    int32_t merge;
+};
+bool attention_shape_ok(const AttentionArgs &a);       // d in {32, 64, 128}, Sk <= 512
+int launch_attention(const AttentionArgs &a, void *stream);
+
 // ---- concat: y[r][...] = x_0[r][...] x_1[r][...] ..., r < outer ---------------------------------
 struct ConcatArgs {
     int32_t n;                             // operands, at most 8

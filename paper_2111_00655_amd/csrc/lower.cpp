@@ -110,6 +110,17 @@ int32_t check_pattern(const Context &ctx, Pattern *p) {
             for (int t = 1; t < len - 2; ++t) ok = ok && kind(t) != CLG_OP_RESHAPE;
         }
         break;
+    case FAM_ATTENTION: {
+        // batch_matmul [mul_scalar] softmax batch_matmul [transpose reshape]; the probabilities are the
+        // first operand of the second product
+        int t = 0;
+        ok = kind(t++) == CLG_OP_BATCH_MATMUL;
+        if (ok && t < len && kind(t) == CLG_OP_MUL_SCALAR) ++t;
+        ok = ok && t + 1 < len && kind(t) == CLG_OP_SOFTMAX && kind(t + 1) == CLG_OP_BATCH_MATMUL && p->main_arg[t + 1] == 0;
+        t += 2;
+        ok = ok && (t == len || (t + 2 == len && kind(t) == CLG_OP_TRANSPOSE && kind(t + 1) == CLG_OP_RESHAPE));
+        break;
+    }
     case FAM_SEPCONV: {
         // [relu] conv2d [conv2d] tail: a depthwise + 1x1 pair, or a 1x1 convolution behind a relu;
         // which convolution is which is checked per match
@@ -254,7 +265,36 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
 
     Epilogue epi{};
     int32_t rc = CLG_OK;
-    if (be.family == FAM_SEPCONV) {
+    if (be.family == FAM_ATTENTION) {
+        AttentionArgs &a = c.att;
+        int t = 1;
+        a.scale = 1.f;
+        if (cv.op(t) == CLG_OP_MUL_SCALAR) a.scale = (float)g.nodes[cv.node(t++)].attrs.scalar;
+        const int t_pv = t + 1;
+        const Node &qk = g.nodes[cv.node(0)], &pv = g.nodes[cv.node(t_pv)];
+        const int32_t q = cv.arg(0, 0), k = cv.arg(0, 1), v = cv.arg(t_pv, 1);
+        const Shape &qs = g.nodes[q].shape, &ks = g.nodes[k].shape, &vs = g.nodes[v].shape;
+        if (!qk.attrs.transpose_b || pv.attrs.transpose_b)
+            return fail(CLG_NO_KERNEL, "attention needs q k^T with k as [B, Sk, d] and p v with v as [B, Sk, d]");
+        if (qs.ndim != 3 || ks.ndim != 3 || vs.ndim != 3 || vs.d[2] != qs.d[2] || vs.d[1] != ks.d[1])
+            return fail(CLG_NO_KERNEL, "attention: q, k, v must be [B, S, d] with one head size");
+        a.B = (int)qs.d[0]; a.Sq = (int)qs.d[1]; a.Sk = (int)ks.d[1]; a.d = (int)qs.d[2];
+        if (!attention_shape_ok(a)) return fail(CLG_NO_KERNEL, "attention kernel takes head sizes 32 / 64 / 128 and up to 512 keys");
+        a.merge = 0;
+        if (t_pv + 1 < len) {                                // [B, Sq, d] -> transpose (1, 0, 2) -> reshape [Sq, B*d]
+            const Node &tr = g.nodes[cv.node(t_pv + 1)], &rs = g.nodes[cv.node(t_pv + 2)];
+            if (tr.attrs.ndims != 3 || tr.attrs.dims[0] != 1 || tr.attrs.dims[1] != 0 || tr.attrs.dims[2] != 2 ||
+                rs.shape.ndim != 2 || rs.shape.d[0] != a.Sq || rs.shape.d[1] != (int64_t)a.B * a.d)
+                return fail(CLG_NO_KERNEL, "attention stores only the head merge [B, S, d] -> [S, B*d] permuted");
+            a.merge = 1;
+        }
+        c.kind = CALL_ATTENTION;
+        c.a_node = q; c.b_node = k; c.c_node = v;
+        use(q); use(k); use(v);
+        c.flops = 2.0 * a.B * a.Sq * (double)a.Sk * a.d * 2.0;
+        c.bound = 0;
+        c.name = std::string("attention_d") + std::to_string(a.d) + (a.merge ? "_merge" : "");
+    } else if (be.family == FAM_SEPCONV) {
         int t = 0;
         SepConvArgs &a = c.sep;
         a.pro_relu = k0 == CLG_OP_RELU ? 1 : 0;

@@ -375,6 +375,12 @@ int32_t launch_call(const KernelCall &c, const void *a, const void *b, const voi
         err = launch_sepconv(k, stream);
         break;
     }
+    case CALL_ATTENTION: {
+        AttentionArgs k = c.att;
+        k.q = (const float *)a; k.k = (const float *)b; k.v = (const float *)c3; k.y = (float *)out;
+        err = launch_attention(k, stream);
+        break;
+    }
     case CALL_CONCAT: {
         ConcatArgs k = c.cat;
         for (int s = 0; s < k.n; ++s) k.src[s] = (const float *)epi_ptrs[s];

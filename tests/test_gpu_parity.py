@@ -219,6 +219,58 @@ def test_resnet3d_whole_path():
     s.close()
 
 
+ATT_CASES = [
+    # heads, Sq, Sk, d, scale?, merged store?
+    (12, 128, 128, 64, True, True),        # BERT-base
+    (3, 50, 70, 32, False, False),         # ragged rows and keys, no scale, heads kept apart
+    (2, 16, 512, 128, True, True),         # the most keys and the largest head the kernel takes
+    (1, 1, 5, 32, True, False),            # a single query
+    (5, 33, 17, 64, True, True),
+    (2, 200, 129, 32, True, False),
+]
+
+
+@pytest.mark.parametrize("case", ATT_CASES)
+def test_attention_in_one_kernel(case):
+    """softmax(scale q k^T) v per head as one kernel against the oracle's operator-by-operator result."""
+    heads, sq, sk, dd, scaled, merged = case
+    r = rng_for(41, heads, sq, sk, dd)
+    d = wl.GraphDesc("attention_case")
+    q, k, v = d.input(f32(r, heads, sq, dd)), d.input(f32(r, heads, sk, dd)), d.input(f32(r, heads, sk, dd))
+    y = d.op("batch_matmul", [q, k], transpose_b=True)
+    pat = P("batch_matmul", W, W)
+    if scaled:
+        y = d.op("mul_scalar", [y], scalar=float(1.0 / np.sqrt(dd)))
+        pat = P("mul_scalar", pat)
+    y = d.op("softmax", [y])
+    y = d.op("batch_matmul", [y, v], transpose_b=False)
+    pat = P("batch_matmul", P("softmax", pat), W)
+    if merged:
+        y = d.op("transpose", [y], dims=(1, 0, 2))
+        y = d.op("reshape", [y], dims=(sq, heads * dd))
+        pat = P("reshape", P("transpose", pat))
+    d.mark_output(y)
+    name, _ = run_single_group(d, "attention", pat)
+    assert name == f"attention_d{dd}" + ("_merge" if merged else ""), name
+
+
+def test_attention_refuses_what_it_cannot_run():
+    r = rng_for(42)
+    d = wl.GraphDesc("att_small_head")
+    q, k, v = d.input(f32(r, 2, 8, 8)), d.input(f32(r, 2, 8, 8)), d.input(f32(r, 2, 8, 8))
+    y = d.op("batch_matmul", [d.op("softmax", [d.op("batch_matmul", [q, k], transpose_b=True)]), v], transpose_b=False)
+    d.mark_output(y)
+    s = clg.Session(d, [("attention", P("batch_matmul", P("softmax", P("batch_matmul", W, W)), W))], device=0)
+    assert len(s.match()) == 1
+    assert B.clg_profile_match(s.ctx, s.graph, 0) >= B.COST_INF      # head size 8
+    with pytest.raises(clg.ClgError) as e:
+        s.compile([0])
+    assert e.value.status == "NO_KERNEL"
+    s.close()
+    with pytest.raises(clg.ClgError):                                  # a lone product is not this family's
+        clg.Session(d, [("attention", P("batch_matmul", W, W))], device=0)
+
+
 SEP_CASES = [
     # batch, c, cout, h, w, k (0 = no depthwise stage), stride, pre-relu, tail
     (1, 44, 44, 28, 28, 3, 1, True, ("bias_add",)),
@@ -622,13 +674,13 @@ def test_model_under_searched_placement(name):
     s.close()
 
 
-@pytest.mark.parametrize("name", ["resnet50", "nasnet_a", "resnet3d_50"])
+@pytest.mark.parametrize("name", ["resnet50", "bert_base", "nasnet_a", "resnet3d_50"])
 def test_model_in_the_benchmark_s_configuration(name):
     """Full size, the registry and measurer options bench.py uses (all kernel variants and the
     one-kernel separable convolution family)."""
     import bench
     desc = wl.MODEL_BUILDERS[name](0)
-    reg = wl.default_registry(bench.VARIANTS, sepconv=True)
+    reg = wl.default_registry(bench.VARIANTS, sepconv=True, attention=True)
     s, g, oms = _session_and_oracle(desc, reg)
     costs = s.profile(B.ProfileOpts(warmup=10, batches=5, min_batch_us=200, max_launches=500))
     got_search = s.search(costs, 0)

@@ -52,12 +52,13 @@ def _tails(anchor, tails):
     return out
 
 
-def default_registry(variants=("igemm",), sepconv=False):
+def default_registry(variants=("igemm",), sepconv=False, attention=False):
     """The registry the benchmarks and the GPU parity tests use.  `variants`
     lists the MFMA implicit-GEMM kernel variants to register as separate
     backends (same patterns each), so that the search can pick a tile
     configuration per layer.  `sepconv` adds the one-kernel separable
-    convolution family (NasNet-A's building block)."""
+    convolution family (NasNet-A's building block), `attention` the one-kernel
+    scaled-dot-product attention."""
     reg = []
 
     def add(backend, pats):
@@ -100,6 +101,13 @@ def default_registry(variants=("igemm",), sepconv=False):
     for anchor in sep_anchors if sepconv else ():
         add("sepconv", _tails(anchor, [(), ("bias_add",), ("bias_add", "relu"), ("bias_add", "add"),
                                        ("bias_add", "add", "relu")]))
+
+    # --- attention in one kernel: q k^T, scale, softmax, p v, heads merged on store
+    if attention:
+        qk = P("batch_matmul", W, W)
+        for scores in (P("mul_scalar", qk), qk):
+            pv = P("batch_matmul", P("softmax", scores), W)
+            add("attention", [P("reshape", P("transpose", pv)), pv])
 
     # --- MFMA implicit GEMM / GEMM variants
     for be in variants:
