@@ -43,9 +43,9 @@ def kernel_sources_fingerprint():
     import hashlib
     h = hashlib.sha256()
     d = os.path.join(ROOT, "paper_2111_00655_amd", "csrc")
-    files = glob.glob(os.path.join(d, "*.hip")) + glob.glob(os.path.join(d, "gemm_*.h"))
-    files += [os.path.join(d, "device_common.h"), os.path.join(d, "kernels.h")]
-    for f in sorted(files):                     # the device code: kernels, their headers and argument blocks
+    files = glob.glob(os.path.join(d, "gemm_*.hip")) + glob.glob(os.path.join(d, "gemm_*.h"))
+    files += [os.path.join(d, n) for n in ("kernels_gemm.hip", "device_common.h", "kernels.h")]
+    for f in sorted(files):                     # the convolution / GEMM kernels, their headers and argument blocks
         with open(f, "rb") as fh:
             h.update(fh.read())
     return h.hexdigest()[:16]

@@ -48,11 +48,15 @@ __device__ __forceinline__ float row16_sum(float v) {
 }
 
 constexpr int kRows = 16;          // query rows per workgroup
-constexpr int kMaxTiles = 8;       // score tiles per wave: Sk <= 4 waves * 8 tiles * 16 = 512
+constexpr int kMaxKeys = 512;
 constexpr int kVPre = 8;           // key groups whose v operands a wave loads ahead
 
-template <int D16>                 // head size / 16
+// D16 = head size / 16.  MAXT = score tiles per wave the code is unrolled for: 2 (up to 128 keys) or
+// 8 (up to 512); the short form is a third of the code, and a kernel of a few microseconds that starts
+// with a cold instruction cache feels its length.
+template <int D16, int MAXT>
 __global__ __launch_bounds__(256) void attention_kernel(AttentionArgs a) {
+    constexpr int kMaxTiles = MAXT;
     extern __shared__ float lds[];                           // [16][ldp]: scores, then probabilities
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -70,22 +74,33 @@ __global__ __launch_bounds__(256) void attention_kernel(AttentionArgs a) {
     float4 qa[D16];
 #pragma unroll
     for (int g = 0; g < D16; ++g) qa[g] = qp[4 * g];
+    // two tiles per round: their k rows are loaded together (one memory latency per round, tiles past
+    // the end re-read the last key row and are not stored), and their MFMA chains are interleaved
     floatx4 acc[kMaxTiles];
 #pragma unroll
-    for (int u = 0; u < kMaxTiles; ++u) {
+    for (int u = 0; u < kMaxTiles; u += 2) {
         acc[u] = floatx4{0.f, 0.f, 0.f, 0.f};
-        const int t = wave + 4 * u;
-        if (t < nct) {                                       // uniform over the wave
-            const float4 *kp = reinterpret_cast<const float4 *>(K + (int64_t)min(t * 16 + r, a.Sk - 1) * d) + s;
-            float4 kb[D16];
-#pragma unroll
-            for (int g = 0; g < D16; ++g) kb[g] = kp[4 * g];
+        acc[u + 1] = floatx4{0.f, 0.f, 0.f, 0.f};
+        const int t0 = wave + 4 * u, t1 = t0 + 4;
+        if (t0 < nct) {                                      // uniform over the wave
+            const float4 *kp0 = reinterpret_cast<const float4 *>(K + (int64_t)min(t0 * 16 + r, a.Sk - 1) * d) + s;
+            const float4 *kp1 = reinterpret_cast<const float4 *>(K + (int64_t)min(t1 * 16 + r, a.Sk - 1) * d) + s;
+            float4 kb0[D16], kb1[D16];
 #pragma unroll
             for (int g = 0; g < D16; ++g) {
-                acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(qa[g].x, kb[g].x, acc[u], 0, 0, 0);
-                acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(qa[g].y, kb[g].y, acc[u], 0, 0, 0);
-                acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(qa[g].z, kb[g].z, acc[u], 0, 0, 0);
-                acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(qa[g].w, kb[g].w, acc[u], 0, 0, 0);
+                kb0[g] = kp0[4 * g];
+                kb1[g] = kp1[4 * g];
+            }
+#pragma unroll
+            for (int g = 0; g < D16; ++g) {
+                acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(qa[g].x, kb0[g].x, acc[u], 0, 0, 0);
+                acc[u + 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(qa[g].x, kb1[g].x, acc[u + 1], 0, 0, 0);
+                acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(qa[g].y, kb0[g].y, acc[u], 0, 0, 0);
+                acc[u + 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(qa[g].y, kb1[g].y, acc[u + 1], 0, 0, 0);
+                acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(qa[g].z, kb0[g].z, acc[u], 0, 0, 0);
+                acc[u + 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(qa[g].z, kb1[g].z, acc[u + 1], 0, 0, 0);
+                acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(qa[g].w, kb0[g].w, acc[u], 0, 0, 0);
+                acc[u + 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(qa[g].w, kb1[g].w, acc[u + 1], 0, 0, 0);
             }
         }
     }
@@ -116,7 +131,7 @@ __global__ __launch_bounds__(256) void attention_kernel(AttentionArgs a) {
     // and one pass instead of four)
     {
         float *row = lds + (4 * wave + s) * ldp;
-        float v[4 * kMaxTiles];
+        float v[4 * kMaxTiles];                                            // 4 * MAXT >= nct
         float mx = -INFINITY;
 #pragma unroll
         for (int i = 0; i < 4 * kMaxTiles; ++i) {
@@ -140,18 +155,25 @@ __global__ __launch_bounds__(256) void attention_kernel(AttentionArgs a) {
 
     // ---- out tile = P[16 x Sk] V[Sk x 16]; A operand from LDS (row r), 16 bytes per lane
     for (int t = wave; t < D16; t += 4) {
-        floatx4 o = {0.f, 0.f, 0.f, 0.f};
+        // two accumulators, even and odd key groups: half as long a chain of dependent MFMAs
+        floatx4 o = {0.f, 0.f, 0.f, 0.f}, o2 = {0.f, 0.f, 0.f, 0.f};
         const float *prow = lds + r * ldp + 4 * s;
         int g = 0;
         if (t == vt) {                                       // the key groups whose v operands are already in registers
 #pragma unroll
-            for (int gg = 0; gg < kVPre; ++gg) {
+            for (int gg = 0; gg < kVPre; gg += 2) {
                 if (gg < nct) {
                     const float4 pa = *reinterpret_cast<const float4 *>(prow + 16 * gg);
+                    float4 pb = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (gg + 1 < nct) pb = *reinterpret_cast<const float4 *>(prow + 16 * (gg + 1));
                     o = __builtin_amdgcn_mfma_f32_16x16x4f32(pa.x, vb[gg][0], o, 0, 0, 0);
+                    o2 = __builtin_amdgcn_mfma_f32_16x16x4f32(pb.x, vb[gg + 1][0], o2, 0, 0, 0);
                     o = __builtin_amdgcn_mfma_f32_16x16x4f32(pa.y, vb[gg][1], o, 0, 0, 0);
+                    o2 = __builtin_amdgcn_mfma_f32_16x16x4f32(pb.y, vb[gg + 1][1], o2, 0, 0, 0);
                     o = __builtin_amdgcn_mfma_f32_16x16x4f32(pa.z, vb[gg][2], o, 0, 0, 0);
+                    o2 = __builtin_amdgcn_mfma_f32_16x16x4f32(pb.z, vb[gg + 1][2], o2, 0, 0, 0);
                     o = __builtin_amdgcn_mfma_f32_16x16x4f32(pa.w, vb[gg][3], o, 0, 0, 0);
+                    o2 = __builtin_amdgcn_mfma_f32_16x16x4f32(pb.w, vb[gg + 1][3], o2, 0, 0, 0);
                 }
             }
             g = min(nct, kVPre);
@@ -167,6 +189,8 @@ __global__ __launch_bounds__(256) void attention_kernel(AttentionArgs a) {
             o = __builtin_amdgcn_mfma_f32_16x16x4f32(pa.w, b[3], o, 0, 0, 0);
         }
 #pragma unroll
+        for (int g = 0; g < 4; ++g) o[g] += o2[g];
+#pragma unroll
         for (int g = 0; g < 4; ++g) {
             const int qi = q0 + 4 * s + g;
             if (qi >= a.Sq) continue;
@@ -179,7 +203,7 @@ __global__ __launch_bounds__(256) void attention_kernel(AttentionArgs a) {
 }  // namespace
 
 bool attention_shape_ok(const AttentionArgs &a) {
-    return a.B >= 1 && a.B <= 65535 && a.Sq >= 1 && a.Sk >= 1 && a.Sk <= 4 * kMaxTiles * 16 &&
+    return a.B >= 1 && a.B <= 65535 && a.Sq >= 1 && a.Sk >= 1 && a.Sk <= kMaxKeys &&
            (a.d == 32 || a.d == 64 || a.d == 128) && (int64_t)a.Sq * a.d < ((int64_t)1 << 31);
 }
 
@@ -190,9 +214,10 @@ int launch_attention(const AttentionArgs &a, void *stream) {
     const dim3 grid((unsigned)((a.Sq + kRows - 1) / kRows), (unsigned)a.B);
     const int nct = (a.Sk + 15) / 16;
     const size_t lds = (size_t)kRows * (nct * 16 + 4) * sizeof(float);
-    if (a.d == 32) hipLaunchKernelGGL(attention_kernel<2>, grid, dim3(256), lds, (hipStream_t)stream, a);
-    else if (a.d == 64) hipLaunchKernelGGL(attention_kernel<4>, grid, dim3(256), lds, (hipStream_t)stream, a);
-    else hipLaunchKernelGGL(attention_kernel<8>, grid, dim3(256), lds, (hipStream_t)stream, a);
+    void (*kern)(AttentionArgs);
+    if (a.Sk <= 128) kern = a.d == 32 ? attention_kernel<2, 2> : (a.d == 64 ? attention_kernel<4, 2> : attention_kernel<8, 2>);
+    else kern = a.d == 32 ? attention_kernel<2, 8> : (a.d == 64 ? attention_kernel<4, 8> : attention_kernel<8, 8>);
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, (hipStream_t)stream, a);
     return (int)hipGetLastError();
 }
 
