@@ -126,8 +126,11 @@ struct DirectConvArgs {
     const float *w;
     float *y;
     int32_t N, C, H, W, O, KH, KW, sh, sw, ph, pw, G, HO, WO;
+    int32_t pro_relu;                      // relu on x first; only the depthwise kernel (G = C = O, 3x3 / 5x5 / 7x7) takes it
+    EpiFast ef;                            // filled by launch_direct_conv from epi
     Epilogue epi;
 };
+bool depthwise_fast_ok(const DirectConvArgs &a);
 
 struct PoolArgs {
     const float *x;

@@ -292,7 +292,84 @@ __global__ __launch_bounds__(256) void direct_conv_kernel(DirectConvArgs a) {
     }
 }
 
-int launch_direct_conv(const DirectConvArgs &a, void *stream) {
+// Depthwise convolution (one input channel per output channel), square filter KS: one output per
+// thread, taps unrolled, loads without branches (clamped addresses, masked values) so that they all
+// go out together; optional relu on the input, fused tail.
+template <int KS>
+__global__ __launch_bounds__(256) void depthwise_kernel(DirectConvArgs a) {
+    const uint32_t npix = (uint32_t)(a.HO * a.WO);
+    const uint32_t total = (uint32_t)(a.N * a.C) * npix;
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const uint32_t nc = i / npix, p = i - nc * npix;
+    const uint32_t c = nc % (uint32_t)a.C;
+    const int oh = (int)(p / (uint32_t)a.WO), ow = (int)(p - (uint32_t)oh * a.WO);
+    const int ih0 = oh * a.sh - a.ph, iw0 = ow * a.sw - a.pw;
+    const float *xc = a.x + (int64_t)nc * a.H * a.W;
+    const float *wc = a.w + c * (KS * KS);
+    const float lo = a.pro_relu ? 0.f : -INFINITY;
+    int ro[KS], co[KS];
+    bool vr[KS], vc[KS];
+#pragma unroll
+    for (int t = 0; t < KS; ++t) {
+        const int ih = ih0 + t, iw = iw0 + t;
+        vr[t] = ih >= 0 && ih < a.H;
+        vc[t] = iw >= 0 && iw < a.W;
+        ro[t] = (ih < 0 ? 0 : (ih >= a.H ? a.H - 1 : ih)) * a.W;
+        co[t] = iw < 0 ? 0 : (iw >= a.W ? a.W - 1 : iw);
+    }
+    float xv[KS * KS], wv[KS * KS];
+#pragma unroll
+    for (int kh = 0; kh < KS; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < KS; ++kw) {
+            xv[kh * KS + kw] = xc[ro[kh] + co[kw]];
+            wv[kh * KS + kw] = wc[kh * KS + kw];
+        }
+    // bias and residual of this output, fetched with the taps
+    const int f = a.ef.flags;
+    const bool fast = !(f & EF_GENERIC);
+    float bias_v = 0.f, add_v = 0.f;
+    if (fast && (f & EF_BIAS)) bias_v = a.ef.bias[c];
+    if (fast && (f & EF_ADD)) add_v = a.ef.add[i];
+    float v = 0.f;
+#pragma unroll
+    for (int kh = 0; kh < KS; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < KS; ++kw) {
+            const float t = (vr[kh] && vc[kw]) ? fmaxf(xv[kh * KS + kw], lo) : 0.f;
+            v = fmaf(wv[kh * KS + kw], t, v);
+        }
+    if (fast) {
+        if (f & EF_SCALE) v *= a.ef.scale;
+        v += bias_v;
+        v += add_v;
+        if (f & EF_RELU) v = v > 0.f ? v : 0.f;
+        else if (f & EF_GELU) v = gelu_erf(v);
+        else if (f & EF_TANH) v = tanhf(v);
+    } else {
+        v = apply_steps(a.epi, v, i, (int)c);
+    }
+    a.y[i] = v;
+}
+
+bool depthwise_fast_ok(const DirectConvArgs &a) {
+    return a.G == a.C && a.O == a.C && a.KH == a.KW && (a.KH == 3 || a.KH == 5 || a.KH == 7) &&
+           (int64_t)a.N * a.C * a.HO * a.WO < ((int64_t)1 << 31) && (int64_t)a.H * a.W < ((int64_t)1 << 31);
+}
+
+int launch_direct_conv(const DirectConvArgs &a_in, void *stream) {
+    DirectConvArgs a = a_in;
+    a.ef = make_epi_fast(a.epi);
+    if (depthwise_fast_ok(a)) {
+        const int64_t total = (int64_t)a.N * a.C * a.HO * a.WO;
+        const dim3 grid((unsigned)((total + 255) / 256));
+        if (a.KH == 3) hipLaunchKernelGGL(depthwise_kernel<3>, grid, dim3(256), 0, (hipStream_t)stream, a);
+        else if (a.KH == 5) hipLaunchKernelGGL(depthwise_kernel<5>, grid, dim3(256), 0, (hipStream_t)stream, a);
+        else hipLaunchKernelGGL(depthwise_kernel<7>, grid, dim3(256), 0, (hipStream_t)stream, a);
+        return (int)hipGetLastError();
+    }
+    if (a.pro_relu) return (int)hipErrorInvalidValue;      // only the depthwise kernel applies the relu
     const int npix = a.HO * a.WO;
     const int Og = a.O / a.G;
     const int block = npix >= 256 ? 256 : (npix > 64 ? 128 : 64);

@@ -329,6 +329,30 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
             macs += (double)first.shape.numel() * a.KH * a.KW;
         }
         const int Gp = pwn.attrs.groups > 0 ? pwn.attrs.groups : 1;
+        if (t_pw == t_first && a.pro_relu && Gp == a.C && wps.d[0] == a.C && wps.d[1] == 1) {
+            // relu -> depthwise convolution -> tail: the depthwise kernel of the direct family, with the relu as its prologue
+            DirectConvArgs &dc = c.dconv;
+            dc.N = a.N; dc.C = a.C; dc.H = a.H; dc.W = a.W; dc.O = a.C; dc.G = a.C;
+            dc.KH = (int)wps.d[2]; dc.KW = (int)wps.d[3];
+            dc.sh = a.sh; dc.sw = a.sw; dc.ph = pwn.attrs.pad[0]; dc.pw = pwn.attrs.pad[1];
+            dc.HO = (int)pwn.shape.d[2]; dc.WO = (int)pwn.shape.d[3];
+            dc.pro_relu = 1;
+            if (!depthwise_fast_ok(dc)) return fail(CLG_NO_KERNEL, "relu + depthwise convolution: the kernel takes 3x3, 5x5 and 7x7 filters");
+            for (int u = t_pw + 1; u < len; ++u)
+                if ((rc = add_step(cv, u, false, &epi, c.epi_nodes)) != CLG_OK) return rc;
+            if (epi.bias_c && (epi.bias_inner != (int64_t)dc.HO * dc.WO || epi.bias_c != dc.O))
+                return fail(CLG_NO_KERNEL, "bias_add axis does not match the kernel's channel dimension");
+            for (int s = 0; s < epi.n; ++s) use(c.epi_nodes[s]);
+            dc.epi = epi;
+            c.kind = CALL_DIRECT_CONV;
+            c.a_node = xa;
+            c.b_node = wp;
+            use(xa);
+            use(wp);
+            c.flops = 2.0 * (double)pwn.shape.numel() * dc.KH * dc.KW;
+            c.bound = 1;
+            c.name = "relu_dwconv" + std::to_string(dc.KH) + (epi.n ? "_epi" + std::to_string(epi.n) : std::string());
+        } else {
         if (Gp != 1 || wps.d[2] != 1 || wps.d[3] != 1 || pwn.attrs.pad[0] != 0 || pwn.attrs.pad[1] != 0 ||
             wps.d[1] != a.C || g.nodes[wp].kind != NODE_CONST)
             return fail(CLG_NO_KERNEL, "sepconv ends in an ungrouped 1x1 convolution without padding and with constant weights");
@@ -354,6 +378,7 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
         c.bound = 0;
         c.name = std::string(a.pro_relu ? "relu_" : "") + (c.c_node >= 0 ? "sepconv" + std::to_string(a.KH) : std::string("pwconv")) +
                  "_w" + std::to_string(a.nwaves) + "m" + std::to_string(a.mt_per_wg) + (epi.n ? "_epi" + std::to_string(epi.n) : std::string());
+        }
     } else if (is_contraction(k0)) {
         const int32_t xa = cv.arg(0, 0), wb = cv.arg(0, 1);
         const Shape &xs = g.nodes[xa].shape, &ws = g.nodes[wb].shape, &ys = anchor.shape;

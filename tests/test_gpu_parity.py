@@ -317,6 +317,29 @@ def test_separable_conv_in_one_kernel(case):
     assert ("sepconv" in name) == bool(k) and name.startswith("relu_") == pre, name
 
 
+@pytest.mark.parametrize("case", [(1, 44, 28, 28, 3, 1, ()), (1, 22, 15, 13, 7, 2, ("bias_add",)), (2, 176, 7, 7, 5, 1, ("bias_add", "add")),
+                                  (1, 11, 56, 56, 5, 2, ("bias_add", "relu")), (3, 5, 9, 6, 3, 1, ("tanh",))])
+def test_relu_then_depthwise_conv(case):
+    """relu -> depthwise convolution -> tail as one launch of the depthwise kernel (the first half of a
+    separable convolution where the search keeps its 1x1 half on another kernel)."""
+    batch, c, h, w, k, s, tail = case
+    r = rng_for(23, c, h, k)
+    d = wl.GraphDesc("relu_dw")
+    x = d.input(f32(r, batch, c, h, w))
+    y = d.op("conv2d", [d.op("relu", [x]), d.const(f32(r, c, 1, k, k, scale=1.0 / k))], stride=(s, s), pad=(k // 2, k // 2), groups=c)
+    ho, wo = (h + 2 * (k // 2) - k) // s + 1, (w + 2 * (k // 2) - k) // s + 1
+    for op in tail:
+        if op == "bias_add":
+            y = d.op("bias_add", [y, d.const(f32(r, c))], axis=1)
+        elif op == "add":
+            y = d.op("add", [y, d.input(f32(r, batch, c, ho, wo))])
+        else:
+            y = d.op(op, [y])
+    d.mark_output(y)
+    name, _ = run_single_group(d, "sepconv", tail_pattern(P("conv2d", P("relu", W), W), tail))
+    assert name.startswith(f"relu_dwconv{k}"), name
+
+
 def test_sepconv_refuses_what_it_cannot_run():
     r = rng_for(22)
     d = wl.GraphDesc("not_sep")
