@@ -81,7 +81,8 @@ struct RfMfma<16> {
 // 2x2 phases.
 
 // GEO: 0 = 2-D convolution, 1 = transposed convolution, 2 = 3-D convolution with the depth taps
-// folded into the channel index, 3 = 3-D convolution with a single depth tap.  The depth code is
+// folded into the channel index, 3 = 3-D convolution with a single depth tap, 4 = 2-D 1x1 convolution
+// with a relu on its input (the operand values are clamped on their way into the MFMA).  The depth code is
 // compiled into GEO 2 and 3 only: a few more kernel arguments and one division are a measurable
 // part of a four-microsecond kernel.
 template <int TS, int TAPK, int WGK, int GEO>
@@ -95,7 +96,8 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
     extern __shared__ float red[];
     constexpr bool CONVT = GEO == 1;
     constexpr bool FOLD = GEO == 2;
-    constexpr bool DEPTH = GEO >= 2;
+    constexpr bool DEPTH = GEO == 2 || GEO == 3;
+    constexpr bool PRELU = GEO == 4;
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -199,7 +201,8 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
     } while (0)
 #define CLG_RF_MMA(set)                                                                       \
     do {                                                                                      \
-        _Pragma("unroll") for (int u = 0; u < 16; ++u) acc = MF::mma(a[set][u / 4][u % 4], b[set][u], acc); \
+        _Pragma("unroll") for (int u = 0; u < 16; ++u)                                        \
+            acc = MF::mma(a[set][u / 4][u % 4], PRELU ? fmaxf(b[set][u], 0.f) : b[set][u], acc); \
     } while (0)
         CLG_RF_LOAD(0, 0);
         int c = 0;

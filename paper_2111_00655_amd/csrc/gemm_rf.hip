@@ -30,6 +30,10 @@ int launch_rf_one(const GemmArgs &a, hipStream_t s) {
         if (a.rf_fold && !a.rf_convt) return launch_rf_one_t<TS, TAPK, WGK, 2>(a, s);
     }
     if (a.rf_convt || a.rf_fold) return (int)hipErrorInvalidValue;
+    if constexpr (TAPK == 1) {
+        if (a.rf_prelu && a.D <= 1) return launch_rf_one_t<TS, TAPK, WGK, 4>(a, s);
+    }
+    if (a.rf_prelu) return (int)hipErrorInvalidValue;        // only the 2-D 1x1 path clamps its input
     if constexpr (TAPK != 4) {
         if (a.D > 1) return launch_rf_one_t<TS, TAPK, WGK, 3>(a, s);
     }

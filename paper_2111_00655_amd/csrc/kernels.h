@@ -113,9 +113,9 @@ struct GemmArgs {
     // 3-D convolution on the register-fed kernels: one grid.y slice per (image, output depth);
     // the depth taps are folded into the channel index (channel' = c * KD + kd, Cin holds Cin * KD)
     int32_t D, KD, sd, pd, DO;             // input depth, depth taps, depth stride / padding, output depth (1, 1, 1, 0, 1 for 2-D)
+    int32_t rf_prelu;                      // 1: relu on the input of a 2-D 1x1 convolution
     int32_t rf_fold;                       // 1: KD > 1
     int32_t rf_cs;                         // elements between two input channels (D * H * W)
-    int32_t rf_pad3_;
     int64_t rf_img_stride;                 // elements between two images of x
     uint64_t rf_kd_magic;                  // floor(2^32 / KD) + 1
 };

@@ -353,6 +353,52 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
             c.bound = 1;
             c.name = "relu_dwconv" + std::to_string(dc.KH) + (epi.n ? "_epi" + std::to_string(epi.n) : std::string());
         } else {
+        // relu -> 1x1 convolution -> tail: the register-fed 1x1 kernel with the relu on its operand, if it takes the shape
+        bool on_rf = false;
+        if (t_pw == t_first && a.pro_relu && Gp == 1 && wps.ndim == 4 && wps.d[2] == 1 && wps.d[3] == 1 &&
+            pwn.attrs.pad[0] == 0 && pwn.attrs.pad[1] == 0 && wps.d[1] == a.C && g.nodes[wp].kind == NODE_CONST) {
+            Epilogue e2{};
+            int32_t nodes2[kMaxEpi];
+            for (auto &n2 : nodes2) n2 = -1;
+            bool ok2 = true;
+            for (int u = t_pw + 1; u < len && ok2; ++u) ok2 = add_step(cv, u, false, &e2, nodes2) == CLG_OK;
+            GemmArgs ga{};
+            ga.tile = TILE_R16;
+            ga.batch = 1;
+            ga.epi = e2;
+            ga.Nimg = a.N; ga.Cin = a.C; ga.H = a.H; ga.W = a.W;
+            ga.Cout = (int)wps.d[0]; ga.KH = ga.KW = 1; ga.sh = a.sh; ga.sw = a.sw; ga.ph = ga.pw = 0;
+            ga.HO = (int)pwn.shape.d[2]; ga.WO = (int)pwn.shape.d[3];
+            ga.c_numel = pwn.shape.numel();
+            ga.bias_on_row = 1;
+            ga.mode = GM_CONV;
+            ga.M = ga.Cout; ga.N = ga.Nimg * ga.HO * ga.WO; ga.K = ga.Cin;
+            ga.lda = ga.K;
+            ga.rf_groups = 1;
+            if (ok2 && (!e2.bias_c || (e2.bias_inner == (int64_t)ga.HO * ga.WO && e2.bias_c == ga.Cout)) &&
+                rf_resolve(&ga, 16, epi_fast_flags(e2), ctx.n_cus) && ga.rf_tapk == 1) {
+                ga.rf_prelu = 1;
+                c.gemm = ga;
+                for (int s2 = 0; s2 < e2.n; ++s2) {
+                    c.epi_nodes[s2] = nodes2[s2];
+                    use(nodes2[s2]);
+                }
+                epi = e2;
+                c.kind = CALL_GEMM;
+                c.gemm_swap = true;
+                c.a_node = xa;
+                c.b_node = wp;
+                use(xa);
+                use(wp);
+                c.pack_bytes = rf_pack_bytes(ga);
+                c.scratch_bytes = gemm_scratch_bytes(ga);
+                c.flops = 2.0 * (double)ga.M * ga.N * ga.K;
+                c.bound = 0;
+                c.name = "relu_conv_rf16_t1_w" + std::to_string(ga.rf_wgk);
+                on_rf = true;
+            }
+        }
+        if (!on_rf) {
         if (Gp != 1 || wps.d[2] != 1 || wps.d[3] != 1 || pwn.attrs.pad[0] != 0 || pwn.attrs.pad[1] != 0 ||
             wps.d[1] != a.C || g.nodes[wp].kind != NODE_CONST)
             return fail(CLG_NO_KERNEL, "sepconv ends in an ungrouped 1x1 convolution without padding and with constant weights");
@@ -378,6 +424,7 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
         c.bound = 0;
         c.name = std::string(a.pro_relu ? "relu_" : "") + (c.c_node >= 0 ? "sepconv" + std::to_string(a.KH) : std::string("pwconv")) +
                  "_w" + std::to_string(a.nwaves) + "m" + std::to_string(a.mt_per_wg) + (epi.n ? "_epi" + std::to_string(epi.n) : std::string());
+        }
         }
     } else if (is_contraction(k0)) {
         const int32_t xa = cv.arg(0, 0), wb = cv.arg(0, 1);
