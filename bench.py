@@ -35,7 +35,7 @@ VARIANTS = ("igemm", "igemm_s", "igemm_s8", "igemm_s16", "igemm_m", "igemm_l", "
 # the steps of the run).  Scale factors from the 256 MiB plain device copy of --calib-copy in the same runs:
 # WRITE_SIZE read 262144.0 KiB for it (factor 1.000), FETCH_SIZE 131083.5 KiB (factor 2.000).  The figures hold
 # for the kernel sources they were taken with; after any change to them `traffic` is reported as null.
-TRAFFIC = {"resnet50": {"sources": "d67029f8fea3912a", "fetch_bytes": 296.64e6, "write_bytes": 46.86e6}}
+TRAFFIC = {"resnet50": {"sources": "73eadad6ff06c17b", "fetch_bytes": 296.50e6, "write_bytes": 46.86e6}}
 
 
 def kernel_sources_fingerprint():
