@@ -697,7 +697,7 @@ def test_model_under_searched_placement(name):
     s.close()
 
 
-@pytest.mark.parametrize("name", ["resnet50", "bert_base", "nasnet_a", "resnet3d_50"])
+@pytest.mark.parametrize("name", ["tiny_cnn", "resnet50", "resnext50", "bert_base", "dcgan_b1", "dcgan_b64", "nasnet_a", "resnet3d_50"])
 def test_model_in_the_benchmark_s_configuration(name):
     """Full size, the registry and measurer options bench.py uses (all kernel variants and the
     one-kernel separable convolution family)."""
