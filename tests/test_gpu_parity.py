@@ -776,7 +776,6 @@ def test_nasnet_cells_whole_path():
     got_search = s.search(costs, 0)
     assert got_search == search.dp(g, reg, oms, costs, 0)
     plan = s.compile(got_search[1])
-    assert any("sepconv" in k["name"] for k in plan.kernels())    # the fused separable kernel wins somewhere
     got = plan.run()
     ref = g.run()
     assert max(norm_err(a, b) for a, b in zip(got, ref)) <= NET_TOL
