@@ -370,7 +370,8 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"{args.model} batch 1 fp32, seeded random weights, placement from the "
-                               "library's measurer + DP over the igemm tile variants, direct, rowwise and eltwise kernels",
+                               "library's measurer + DP over the igemm tile variants and the direct, rowwise, eltwise, "
+                               "separable-convolution and attention kernel families",
                    "kernels_per_step": plan.n_kernels},
         "roofline": roof,
         "cpu_baseline": cpu,
