@@ -198,7 +198,10 @@ int32_t clg_version(void);
 /* ---- computation graph G (Sec. 4.1: a DAG of tensor operators) ------------ */
 /* Nodes are added in topological order; a node's id is its insertion index
  * (returned in *node).  Shapes are inferred when an operator is added;
- * SHAPE_MISMATCH is returned, and the node not added, if operands do not fit. */
+ * SHAPE_MISMATCH is returned, and the node not added, if operands do not fit.
+ * No tensor may hold more than 2^29 elements (2 GiB of fp32): the kernels
+ * index with 32-bit element and byte offsets.  A larger input or constant is
+ * INVALID_ARG, a larger operator result SHAPE_MISMATCH. */
 int32_t clg_graph_create(clg_ctx *ctx, clg_graph **out);
 int32_t clg_graph_destroy(clg_graph *g);
 /* A run-time input.  dims: host array of ndim entries (1..CLG_MAX_DIMS). */

@@ -87,7 +87,7 @@ static int32_t add_leaf(clg_graph *g, int32_t kind, int32_t dtype, int32_t ndim,
         if (dims[i] < 1) return fail(CLG_INVALID_ARG, "dims[%d] = %lld", i, (long long)dims[i]);
         nd.shape.d[i] = dims[i];
     }
-    if (nd.shape.numel() > ((int64_t)1 << 31)) return fail(CLG_INVALID_ARG, "tensor has more than 2^31 elements");
+    if (nd.shape.numel() > kMaxTensorElems) return fail(CLG_INVALID_ARG, "tensor has more than 2^29 elements");
     nd.dev_ptr = ptr;
     if (kind == NODE_INPUT) nd.input_index = g->g.n_inputs++;
     g->g.nodes.push_back(nd);

@@ -21,12 +21,20 @@ void set_error(const char *msg);
 // ---- graph -----------------------------------------------------------------------
 enum NodeKind : int32_t { NODE_INPUT = -3, NODE_CONST = -2 };   // else clg_op_kind
 
+// Largest tensor the library takes: the kernels index with 32-bit element and byte offsets.
+constexpr int64_t kMaxTensorElems = (int64_t)1 << 29;
+
 struct Shape {
     int32_t ndim = 0;
     int64_t d[CLG_MAX_DIMS] = {0, 0, 0, 0, 0, 0};
+    // Element count; saturates just above kMaxTensorElems so that absurd extents cannot wrap around.
     int64_t numel() const {
         int64_t n = 1;
-        for (int i = 0; i < ndim; ++i) n *= d[i];
+        for (int i = 0; i < ndim; ++i) {
+            if (d[i] <= 0) return 0;
+            if (d[i] > kMaxTensorElems || n * d[i] > kMaxTensorElems) return kMaxTensorElems + 1;
+            n *= d[i];
+        }
         return n;
     }
     bool operator==(const Shape &o) const {

@@ -234,8 +234,8 @@ int32_t infer_shape(const Graph &g, int32_t kind, const std::vector<int32_t> &in
     default:
         return fail(CLG_INVALID_ARG, "unknown op kind %d", kind);
     }
-    if (y.numel() <= 0 || y.numel() > (int64_t)1 << 31)
-        return bad("tensor is empty or has more than 2^31 elements");
+    if (y.numel() <= 0 || y.numel() > kMaxTensorElems)
+        return bad("tensor is empty or has more than 2^29 elements");
     *out = y;
     return CLG_OK;
 }

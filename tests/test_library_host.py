@@ -203,6 +203,16 @@ def test_graph_building_errors():
     with pytest.raises(clg.ClgError) as e:
         clg.clg_graph_input(g, B.F32, (0, 3))
     assert e.value.status == "INVALID_ARG"
+    # the size limit: 2^29 elements fit, one more row does not, and absurd extents do not wrap around
+    big = clg.clg_graph_input(g, B.F32, (1 << 14, 1 << 15))
+    assert clg.clg_graph_node_shape(g, big)[1] == (1 << 14, 1 << 15)
+    for dims in ((1 << 14, (1 << 15) + 1), (1 << 62, 4), (1 << 40, 1 << 40, 1 << 40)):
+        with pytest.raises(clg.ClgError) as e:
+            clg.clg_graph_input(g, B.F32, dims)
+        assert e.value.status == "INVALID_ARG"
+    with pytest.raises(clg.ClgError) as e:
+        clg.clg_graph_op(g, "concat", [big, big], B.make_attrs(axis=0))
+    assert e.value.status == "SHAPE_MISMATCH"
     r = clg.clg_graph_op(g, "relu", [x])
     assert clg.clg_graph_node_shape(g, r) == (B.F32, (1, 3, 8, 8))
     t = clg.clg_graph_op(g, "transpose", [r], B.make_attrs(dims=(0, 2, 3, 1)))
@@ -211,7 +221,7 @@ def test_graph_building_errors():
         clg.clg_graph_op(g, "transpose", [r], B.make_attrs(dims=(0, 2, 2, 1)))
     with pytest.raises(clg.ClgError):
         clg.clg_graph_op(g, "reshape", [r], B.make_attrs(dims=(5, 5)))
-    assert clg.clg_graph_num_nodes(g) == 4
+    assert clg.clg_graph_num_nodes(g) == 5
     clg.clg_graph_destroy(g)
     clg.clg_destroy(ctx)
 
