@@ -77,6 +77,52 @@ def optimise(desc, reg, opts, cost_log="", rules=()):
     return s, plan, costs, ids, timing
 
 
+def large_shapes(path):
+    """Single operators large enough to be bound by the matrix cores, priced under every MFMA variant backend by the
+    library's measurer (launch-inclusive time of back-to-back launches).  Returns {case: {backend: TFLOP/s}}."""
+    import numpy as np
+    import workloads as wl
+    import paper_2111_00655_amd as clg
+    from paper_2111_00655_amd import binding as B
+    reg = wl.default_registry(VARIANTS)
+    opts = B.ProfileOpts(warmup=5, batches=5, min_batch_us=200, max_launches=200)
+    r = np.random.default_rng(0)
+    cases = []
+    for (m, n, k) in ((4096, 4096, 4096), (2048, 2048, 2048), (8192, 1024, 1024)):
+        d = wl.GraphDesc("large_dense")
+        x = d.input(r.standard_normal((m, k), dtype=np.float32))
+        w = d.const(r.standard_normal((n, k), dtype=np.float32))
+        d.mark_output(d.op("dense", [x, w]))
+        cases.append((f"dense {m}x{k} . {n}x{k}^T", d, 2.0 * m * n * k))
+    for (b, c, co, h) in ((32, 256, 256, 56), (32, 512, 512, 28)):
+        d = wl.GraphDesc("large_conv")
+        x = d.input(r.standard_normal((b, c, h, h), dtype=np.float32))
+        w = d.const(r.standard_normal((co, c, 3, 3), dtype=np.float32))
+        d.mark_output(d.op("conv2d", [x, w], stride=(1, 1), pad=(1, 1), groups=1))
+        cases.append((f"conv2d 3x3 batch {b} {c}->{co} {h}x{h}", d, 2.0 * b * co * h * h * c * 9))
+    out = {}
+    lines = ["Compute-bound single operators, fp32, one MI355X: launch-inclusive time per launch from the library's measurer",
+             f"and the operator's own flops over it; fp32 MFMA peak {PEAK_MFMA_F32_TFLOPS} TFLOP/s.", "",
+             f"{'operator':40s} {'backend':14s} {'us':>9s} {'TFLOP/s':>8s} {'of peak':>8s}"]
+    for label, d, flops in cases:
+        s = clg.Session(d, reg, device=0)
+        ms = s.match()
+        costs = s.profile(opts)
+        out[label] = {}
+        for i, m in enumerate(ms):
+            backend = reg[m.pattern][0]
+            if backend == "direct" or costs[i] >= B.COST_INF:
+                continue
+            tf = flops / costs[i] / 1e3
+            out[label][backend] = round(tf, 1)
+            lines.append(f"{label:40s} {backend:14s} {costs[i] / 1e3:9.1f} {tf:8.1f} {tf / PEAK_MFMA_F32_TFLOPS:8.3f}")
+        s.close()
+    os.makedirs(os.path.dirname(os.path.abspath(path)), exist_ok=True)
+    with open(path, "w") as f:
+        f.write("\n".join(lines) + "\n")
+    return out
+
+
 def time_steps(plan, steps, warmup):
     import torch
     for _ in range(warmup):
@@ -217,6 +263,16 @@ def cpu_baseline(desc):
                 single_thread_ms=round(dt1 * 1e3, 2))
 
 
+def oracle_us_per_group(desc, groups):
+    """The oracle's time for each fused group (all host cores): every operator timed while the oracle evaluates the
+    graph once (after one untimed pass), summed over the operators of the group."""
+    from oracle.graph import Graph
+    g = Graph(desc)
+    g.run()
+    _, secs = g.run_timed()
+    return [sum(secs[v] for v in grp) * 1e6 for grp in groups]
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -237,6 +293,10 @@ def main():
                     help="also run the graph-level evolutionary search (paper Sec. 4.2) on these workloads' op-level plans")
     ap.add_argument("--rules", action="store_true",
                     help="build the registry with the pattern generator from pattern rules instead of the listed patterns")
+    ap.add_argument("--large-shapes", default="", metavar="FILE",
+                    help="also price a few compute-bound single operators (large dense, batch-32 3x3 convolutions) under every "
+                         "MFMA kernel variant with the library's measurer and write TFLOP/s per variant to FILE: what the "
+                         "kernels reach where launch and memory latency do not bound them")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MIB",
                     help="also run three plain device copies of MIB MiB (read MIB, write MIB): the known-size kernel "
                          "against which hardware byte counters of a profiled run are scaled")
@@ -303,6 +363,10 @@ def main():
             p2.destroy()
             s2.close()
 
+    large = None
+    if args.large_shapes:
+        large = large_shapes(args.large_shapes)
+
     graph_level = None
     if args.graph_level:
         import numpy as np
@@ -334,19 +398,29 @@ def main():
 
     if args.table:
         scale = ms_per_step * 1e6 / sum(r["ns"] for r in rows)
+        cpu_us = None
+        if not args.no_cpu:
+            cpu_us = oracle_us_per_group(desc, [list(s.matches[r["match"]].nodes[:s.matches[r["match"]].n_nodes]) for r in rows])
         lines = [f"{args.model} batch 1 fp32, one MI355X: the {len(rows)} fused kernels of one step in execution order.",
                  f"Durations: HIP event pair around every launch, scaled by {scale:.3f} so that they add up to the step time "
                  f"measured without the events ({ms_per_step * 1e3:.1f} us).",
                  f"Peaks: fp32 MFMA {PEAK_MFMA_F32_TFLOPS} TFLOP/s, HBM {PEAK_HBM_GBPS} GB/s.  flops / bytes are the operator's own "
                  "(no padding or tile waste; every operand and the output once).",
+                 ] + (["oracle us: the CPU oracle's time for the same fused group (sum over its operators, all host cores)."]
+                      if cpu_us else []) + [
                  "",
-                 f"{'#':>3s} {'kernel':34s} {'bound':5s} {'us':>7s} {'MFLOP':>9s} {'KB':>9s} {'TFLOP/s':>8s} {'GB/s':>8s} {'of peak':>8s}"]
+                 f"{'#':>3s} {'kernel':34s} {'bound':5s} {'us':>7s} {'MFLOP':>9s} {'KB':>9s} {'TFLOP/s':>8s} {'GB/s':>8s} {'of peak':>8s}"
+                 + (f" {'oracle us':>10s}" if cpu_us else "")]
         for i, r in enumerate(rows):
             t = r["ns"] * scale
             tf, gb = r["flops"] / t / 1e3, r["bytes"] / t
             frac = tf / PEAK_MFMA_F32_TFLOPS if r["bound"] == "mfma" else gb / PEAK_HBM_GBPS
             lines.append(f"{i:3d} {r['name'][:34]:34s} {r['bound']:5s} {t / 1e3:7.2f} {r['flops'] / 1e6:9.1f} "
-                         f"{r['bytes'] / 1e3:9.1f} {tf:8.2f} {gb:8.1f} {frac:8.4f}")
+                         f"{r['bytes'] / 1e3:9.1f} {tf:8.2f} {gb:8.1f} {frac:8.4f}"
+                         + (f" {cpu_us[i]:10.0f}" if cpu_us else ""))
+        if cpu_us:
+            lines.append(f"{'':3s} {'sum':34s} {'':5s} {sum(r['ns'] for r in rows) * scale / 1e3:7.2f} {'':9s} {'':9s} {'':8s} {'':8s} {'':8s} "
+                         f"{sum(cpu_us):10.0f}")
         os.makedirs(os.path.dirname(os.path.abspath(args.table)), exist_ok=True)
         with open(args.table, "w") as f:
             f.write("\n".join(lines) + "\n")
@@ -380,6 +454,7 @@ def main():
         "cold_cache_ms": round(cold_ms, 4),
         "ablation_ms": abl,
         "resnext50_batch_sweep": sweep,
+        "large_shapes_tflops": large,
         "graph_level_search": graph_level,
         "empty_launch_ns": int(empty_ns),
         "optimise": {k: (round(v, 4) if isinstance(v, float) else v) for k, v in timing.items()},
