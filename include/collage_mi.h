@@ -446,7 +446,14 @@ int32_t clg_search_stats(const clg_graph *g, int64_t stats[5]);
  * device memory for it (OUT_OF_MEMORY on failure), fills it on the null
  * stream and waits for that; the constants' device pointers must therefore
  * be valid at this call.  clg_plan_destroy frees those copies; the plan must
- * not be destroyed while one of its executions is still running. */
+ * not be destroyed while one of its executions is still running.
+ * A concat whose operands are contiguous pieces of its result (all extents
+ * before the axis are 1) costs nothing at run time when every operand is the
+ * result of a kernel of this plan, is not a graph output, belongs to no other
+ * such concat and starts on a 16-byte boundary: the producers write into the
+ * result directly and the concat stays in the kernel list as an entry that
+ * launches nothing (its name ends in "_alias", its bytes are 0).  Output
+ * buffers must therefore be 16-byte aligned like every other tensor. */
 int32_t clg_compile(clg_ctx *ctx, clg_graph *g, const int32_t *matches,
                     size_t n, clg_plan **out);
 int32_t clg_plan_destroy(clg_plan *plan);
@@ -481,7 +488,8 @@ int32_t clg_execute(clg_plan *plan, const void *const *inputs,
                     void *stream);
 /* As clg_execute, with a HIP event pair around every kernel on `stream`;
  * synchronises, then writes each kernel's duration in nanoseconds to
- * kernel_ns (host array, one entry per plan kernel). */
+ * kernel_ns (host array, one entry per plan kernel; 0 for an entry that
+ * launches nothing). */
 int32_t clg_execute_timed(clg_plan *plan, const void *const *inputs,
                           void *const *outputs, void *workspace,
                           size_t ws_bytes, void *stream, int64_t *kernel_ns,

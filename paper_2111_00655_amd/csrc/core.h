@@ -169,7 +169,9 @@ struct Plan {
     Graph *graph = nullptr;
     std::vector<KernelCall> calls;
     std::vector<int64_t> value_offset;     // node -> workspace byte offset, -1 none
-    std::vector<int32_t> value_output;     // node -> index in outputs[], -1 none
+    std::vector<int32_t> value_output;     // node -> index in outputs[] of the buffer it lives in, -1 none
+    std::vector<int64_t> value_delta;      // node -> byte offset inside that output buffer (a piece of a concatenation)
+    std::vector<char> elided;              // call -> launches nothing (a concatenation whose operands are written in place)
     std::vector<int64_t> scratch_offset;   // call -> workspace byte offset of its scratch
     std::vector<void *> packed;            // call -> re-packed weights (device memory owned by the plan) or null
     size_t workspace_bytes = 0;

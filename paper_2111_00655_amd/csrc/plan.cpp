@@ -97,31 +97,78 @@ int32_t compile_plan(Context &ctx, Graph &g, const int32_t *ids, size_t n, Plan 
         produced_at[plan->calls[i].out_node] = (int32_t)i;
     }
 
-    // workspace: one buffer per group output that is not a graph output, reused
-    // once its last reader has run; per-call scratch lives for its call only
+    // Concatenation without a copy (Sec. 5.1 hands tensors over by pointer): when the extents before the
+    // axis are all 1, every operand is one contiguous piece of the result.  If each operand is produced by a
+    // kernel of this plan, has no buffer of its own to go to (not a graph output), is not already part of
+    // another concatenation and starts on a 16-byte boundary, its producer writes it straight into its place
+    // in the result and the concatenation launches nothing.  Such results nest (root = outermost one).
     plan->value_offset.assign(n_nodes, -1);
     plan->value_output.assign(n_nodes, -1);
     plan->scratch_offset.assign(nc, -1);
+    plan->elided.assign(nc, 0);
+    std::vector<int32_t> alias_of(n_nodes, -1);
+    std::vector<int64_t> alias_delta(n_nodes, 0);
     for (size_t k = 0; k < g.outputs.size(); ++k) plan->value_output[g.outputs[k]] = (int32_t)k;
-    std::vector<int32_t> last_use(n_nodes, -1);
-    for (size_t i = 0; i < nc; ++i)
-        for (int32_t v : operands_of(plan->calls[i])) last_use[v] = (int32_t)i;
+    for (size_t i = 0; i < nc; ++i) {
+        const KernelCall &c = plan->calls[i];
+        if (c.kind != CALL_CONCAT || c.cat.outer != 1) continue;
+        bool ok = true;
+        int64_t off = 0;
+        for (int k = 0; k < c.cat.n && ok; ++k) {
+            const int32_t v = c.epi_nodes[k];
+            ok = g.nodes[v].is_op() && plan->value_output[v] < 0 && alias_of[v] < 0 && off % 16 == 0;
+            for (int j = 0; j < k; ++j) ok = ok && c.epi_nodes[j] != v;
+            off += 4 * c.cat.chunk[k];
+        }
+        if (!ok) continue;
+        off = 0;
+        for (int k = 0; k < c.cat.n; ++k) {
+            alias_of[c.epi_nodes[k]] = c.out_node;
+            alias_delta[c.epi_nodes[k]] = off;
+            off += 4 * c.cat.chunk[k];
+        }
+        plan->elided[i] = 1;
+        plan->calls[i].name += "_alias";
+        plan->calls[i].bytes = 0;
+    }
+    std::vector<int32_t> root(n_nodes);
+    std::vector<int64_t> delta(n_nodes, 0);                  // byte offset of a value inside its root's buffer
+    for (int v = n_nodes - 1; v >= 0; --v) {                 // a result comes after its operands: roots resolve first
+        root[v] = alias_of[v] < 0 ? v : root[alias_of[v]];
+        delta[v] = alias_of[v] < 0 ? 0 : delta[alias_of[v]] + alias_delta[v];
+    }
+
+    // workspace: one buffer per root value that is not a graph output, reused once the last reader of the
+    // root or of any value inside it has run; per-call scratch lives for its call only
+    plan->value_delta.assign(n_nodes, 0);
+    std::vector<int32_t> release_at(n_nodes, -1);            // root -> call after which its buffer is free
+    for (size_t i = 0; i < nc; ++i) {
+        const int32_t r = root[plan->calls[i].out_node];
+        release_at[r] = std::max(release_at[r], (int32_t)i);
+        for (int32_t v : operands_of(plan->calls[i])) release_at[root[v]] = std::max(release_at[root[v]], (int32_t)i);
+    }
+    std::vector<std::vector<int32_t>> releases(nc);
+    for (int v = 0; v < n_nodes; ++v)
+        if (root[v] == v && release_at[v] >= 0 && g.nodes[v].is_op() && plan->value_output[v] < 0)
+            releases[(size_t)release_at[v]].push_back(v);
     Arena arena;
     for (size_t i = 0; i < nc; ++i) {
         const KernelCall &c = plan->calls[i];
-        if (plan->value_output[c.out_node] < 0)
-            plan->value_offset[c.out_node] = arena.alloc(4 * g.nodes[c.out_node].shape.numel());
+        const int32_t v = c.out_node, r = root[v];
+        if (plan->value_output[r] >= 0) {
+            if (v != r) {
+                plan->value_output[v] = plan->value_output[r];
+                plan->value_delta[v] = delta[v];
+            }
+        } else {
+            if (plan->value_offset[r] < 0) plan->value_offset[r] = arena.alloc(4 * g.nodes[r].shape.numel());
+            plan->value_offset[v] = plan->value_offset[r] + delta[v];
+        }
         if (c.scratch_bytes) {
             plan->scratch_offset[i] = arena.alloc((int64_t)c.scratch_bytes);
             arena.release(plan->scratch_offset[i]);
         }
-        for (int32_t v : operands_of(c))
-            if (last_use[v] == (int32_t)i && plan->value_offset[v] >= 0) {
-                arena.release(plan->value_offset[v]);
-                last_use[v] = -2;            // released once, even if read twice by this call
-            }
-        if (last_use[c.out_node] < 0 && plan->value_offset[c.out_node] >= 0)
-            arena.release(plan->value_offset[c.out_node]);     // value nobody reads
+        for (int32_t r2 : releases[i]) arena.release(plan->value_offset[r2]);
     }
     plan->workspace_bytes = (size_t)arena.peak;
     schedule_lanes(plan);
@@ -416,7 +463,7 @@ int32_t execute_plan(Plan &p, const void *const *inputs, void *const *outputs, v
         const Node &nd = g.nodes[v];
         if (nd.kind == NODE_CONST) return nd.dev_ptr;
         if (nd.kind == NODE_INPUT) return inputs[nd.input_index];
-        if (p.value_output[v] >= 0) return outputs[p.value_output[v]];
+        if (p.value_output[v] >= 0) return (const char *)outputs[p.value_output[v]] + p.value_delta[v];
         return (const char *)workspace + p.value_offset[v];
     };
     std::vector<hipEvent_t> ev;
@@ -470,10 +517,11 @@ int32_t execute_plan(Plan &p, const void *const *inputs, void *const *outputs, v
                 if (hipStreamWaitEvent((hipStream_t)st, (hipEvent_t)p.events[w], 0) != hipSuccess)
                     rc = fail(CLG_HIP_ERROR, "hipStreamWaitEvent failed");
         if (rc != CLG_OK) break;
-        if (kernel_ns) (void)hipEventRecord(ev[2 * i], (hipStream_t)stream);
-        rc = launch_call(c, ptr_of(c.a_node), ptr_of(c.b_node), ptr_of(c.c_node),
-                         const_cast<void *>(ptr_of(c.out_node)), epi, scratch, p.packed[i], st);
-        if (kernel_ns) (void)hipEventRecord(ev[2 * i + 1], (hipStream_t)stream);
+        if (kernel_ns && !p.elided[i]) (void)hipEventRecord(ev[2 * i], (hipStream_t)stream);
+        if (!p.elided[i])                                // an aliased concatenation: its operands are already in place
+            rc = launch_call(c, ptr_of(c.a_node), ptr_of(c.b_node), ptr_of(c.c_node),
+                             const_cast<void *>(ptr_of(c.out_node)), epi, scratch, p.packed[i], st);
+        if (kernel_ns && !p.elided[i]) (void)hipEventRecord(ev[2 * i + 1], (hipStream_t)stream);
         if (lanes && p.signals[i] && rc == CLG_OK && hipEventRecord((hipEvent_t)p.events[i], (hipStream_t)st) != hipSuccess)
             rc = fail(CLG_HIP_ERROR, "hipEventRecord failed");
     }
@@ -491,6 +539,10 @@ int32_t execute_plan(Plan &p, const void *const *inputs, void *const *outputs, v
             rc = fail(CLG_HIP_ERROR, "stream synchronisation failed: %s", hipGetErrorString(hipGetLastError()));
         for (size_t i = 0; i < p.calls.size() && rc == CLG_OK; ++i) {
             float ms = 0.f;
+            if (p.elided[i]) {
+                kernel_ns[i] = 0;
+                continue;
+            }
             if (hipEventElapsedTime(&ms, ev[2 * i], ev[2 * i + 1]) != hipSuccess)
                 rc = fail(CLG_HIP_ERROR, "hipEventElapsedTime failed");
             kernel_ns[i] = (int64_t)((double)ms * 1.0e6 + 0.5);

@@ -113,6 +113,11 @@ class Plan:
     def kernels(self):
         return [B.clg_plan_kernel_info(self.h, i) for i in range(self.n_kernels)]
 
+    @property
+    def n_launches(self):
+        """Kernels one execution launches: the kernel list without the concatenations planned as aliases."""
+        return sum(1 for k in self.kernels() if not k["name"].endswith("_alias"))
+
     def set_lanes(self, lanes):
         B.clg_plan_set_lanes(self.h, lanes)
         return self

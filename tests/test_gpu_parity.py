@@ -928,3 +928,105 @@ def test_lanes_give_the_same_result_as_one_stream(name):
     assert max(norm_err(a, b) for a, b in zip(single, ref)) <= NET_TOL
     plan.destroy()
     s.close()
+
+
+# ---------------------------------------------------------- concatenation planned as an alias
+def _concat_graph(case):
+    """Small graphs around one concat; returns (desc, expected kernel-name suffix of the concat)."""
+    r = rng_for(61)
+    d = wl.GraphDesc("concat_alias_" + case)
+    x = d.input(f32(r, 1, 8, 6, 6))
+
+    def branch(cout, src=None, k=1):
+        w = d.const(f32(r, cout, 8, k, k) * 0.3)
+        b = d.const(f32(r, cout))
+        y = d.op("conv2d", [x if src is None else src, w], stride=(1, 1), pad=(k // 2, k // 2), groups=1)
+        return d.op("relu", [d.op("bias_add", [y, b])])
+
+    if case == "three_branches":                 # every operand produced by a kernel: no copy
+        c = d.op("concat", [branch(4), branch(8, k=3), branch(12)], axis=1)
+        d.mark_output(d.op("relu", [c]))
+        return d, "_alias"
+    if case == "result_is_an_output":            # the pieces go straight into the caller's buffer
+        a = branch(4)
+        c = d.op("concat", [a, branch(8), d.op("tanh", [a])], axis=1)
+        d.mark_output(c)
+        return d, "_alias"
+    if case == "nested":                         # a concat inside a concat, and a piece read again later
+        a, b = branch(4), branch(8)
+        inner = d.op("concat", [a, b], axis=1)
+        outer = d.op("concat", [branch(4), inner, d.op("relu", [inner])], axis=1)
+        d.mark_output(d.op("add", [d.op("relu", [outer]), d.op("concat", [b, b, d.op("tanh", [b]), a], axis=1)]))
+        return d, "nested"
+    if case == "graph_input_operand":            # the caller's memory cannot move: a real copy
+        c = d.op("concat", [branch(4), x], axis=1)
+        d.mark_output(d.op("relu", [c]))
+        return d, ""
+    if case == "same_operand_twice":
+        a = branch(4)
+        c = d.op("concat", [a, a], axis=1)
+        d.mark_output(d.op("relu", [c]))
+        return d, ""
+    if case == "operand_is_an_output":
+        a = branch(4)
+        d.mark_output(a)
+        d.mark_output(d.op("relu", [d.op("concat", [a, branch(4)], axis=1)]))
+        return d, ""
+    if case == "operand_in_two_concats":         # the first concat gets it, the second copies
+        a, b = branch(4), branch(8)
+        c1 = d.op("concat", [a, b], axis=1)
+        c2 = d.op("concat", [b, a], axis=1)
+        d.mark_output(d.op("add", [d.op("relu", [c1]), d.op("relu", [c2])]))
+        return d, "mixed"
+    if case == "pieces_not_contiguous":          # batch 2: channel slices of different images interleave
+        d = wl.GraphDesc("concat_alias_" + case)
+        x2 = d.input(f32(r, 2, 8, 6, 6))
+        ys = []
+        for cout in (4, 8):
+            w = d.const(f32(r, cout, 8, 1, 1) * 0.3)
+            ys.append(d.op("relu", [d.op("conv2d", [x2, w], stride=(1, 1), pad=(0, 0), groups=1)]))
+        d.mark_output(d.op("relu", [d.op("concat", ys, axis=1)]))
+        return d, ""
+    if case == "misaligned_piece":               # 3 x 3 x 3 floats: the second piece would start at byte 108
+        d = wl.GraphDesc("concat_alias_" + case)
+        x3 = d.input(f32(r, 1, 8, 3, 3))
+        ys = []
+        for cout in (3, 5):
+            w = d.const(f32(r, cout, 8, 1, 1) * 0.3)
+            ys.append(d.op("relu", [d.op("conv2d", [x3, w], stride=(1, 1), pad=(0, 0), groups=1)]))
+        d.mark_output(d.op("relu", [d.op("concat", ys, axis=1)]))
+        return d, ""
+    raise KeyError(case)
+
+
+CONCAT_ALIAS_CASES = ["three_branches", "result_is_an_output", "nested", "graph_input_operand", "same_operand_twice",
+                      "operand_is_an_output", "operand_in_two_concats", "pieces_not_contiguous", "misaligned_piece"]
+
+
+@pytest.mark.parametrize("case", CONCAT_ALIAS_CASES)
+def test_concat_planned_as_an_alias(case):
+    """A concat whose operands can be produced in place launches nothing; one that cannot still copies.  Either
+    way the graph's outputs equal the oracle's, on two executions in a row."""
+    desc, suffix = _concat_graph(case)
+    reg = wl.default_registry(("igemm", "igemm_r16"))
+    s = clg.Session(desc, reg, device=0)
+    ms = s.match()
+    costs = [1000 * m.n_nodes for m in ms]              # any cost table: operator by operator is the cheapest cover
+    _, ids = s.search(costs, 0)
+    plan = s.compile(ids)
+    names = [k["name"] for k in plan.kernels() if k["name"].startswith("concat")]
+    if suffix == "mixed":
+        assert sorted(n.endswith("_alias") for n in names) == [False, True], names
+    elif suffix == "nested":                            # inner and outer are aliases, the one that repeats b copies
+        assert sorted(names) == ["concat2_alias", "concat3_alias", "concat4"], names
+    else:
+        assert names and all(n.endswith("_alias") == (suffix == "_alias") for n in names), names
+    assert plan.n_launches == plan.n_kernels - sum(n.endswith("_alias") for n in names)
+    ref = Graph(desc).run()
+    got = plan.run()
+    again = plan.run()
+    plan.destroy()
+    s.close()
+    for a, b, c in zip(got, ref, again):
+        assert norm_err(a, b) <= OP_TOL, case
+        assert np.array_equal(a, c)

@@ -300,3 +300,25 @@ def test_match_keys_identify_shape_and_fused_kind():
         assert k.split("|")[0] == reg[ms[ids[0]].pattern][0]
     assert any(len(v) > 1 for v in keys.values())      # repeated blocks share entries
     s.close()
+
+
+def test_concat_of_kernel_results_is_planned_without_a_copy():
+    """Host-only: the plan lists an aliasable concat as an entry that launches nothing and keeps one buffer for
+    the result and its pieces; a concat with a graph input among its operands stays a copy."""
+    r = np.random.default_rng(3)
+    for with_input in (False, True):
+        d = wl.GraphDesc("cat")
+        x = d.input(r.standard_normal((1, 8, 4, 4)).astype(np.float32))
+        parts = [d.op("relu", [x]), d.op("tanh", [x])] + ([x] if with_input else [d.op("gelu", [x])])
+        d.mark_output(d.op("relu", [d.op("concat", parts, axis=1)]))
+        s = clg.Session(d, wl.default_registry(), device=None)
+        ms = s.match()
+        _, ids = s.search([1000 * m.n_nodes for m in ms], 0)
+        plan = s.compile(ids)
+        names = [k["name"] for k in plan.kernels()]
+        assert ("concat3" if with_input else "concat3_alias") in names, names
+        assert plan.n_launches == plan.n_kernels - (0 if with_input else 1)
+        ws = B.clg_plan_workspace_bytes(plan.h)
+        # aliased: the three pieces live inside the result's 3 x 512 bytes; copied: two pieces + the result
+        assert ws == (1536 if not with_input else 1024 + 1536), ws
+        s.close()
