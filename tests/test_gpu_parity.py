@@ -930,6 +930,30 @@ def test_lanes_give_the_same_result_as_one_stream(name):
     s.close()
 
 
+def test_lanes_with_concats_planned_as_aliases():
+    """The lane scheduler on a plan whose concats launch nothing (reduced NasNet-A: many parallel branches
+    writing pieces of one buffer): same bits as on one stream."""
+    desc = wl.nasnet_a(0, image=32, stem=8, filters=8, cells=1, classes=10)
+    reg = wl.default_registry(("igemm_r16",), sepconv=True)
+    s = clg.Session(desc, reg, device=0)
+    s.match()
+    costs = s.profile(B.ProfileOpts(warmup=2, batches=2, min_batch_us=30, max_launches=30))
+    _, ids = s.search(costs, 0)
+    plan = s.compile(ids).bind()
+    assert any(k["name"].endswith("_alias") for k in plan.kernels())
+    single = plan.run()
+    plan.set_lanes(4)
+    assert plan.n_lanes > 1
+    multi = [plan.run() for _ in range(3)]
+    plan.set_handover([i % 2 for i in range(plan.n_kernels)], lanes=3)
+    mixed = plan.run()
+    for outs in multi + [mixed]:
+        assert all(np.array_equal(a, b) for a, b in zip(outs, single))
+    assert max(norm_err(a, b) for a, b in zip(single, Graph(desc).run())) <= NET_TOL
+    plan.destroy()
+    s.close()
+
+
 # ---------------------------------------------------------- concatenation planned as an alias
 def _concat_graph(case):
     """Small graphs around one concat; returns (desc, expected kernel-name suffix of the concat)."""
