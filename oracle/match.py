@@ -10,8 +10,11 @@ paper leaves open, fixed here:
  * v_s is the first node of g in the total order (depth, node id); the pattern
    text itself is sink-rooted as in the paper's listing.
  * A match is legal as one kernel only if every non-sink node of g has all of
-   its consumers inside g and is not a graph output (single exit), and the
-   pattern's operator nodes bind distinct graph nodes.
+   its consumers inside g and is not a graph output (single exit), the
+   pattern's operator nodes bind distinct graph nodes, and no wildcard is bound
+   to a non-sink operator of g itself: a wildcard is an operand that comes from
+   outside the kernel, while a non-sink value of g exists only inside it (the
+   subgraph is lowered to one kernel, Sec. 4.2) and no kernel ever writes it.
  * `add` is commutative: its operands are tried as written, then swapped.
  * At most one match is kept per (v_s, pattern): the first found when sinks are
    scanned in node order and operand orders in the order above.
@@ -61,9 +64,10 @@ def _attr_value(graph, nid, name):
 
 def _assignments(graph, pat, nid):
     """All ways to match pattern `pat` with its root bound to graph value
-    `nid`; each is a list of bound graph nodes in pattern post-order."""
+    `nid`; each is a pair (graph nodes bound to the pattern's operators in
+    pattern post-order, graph values bound to its wildcards)."""
     if pat == WILD:
-        yield []
+        yield [], [nid]
         return
     op, args, constraints = pat
     nd = graph.nodes[nid]
@@ -79,22 +83,24 @@ def _assignments(graph, pat, nid):
 
     def rec(k, operands):
         if k == len(args):
-            yield []
+            yield [], []
             return
-        for head in _assignments(graph, args[k], operands[k]):
-            for tail in rec(k + 1, operands):
-                yield head + tail
+        for head, hw in _assignments(graph, args[k], operands[k]):
+            for tail, tw in rec(k + 1, operands):
+                yield head + tail, hw + tw
 
     for operands in orders:
-        for sub in rec(0, operands):
-            yield sub + [nid]
+        for sub, wild in rec(0, operands):
+            yield sub + [nid], wild
 
 
-def _legal(graph, bound):
+def _legal(graph, bound, wild):
     if len(set(bound)) != len(bound):
         return False
     sink = bound[-1]
     inside = set(bound)
+    if any(v in inside and v != sink for v in wild):
+        return False
     outs = set(graph.outputs)
     for v in bound:
         if v == sink:
@@ -110,8 +116,8 @@ def enumerate_matches(graph, registry):
     found = {}
     for pi, (backend, pat) in enumerate(registry):
         for sink in graph.op_ids:
-            for bound in _assignments(graph, pat, sink):
-                if not _legal(graph, bound):
+            for bound, wild in _assignments(graph, pat, sink):
+                if not _legal(graph, bound, wild):
                     continue
                 first = min(bound, key=lambda v: graph.rank[v])
                 key = (graph.rank[first], pi)

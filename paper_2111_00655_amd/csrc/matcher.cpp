@@ -4,8 +4,10 @@
 //
 // Readings fixed here (the paper is silent): v_s is the first node of g in the
 // order (depth, node id); a match is legal only with a single exit (every
-// non-sink node has all consumers inside g and is no graph output) and with
-// distinct nodes bound to the pattern's operators; `add` operands are tried as
+// non-sink node has all consumers inside g and is no graph output), with
+// distinct nodes bound to the pattern's operators and with no wildcard bound to
+// a non-sink operator of g (a wildcard is an operand from outside the kernel; a
+// non-sink value of g lives only inside it); `add` operands are tried as
 // written, then swapped; one match is kept per (v_s, pattern), the first found
 // scanning sinks in node order; match ids rank (order of v_s, pattern id).
 #include <algorithm>
@@ -73,6 +75,9 @@ bool legal(const Graph &g, const Pattern &p, const std::vector<int32_t> &bound,
     std::sort(sorted.begin(), sorted.end());
     if (std::adjacent_find(sorted.begin(), sorted.end()) != sorted.end()) return false;
     const int32_t sink = ops->back();
+    for (size_t i = 0; i < p.nodes.size(); ++i)
+        if (p.nodes[i].op == CLG_WILDCARD && bound[i] != sink && std::binary_search(sorted.begin(), sorted.end(), bound[i]))
+            return false;
     for (int32_t v : *ops) {
         if (v == sink) continue;
         if (g.is_output[v]) return false;

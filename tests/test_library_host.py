@@ -106,6 +106,40 @@ def test_search_equals_exhaustive_on_random_dags(seed):
     s.close()
 
 
+@pytest.mark.parametrize("seed", range(40))
+def test_every_searched_or_enumerated_placement_compiles_on_random_dags(seed):
+    """Search-then-compile contract (Sec. 4.1 / 4.2): whatever cover the search returns, and any other
+    cover of the match list, must lower to a kernel sequence in which every operand has been produced."""
+    d = wl.random_dag(seed, n_ops=6 + seed % 9)
+    reg = []
+    for be, p in wl.small_registry():
+        reg.append(("igemm" if p[0] != "add" and _anchor(p) == "conv2d" else "eltwise", p))
+    ctx = clg.clg_create(-1)
+    ok = []
+    for be, p in reg:
+        try:
+            clg.clg_register_pattern(ctx, clg.clg_register_backend(ctx, be), p)
+            ok.append((be, p))
+        except clg.ClgError as e:
+            assert e.status == "NO_KERNEL"
+    clg.clg_destroy(ctx)
+    s = clg.Session(d, ok, device=None)
+    g = Graph(d)
+    oms = enumerate_matches(g, ok)
+    _same_matches(s.match(), oms)
+    for cs in range(6):
+        costs = wl.synthetic_costs(len(oms), 77 * seed + cs, ties=(cs % 2 == 1))
+        _, ids = s.search(costs, 0)
+        plan = s.compile(ids)
+        assert plan.n_kernels == len(ids)
+        plan.destroy()
+    covers = list(search.all_placements(g, oms))
+    pick = np.random.default_rng(seed).permutation(len(covers))[:8]
+    for pi in pick:
+        s.compile(covers[pi]).destroy()
+    s.close()
+
+
 def _anchor(p):
     while True:
         subs = [a for a in p[1] if a != W]

@@ -88,6 +88,29 @@ def test_add_is_commutative_for_matching():
     assert len(ms) == 1 and ms[0].nodes == (c, cb, a, r) and ms[0].first == c
 
 
+def test_a_wildcard_never_binds_a_value_inside_the_match():
+    # y = conv(x); a = add(bias(y), y): relu(add(bias_add(conv2d(*,*),*),*)) would need y both as the
+    # conv inside the kernel and as an outside operand of the add; y has no consumer outside, so no
+    # kernel ever writes it: the four-operator match is illegal, the shorter ones stay
+    d = wl.GraphDesc("self_wild")
+    x = d.input(np.zeros((1, 2, 4, 4), np.float32))
+    w = d.const(np.zeros((2, 2, 3, 3), np.float32))
+    b = d.const(np.zeros(2, np.float32))
+    y = d.op("conv2d", [x, w], stride=(1, 1), pad=(1, 1), groups=1)
+    yb = d.op("bias_add", [y, b], axis=1)
+    a = d.op("add", [yb, y])
+    r = d.op("relu", [a])
+    d.mark_output(r)
+    g = Graph(d)
+    full = P("relu", P("add", P("bias_add", P("conv2d", W, W), W), W))
+    assert enumerate_matches(g, [("k", full)]) == []
+    ms = enumerate_matches(g, [("k", P("relu", P("add", W, W))), ("k", P("bias_add", W, W)), ("k", P("conv2d", W, W))])
+    assert sorted(m.nodes for m in ms) == [(y,), (yb,), (a, r)]
+    # with a second consumer outside the would-be match the single-exit rule already forbids it
+    d.mark_output(d.op("tanh", [y]))
+    assert enumerate_matches(Graph(d), [("k", full)]) == []
+
+
 def test_both_branches_of_a_projection_block_match():
     # add(bias(convA), bias(convB)): one match per entry convolution
     d = wl.resnet50(0, image=32, width=8, blocks=(1,), classes=4)
