@@ -290,7 +290,7 @@ def main():
     ap.add_argument("--batch-sweep", default="", metavar="B1,B2,...",
                     help="also time ResNeXt-50 at these batch sizes (the paper's Fig. 8 varies the batch for this model)")
     ap.add_argument("--graph-level", default="", metavar="MODEL,...",
-                    help="also run the graph-level evolutionary search (paper Sec. 4.2) on these workloads' op-level plans")
+                    help="also run the graph-level evolutionary search (paper Sec. 4.3) on these workloads' op-level plans")
     ap.add_argument("--rules", action="store_true",
                     help="build the registry with the pattern generator from pattern rules instead of the listed patterns")
     ap.add_argument("--large-shapes", default="", metavar="FILE",

@@ -164,8 +164,8 @@ typedef struct clg_match {
 /* Cost the measurer reports for a match its backend cannot run. */
 #define CLG_COST_INF ((int64_t)1 << 60)
 
-/* Measurer protocol (Sec. 4.2: "compilation + multiple runs on the actual
- * hardware").  Zero in a field selects the default given in brackets. */
+/* Measurer protocol (Sec. 4.2: a candidate is built and run several times on
+ * the device).  Zero in a field selects the default given in brackets. */
 typedef struct clg_profile_opts {
     int32_t warmup;         /* untimed launches first [20]                    */
     int32_t batches;        /* timed batches; the cost is the fastest one [7] */
@@ -299,7 +299,7 @@ typedef struct clg_pattern_rule {
 int32_t clg_generate_patterns(clg_ctx *ctx, clg_graph *g, int32_t backend,
                               const clg_pattern_rule *rule, int32_t *n_added);
 
-/* ---- matches (Alg. 1: "find a subgraph g rooted at v_s that matches b_i") - */
+/* ---- matches (Alg. 1, matching step: the subgraph g at v_s for entry b_i) -- */
 /* Enumerates every legal match of every registered pattern.  Legal: pattern
  * operators bind distinct nodes, only the sink has consumers outside g, and no
  * non-sink node is a graph output (g becomes ONE kernel).  `add` operands are
@@ -352,7 +352,7 @@ int32_t clg_match_key(clg_ctx *ctx, clg_graph *g, int32_t match, char *buf,
 int32_t clg_search_dp(clg_ctx *ctx, clg_graph *g, const int64_t *cost_ns,
                       size_t n_costs, int64_t eps_ns, int32_t *chosen,
                       size_t cap, size_t *n_chosen, int64_t *total_ns);
-/* ---- graph-level placement search (Sec. 4.2) ------------------------------ */
+/* ---- graph-level placement search (Sec. 4.3) ------------------------------ */
 /* Evolutionary search over strings of n digits.  Digit i = 0 keeps the
  * op-level decision for item i, 1 hands item i to the graph-level backend;
  * what an item is and what the handing-over does is the fitness function's

@@ -2,7 +2,7 @@
 
 TEST INFRASTRUCTURE ONLY (parity anchor; never imported by the product path).
 
-Paper Sec. 4.2: a placement is written as a string of digits, one per operator
+Paper Sec. 4.3: a placement is written as a string of digits, one per operator
 the graph-level backend does not hold yet; 0 keeps the operator-level decision,
 1 hands the operator over.  The search starts from a population that contains
 the operator-level placement itself (all zeros) and repeats mutation, selection

@@ -3,9 +3,9 @@
 TEST INFRASTRUCTURE ONLY (parity anchor; never imported by the product path).
 
 Paper Sec. 3: a pattern is a tree of is_op(name)(args...) nodes, wildcards and
-attribute constraints; Alg. 1 asks, for a frontier node v_s and a backend
-pattern b_i, for "a subgraph g rooted at v_s that matches b_i".  Readings the
-paper leaves open, fixed here:
+attribute constraints; the matching step of Alg. 1 asks, for a frontier node
+v_s and a backend pattern b_i, for the subgraph g at v_s that b_i matches.
+Readings the paper leaves open, fixed here:
 
  * v_s is the first node of g in the total order (depth, node id); the pattern
    text itself is sink-rooted as in the paper's listing.

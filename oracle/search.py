@@ -20,12 +20,24 @@ Readings fixed here where the paper is silent:
    order (depth, node id);
  * S for a match g found at v_s is every stored sub-placement whose lowest
    uncovered node is v_s and that is disjoint from g; the new frontier nodes F
-   are the lowest uncovered nodes of s_j + g.
+   are the lowest uncovered nodes of s_j + g;
+ * a cost of COST_INF or more is the measurer's word for "this backend cannot
+   run this match" (Sec. 4.2: the measurer prices what a backend executes; the
+   paper always has a fallback backend, so it never meets the case): such a
+   match is no candidate, and a graph that only such matches could cover has
+   no placement.
 """
 from __future__ import annotations
 
 import heapq
 from itertools import combinations
+
+
+COST_INF = 1 << 60
+
+
+def _usable(costs, i):
+    return int(costs[i]) < COST_INF
 
 
 def _key(total, ids):
@@ -53,7 +65,7 @@ def brute_force_subsets(graph, matches, costs, eps=0, limit=22):
                     ok = False
                     break
                 covered.update(g)
-            if not ok or covered != need:
+            if not ok or covered != need or not all(_usable(costs, i) for i in ids):
                 continue
             k = _key(placement_cost(matches, costs, eps, ids), ids)
             if best is None or k < best:
@@ -89,6 +101,8 @@ def exhaustive(graph, matches, costs, eps=0):
     count = 0
     for ids in all_placements(graph, matches):
         count += 1
+        if not all(_usable(costs, i) for i in ids):
+            continue
         k = _key(placement_cost(matches, costs, eps, ids), ids)
         if best is None or k < best:
             best = k
@@ -123,6 +137,8 @@ def dp(graph, registry, matches, costs, eps=0, stats=None):
             if mid is None:
                 continue
             n_matched += 1
+            if not _usable(costs, mid):
+                continue
             g = frozenset(matches[mid].nodes)
             S = [s for s in at_frontier.get(v_s, []) if s.isdisjoint(g)]
             max_s = max(max_s, len(S))

@@ -1,4 +1,4 @@
-// Graph-level placement search (paper Sec. 4.2): evolutionary search over
+// Graph-level placement search (paper Sec. 4.3): evolutionary search over
 // digit strings.  Digit i = 0 keeps the operator-level decision for item i,
 // 1 hands the item to the graph-level backend.  The cost of a string is
 // whatever the caller's function measures on the whole graph; it is not
@@ -75,6 +75,8 @@ int32_t evolve(size_t n, const clg_es_opts &o, const uint32_t *rand, size_t n_ra
             if (rs.chance(o.p_mutate))
                 for (size_t b = 0; b < n; ++b)
                     if (rs.chance(o.p_flip)) d[b] ^= 1;
+        // a missing draw reads as 0: strings built from such draws are never measured
+        if (rs.dry) return fail(CLG_INVALID_ARG, "random draws exhausted in generation %d (%zu given)", gen, n_rand);
         for (size_t i = 0; i < P; ++i) cost[i] = led.of(pop[i]);
         for (size_t i = 0; i < P; ++i) {                              // selection
             uint32_t w = rs.below((uint32_t)P);

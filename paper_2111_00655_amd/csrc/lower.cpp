@@ -1,7 +1,7 @@
 // Lowering: a backend pattern's structure check at registration, and the
 // translation of one match into one kernel call (paper Sec. 4.2: a matched
-// subgraph is "single or multiple operators (operator fusion) that will be
-// lowered to a single low-level kernel").
+// subgraph, whether one operator or several fused ones, becomes exactly one
+// low-level kernel).
 //
 // Every pattern the kernel families accept is a chain: an anchor operator
 // whose arguments are all wildcards, followed by operators that each take the

@@ -1,6 +1,6 @@
 // Pattern matcher: enumerates every legal match (v_s, b_i) -> g of the
-// registry on a graph (paper Sec. 3 pattern language; Alg. 1 "find a subgraph
-// g rooted at v_s that matches b_i").
+// registry on a graph (paper Sec. 3 pattern language; the matching step of
+// Alg. 1: for a frontier node v_s and a registry entry b_i, the subgraph g).
 //
 // Readings fixed here (the paper is silent): v_s is the first node of g in the
 // order (depth, node id); a match is legal only with a single exit (every

@@ -1,7 +1,7 @@
-// The measurer M of paper Sec. 4.2: "takes a backend placement strategy and
-// returns its actual run-time cost", queried at the granularity of one matched
-// subgraph = one kernel, with "compilation + multiple runs on the actual
-// hardware" and results cached in a log.
+// The measurer M of paper Sec. 4.2: given a placement it reports what the
+// placement really costs at run time.  It is asked about one matched subgraph,
+// i.e. one kernel, at a time; pricing means building the kernel and running it
+// several times on the device, and every result is kept in a log for reuse.
 //
 // Protocol: a few launches to size the batches, one untimed batch (the
 // measurer's host work between two candidates leaves the GPU idle long enough

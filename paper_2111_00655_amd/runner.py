@@ -131,7 +131,7 @@ class Plan:
         return B.clg_plan_measure(self.h, *self._args(), warmup=warmup, batches=batches, reps=reps)
 
     def search_graph_level(self, opts, rand, lanes=2, warmup=3, batches=3, reps=20):
-        """Sec. 4.2 on this plan: (best digits, best ns, seed ns, evaluations, history); leaves the plan set to best."""
+        """Sec. 4.3 on this plan: (best digits, best ns, seed ns, evaluations, history); leaves the plan set to best."""
         return B.clg_search_graph_level(self.h, *self._args(), lanes, opts, rand, warmup=warmup, batches=batches, reps=reps)
 
     @property

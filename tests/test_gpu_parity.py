@@ -840,7 +840,7 @@ def _rand_u32(seed, n=200000):
 
 @pytest.mark.parametrize("name", ["resnet_small", "tiny_cnn"])
 def test_graph_level_search_keeps_outputs_and_never_loses_to_the_seed(name):
-    """Sec. 4.2: digit strings over the kernels of the op-level plan, priced by timing the whole
+    """Sec. 4.3: digit strings over the kernels of the op-level plan, priced by timing the whole
     sequence.  Whatever string wins, the plan must compute the same values as the op-level plan
     (bit for bit: the same kernels, another schedule), equal the oracle, and its measured time is
     by construction at most the all-zero seed's."""

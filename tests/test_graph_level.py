@@ -1,4 +1,4 @@
-"""Graph-level placement (paper Sec. 4.2): the evolutionary search over digit strings.
+"""Graph-level placement (paper Sec. 4.3): the evolutionary search over digit strings.
 
 The oracle's search is pinned by a generation worked by hand and by what must hold for any
 fitness; the library's search must then equal the oracle's draw for draw."""
@@ -182,6 +182,15 @@ def test_library_search_errors():
         B.clg_evolve(8, ok, draws(0), lambda d: float("nan"))
     with pytest.raises(ZeroDivisionError):
         B.clg_evolve(8, ok, draws(0), lambda d: 1 / 0)
+    # draws that run dry in the middle of a generation: like the oracle, the library measures no string
+    # that was built from missing draws
+    for k in range(24, 80, 3):
+        a, b = [], []
+        with pytest.raises(ValueError, match="exhausted"):
+            oe.evolve(8, lambda d: (a.append(tuple(d)), 1.0 + sum(d))[1], draws(3, k), population=4, generations=3)
+        with pytest.raises(B.ClgError, match="draws"):
+            B.clg_evolve(8, ok, draws(3, k), lambda d: (b.append(tuple(d)), 1.0 + sum(d))[1])
+        assert a == b, k
     # no digits: the seed is the only string
     best, cost, evals, hist = B.clg_evolve(0, ok, draws(0), lambda d: 3.0)
     assert best == [] and cost == 3.0 and evals == 1 and hist == [3.0] * 4

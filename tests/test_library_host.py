@@ -158,10 +158,26 @@ def test_infinite_costs_are_never_chosen_and_uncoverable_is_reported():
     costs[direct] = B.COST_INF
     total, ids = s.search(costs, 0)
     assert not set(ids) & set(direct)
+    g, oms = Graph(d), enumerate_matches(Graph(d), reg)
+    assert (total, ids) == search.dp(g, reg, oms, costs, 0)
     costs[:] = B.COST_INF
     with pytest.raises(clg.ClgError) as e:
         s.search(costs, 0)
     assert e.value.status == "NOT_A_COVER"
+    assert search.dp(g, reg, oms, costs, 0) is None            # the oracle agrees: no placement
+    # random tables with dead entries: library and oracle agree on the optimum or on there being none
+    r = np.random.default_rng(3)
+    for trial in range(20):
+        costs = r.integers(100, 5000, len(ms)).astype(np.int64)
+        costs[r.random(len(ms)) < 0.4] = B.COST_INF
+        want = search.dp(g, reg, oms, costs, 11)
+        if want is None:
+            with pytest.raises(clg.ClgError) as e:
+                s.search(costs, 11)
+            assert e.value.status == "NOT_A_COVER"
+        else:
+            assert s.search(costs, 11) == want
+    costs = np.full(len(ms), 1000, np.int64)
     with pytest.raises(clg.ClgError) as e:
         s.search(-np.ones(len(ms), np.int64), 0)
     assert e.value.status == "INVALID_ARG"

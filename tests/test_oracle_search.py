@@ -332,3 +332,34 @@ def test_interleaved_branches_need_non_prefix_states():
     assert total == 102
     assert sorted(ms[i].nodes for i in ids) == [(a1, a2), (b1, b2), (out,)]
     assert (total, ids) == search.brute_force_subsets(g, ms, costs, 0)
+
+
+def test_unusable_matches_are_no_candidates():
+    """Costs of COST_INF or more mark matches no backend can run: the optimum is taken over the
+    placements without them (DP == exhaustive == subset brute force), and when every cover needs
+    one there is no placement at all."""
+    d = wl.tiny_cnn(0, image=8)
+    g = Graph(d)
+    reg = wl.small_registry()
+    ms = enumerate_matches(g, reg)
+    r = np.random.default_rng(17)
+    for trial in range(12):
+        costs = r.integers(100, 2000, len(ms)).astype(object)
+        dead = r.random(len(ms)) < 0.35
+        for i in np.flatnonzero(dead):
+            costs[i] = search.COST_INF + int(r.integers(0, 3))
+        best, _ = search.exhaustive(g, ms, costs, 7)
+        assert search.dp(g, reg, ms, costs, 7) == best
+        if len(ms) <= 22:
+            assert search.brute_force_subsets(g, ms, costs, 7) == best
+        if best is not None:
+            assert all(costs[i] < search.COST_INF for i in best[1]) and best[0] < search.COST_INF
+    costs = [search.COST_INF] * len(ms)
+    assert search.dp(g, reg, ms, costs, 0) is None and search.exhaustive(g, ms, costs, 0)[0] is None
+    # one operator whose every match is dead: no cover, however cheap the rest
+    costs = [10] * len(ms)
+    victim = g.op_ids[3]
+    for i, m in enumerate(ms):
+        if victim in m.nodes:
+            costs[i] = search.COST_INF
+    assert search.dp(g, reg, ms, costs, 0) is None
