@@ -80,7 +80,11 @@ typedef enum clg_op_kind {
     CLG_OP_LAYER_NORM = 11,         /* (x, gamma[L], beta[L]); eps; last axis     */
     CLG_OP_MAX_POOL2D = 12,         /* (x); kernel stride pad; padding = -inf     */
     CLG_OP_GLOBAL_AVG_POOL2D = 13,  /* (x[N,C,H,W]) -> [N,C]                      */
-    CLG_OP_TAKE = 14,               /* (table[V,H], ids[L] int32) -> [L,H]        */
+    CLG_OP_TAKE = 14,               /* (table[V,H], ids[L] int32) -> [L,H]; ids live in
+                                       device memory, which no host call can inspect:
+                                       an id outside [0, V) is not an error, the kernel
+                                       reads row 0 or V-1 instead (it never reads
+                                       outside the table)                         */
     CLG_OP_RESHAPE = 15,            /* (x); dims = new shape                      */
     CLG_OP_TRANSPOSE = 16,          /* (x); dims = permutation                    */
     CLG_OP_AVG_POOL2D = 17,         /* (x); kernel stride pad; mean over the window's
@@ -201,7 +205,11 @@ int32_t clg_version(void);
  * SHAPE_MISMATCH is returned, and the node not added, if operands do not fit.
  * No tensor may hold more than 2^29 elements (2 GiB of fp32): the kernels
  * index with 32-bit element and byte offsets.  A larger input or constant is
- * INVALID_ARG, a larger operator result SHAPE_MISMATCH. */
+ * INVALID_ARG, a larger operator result SHAPE_MISMATCH.
+ * A compiled plan refers to its graph at every execution: while a graph has
+ * plans (clg_compile .. clg_plan_destroy) it can neither be destroyed nor
+ * changed (clg_graph_destroy, clg_graph_input / _const / _op / _mark_output
+ * then return INVALID_ARG). */
 int32_t clg_graph_create(clg_ctx *ctx, clg_graph **out);
 int32_t clg_graph_destroy(clg_graph *g);
 /* A run-time input.  dims: host array of ndim entries (1..CLG_MAX_DIMS). */

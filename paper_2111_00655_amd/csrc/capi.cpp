@@ -70,13 +70,23 @@ int32_t clg_graph_create(clg_ctx *ctx, clg_graph **out) {
 }
 
 int32_t clg_graph_destroy(clg_graph *g) {
+    if (g && g->g.live_plans > 0)
+        return fail(CLG_INVALID_ARG, "the graph still has %d compiled plan(s): destroy them first", g->g.live_plans);
     delete g;
+    return CLG_OK;
+}
+
+// A plan keeps node kinds, shapes and constant pointers of its graph by reference.
+static int32_t graph_is_open(const clg_graph *g) {
+    if (g->g.live_plans > 0)
+        return fail(CLG_INVALID_ARG, "the graph has %d compiled plan(s) and can no longer be changed", g->g.live_plans);
     return CLG_OK;
 }
 
 static int32_t add_leaf(clg_graph *g, int32_t kind, int32_t dtype, int32_t ndim, const int64_t *dims,
                         const void *ptr, int32_t *node) {
     NEED(g); NEED(dims); NEED(node);
+    if (graph_is_open(g) != CLG_OK) return CLG_INVALID_ARG;
     if (dtype != CLG_F32 && dtype != CLG_I32) return fail(CLG_INVALID_ARG, "dtype %d", dtype);
     if (ndim < 1 || ndim > CLG_MAX_DIMS) return fail(CLG_INVALID_ARG, "ndim %d", ndim);
     Node nd;
@@ -114,6 +124,7 @@ int32_t clg_graph_op(clg_graph *g, int32_t op_kind, int32_t n_in, const int32_t 
                      int32_t *node) {
     CLG_TRY
     NEED(g); NEED(node);
+    if (graph_is_open(g) != CLG_OK) return CLG_INVALID_ARG;
     if (n_in < 1 || n_in > CLG_MAX_PATTERN_ARGS) return fail(CLG_INVALID_ARG, "n_in %d", n_in);
     NEED(in_nodes);
     Node nd;
@@ -137,6 +148,7 @@ int32_t clg_graph_op(clg_graph *g, int32_t op_kind, int32_t n_in, const int32_t 
 int32_t clg_graph_mark_output(clg_graph *g, int32_t node) {
     CLG_TRY
     NEED(g);
+    if (graph_is_open(g) != CLG_OK) return CLG_INVALID_ARG;
     if (node < 0 || node >= (int32_t)g->g.nodes.size()) return fail(CLG_UNKNOWN_ID, "node id %d", node);
     if (!g->g.nodes[node].is_op()) return fail(CLG_INVALID_ARG, "node %d is not an operator", node);
     for (int32_t o : g->g.outputs)
@@ -363,6 +375,8 @@ int32_t clg_compile(clg_ctx *ctx, clg_graph *g, const int32_t *matches, size_t n
         delete p;
         return rc;
     }
+    ++g->g.live_plans;
+    p->p.counted = true;
     *out = p;
     return CLG_OK;
     CLG_CATCH

@@ -84,6 +84,7 @@ struct Graph {
     std::vector<MatchRec> matches;
     bool matched = false;
     int64_t stats[5] = {0, 0, 0, 0, 0};
+    int32_t live_plans = 0;           // compiled plans that still refer to this graph
     void finalize();
 };
 
@@ -166,7 +167,8 @@ int32_t generate_patterns(Context &ctx, Graph &g, int32_t backend, const clg_pat
 // ---- plan -----------------------------------------------------------------------------
 struct Plan {
     Context *ctx = nullptr;
-    Graph *graph = nullptr;
+    Graph *graph = nullptr;            // read at every execution: the graph outlives its plans, unchanged
+    bool counted = false;              // this plan is among graph->live_plans
     std::vector<KernelCall> calls;
     std::vector<int64_t> value_offset;     // node -> workspace byte offset, -1 none
     std::vector<int32_t> value_output;     // node -> index in outputs[] of the buffer it lives in, -1 none

@@ -232,8 +232,9 @@ int launch_eltwise(const EltwiseArgs &a, void *stream);
 int launch_layout(const LayoutArgs &a, void *stream);
 int launch_concat(const ConcatArgs &a, void *stream);
 // Scratch-operand fill for the measurer: uniform values in [-1, 1) from a
-// counter hash of (seed, index); ids: zeros.
+// counter hash of (seed, index); row ids of a gather: uniform over [0, rows).
 int launch_fill(float *p, int64_t n, uint64_t seed, void *stream);
+int launch_fill_ids(int32_t *p, int64_t n, int32_t rows, uint64_t seed, void *stream);
 int launch_empty(void *stream);
 
 // Tile choice and split-K factor the GEMM launcher will use for these sizes

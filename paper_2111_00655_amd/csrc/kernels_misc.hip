@@ -518,6 +518,25 @@ int launch_fill(float *p, int64_t n, uint64_t seed, void *stream) {
     return (int)hipGetLastError();
 }
 
+// Row ids for a gather: uniform over [0, rows) from the same counter hash, so that a measured
+// gather touches rows spread over the whole table, as a real one does.
+__global__ __launch_bounds__(256) void fill_ids_kernel(int32_t *p, int64_t n, int32_t rows, uint64_t seed) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        uint64_t z = seed + 0x9E3779B97F4A7C15ull * (uint64_t)(i + 1);
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+        z ^= z >> 31;
+        p[i] = (int32_t)(((z >> 32) * (uint64_t)(rows > 0 ? rows : 1)) >> 32);
+    }
+}
+
+int launch_fill_ids(int32_t *p, int64_t n, int32_t rows, uint64_t seed, void *stream) {
+    const int grid = (int)std::min<int64_t>((n + 255) / 256, 256 * 16);
+    hipLaunchKernelGGL(fill_ids_kernel, dim3(grid > 0 ? grid : 1), dim3(256), 0, (hipStream_t)stream, p, n, rows, seed);
+    return (int)hipGetLastError();
+}
+
 __global__ void empty_kernel() {}
 
 int launch_empty(void *stream) {

@@ -199,6 +199,7 @@ int32_t compile_plan(Context &ctx, Graph &g, const int32_t *ids, size_t n, Plan 
 }
 
 Plan::~Plan() {
+    if (counted && graph) --graph->live_plans;
     for (void *p : packed)
         if (p) (void)hipFree(p);
     for (void *e : events)

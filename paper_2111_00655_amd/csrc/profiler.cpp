@@ -168,10 +168,12 @@ int32_t profile_match(Context &ctx, Graph &g, int32_t match, const clg_profile_o
         ptrs[i] = base + offs[i];
         if (is_out) continue;
         const int64_t n = g.nodes[v].shape.numel();
-        hipError_t he;
         if (g.nodes[v].dtype == CLG_I32) {
-            if ((he = hipMemsetAsync(base + offs[i], 0, 4 * (size_t)n, nullptr)) != hipSuccess)
-                return hip_fail("hipMemsetAsync", he);
+            // the only int32 operand is a gather's row ids: seeded ids spread over the table (all zeros would
+            // time the gather of one cache-hot row)
+            const int32_t rows = c.kind == CALL_ELTWISE && c.elt.table_rows > 0 ? c.elt.table_rows : 1;
+            const int e = launch_fill_ids((int32_t *)(base + offs[i]), n, rows, o.seed + 7919u * (uint64_t)i, nullptr);
+            if (e) return hip_fail("id fill kernel", (hipError_t)e);
         } else {
             const int e = launch_fill((float *)(base + offs[i]), n, o.seed + 7919u * (uint64_t)i, nullptr);
             if (e) return hip_fail("fill kernel", (hipError_t)e);

@@ -26,6 +26,7 @@ class Session:
         self._torch = None
         self._keep = []          # device tensors the graph borrows
         self.matches = None
+        self._plans = []         # plans compiled from the graph: it cannot go before they do
         if device is not None:
             import torch
             self._torch = torch
@@ -90,9 +91,14 @@ class Session:
         return B.clg_search_dp(self.ctx, self.graph, costs, eps)
 
     def compile(self, match_ids):
-        return Plan(self, B.clg_compile(self.ctx, self.graph, list(match_ids)))
+        plan = Plan(self, B.clg_compile(self.ctx, self.graph, list(match_ids)))
+        self._plans.append(plan)
+        return plan
 
     def close(self):
+        for plan in self._plans:
+            plan.destroy()
+        self._plans = []
         if self.graph is not None:
             B.clg_graph_destroy(self.graph)
             B.clg_destroy(self.ctx)

@@ -372,3 +372,26 @@ def test_concat_of_kernel_results_is_planned_without_a_copy():
         # aliased: the three pieces live inside the result's 3 x 512 bytes; copied: two pieces + the result
         assert ws == (1536 if not with_input else 1024 + 1536), ws
         s.close()
+
+
+def test_a_graph_with_plans_can_neither_go_nor_change():
+    d = wl.tiny_cnn(0, image=8)
+    s = clg.Session(d, wl.default_registry(), device=None)
+    ms = s.match()
+    _, ids = s.search(wl.synthetic_costs(len(ms), 0), 0)
+    h1 = B.clg_compile(s.ctx, s.graph, list(ids))
+    h2 = B.clg_compile(s.ctx, s.graph, list(ids))
+    for call in (lambda: B.clg_graph_destroy(s.graph), lambda: B.clg_graph_op(s.graph, "relu", [d.outputs[0]]),
+                 lambda: B.clg_graph_input(s.graph, B.F32, (1, 2)), lambda: B.clg_graph_mark_output(s.graph, ms[0].sink)):
+        with pytest.raises(clg.ClgError, match="plan") as e:
+            call()
+        assert e.value.status == "INVALID_ARG"
+    B.clg_plan_destroy(h1)
+    with pytest.raises(clg.ClgError, match="1 compiled plan"):
+        B.clg_graph_destroy(s.graph)
+    with pytest.raises(clg.ClgError):                          # a failed compile leaves no claim on the graph
+        B.clg_compile(s.ctx, s.graph, list(ids[:-1]))
+    B.clg_plan_destroy(h2)
+    n = B.clg_graph_num_nodes(s.graph)
+    assert B.clg_graph_op(s.graph, "relu", [d.outputs[0]]) == n        # open again
+    s.close()
