@@ -494,6 +494,26 @@ int32_t clg_plan_num_lanes(const clg_plan *plan, int32_t *lanes);
 int32_t clg_execute(clg_plan *plan, const void *const *inputs,
                     void *const *outputs, void *workspace, size_t ws_bytes,
                     void *stream);
+/* For callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid it): clg_execute without the
+ * workspace argument.  The plan's intermediate tensors and split-K partial
+ * sums go to a fixed array of CLG_STATIC_WORKSPACE_BYTES that is part of the
+ * library's device code; each GPU holds its own copy from the moment the
+ * library is loaded until the process ends.  The call allocates and frees
+ * nothing, on the device or through any library; inputs and outputs are the
+ * caller's as in clg_execute, and the results are bit for bit those of
+ * clg_execute.  Nothing in the array has to start at zero (every kernel writes
+ * what a later one reads), and it keeps the last call's contents.  All calls
+ * on one GPU share the array: two executions that overlap in time on one GPU -
+ * of one plan or of different plans, on any streams - race; order them on one
+ * stream or with events.  Errors: WORKSPACE_TOO_SMALL if the plan needs more
+ * than CLG_STATIC_WORKSPACE_BYTES (clg_plan_workspace_bytes tells; use
+ * clg_execute then), INVALID_ARG for a plan with more than one lane that has
+ * not yet been run by clg_execute (its streams are created there), otherwise
+ * as clg_execute. */
+#define CLG_STATIC_WORKSPACE_BYTES ((size_t)32 << 20)
+int32_t clg_execute_static(clg_plan *plan, const void *const *inputs,
+                           void *const *outputs, void *stream);
 /* As clg_execute, with a HIP event pair around every kernel on `stream`;
  * synchronises, then writes each kernel's duration in nanoseconds to
  * kernel_ns (host array, one entry per plan kernel; 0 for an entry that

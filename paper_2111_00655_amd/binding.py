@@ -148,6 +148,7 @@ SYMBOLS = {
                                C.c_void_p, C.POINTER(C.c_uint8), C.POINTER(C.c_double), C.POINTER(C.c_int64),
                                C.POINTER(C.c_double), _i32p]),
     "clg_execute": (C.c_int32, [_P, C.POINTER(_P), C.POINTER(_P), _P, C.c_size_t, _P]),
+    "clg_execute_static": (C.c_int32, [_P, C.POINTER(_P), C.POINTER(_P), _P]),
     "clg_execute_timed": (C.c_int32, [_P, C.POINTER(_P), C.POINTER(_P), _P, C.c_size_t, _P, _i64p, C.c_size_t]),
 }
 
@@ -497,6 +498,14 @@ def clg_execute(plan, inputs, outputs, workspace, ws_bytes, stream=0):
     """inputs / outputs: sequences of device addresses (ints); workspace: device address."""
     _check(lib().clg_execute(plan, _ptr_array(inputs), _ptr_array(outputs), _P(int(workspace) or None),
                              int(ws_bytes), _P(int(stream) or None)))
+
+
+STATIC_WORKSPACE_BYTES = 32 << 20
+
+
+def clg_execute_static(plan, inputs, outputs, stream=0):
+    """clg_execute on the library's own fixed workspace: nothing is allocated anywhere."""
+    _check(lib().clg_execute_static(plan, _ptr_array(inputs), _ptr_array(outputs), _P(int(stream) or None)))
 
 
 def clg_execute_timed(plan, inputs, outputs, workspace, ws_bytes, stream=0):

@@ -21,7 +21,7 @@ LIB = os.path.join(HERE, "libcollage_mi.so")
 SOURCES = ["graph.cpp", "matcher.cpp", "search.cpp", "lower.cpp", "plan.cpp",
            "profiler.cpp", "rules.cpp", "evolve.cpp", "capi.cpp", "kernels_gemm.hip", "gemm_fast_mm.hip", "gemm_fast_conv.hip",
            "gemm_lean_mm.hip", "gemm_lean_conv.hip", "gemm_rf.hip",
-           "kernels_misc.hip", "sepconv.hip", "attention.hip"]
+           "kernels_misc.hip", "sepconv.hip", "attention.hip", "static_ws.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra", "-Wno-unused-parameter",

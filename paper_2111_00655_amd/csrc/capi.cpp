@@ -44,6 +44,11 @@ int32_t clg_create(clg_ctx **out, int32_t device) {
             delete c;
             return fail(CLG_HIP_ERROR, "hipSetDevice(%d): %s", device, hipGetErrorString(e));
         }
+        const int32_t src = static_workspace_init(device);
+        if (src != CLG_OK) {
+            delete c;
+            return src;
+        }
         int cus = 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && cus > 0)
             c->c.n_cus = cus;
@@ -540,6 +545,13 @@ int32_t clg_execute(clg_plan *plan, const void *const *inputs, void *const *outp
     CLG_TRY
     NEED(plan);
     return execute_plan(plan->p, inputs, outputs, workspace, ws_bytes, stream, nullptr);
+    CLG_CATCH
+}
+
+int32_t clg_execute_static(clg_plan *plan, const void *const *inputs, void *const *outputs, void *stream) {
+    CLG_TRY
+    NEED(plan);
+    return execute_plan_static(plan->p, inputs, outputs, stream);
     CLG_CATCH
 }
 

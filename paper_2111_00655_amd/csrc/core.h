@@ -222,6 +222,9 @@ int32_t measure_plan(Plan &p, const void *const *inputs, void *const *outputs, v
                      void *stream, const clg_measure_opts &o, int64_t *ns);
 int32_t execute_plan(Plan &p, const void *const *inputs, void *const *outputs, void *workspace,
                      size_t ws_bytes, void *stream, int64_t *kernel_ns);
+// static_ws.hip: execution with the library's own fixed workspace (no allocation anywhere)
+int32_t static_workspace_init(int32_t device);
+int32_t execute_plan_static(Plan &p, const void *const *inputs, void *const *outputs, void *stream);
 int32_t profile_match(Context &ctx, Graph &g, int32_t match, const clg_profile_opts *opts, int64_t *cost_ns);
 int32_t profile_empty(Context &ctx, const clg_profile_opts *opts, int64_t *cost_ns);
 int32_t cost_log_load(Context &ctx, const char *path);

@@ -169,6 +169,11 @@ class Plan:
         """One asynchronous pass over the kernel sequence."""
         B.clg_execute(self.h, *self._args())
 
+    def execute_static(self):
+        """One asynchronous pass with the intermediates in the library's fixed device array."""
+        ins, outs, _, _, stream = self._args()
+        B.clg_execute_static(self.h, ins, outs, stream)
+
     def execute_timed(self):
         return B.clg_execute_timed(self.h, *self._args())
 

@@ -209,6 +209,9 @@ def test_compile_validates_the_placement():
         B.clg_execute(plan.h, [1], [1, 1], 256, plan.ws_bytes)
     assert e.value.status == "HIP_ERROR"
     with pytest.raises(clg.ClgError) as e:
+        B.clg_execute_static(plan.h, [1], [1, 1])
+    assert e.value.status == "HIP_ERROR"
+    with pytest.raises(clg.ClgError) as e:
         B.clg_profile_match(s.ctx, s.graph, 0)
     assert e.value.status == "HIP_ERROR"
     s.close()
