@@ -12,7 +12,8 @@ import os
 import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libcollage_mi.so")
+# CLG_LIBRARY selects another build of the library (the host-sanitized one for CPU-only runs)
+LIB_PATH = os.environ.get("CLG_LIBRARY") or os.path.join(HERE, "libcollage_mi.so")
 
 MAX_DIMS = 6
 MAX_PATTERN_ARGS = 8
