@@ -243,6 +243,26 @@ def roofline_of(rows, step_ns=None):
                 share_of_kernel_time=round(t / max(total * scale, 1), 4))
 
 
+def measurer_spread(s, plan, repeats=5):
+    """Run-to-run spread of the measurer: every distinct kernel of the plan priced `repeats` times with the
+    cost log off; per kernel (max - min) / median, then the median and the largest of those figures."""
+    import numpy as np
+    from paper_2111_00655_amd import binding as B
+    nocache = B.ProfileOpts(warmup=10, batches=5, min_batch_us=200, max_launches=500, no_cache=1)
+    seen, rel = set(), []
+    for k in plan.kernels():
+        if k["name"].endswith("_alias"):
+            continue
+        key = B.clg_match_key(s.ctx, s.graph, k["match"])
+        if key in seen:
+            continue
+        seen.add(key)
+        c = [B.clg_profile_match(s.ctx, s.graph, k["match"], nocache) for _ in range(repeats)]
+        rel.append((max(c) - min(c)) / float(np.median(c)))
+    return dict(kernels=len(rel), repeats=repeats, median_rel_spread=round(float(np.median(rel)), 4),
+                p90_rel_spread=round(float(np.quantile(rel, 0.9)), 4), max_rel_spread=round(float(max(rel)), 4))
+
+
 def cpu_baseline(desc):
     """The oracle as it stands, one full forward pass on the host cores (and one on a single thread)."""
     from oracle.graph import Graph
@@ -297,6 +317,9 @@ def main():
                     help="also price a few compute-bound single operators (large dense, batch-32 3x3 convolutions) under every "
                          "MFMA kernel variant with the library's measurer and write TFLOP/s per variant to FILE: what the "
                          "kernels reach where launch and memory latency do not bound them")
+    ap.add_argument("--summary", default="", metavar="FILE",
+                    help="write a short text summary of the run (headline figure, and whichever of --ablation, --batch-sweep, "
+                         "--graph-level were asked for, and the measurer's run-to-run spread) with the command that made it")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MIB",
                     help="also run three plain device copies of MIB MiB (read MIB, write MIB): the known-size kernel "
                          "against which hardware byte counters of a profiled run are scaled")
@@ -327,11 +350,13 @@ def main():
     rows = kernel_table(plan)
     roof = roofline_of(rows, ms_per_step * 1e6)
     roof["algorithmic_bytes"] = int(sum(r["bytes"] for r in rows if r["bound"] == "mfma"))
+    roof["algorithmic_flops"] = int(sum(r["flops"] for r in rows if r["bound"] == "mfma"))
     tr = TRAFFIC.get(args.model)
     if tr and tr["sources"] == kernel_sources_fingerprint():
         roof["traffic"] = int(tr["fetch_bytes"] + tr["write_bytes"])      # bytes per step, same launches as `achieved`
     kernel_only_ms = sum(r["ns"] for r in rows) / 1e6
     empty_ns = B.clg_profile_empty(s.ctx)
+    spread = measurer_spread(s, plan)
     graph_ms = graph_replay_ms(plan, args.steps, args.warmup)
     cold_ms = cold_cache_ms(plan)
     abl = ablation(desc, VARIANTS, opts, args.cost_log, max(20, args.steps // 2), args.warmup) if args.ablation else None
@@ -345,9 +370,12 @@ def main():
             s2, p2, _, _, t2 = optimise(d2, reg, opts, "", rules)
             ms2 = time_steps(p2, max(20, args.steps // 2), args.warmup)
             r2 = kernel_table(p2, reps=5)
+            roof2 = roofline_of(r2, ms2 * 1e6)
+            roof2["algorithmic_bytes"] = int(sum(r["bytes"] for r in r2 if r["bound"] == "mfma"))
+            roof2["algorithmic_flops"] = int(sum(r["flops"] for r in r2 if r["bound"] == "mfma"))
             extra[name] = dict(ms_per_step=round(ms2, 4), kernels=p2.n_launches,
                                kernel_only_ms=round(sum(r["ns"] for r in r2) / 1e6, 4),
-                               mfma_tflops=roofline_of(r2, ms2 * 1e6)["achieved"], optimise_s=round(sum(
+                               mfma_tflops=roof2["achieved"], roofline=roof2, optimise_s=round(sum(
                                    v for k, v in t2.items() if k.endswith("_s")), 2))
             p2.destroy()
             s2.close()
@@ -480,10 +508,43 @@ def main():
         "large_shapes_tflops": large,
         "graph_level_search": graph_level,
         "empty_launch_ns": int(empty_ns),
+        "measurer_spread": spread,
         "optimise": {k: (round(v, 4) if isinstance(v, float) else v) for k, v in timing.items()},
         "other_workloads": extra,
     }
     print(json.dumps(out))
+    if args.summary:
+        lines = [f"{args.model} batch 1 fp32 on one MI355X, placement searched over all kernel-variant backends: "
+                 f"{ms_per_step:.4f} ms per step, {plan.n_launches} launches "
+                 f"(predicted by the cost table {timing['predicted_ms']:.4f} ms).",
+                 "command: python3 bench.py " + " ".join(sys.argv[1:]), ""]
+        if abl is not None:
+            lines += ["Placement under a single MFMA kernel variant (every fused-operator kind on that one backend; glue on",
+                      "the direct / rowwise / eltwise families as always), ms per step; '-' = the variant alone cannot cover the graph:",
+                      f"  {'search over all variants':28s} {ms_per_step:8.4f}"]
+            lines += [f"  {v:28s} {(f'{t:8.4f}' if t is not None else '       -')}" for v, t in abl.items()]
+            best = min((t for t in abl.values() if t is not None), default=None)
+            if best is not None:
+                lines += [f"  best single variant / searched mix = {best / ms_per_step:.3f}", ""]
+        if sweep is not None:
+            lines += ["ResNeXt-50 32x4d at growing batch (placement searched anew per batch size):",
+                      f"  {'batch':>5s} {'ms/step':>9s} {'images/s':>9s} {'launches':>8s}"]
+            lines += [f"  {b:>5s} {v['ms_per_step']:9.4f} {v['images_per_s']:9.1f} {v['kernels']:8d}" for b, v in sweep.items()]
+            lines += [""]
+        if graph_level is not None:
+            lines += ["Graph-level search (evolutionary, seeded with the op-level placement), whole-sequence time:",
+                      f"  {'workload':12s} {'op-level ms':>11s} {'graph-level ms':>14s} {'gain':>6s} {'launches':>9s} {'digits=1':>8s} {'strings':>7s} {'search s':>8s}"]
+            for n, v in graph_level.items():
+                lines.append(f"  {n:12s} {v['op_level_ms']:11.4f} {v['graph_level_ms']:14.4f} {v['op_level_ms'] / v['graph_level_ms']:6.3f} "
+                             f"{str(v.get('launches_before', '')) + '->' + str(v.get('launches_after', '')):>9s} {v['handed_over']:8d} "
+                             f"{v['strings_measured']:7d} {v['search_s']:8.2f}")
+            lines += [""]
+        lines += [f"Measurer: {spread['kernels']} distinct kernels priced {spread['repeats']} times each with the cost log off; "
+                  f"(max - min) / median per kernel: median {spread['median_rel_spread']:.4f}, 90th percentile "
+                  f"{spread['p90_rel_spread']:.4f}, largest {spread['max_rel_spread']:.4f}."]
+        os.makedirs(os.path.dirname(os.path.abspath(args.summary)), exist_ok=True)
+        with open(args.summary, "w") as f:
+            f.write("\n".join(lines) + "\n")
     plan.destroy()
     s.close()
 
