@@ -400,15 +400,34 @@ int32_t clg_evolve(size_t n, const clg_es_opts *opts, const uint32_t *rand,
                    uint8_t *best, double *best_cost, int64_t *evaluations,
                    double *history, int32_t *generations_run);
 
-/* The library's own graph-level backend is the plan's lane scheduler (see
- * clg_plan_set_lanes): an item is one kernel of the compiled op-level
- * placement, digit 1 hands it to the scheduler, which may then run it on
- * another HIP stream beside independent kernels, digit 0 keeps it in its place
- * on the caller's stream.  What a handed-over kernel gains or loses depends
- * on which of its neighbours are handed over as well, so strings are priced
- * by timing the whole sequence.
- * clg_plan_set_handover: digits: host, n = clg_plan_num_kernels bytes (0/1);
- * lanes: 2..4 streams for the scheduler.  All zeros = the op-level plan.
+/* The library's own graph-level backends work on a compiled op-level plan: an
+ * item is one kernel of the plan, digit 0 keeps it exactly as the op-level
+ * search placed it, digit 1 hands it over.  What a handed-over kernel gains or
+ * loses depends on which of its neighbours are handed over as well (the cost
+ * is not a sum over digits), so strings are priced by timing the whole
+ * sequence.  Two backends, selected by `lanes`:
+ *  lanes = 1  REGIONS (the paper's cross-kernel optimisation, Sec. 4.3, with
+ *    our own kernels).  clg_compile groups kernels that do not depend on each
+ *    other and run the same kind of register-fed MFMA kernel (dense layers with
+ *    constant weights; 1x1 convolutions) into regions of at most 4: e.g. the
+ *    query, key and value projections of an attention layer, or the projection
+ *    shortcut and the first 1x1 convolution of a residual block.  The
+ *    handed-over members of a region, if there are two or more, run as ONE
+ *    launch of a kernel that works on several problems at once (all members in
+ *    one common tile shape, that of the member with the most flops; members
+ *    that needed another shape get a second packed copy of their weights at
+ *    compile time).  A handed-over kernel without a handed-over sibling runs
+ *    as before.  Results agree with the op-level plan's to rounding (another
+ *    tile shape adds in another order), not bit for bit.  The workspace size
+ *    does not depend on the digits.  clg_plan_region_of tells which region a
+ *    kernel belongs to (-1: none), clg_plan_num_launches how many launches
+ *    one execution makes under the current digits.
+ *  lanes = 2..4  the LANE SCHEDULER (see clg_plan_set_lanes): a handed-over
+ *    kernel may run on another HIP stream beside independent kernels, the
+ *    others stay in place on the caller's stream.  Results are bit for bit
+ *    those of the op-level plan.
+ * clg_plan_set_handover: digits: host, n = clg_plan_num_kernels bytes (0/1).
+ * All zeros = the op-level plan.
  * Waits for the plan's streams; not to be called while the plan executes.
  * clg_plan_measure: time of one clg_execute in ns: opts->warmup executions,
  * then opts->batches (>= 1) batches of opts->reps (>= 1) executions between
@@ -418,8 +437,9 @@ int32_t clg_evolve(size_t n, const clg_es_opts *opts, const uint32_t *rand,
  * measurement as the fitness; every distinct string is set, timed and kept.
  * best: host, clg_plan_num_kernels bytes; *best_ns its time; *seed_ns (may be
  * null) the time of the all-zero string, i.e. of the op-level placement, so
- * *best_ns <= *seed_ns.  On return the plan is set to `best`.  evaluations,
- * history, generations_run as in clg_evolve (history in ns). */
+ * *best_ns <= *seed_ns.  On return the plan is set to `best`; after an error
+ * it is set to all zeros (the op-level plan).  evaluations, history,
+ * generations_run as in clg_evolve (history in ns). */
 typedef struct clg_measure_opts {
     int32_t warmup, batches, reps;
 } clg_measure_opts;
@@ -429,6 +449,8 @@ int32_t clg_plan_measure(clg_plan *plan, const void *const *inputs,
                          void *const *outputs, void *workspace,
                          size_t workspace_bytes, void *stream,
                          const clg_measure_opts *opts, int64_t *ns);
+int32_t clg_plan_num_launches(const clg_plan *plan, size_t *n);
+int32_t clg_plan_region_of(const clg_plan *plan, size_t index, int32_t *region);
 int32_t clg_search_graph_level(clg_plan *plan, const void *const *inputs,
                                void *const *outputs, void *workspace,
                                size_t workspace_bytes, void *stream,

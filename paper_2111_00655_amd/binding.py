@@ -148,6 +148,8 @@ SYMBOLS = {
     "clg_evolve": (C.c_int32, [C.c_size_t, C.POINTER(EsOpts), C.POINTER(C.c_uint32), C.c_size_t, FITNESS_FN,
                                C.c_void_p, C.POINTER(C.c_uint8), C.POINTER(C.c_double), C.POINTER(C.c_int64),
                                C.POINTER(C.c_double), _i32p]),
+    "clg_plan_num_launches": (C.c_int32, [_P, C.POINTER(C.c_size_t)]),
+    "clg_plan_region_of": (C.c_int32, [_P, C.c_size_t, _i32p]),
     "clg_execute": (C.c_int32, [_P, C.POINTER(_P), C.POINTER(_P), _P, C.c_size_t, _P]),
     "clg_execute_static": (C.c_int32, [_P, C.POINTER(_P), C.POINTER(_P), _P]),
     "clg_execute_timed": (C.c_int32, [_P, C.POINTER(_P), C.POINTER(_P), _P, C.c_size_t, _P, _i64p, C.c_size_t]),
@@ -499,6 +501,18 @@ def clg_execute(plan, inputs, outputs, workspace, ws_bytes, stream=0):
     """inputs / outputs: sequences of device addresses (ints); workspace: device address."""
     _check(lib().clg_execute(plan, _ptr_array(inputs), _ptr_array(outputs), _P(int(workspace) or None),
                              int(ws_bytes), _P(int(stream) or None)))
+
+
+def clg_plan_num_launches(plan):
+    n = C.c_size_t(0)
+    _check(lib().clg_plan_num_launches(plan, C.byref(n)))
+    return n.value
+
+
+def clg_plan_region_of(plan, index):
+    r = C.c_int32(0)
+    _check(lib().clg_plan_region_of(plan, int(index), C.byref(r)))
+    return r.value
 
 
 STATIC_WORKSPACE_BYTES = 32 << 20

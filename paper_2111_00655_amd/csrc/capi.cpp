@@ -439,7 +439,7 @@ int32_t clg_plan_set_handover(clg_plan *plan, const uint8_t *digits, size_t n, i
     NEED(plan);
     if (n != plan->p.calls.size()) return fail(CLG_INVALID_ARG, "%zu digits for a plan of %zu kernels", n, plan->p.calls.size());
     if (n && !digits) return fail(CLG_INVALID_ARG, "clg_plan_set_handover: digits is null");
-    if (lanes < 2 || lanes > 4) return fail(CLG_INVALID_ARG, "lanes must be 2..4 (got %d)", lanes);
+    if (lanes < 1 || lanes > 4) return fail(CLG_INVALID_ARG, "lanes must be 1..4 (got %d)", lanes);
     for (size_t i = 0; i < n; ++i)
         if (digits[i] > 1) return fail(CLG_INVALID_ARG, "digit %zu is %d", i, (int)digits[i]);
     plan->p.handed.assign(digits, digits + n);
@@ -496,7 +496,7 @@ int32_t clg_search_graph_level(clg_plan *plan, const void *const *inputs, void *
     CLG_TRY
     NEED(plan); NEED(opts); NEED(measure); NEED(best); NEED(best_ns);
     if (n_rand && !rand) return fail(CLG_INVALID_ARG, "clg_search_graph_level: rand is null");
-    if (lanes < 2 || lanes > 4) return fail(CLG_INVALID_ARG, "lanes must be 2..4 (got %d)", lanes);
+    if (lanes < 1 || lanes > 4) return fail(CLG_INVALID_ARG, "lanes must be 1..4 (got %d)", lanes);
     int32_t rc = check_es_opts(opts);
     if (rc == CLG_OK) rc = check_measure_opts(measure);
     if (rc != CLG_OK) return rc;
@@ -504,8 +504,13 @@ int32_t clg_search_graph_level(clg_plan *plan, const void *const *inputs, void *
     const size_t n = plan->p.calls.size();
     double cost = 0;
     rc = evolve(n, *opts, rand, n_rand, graph_level_cost, &job, best, &cost, evaluations, history, generations_run);
-    if (job.rc != CLG_OK) return fail(job.rc, "%s", job.message.c_str());     // the measurement's own error
-    if (rc != CLG_OK) return rc;
+    if (job.rc != CLG_OK || rc != CLG_OK) {
+        // leave the plan as the op-level placement, not as whatever string was tried last
+        const std::string msg = job.rc != CLG_OK ? job.message : std::string(last_error());
+        const std::vector<uint8_t> zeros(n, 0);
+        (void)clg_plan_set_handover(plan, zeros.data(), n, lanes);
+        return fail(job.rc != CLG_OK ? job.rc : rc, "%s", msg.c_str());
+    }
     *best_ns = (int64_t)cost;
     if (seed_ns) *seed_ns = job.seed_ns;
     return clg_plan_set_handover(plan, best, n, lanes);
@@ -519,6 +524,19 @@ int32_t clg_plan_set_lanes(clg_plan *plan, int32_t lanes) {
     plan->p.handed.clear();                            // every kernel may move
     return set_plan_lanes(plan->p, lanes);
     CLG_CATCH
+}
+
+int32_t clg_plan_num_launches(const clg_plan *plan, size_t *n) {
+    NEED(plan); NEED(n);
+    *n = plan_num_launches(plan->p);
+    return CLG_OK;
+}
+
+int32_t clg_plan_region_of(const clg_plan *plan, size_t index, int32_t *region) {
+    NEED(plan); NEED(region);
+    if (index >= plan->p.calls.size()) return fail(CLG_UNKNOWN_ID, "kernel index %zu", index);
+    *region = plan->p.region_of.empty() ? -1 : plan->p.region_of[index];
+    return CLG_OK;
 }
 
 int32_t clg_plan_num_lanes(const clg_plan *plan, int32_t *lanes) {

@@ -165,6 +165,15 @@ int32_t check_pattern(const Context &ctx, Pattern *p);
 int32_t generate_patterns(Context &ctx, Graph &g, int32_t backend, const clg_pattern_rule &rule, int32_t *n_added);
 
 // ---- plan -----------------------------------------------------------------------------
+// A region: kernels of the plan that do not depend on each other and run the same kind of
+// register-fed kernel, so that those of them that are handed over (clg_plan_set_handover) can
+// share one launch.  Members are adjacent in the plan's order.
+struct Region {
+    std::vector<int32_t> members;          // call indices, ascending
+    std::vector<KernelCall> fused;         // per member: the call lowered again for the region's common kernel shape
+    std::vector<void *> packed;            // per member: weights packed for that shape (owned by the plan)
+};
+
 struct Plan {
     Context *ctx = nullptr;
     Graph *graph = nullptr;            // read at every execution: the graph outlives its plans, unchanged
@@ -176,6 +185,9 @@ struct Plan {
     std::vector<char> elided;              // call -> launches nothing (a concatenation whose operands are written in place)
     std::vector<int64_t> scratch_offset;   // call -> workspace byte offset of its scratch
     std::vector<void *> packed;            // call -> re-packed weights (device memory owned by the plan) or null
+    std::vector<Region> regions;
+    std::vector<int32_t> region_of;        // call -> index into regions, -1 none
+    std::vector<char> fuse_mark;           // per call, scratch of an execution: 1 launched with its region, 2 carried its region
     size_t workspace_bytes = 0;
     // concurrent lanes: kernels of independent branches go to different HIP streams
     int32_t max_lanes = 1;                 // 1 = everything on the caller's stream (default: see clg_plan_set_lanes)
@@ -197,6 +209,12 @@ struct Plan {
 // `packed`: the re-packed weights when c.pack_bytes != 0 (see pack_weights), else ignored.
 int32_t launch_call(const KernelCall &c, const void *a, const void *b, const void *c3,
                     void *out, const void *const *epi_ptrs, void *scratch, const void *packed, void *stream);
+// The kernel arguments of a CALL_GEMM call with every pointer bound.
+int32_t bind_gemm(const KernelCall &c, const void *a, const void *b, void *out, const void *const *epi_ptrs,
+                  void *scratch, const void *packed, GemmArgs *k);
+// Kernel-list entries that launch something under the plan's current digits (aliased concatenations
+// launch nothing; the handed-over members of a region share one launch).
+size_t plan_num_launches(const Plan &p);
 // Runs the weight re-packing kernel of call `c` (c.pack_bytes != 0): w -> dst.
 int32_t pack_weights(const KernelCall &c, const void *w, void *dst, void *stream);
 

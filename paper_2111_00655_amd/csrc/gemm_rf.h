@@ -85,8 +85,10 @@ struct RfMfma<16> {
 // with a relu on its input (the operand values are clamped on their way into the MFMA).  The depth code is
 // compiled into GEO 2 and 3 only: a few more kernel arguments and one division are a measurable
 // part of a four-microsecond kernel.
+// The body takes its tile number as (bx of gx) instead of reading blockIdx.x, so that one launch can
+// run the tiles of several convolutions (conv_rf_multi_kernel below); grid.y and grid.z are read as usual.
 template <int TS, int TAPK, int WGK, int GEO>
-__global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
+__device__ __forceinline__ void conv_rf_body(const GemmArgs &p, const int bx, const int gx) {
     using MF = RfMfma<TS>;
     typedef typename MF::acc_t acc_t;
     constexpr int NSLOT = MF::NSLOT, NACC = MF::NACC;
@@ -122,7 +124,7 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
     }
     const int npix = HOe * WOe;
     const int tiles_m = (p.Cout + TS - 1) / TS;
-    const int tile = xcd_remap(blockIdx.x, gridDim.x);
+    const int tile = xcd_remap(bx, gx);
     // neighbouring workgroups share the larger operand: weights rows (i-major) or pixels (j-major);
     // tile / rf_tile_div by multiply-high (an integer division costs some thirty instructions)
     const int t_hi = (int)(((uint64_t)(uint32_t)tile * p.rf_tile_magic) >> 32), t_lo = tile - t_hi * p.rf_tile_div;
@@ -361,6 +363,27 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
     }
 }
 
+template <int TS, int TAPK, int WGK, int GEO>
+__global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
+    conv_rf_body<TS, TAPK, WGK, GEO>(p, blockIdx.x, gridDim.x);
+}
+
+// Several independent problems of one kernel shape in ONE launch (a region of sibling kernels,
+// paper Sec. 4.3: what a graph-level backend gains over kernels placed one by one is work across
+// kernel boundaries; here, two or more kernels that do not depend on each other share a dispatch
+// and fill the chip together).  Workgroup bx belongs to problem k with tile_end[k-1] <= bx <
+// tile_end[k]; the choice is wave-uniform and the problem's arguments are read from the
+// kernel-argument segment at a uniform offset, so each problem runs exactly the code it runs alone.
+template <int TS, int WGK, int GEO>
+__global__ __launch_bounds__(WGK *kWave) void conv_rf_multi_kernel(RfMultiArgs m) {
+    const int bx = blockIdx.x;
+    int k = 0;
+#pragma unroll
+    for (int i = 0; i + 1 < kMaxRegion; ++i) k += (i + 1 < m.n && bx >= m.tile_end[i]) ? 1 : 0;
+    const int start = k ? m.tile_end[k - 1] : 0;
+    conv_rf_body<TS, 1, WGK, GEO>(m.p[k], bx - start, m.tile_end[k] - start);
+}
+
 // ---- dense: y[m][n] = sum_k x[m][k] * w[n][k] -------------------------------------------------
 // The weights are the A operand (rows i = n, packed), the activations the B
 // operand (columns j = m): lane (slot s, column r) reads 16 bytes of row j0 + r,
@@ -385,7 +408,7 @@ struct RfPark<16> {
 };
 
 template <int TS, int WGK>
-__global__ __launch_bounds__(WGK *kWave) void dense_rf_kernel(GemmArgs p) {
+__device__ __forceinline__ void dense_rf_body(const GemmArgs &p, const int bx, const int gx) {
     using MF = RfMfma<TS>;
     using PK = RfPark<TS>;
     typedef typename MF::acc_t acc_t;
@@ -400,7 +423,7 @@ __global__ __launch_bounds__(WGK *kWave) void dense_rf_kernel(GemmArgs p) {
     const int w = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int r = lane % TS, s = lane / TS;
 
-    const int tile = xcd_remap(blockIdx.x, gridDim.x);
+    const int tile = xcd_remap(bx, gx);
     const int t_hi = (int)(((uint64_t)(uint32_t)tile * p.rf_tile_magic) >> 32), t_lo = tile - t_hi * p.rf_tile_div;
     const int mt = p.rf_jmajor ? t_lo : t_hi;     // weight-row tile
     const int nt = p.rf_jmajor ? t_hi : t_lo;     // activation-row tile
@@ -488,6 +511,23 @@ __global__ __launch_bounds__(WGK *kWave) void dense_rf_kernel(GemmArgs p) {
     }
 }
 
+template <int TS, int WGK>
+__global__ __launch_bounds__(WGK *kWave) void dense_rf_kernel(GemmArgs p) {
+    dense_rf_body<TS, WGK>(p, blockIdx.x, gridDim.x);
+}
+
+// Several dense problems in one launch (see conv_rf_multi_kernel): e.g. the query, key and value
+// projections of an attention layer, which read the same activations.
+template <int TS, int WGK>
+__global__ __launch_bounds__(WGK *kWave) void dense_rf_multi_kernel(RfMultiArgs m) {
+    const int bx = blockIdx.x;
+    int k = 0;
+#pragma unroll
+    for (int i = 0; i + 1 < kMaxRegion; ++i) k += (i + 1 < m.n && bx >= m.tile_end[i]) ? 1 : 0;
+    const int start = k ? m.tile_end[k - 1] : 0;
+    dense_rf_body<TS, WGK>(m.p[k], bx - start, m.tile_end[k] - start);
+}
+
 // Dense weights w [N][K] -> [n-tile][group][lane][4] in the k order above.
 template <int TS>
 __global__ void rf_pack_dense_kernel(const float *w, float *dst, GemmArgs p, int64_t total) {
@@ -539,5 +579,6 @@ __global__ void rf_pack_kernel(const float *w, float *dst, GemmArgs p, int64_t t
 
 // gemm_rf.hip
 int launch_rf_conv(const GemmArgs &a, hipStream_t s);
+int launch_rf_multi(const GemmArgs *members, int n, hipStream_t s);
 
 }  // namespace clg

@@ -92,6 +92,78 @@ int launch_rfd_wgk(const GemmArgs &a, hipStream_t s) {
     }
 }
 
+// geometry variant of the convolution kernel that runs `a` (its fourth template argument)
+int rf_geo(const GemmArgs &a) {
+    if (a.rf_convt) return 1;
+    if (a.rf_fold) return 2;
+    if (a.rf_prelu) return 4;
+    return a.D > 1 ? 3 : 0;
+}
+
+int conv_tiles(const GemmArgs &a) {
+    const int npix = a.rf_convt ? (a.HO / a.sh) * (a.WO / a.sw) : a.HO * a.WO;
+    return ((a.Cout + a.rf_ts - 1) / a.rf_ts) * ((npix + a.rf_ts - 1) / a.rf_ts);
+}
+
+int dense_tiles(const GemmArgs &a) { return ((a.N + a.rf_ts - 1) / a.rf_ts) * ((a.M + a.rf_ts - 1) / a.rf_ts); }
+
+template <int TS, int WGK, int GEO>
+int launch_rf_multi_t(const RfMultiArgs &m, int gy, hipStream_t s) {
+    const size_t lds = WGK > 1 ? (size_t)WGK * RfMfma<TS>::NACC * kWave * sizeof(float) : 0;
+    hipLaunchKernelGGL((conv_rf_multi_kernel<TS, WGK, GEO>), dim3(m.tile_end[m.n - 1], gy, 1), dim3(WGK * kWave), lds, s, m);
+    return (int)hipGetLastError();
+}
+
+template <int TS, int WGK>
+int launch_rf_multi_geo(const RfMultiArgs &m, int geo, int gy, hipStream_t s) {
+    switch (geo) {
+    case 0: return launch_rf_multi_t<TS, WGK, 0>(m, gy, s);
+    case 3: return launch_rf_multi_t<TS, WGK, 3>(m, gy, s);
+    case 4: return launch_rf_multi_t<TS, WGK, 4>(m, gy, s);
+    default: return (int)hipErrorInvalidValue;
+    }
+}
+
+template <int TS>
+int launch_rf_multi_wgk(const RfMultiArgs &m, int wgk, int geo, int gy, hipStream_t s) {
+    switch (wgk) {
+    case 1: return launch_rf_multi_geo<TS, 1>(m, geo, gy, s);
+    case 2: return launch_rf_multi_geo<TS, 2>(m, geo, gy, s);
+    case 4: return launch_rf_multi_geo<TS, 4>(m, geo, gy, s);
+    case 8: return launch_rf_multi_geo<TS, 8>(m, geo, gy, s);
+    case 16: return launch_rf_multi_geo<TS, 16>(m, geo, gy, s);
+    default: return (int)hipErrorInvalidValue;
+    }
+}
+
+template <int TS, int WGK>
+int launch_rfd_multi_t(const RfMultiArgs &m, hipStream_t s) {
+    const size_t lds = (size_t)WGK * RfPark<TS>::PERW * sizeof(float);
+    if (lds > 64 * 1024) {
+        static bool raised = false;
+        if (!raised) {
+            const hipError_t e = hipFuncSetAttribute((const void *)dense_rf_multi_kernel<TS, WGK>,
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return (int)e;
+            raised = true;
+        }
+    }
+    hipLaunchKernelGGL((dense_rf_multi_kernel<TS, WGK>), dim3(m.tile_end[m.n - 1], 1, 1), dim3(WGK * kWave), lds, s, m);
+    return (int)hipGetLastError();
+}
+
+template <int TS>
+int launch_rfd_multi_wgk(const RfMultiArgs &m, int wgk, hipStream_t s) {
+    switch (wgk) {
+    case 1: return launch_rfd_multi_t<TS, 1>(m, s);
+    case 2: return launch_rfd_multi_t<TS, 2>(m, s);
+    case 4: return launch_rfd_multi_t<TS, 4>(m, s);
+    case 8: return launch_rfd_multi_t<TS, 8>(m, s);
+    case 16: return launch_rfd_multi_t<TS, 16>(m, s);
+    default: return (int)hipErrorInvalidValue;
+    }
+}
+
 // K-waves per workgroup: enough to give every wave one chunk.  With `cap_grid`
 // (dense, and the per-MFMA tap path, whose chunks are short) no more than keeps
 // the whole grid at about four waves per SIMD (1024 SIMDs): a tile whose K is
@@ -125,6 +197,38 @@ int launch_rf_conv(const GemmArgs &a, hipStream_t s) {
         return a.rf_ts == 32 ? launch_rfd_wgk<32>(a, s) : launch_rfd_wgk<16>(a, s);
     }
     return a.rf_ts == 32 ? launch_rf_tap<32>(a, s) : launch_rf_tap<16>(a, s);
+}
+
+bool rf_same_launch_shape(const GemmArgs &a, const GemmArgs &b) {
+    if (!a.rf_ts || a.rf_ts != b.rf_ts || a.rf_tapk != b.rf_tapk || a.rf_wgk != b.rf_wgk) return false;
+    if (a.splitk != 1 || b.splitk != 1) return false;
+    if (a.rf_tapk == -1) return true;                         // dense: grid.y = grid.z = 1
+    if (a.rf_tapk != 1) return false;                         // of the convolutions the 1x1 path is built as a region kernel
+    const int ga = rf_geo(a), gb = rf_geo(b);
+    if (ga != gb || (ga != 0 && ga != 3 && ga != 4)) return false;
+    return a.Nimg * (a.DO > 1 ? a.DO : 1) == b.Nimg * (b.DO > 1 ? b.DO : 1);
+}
+
+int launch_rf_multi(const GemmArgs *members, int n, hipStream_t s) {
+    if (n < 2 || n > kMaxRegion) return (int)hipErrorInvalidValue;
+    RfMultiArgs m{};
+    m.n = n;
+    const GemmArgs &a = members[0];
+    const bool dense = a.rf_tapk == -1;
+    int end = 0;
+    for (int k = 0; k < n; ++k) {
+        if (k && !rf_same_launch_shape(a, members[k])) return (int)hipErrorInvalidValue;
+        if (dense && ((uintptr_t)members[k].A & 15) != 0) return (int)hipErrorInvalidValue;
+        end += dense ? dense_tiles(members[k]) : conv_tiles(members[k]);
+        m.tile_end[k] = end;
+        m.p[k] = members[k];
+    }
+    for (int k = n; k < kMaxRegion; ++k) m.tile_end[k] = end;
+    if (dense) return a.rf_ts == 32 ? launch_rfd_multi_wgk<32>(m, a.rf_wgk, s) : launch_rfd_multi_wgk<16>(m, a.rf_wgk, s);
+    const int gy = a.Nimg * (a.DO > 1 ? a.DO : 1);
+    if (gy > 65535) return (int)hipErrorInvalidValue;
+    return a.rf_ts == 32 ? launch_rf_multi_wgk<32>(m, a.rf_wgk, rf_geo(a), gy, s)
+                         : launch_rf_multi_wgk<16>(m, a.rf_wgk, rf_geo(a), gy, s);
 }
 
 bool rf_resolve_dense(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves) {

@@ -120,6 +120,20 @@ struct GemmArgs {
     uint64_t rf_kd_magic;                  // floor(2^32 / KD) + 1
 };
 
+// Several register-fed problems of one kernel shape in one launch (a region of sibling kernels).
+constexpr int kMaxRegion = 4;
+struct RfMultiArgs {
+    int32_t n;                             // problems, 2..kMaxRegion
+    int32_t tile_end[kMaxRegion];          // problem k owns workgroups tile_end[k-1] .. tile_end[k] - 1 of grid.x
+    int32_t pad_[3];
+    GemmArgs p[kMaxRegion];
+};
+// Whether `a` and `b` (both resolved for a register-fed kernel) can share a launch: same kernel
+// instantiation (tile, tap mode, K-waves, geometry variant) and the same grid.y / grid.z extent.
+bool rf_same_launch_shape(const GemmArgs &a, const GemmArgs &b);
+// Launches the members (GemmArgs with all pointers bound and ef filled) as one kernel.
+int launch_gemm_region(const GemmArgs *members, int n, void *stream);
+
 // ---- direct convolution (any groups) -----------------------------------------------------
 struct DirectConvArgs {
     const float *x;

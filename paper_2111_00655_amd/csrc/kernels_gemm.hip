@@ -421,6 +421,16 @@ bool gemv_shape_ok(const GemmArgs &a, int epi_flags) {
            a.ldb % 4 == 0 && a.cs_len == 0 && !(epi_flags & EF_GENERIC);
 }
 
+int launch_gemm_region(const GemmArgs *members, int n, void *stream) {
+    if (n < 2 || n > kMaxRegion) return (int)hipErrorInvalidValue;
+    GemmArgs local[kMaxRegion];
+    for (int k = 0; k < n; ++k) {
+        local[k] = members[k];
+        local[k].ef = make_epi_fast(local[k].epi);
+    }
+    return launch_rf_multi(local, n, (hipStream_t)stream);
+}
+
 int launch_gemm(const GemmArgs &a_in, void *stream) {
     hipStream_t s = (hipStream_t)stream;
     GemmArgs a = a_in;

@@ -49,7 +49,119 @@ std::vector<int32_t> operands_of(const KernelCall &c) {
     return v;
 }
 
+// ---- regions (the graph-level backend, paper Sec. 4.3) -------------------------------------------
+// Whether the call runs a register-fed kernel that also exists in a several-problems-per-launch form.
+bool region_kind(const KernelCall &c) {
+    if (c.kind != CALL_GEMM || !c.gemm.rf_ts || c.gemm.splitk != 1 || !c.pack_bytes) return false;
+    const GemmArgs &a = c.gemm;
+    if (a.rf_tapk == -1) return true;                                  // dense
+    return a.rf_tapk == 1 && !a.rf_convt && !a.rf_fold;               // 1x1 convolution
+}
+
+// Lowers member `c` again for the leader's kernel shape (tile edge, K-waves per workgroup).
+bool relower_for(const Context &ctx, const KernelCall &leader, const KernelCall &c, KernelCall *out) {
+    *out = c;
+    GemmArgs &a = out->gemm;
+    const int ts = leader.gemm.rf_ts, wgk = leader.gemm.rf_wgk;
+    if (a.rf_ts != ts || a.rf_wgk != wgk) {
+        const int flags = epi_fast_flags(a.epi);
+        const bool dense = a.rf_tapk == -1;
+        if (!dense && (a.KD > 1 || a.rf_fold)) return false;
+        const bool ok = dense ? rf_resolve_dense(&a, ts, flags, ctx.n_cus, wgk) : rf_resolve(&a, ts, flags, ctx.n_cus, wgk);
+        if (!ok) return false;
+        out->pack_bytes = rf_pack_bytes(a);
+        out->scratch_bytes = gemm_scratch_bytes(a);
+    }
+    return out->scratch_bytes == 0 && rf_same_launch_shape(leader.gemm, a);
+}
+
+// Finds the regions of a freshly lowered kernel sequence and moves every member next to its region's
+// first one (a member only moves forward past kernels it does not depend on, so the order stays
+// topological).  Greedy and deterministic: scanning in order, a kernel of a fusable kind opens a
+// region; later kernels of the same family join when everything they read was produced before the
+// region's first kernel and the common kernel shape (that of the member with the most flops) takes them.
+void find_regions(const Context &ctx, const Graph &g, Plan *plan) {
+    std::vector<KernelCall> &calls = plan->calls;
+    const size_t nc = calls.size();
+    std::vector<int32_t> produced_at(g.nodes.size(), -1);
+    for (size_t i = 0; i < nc; ++i) produced_at[calls[i].out_node] = (int32_t)i;
+    std::vector<int32_t> reg_of(nc, -1);
+    struct Found { std::vector<int32_t> members; std::vector<KernelCall> fused; };
+    std::vector<Found> found;
+    for (size_t i = 0; i < nc; ++i) {
+        if (reg_of[i] >= 0 || !region_kind(calls[i])) continue;
+        const bool dense = calls[i].gemm.rf_tapk == -1;
+        std::vector<int32_t> cand{(int32_t)i};
+        for (size_t j = i + 1; j < nc && cand.size() < (size_t)kMaxRegion; ++j) {
+            if (reg_of[j] >= 0 || !region_kind(calls[j]) || (calls[j].gemm.rf_tapk == -1) != dense) continue;
+            bool free = true;
+            for (int32_t v : operands_of(calls[j]))
+                if (g.nodes[v].is_op() && produced_at[v] >= (int32_t)i) free = false;
+            if (free) cand.push_back((int32_t)j);
+        }
+        if (cand.size() < 2) continue;
+        int32_t lead = cand[0];
+        for (int32_t c : cand)
+            if (calls[c].flops > calls[lead].flops) lead = c;
+        Found f;
+        for (int32_t c : cand) {
+            KernelCall fc;
+            if (relower_for(ctx, calls[lead], calls[c], &fc)) {
+                f.members.push_back(c);
+                f.fused.push_back(std::move(fc));
+            }
+        }
+        if (f.members.size() < 2 || f.members[0] != (int32_t)i) continue;     // the opener must be in (else try from the next kernel)
+        for (int32_t c : f.members) reg_of[c] = (int32_t)found.size();
+        found.push_back(std::move(f));
+    }
+    plan->regions.clear();
+    plan->region_of.assign(nc, -1);
+    plan->fuse_mark.assign(nc, 0);
+    if (found.empty()) return;
+    // new order: a region's members right behind its first one
+    std::vector<int32_t> order, new_pos(nc, -1);
+    for (size_t i = 0; i < nc; ++i) {
+        if (reg_of[i] >= 0 && found[reg_of[i]].members[0] != (int32_t)i) continue;     // emitted with its region
+        if (reg_of[i] < 0) {
+            new_pos[i] = (int32_t)order.size();
+            order.push_back((int32_t)i);
+        } else {
+            for (int32_t c : found[reg_of[i]].members) {
+                new_pos[c] = (int32_t)order.size();
+                order.push_back(c);
+            }
+        }
+    }
+    std::vector<KernelCall> moved;
+    moved.reserve(nc);
+    for (int32_t c : order) moved.push_back(std::move(calls[c]));
+    calls.swap(moved);
+    for (Found &f : found) {
+        Region r;
+        for (int32_t c : f.members) {
+            r.members.push_back(new_pos[c]);
+            plan->region_of[new_pos[c]] = (int32_t)plan->regions.size();
+        }
+        r.fused = std::move(f.fused);
+        r.packed.assign(r.members.size(), nullptr);
+        plan->regions.push_back(std::move(r));
+    }
+}
+
 }  // namespace
+
+size_t plan_num_launches(const Plan &p) {
+    size_t n = 0;
+    for (size_t i = 0; i < p.calls.size(); ++i) n += p.elided[i] ? 0 : 1;
+    if (p.max_lanes > 1 || p.handed.empty()) return n;
+    for (const Region &r : p.regions) {
+        size_t in = 0;
+        for (int32_t c : r.members) in += p.handed[c] ? 1 : 0;
+        if (in >= 2) n -= in - 1;
+    }
+    return n;
+}
 
 int32_t compile_plan(Context &ctx, Graph &g, const int32_t *ids, size_t n, Plan *plan) {
     g.finalize();
@@ -84,6 +196,7 @@ int32_t compile_plan(Context &ctx, Graph &g, const int32_t *ids, size_t n, Plan 
         if (rc != CLG_OK) return rc;
         plan->calls.push_back(std::move(c));
     }
+    find_regions(ctx, g, plan);
 
     // every operand must be a leaf or the sink of an earlier group
     const size_t nc = plan->calls.size();
@@ -152,9 +265,8 @@ int32_t compile_plan(Context &ctx, Graph &g, const int32_t *ids, size_t n, Plan 
         if (root[v] == v && release_at[v] >= 0 && g.nodes[v].is_op() && plan->value_output[v] < 0)
             releases[(size_t)release_at[v]].push_back(v);
     Arena arena;
-    for (size_t i = 0; i < nc; ++i) {
-        const KernelCall &c = plan->calls[i];
-        const int32_t v = c.out_node, r = root[v];
+    auto place_output = [&](size_t i) {
+        const int32_t v = plan->calls[i].out_node, r = root[v];
         if (plan->value_output[r] >= 0) {
             if (v != r) {
                 plan->value_output[v] = plan->value_output[r];
@@ -164,11 +276,28 @@ int32_t compile_plan(Context &ctx, Graph &g, const int32_t *ids, size_t n, Plan 
             if (plan->value_offset[r] < 0) plan->value_offset[r] = arena.alloc(4 * g.nodes[r].shape.numel());
             plan->value_offset[v] = plan->value_offset[r] + delta[v];
         }
+    };
+    // The members of a region may run as one launch: all their results are placed before any of them
+    // runs, and what they read is released only after the last of them.  The plan so made holds for
+    // every choice of digits (members run one by one use the same buffers in the same order).
+    for (size_t i = 0; i < nc; ++i) {
+        const KernelCall &c = plan->calls[i];
+        const int32_t ri = plan->region_of[i];
+        const bool first_of_region = ri >= 0 && plan->regions[ri].members.front() == (int32_t)i;
+        const bool last_of_region = ri >= 0 && plan->regions[ri].members.back() == (int32_t)i;
+        if (ri < 0) place_output(i);
+        else if (first_of_region)
+            for (int32_t m : plan->regions[ri].members) place_output((size_t)m);
         if (c.scratch_bytes) {
             plan->scratch_offset[i] = arena.alloc((int64_t)c.scratch_bytes);
             arena.release(plan->scratch_offset[i]);
         }
-        for (int32_t r2 : releases[i]) arena.release(plan->value_offset[r2]);
+        if (ri < 0) {
+            for (int32_t r2 : releases[i]) arena.release(plan->value_offset[r2]);
+        } else if (last_of_region) {
+            for (int32_t m : plan->regions[ri].members)
+                for (int32_t r2 : releases[(size_t)m]) arena.release(plan->value_offset[r2]);
+        }
     }
     plan->workspace_bytes = (size_t)arena.peak;
     schedule_lanes(plan);
@@ -192,6 +321,21 @@ int32_t compile_plan(Context &ctx, Graph &g, const int32_t *ids, size_t n, Plan 
             if (rc != CLG_OK) return rc;
             any = true;
         }
+        // a region member whose kernel shape differs inside the region reads a second packed copy
+        for (Region &r : plan->regions)
+            for (size_t k = 0; k < r.members.size(); ++k) {
+                const KernelCall &own = plan->calls[(size_t)r.members[k]], &fc = r.fused[k];
+                if (fc.gemm.rf_ts == own.gemm.rf_ts && fc.gemm.rf_wgk == own.gemm.rf_wgk && fc.pack_bytes == own.pack_bytes) continue;
+                const void *w = g.nodes[fc.b_node].dev_ptr;
+                if (hipMalloc(&r.packed[k], fc.pack_bytes) != hipSuccess) {
+                    (void)hipGetLastError();
+                    r.packed[k] = nullptr;
+                    return fail(CLG_OUT_OF_MEMORY, "allocation of %zu bytes for packed weights failed", fc.pack_bytes);
+                }
+                const int32_t rc = pack_weights(fc, w, r.packed[k], nullptr);
+                if (rc != CLG_OK) return rc;
+                any = true;
+            }
         if (any && hipStreamSynchronize(nullptr) != hipSuccess)
             return fail(CLG_HIP_ERROR, "weight packing failed: %s", hipGetErrorString(hipGetLastError()));
     }
@@ -202,6 +346,9 @@ Plan::~Plan() {
     if (counted && graph) --graph->live_plans;
     for (void *p : packed)
         if (p) (void)hipFree(p);
+    for (Region &r : regions)
+        for (void *p : r.packed)
+            if (p) (void)hipFree(p);
     for (void *e : events)
         if (e) (void)hipEventDestroy((hipEvent_t)e);
     for (void *e : ev_end)
@@ -357,6 +504,24 @@ int32_t pack_weights(const KernelCall &c, const void *w, void *dst, void *stream
     return CLG_OK;
 }
 
+int32_t bind_gemm(const KernelCall &c, const void *a, const void *b, void *out, const void *const *epi_ptrs,
+                  void *scratch, const void *packed, GemmArgs *kp) {
+    GemmArgs &k = *kp;
+    k = c.gemm;
+    k.A = (const float *)a; k.B = (const float *)b; k.C = (float *)out;
+    if (c.gemm_swap) {                               // A = weights, B = activations
+        k.A = (const float *)b; k.B = (const float *)a;
+    }
+    if (c.pack_bytes) {
+        if (!packed) return fail(CLG_INVALID_ARG, "%s needs packed weights, none were prepared", c.name.c_str());
+        if (c.gemm.rf_tapk == -1) k.B = (const float *)packed;      // dense: the weights are the second operand
+        else k.A = (const float *)packed;
+    }
+    k.partial = (float *)scratch;
+    for (int s = 0; s < k.epi.n; ++s) k.epi.s[s].ptr = (const float *)epi_ptrs[s];
+    return CLG_OK;
+}
+
 int32_t launch_call(const KernelCall &c, const void *a, const void *b, const void *c3, void *out,
                     const void *const *epi_ptrs, void *scratch, const void *packed, void *stream) {
     auto bind = [&](Epilogue e) {
@@ -366,18 +531,9 @@ int32_t launch_call(const KernelCall &c, const void *a, const void *b, const voi
     int err = 0;
     switch (c.kind) {
     case CALL_GEMM: {
-        GemmArgs k = c.gemm;
-        k.A = (const float *)a; k.B = (const float *)b; k.C = (float *)out;
-        if (c.gemm_swap) {                               // A = weights, B = activations
-            k.A = (const float *)b; k.B = (const float *)a;
-        }
-        if (c.pack_bytes) {
-            if (!packed) return fail(CLG_INVALID_ARG, "%s needs packed weights, none were prepared", c.name.c_str());
-            if (c.gemm.rf_tapk == -1) k.B = (const float *)packed;      // dense: the weights are the second operand
-            else k.A = (const float *)packed;
-        }
-        k.partial = (float *)scratch;
-        k.epi = bind(c.gemm.epi);
+        GemmArgs k;
+        const int32_t rc = bind_gemm(c, a, b, out, epi_ptrs, scratch, packed, &k);
+        if (rc != CLG_OK) return rc;
         err = launch_gemm(k, stream);
         break;
     }
@@ -504,8 +660,42 @@ int32_t execute_plan(Plan &p, const void *const *inputs, void *const *outputs, v
         return (lanes && p.lane[i] > 0) ? p.side_streams[(size_t)p.lane[i] - 1] : stream;
     };
     int32_t rc = CLG_OK;
+    // regions: with one lane, the handed-over members of a region (two or more) go out as one launch
+    const bool fuse = p.max_lanes <= 1 && !p.handed.empty() && !p.regions.empty();
+    std::vector<char> &done = p.fuse_mark;             // sized at compile time: nothing is allocated here
+    if (fuse) std::fill(done.begin(), done.end(), 0);
     for (size_t i = 0; i < p.calls.size() && rc == CLG_OK; ++i) {
         const KernelCall &c = p.calls[i];
+        if (fuse && done[i]) continue;
+        if (fuse && p.region_of[i] >= 0 && p.handed[i]) {
+            const Region &r = p.regions[(size_t)p.region_of[i]];
+            GemmArgs members[kMaxRegion];
+            size_t idx[kMaxRegion];
+            int nm = 0;
+            for (size_t k = 0; k < r.members.size(); ++k) {
+                const size_t ci = (size_t)r.members[k];
+                if (ci < i || !p.handed[ci]) continue;
+                const KernelCall &fc = r.fused[k];
+                const void *fepi[kMaxEpi];
+                for (int s = 0; s < kMaxEpi; ++s) fepi[s] = ptr_of(fc.epi_nodes[s]);
+                const void *pk = r.packed[k] ? r.packed[k] : p.packed[ci];
+                rc = bind_gemm(fc, ptr_of(fc.a_node), ptr_of(fc.b_node), const_cast<void *>(ptr_of(fc.out_node)), fepi,
+                               nullptr, pk, &members[nm]);
+                if (rc != CLG_OK) break;
+                idx[nm++] = ci;
+            }
+            if (rc != CLG_OK) break;
+            if (nm >= 2) {
+                if (kernel_ns) (void)hipEventRecord(ev[2 * i], (hipStream_t)stream);
+                const int err = launch_gemm_region(members, nm, stream);
+                if (kernel_ns) (void)hipEventRecord(ev[2 * i + 1], (hipStream_t)stream);
+                if (err != 0) rc = fail(CLG_HIP_ERROR, "launch of the region around %s failed: %s", c.name.c_str(),
+                                        hipGetErrorString((hipError_t)err));
+                for (int k = 0; k < nm; ++k) done[idx[k]] = 1;
+                done[i] = 2;                         // carries the region's time
+                continue;
+            }
+        }
         const void *epi[kMaxEpi];
         for (int s = 0; s < kMaxEpi; ++s) epi[s] = ptr_of(c.epi_nodes[s]);
         for (int32_t v : {c.a_node, c.b_node, c.c_node})
@@ -540,7 +730,7 @@ int32_t execute_plan(Plan &p, const void *const *inputs, void *const *outputs, v
             rc = fail(CLG_HIP_ERROR, "stream synchronisation failed: %s", hipGetErrorString(hipGetLastError()));
         for (size_t i = 0; i < p.calls.size() && rc == CLG_OK; ++i) {
             float ms = 0.f;
-            if (p.elided[i]) {
+            if (p.elided[i] || (fuse && done[i] == 1)) {     // nothing launched, or launched with its region's first kernel
                 kernel_ns[i] = 0;
                 continue;
             }

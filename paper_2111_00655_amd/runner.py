@@ -121,8 +121,13 @@ class Plan:
 
     @property
     def n_launches(self):
-        """Kernels one execution launches: the kernel list without the concatenations planned as aliases."""
-        return sum(1 for k in self.kernels() if not k["name"].endswith("_alias"))
+        """Launches of one execution under the current digits: the kernel list without the concatenations
+        planned as aliases, the handed-over members of a region counted once."""
+        return B.clg_plan_num_launches(self.h)
+
+    def regions(self):
+        """Region index of every kernel (-1: in none)."""
+        return [B.clg_plan_region_of(self.h, i) for i in range(self.n_kernels)]
 
     def set_lanes(self, lanes):
         B.clg_plan_set_lanes(self.h, lanes)

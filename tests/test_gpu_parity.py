@@ -855,8 +855,133 @@ def _rand_u32(seed, n=200000):
     return np.random.default_rng(seed).integers(0, 2 ** 32, n, dtype=np.uint64).tolist()
 
 
+# ------------------------------------------------------------------- regions
+def _per_operator_plan(desc, backend="igemm_r16"):
+    """Every operator group on `backend` where it runs it (cost table: the register-fed kernels are cheap)."""
+    reg = wl.default_registry(("igemm_s8", backend), attention=True)
+    s = clg.Session(desc, reg, device=0)
+    ms = s.match()
+    costs = []
+    for i, m in enumerate(ms):
+        try:
+            clg.clg_match_key(s.ctx, s.graph, i)
+            costs.append((10 if reg[m.pattern][0] == backend else 1000) * m.n_nodes)
+        except clg.ClgError:
+            costs.append(B.COST_INF)
+    _, ids = s.search(costs, 0)
+    return s, s.compile(ids).bind()
+
+
+def _dense_branch(d, r, x, k, n, tail, heads=0):
+    y = d.op("dense", [x, d.const(f32(r, n, k, scale=k ** -0.5))])
+    y = d.op("bias_add", [y, d.const(f32(r, n))], axis=-1)
+    for op in tail:
+        y = d.op(op, [y])
+    if heads:
+        m = d.nodes[x]["shape"][0]
+        y = d.op("transpose", [d.op("reshape", [y], dims=(m, heads, n // heads))], dims=(1, 0, 2))
+    return y
+
+
+REGION_DENSE_CASES = {
+    "qkv": [(0, 768, 768, (), 12)] * 3,                                     # BERT's projections: one input, equal shapes
+    "mixed": [(0, 768, 768, (), 12), (0, 768, 3072, ("gelu",), 0), (1, 256, 48, ("relu",), 0), (0, 768, 100, (), 0)],
+    "two_inputs": [(0, 768, 64, ("tanh",), 0), (1, 256, 768, (), 0)],
+}
+
+
+@pytest.mark.parametrize("backend", RF)
+@pytest.mark.parametrize("case", sorted(REGION_DENSE_CASES))
+def test_region_of_sibling_dense_layers(case, backend):
+    """Independent dense layers as one launch (graph-level backend, Sec. 4.3): every subset of the region
+    handed over gives the oracle's values at the per-operator bar."""
+    from parity_util import check_outputs
+    r = rng_for(71, len(case))
+    d = wl.GraphDesc("region_dense_" + case)
+    xs = [d.input(f32(r, 128, 768)), d.input(f32(r, 70, 256))]
+    for which, k, n, tail, heads in REGION_DENSE_CASES[case]:
+        d.mark_output(_dense_branch(d, r, xs[which], k, n, tail, heads))
+    s, plan = _per_operator_plan(d, backend)
+    n = plan.n_kernels
+    rg = plan.regions()
+    assert n == len(REGION_DENSE_CASES[case]) and rg == [0] * n, (rg, [k["name"] for k in plan.kernels()])
+    ref = Graph(d).run()
+    for digits in ([1] * n, [1, 1] + [0] * (n - 2), [0] * (n - 2) + [1, 1], [1] + [0] * (n - 1)):
+        plan.set_handover(digits, lanes=1)
+        assert plan.n_launches == n - max(sum(digits) - 1, 0)
+        got = plan.run()
+        check_outputs(got, ref, OP_TOL, (case, backend, digits))
+        assert all(np.array_equal(a, b) for a, b in zip(got, plan.run()))          # deterministic
+    ns = plan.execute_timed()
+    assert (ns > 0).sum() == plan.n_launches
+    s.close()
+
+
+REGION_CONV_CASES = [
+    # cin, h, [(cout, stride, tail)...]: members read the same input
+    (256, 56, [(512, 2, ("bias_add",)), (128, 1, ("bias_add", "relu"))]),          # ResNet-50 stage 2: projection + c1
+    (1024, 14, [(2048, 2, ("bias_add",)), (512, 1, ("bias_add", "relu"))]),        # stage 4
+    (64, 56, [(256, 1, ("bias_add",)), (64, 1, ("bias_add", "relu"))]),            # stage 1: equal strides
+    (40, 9, [(24, 1, ()), (70, 2, ("bias_add", "relu")), (16, 1, ("bias_add",)), (33, 3, ("bias_add", "tanh"))]),   # ragged, four members
+]
+
+
+@pytest.mark.parametrize("backend", RF)
+@pytest.mark.parametrize("ci", range(len(REGION_CONV_CASES)))
+def test_region_of_sibling_1x1_convolutions(ci, backend):
+    from parity_util import check_outputs
+    cin, h, branches = REGION_CONV_CASES[ci]
+    r = rng_for(72, ci)
+    d = wl.GraphDesc("region_conv")
+    x = d.input(f32(r, 1, cin, h, h))
+    for cout, stride, tail in branches:
+        y = d.op("conv2d", [x, d.const(f32(r, cout, cin, 1, 1, scale=(2.0 / cin) ** 0.5))], stride=(stride, stride), pad=(0, 0), groups=1)
+        for op in tail:
+            y = d.op("bias_add", [y, d.const(f32(r, cout))], axis=1) if op == "bias_add" else d.op(op, [y])
+        d.mark_output(y)
+    s, plan = _per_operator_plan(d, backend)
+    n = plan.n_kernels
+    assert n == len(branches) and plan.regions() == [0] * n, (plan.regions(), [k["name"] for k in plan.kernels()])
+    ref = Graph(d).run()
+    for digits in ([1] * n, [0] * n, [1, 1] + [0] * (n - 2)):
+        plan.set_handover(digits, lanes=1)
+        assert plan.n_launches == n - max(sum(digits) - 1, 0)
+        check_outputs(plan.run(), ref, OP_TOL, (ci, backend, digits))
+    s.close()
+
+
+@pytest.mark.parametrize("name", ["resnet50", "bert_base", "resnext50", "resnet3d_50", "nasnet_a"])
+def test_model_with_every_region_fused(name):
+    """Full size, the benchmark's registry: the searched op-level plan, then every kernel handed over so that
+    each region runs as one launch; outputs against the oracle."""
+    import bench
+    desc = wl.MODEL_BUILDERS[name](0)
+    reg = wl.default_registry(bench.VARIANTS, sepconv=True, attention=True)
+    s = clg.Session(desc, reg, device=0)
+    s.match()
+    costs = s.profile(B.ProfileOpts(warmup=5, batches=3, min_batch_us=100, max_launches=200))
+    _, ids = s.search(costs, 0)
+    plan = s.compile(ids).bind()
+    before = plan.n_launches
+    plan.set_handover([1] * plan.n_kernels, lanes=1)
+    after = plan.n_launches
+    n_regions = max(plan.regions()) + 1
+    print(name, "launches", before, "->", after, "regions", n_regions)
+    if name in ("resnet50", "bert_base", "resnext50", "resnet3d_50"):
+        assert n_regions >= 4 and after <= before - n_regions
+    ref = Graph(desc).run()
+    for _ in range(2):
+        got = plan.run()
+        assert max(norm_err(a, b) for a, b in zip(got, ref)) <= NET_TOL
+    plan.set_handover([0] * plan.n_kernels, lanes=1)
+    assert plan.n_launches == before
+    assert max(norm_err(a, b) for a, b in zip(plan.run(), ref)) <= NET_TOL
+    s.close()
+
+
+@pytest.mark.parametrize("lanes", [1, 3])
 @pytest.mark.parametrize("name", ["resnet_small", "tiny_cnn"])
-def test_graph_level_search_keeps_outputs_and_never_loses_to_the_seed(name):
+def test_graph_level_search_keeps_outputs_and_never_loses_to_the_seed(name, lanes):
     """Sec. 4.3: digit strings over the kernels of the op-level plan, priced by timing the whole
     sequence.  Whatever string wins, the plan must compute the same values as the op-level plan
     (bit for bit: the same kernels, another schedule), equal the oracle, and its measured time is
@@ -872,18 +997,27 @@ def test_graph_level_search_keeps_outputs_and_never_loses_to_the_seed(name):
     plan = s.compile(ids).bind()
     base = plan.run()
     opts = B.make_es_opts(population=6, generations=4, tournament=3, p_init=0.3, p_mutate=0.6, p_flip=0.15, p_cross=0.6)
-    best, best_ns, seed_ns, evals, hist = plan.search_graph_level(opts, _rand_u32(5), lanes=3, warmup=2, batches=2, reps=10)
+    best, best_ns, seed_ns, evals, hist = plan.search_graph_level(opts, _rand_u32(5), lanes=lanes, warmup=2, batches=2, reps=10)
     assert len(best) == plan.n_kernels and set(best) <= {0, 1}
     assert 0 < best_ns <= seed_ns and hist[0] <= seed_ns and hist[-1] == best_ns
     assert all(a >= b for a, b in zip(hist, hist[1:])) and 1 <= evals <= 6 * 5 * 2
+    def same(a_list, b_list):
+        # the lane scheduler runs the same kernels (bit for bit); a region runs its members in one common
+        # tile shape, which adds in another order (to rounding)
+        if lanes > 1:
+            return all(np.array_equal(a, b) for a, b in zip(a_list, b_list))
+        return max(norm_err(a, b) for a, b in zip(a_list, b_list)) <= 1e-5
     got = plan.run()                            # the plan is left set to the best string
-    assert all(np.array_equal(a, b) for a, b in zip(got, base))
-    assert max(norm_err(a, b) for a, b in zip(got, g.run())) <= NET_TOL
+    assert same(got, base)
+    ref = g.run()
+    assert max(norm_err(a, b) for a, b in zip(got, ref)) <= NET_TOL
     # every string gives the same values: all ones, alternating, and back to the seed
     n = plan.n_kernels
     for digits in ([1] * n, [i % 2 for i in range(n)], [0] * n):
-        plan.set_handover(digits, lanes=2)
-        assert all(np.array_equal(a, b) for a, b in zip(plan.run(), base))
+        plan.set_handover(digits, lanes=1 if lanes == 1 else 2)
+        out = plan.run()
+        assert same(out, base) and max(norm_err(a, b) for a, b in zip(out, ref)) <= NET_TOL
+    assert all(np.array_equal(a, b) for a, b in zip(plan.run(), base))      # all zeros: the op-level plan again, bit for bit
     assert plan.n_lanes == 1                    # all zeros is the op-level plan on the caller's stream
     assert plan.measure(warmup=2, batches=2, reps=5) > 0
     plan.destroy()

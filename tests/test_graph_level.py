@@ -215,7 +215,7 @@ def test_handover_digits_on_a_plan():
     with pytest.raises(clg.ClgError, match="digit"):
         plan.set_handover([2] + [0] * (n - 1))
     with pytest.raises(clg.ClgError, match="lanes"):
-        plan.set_handover([0] * n, lanes=1)
+        plan.set_handover([0] * n, lanes=5)
     with pytest.raises(clg.ClgError) as e:                    # no device: nothing to time
         B.clg_plan_measure(plan.h, [256], [256, 256], 256, plan.ws_bytes)
     assert e.value.status == "HIP_ERROR"
@@ -223,3 +223,88 @@ def test_handover_digits_on_a_plan():
     assert plan.n_lanes > 1
     plan.destroy()
     s.close()
+
+
+# ---- regions: sibling kernels that may share a launch (host-only: found and planned without a device) ------
+def _plan_on_register_fed_kernels(d):
+    import workloads as wl
+    import paper_2111_00655_amd as clg
+    reg = wl.default_registry(("igemm_s8", "igemm_r16"), attention=True)
+    s = clg.Session(d, reg, device=None)
+    ms = s.match()
+    costs = []
+    for i, m in enumerate(ms):
+        try:
+            clg.clg_match_key(s.ctx, s.graph, i)
+            costs.append((10 if reg[m.pattern][0] == "igemm_r16" else 1000) * m.n_nodes)
+        except clg.ClgError:
+            costs.append(B.COST_INF)                   # the backend cannot run this match
+    _, ids = s.search(costs, 0)
+    return s, ms, s.compile(ids)
+
+
+def test_regions_of_an_attention_layer_and_of_residual_blocks():
+    import workloads as wl
+    # BERT: the query, key and value projections of a layer read the same activations and are one region
+    d = wl.bert_base(0, layers=2, seq=32, hidden=128, heads=2, ffn=256, vocab=50, max_pos=32)
+    s, ms, plan = _plan_on_register_fed_kernels(d)
+    n = plan.n_kernels
+    rg = plan.regions()
+    assert len(rg) == n and max(rg) == 1                       # one region per layer
+    for r in (0, 1):
+        members = [i for i in range(n) if rg[i] == r]
+        assert len(members) == 3 and members == list(range(members[0], members[0] + 3))      # adjacent in the plan
+        names = {d.nodes[ms[plan.kernels()[i]["match"]].first]["name"].split(".")[1] for i in members}
+        assert names == {"q", "k", "v"}
+    base, ws = plan.n_launches, plan.ws_bytes
+    assert base == n
+    plan.set_handover([1] * n, lanes=1)
+    assert plan.n_launches == n - 4 and plan.n_lanes == 1      # two launches saved per layer
+    assert B.clg_plan_workspace_bytes(plan.h) == ws            # the workspace does not depend on the digits
+    one = [0] * n
+    one[[i for i in range(n) if rg[i] == 0][0]] = 1
+    plan.set_handover(one, lanes=1)
+    assert plan.n_launches == n                                # a lone handed-over member changes nothing
+    two = list(one)
+    two[[i for i in range(n) if rg[i] == 0][2]] = 1
+    plan.set_handover(two, lanes=1)
+    assert plan.n_launches == n - 1                            # the gain needs a sibling: not a sum over digits
+    plan.set_handover([1] * n, lanes=2)
+    assert plan.n_launches == n                                # the lane scheduler fuses nothing
+    plan.set_lanes(1)
+    assert plan.n_launches == n
+    s.close()
+    # ResNet: projection shortcut + first 1x1 convolution of each stage's first block
+    d = wl.resnet50(0, image=64, width=16, blocks=(2, 1, 1), classes=10)
+    s, ms, plan = _plan_on_register_fed_kernels(d)
+    rg = plan.regions()
+    assert max(rg) == 2
+    for r in range(3):
+        firsts = sorted(d.nodes[ms[plan.kernels()[i]["match"]].first]["name"] for i in range(plan.n_kernels) if rg[i] == r)
+        assert firsts == [f"s{r}b0.c1.conv", f"s{r}b0.proj.conv"]
+    s.close()
+
+
+def test_region_members_never_depend_on_each_other():
+    """Whatever the graph: a region's members are adjacent, and none reads a value produced at or after the
+    region's first kernel (checked on the plan's own kernel list through the match list)."""
+    import workloads as wl
+    for d in (wl.nasnet_a(0, image=24, stem=4, filters=4, cells=1, classes=5),
+              wl.resnet3d_50(0, frames=4, image=16, width=8, blocks=(1, 1), classes=5),
+              wl.resnext50(0, image=32, width=8, blocks=(1, 1), groups=4, classes=10)):
+        s, ms, plan = _plan_on_register_fed_kernels(d)
+        ks, rg = plan.kernels(), plan.regions()
+        produced = {}
+        for i, k in enumerate(ks):
+            produced[ms[k["match"]].sink] = i
+        for r in set(rg) - {-1}:
+            members = [i for i in range(len(ks)) if rg[i] == r]
+            assert 2 <= len(members) <= 4 and members == list(range(members[0], members[-1] + 1))
+            for i in members:
+                m = ms[ks[i]["match"]]
+                inside = set(m.nodes[:m.n_nodes])
+                for v in m.nodes[:m.n_nodes]:
+                    for u in d.nodes[v]["inputs"]:
+                        if u not in inside and u in produced:
+                            assert produced[u] < members[0], (d.name, r, i)
+        s.close()
