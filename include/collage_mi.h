@@ -256,7 +256,10 @@ int32_t clg_graph_node_shape(const clg_graph *g, int32_t node, int32_t *dtype,
  *              128, up to 512 keys; the scores never leave the chip
  *   "direct"   direct convolution (any groups), max / average pooling (window
  *              pools also with an elementwise tail), global average pooling
- *   "rowwise"  softmax and layer norm with fused elementwise prologue
+ *   "rowwise"  softmax and layer norm with fused elementwise prologue; also
+ *              layer_norm(add(add(take, take), take), gamma, beta) and the
+ *              two-table form: an embedding's rows gathered, summed and
+ *              normalised in one kernel (row length a multiple of 4, 64..2048)
  *   "eltwise"  elementwise chains, embedding gather, layout copies, concat
  * Returns UNKNOWN_ID for any other name.  Registering a name twice returns
  * the same id.  Registration order of patterns is significant: it is the
@@ -368,8 +371,10 @@ int32_t clg_search_dp(clg_ctx *ctx, clg_graph *g, const int64_t *cost_ns,
  * returns the cost of a string measured on the whole graph (lower is better;
  * NaN aborts the search with INVALID_ARG); it is called once per distinct
  * string, from the calling thread.
- * The population is the all-zero string plus population-1 strings whose
- * digits are 1 with probability p_init.  One generation: every string mutates
+ * The population is the all-zero string (the op-level placement, the seed the
+ * paper names) plus population-1 strings whose digits are 1 with probability
+ * p_init; with seed_ones the first of those is instead the all-ones string, a
+ * second seed from the other end of the search space.  One generation: every string mutates
  * with probability p_mutate (each digit then flips with probability p_flip);
  * `population` tournaments of `tournament` entrants drawn with replacement
  * choose the next population (an entrant wins only when strictly cheaper);
@@ -394,6 +399,11 @@ typedef struct clg_es_opts {
     int32_t tournament;      /* >= 1                                  */
     int32_t patience;        /* 0 = run all generations               */
     double p_init, p_mutate, p_flip, p_cross;   /* each in [0, 1]     */
+    int32_t seed_ones;       /* 1: the second string of the first population is
+                                all ones (everything handed over) instead of a
+                                random one; needs population >= 2 and uses n
+                                fewer draws                                   */
+    int32_t reserved_;
 } clg_es_opts;
 int32_t clg_evolve(size_t n, const clg_es_opts *opts, const uint32_t *rand,
                    size_t n_rand, clg_fitness_fn fitness, void *user,

@@ -17,7 +17,9 @@ readings taken here:
    result, and the earlier one wins a tie, so the result never costs more than
    the all-zero seed;
  * population: the seed, then `population - 1` strings whose digits are 1 with
-   probability `p_init`;
+   probability `p_init`; the paper makes the op-level placement "one of the
+   seeds" without naming the others: with `seed_ones` the second string is all
+   ones (every operator offloaded), the other end of the search space;
  * a generation, in the paper's order: (1) every string is mutated with
    probability `p_mutate`, each of its digits then flipping with probability
    `p_flip`; (2) `population` tournaments of `tournament` entrants drawn with
@@ -55,7 +57,7 @@ class Draws:
 
 
 def evolve(n, fitness, rand, population=8, generations=10, tournament=3, patience=0,
-           p_init=0.25, p_mutate=0.5, p_flip=0.1, p_cross=0.5):
+           p_init=0.25, p_mutate=0.5, p_flip=0.1, p_cross=0.5, seed_ones=False):
     """Returns (best digits, best fitness, evaluations, history) where history[g]
     is the best fitness after generation g-1 (history[0]: the initial population)."""
     d = Draws(rand)
@@ -71,8 +73,11 @@ def evolve(n, fitness, rand, population=8, generations=10, tournament=3, patienc
         return known[key]
 
     pop = [[0] * n]
-    for _ in range(population - 1):
-        pop.append([1 if d.chance(p_init) else 0 for _ in range(n)])
+    for i in range(1, population):
+        if i == 1 and seed_ones:                          # a second seed: every operator offloaded
+            pop.append([1] * n)
+        else:
+            pop.append([1 if d.chance(p_init) else 0 for _ in range(n)])
     for ind in pop:
         fit(ind)
     history = [state["fit"]]

@@ -75,15 +75,15 @@ class Match(C.Structure):
 class EsOpts(C.Structure):
     _fields_ = [("population", C.c_int32), ("generations", C.c_int32), ("tournament", C.c_int32),
                 ("patience", C.c_int32), ("p_init", C.c_double), ("p_mutate", C.c_double),
-                ("p_flip", C.c_double), ("p_cross", C.c_double)]
+                ("p_flip", C.c_double), ("p_cross", C.c_double), ("seed_ones", C.c_int32), ("reserved_", C.c_int32)]
 
 
 FITNESS_FN = C.CFUNCTYPE(C.c_double, C.POINTER(C.c_uint8), C.c_size_t, C.c_void_p)
 
 
 def make_es_opts(population=8, generations=10, tournament=3, patience=0,
-                 p_init=0.25, p_mutate=0.5, p_flip=0.1, p_cross=0.5):
-    return EsOpts(population, generations, tournament, patience, p_init, p_mutate, p_flip, p_cross)
+                 p_init=0.25, p_mutate=0.5, p_flip=0.1, p_cross=0.5, seed_ones=False):
+    return EsOpts(population, generations, tournament, patience, p_init, p_mutate, p_flip, p_cross, int(bool(seed_ones)), 0)
 
 
 class MeasureOpts(C.Structure):

@@ -409,6 +409,7 @@ static int32_t check_es_opts(const clg_es_opts *o) {
     if (o->generations < 0) return fail(CLG_INVALID_ARG, "generations %d", o->generations);
     if (o->tournament < 1 || o->tournament > 4096) return fail(CLG_INVALID_ARG, "tournament must be 1..4096 (got %d)", o->tournament);
     if (o->patience < 0) return fail(CLG_INVALID_ARG, "patience %d", o->patience);
+    if (o->seed_ones != 0 && o->seed_ones != 1) return fail(CLG_INVALID_ARG, "seed_ones %d", o->seed_ones);
     for (double p : {o->p_init, o->p_mutate, o->p_flip, o->p_cross})
         if (!(p >= 0.0 && p <= 1.0)) return fail(CLG_INVALID_ARG, "a probability is outside [0, 1]");
     return CLG_OK;

@@ -106,6 +106,10 @@ struct Pattern {
     // main_arg[t] = which argument of chain[t] holds chain[t-1] (-1 for the anchor)
     std::vector<int32_t> chain;
     std::vector<int32_t> main_arg;
+    // the one tree-shaped fused kind: layer_norm(add(add(take, take), take), *, *) - an embedding's rows
+    // gathered, summed and normalised in one kernel; gather[k] = pattern node of the k-th take, in the
+    // order the sums are taken ((0 + 1) + 2)
+    std::vector<int32_t> gather;
 };
 
 struct Context {

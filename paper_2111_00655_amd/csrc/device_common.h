@@ -44,6 +44,24 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
+// Sum over the 64 lanes on the data-parallel-primitive path of the vector ALU (no LDS traffic, unlike
+// the general lane shuffle): four steps give every lane the sum of its row of 16 lanes, the four row
+// sums are then read as scalars and added in row order.  Every lane gets the same value.
+template <int CTRL>
+__device__ __forceinline__ float dpp_lane(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+__device__ __forceinline__ float wave_sum_dpp(float v) {
+    v += dpp_lane<0xB1>(v);      // quad_perm [1,0,3,2]
+    v += dpp_lane<0x4E>(v);      // quad_perm [2,3,0,1]
+    v += dpp_lane<0x141>(v);     // row_half_mirror
+    v += dpp_lane<0x140>(v);     // row_mirror
+    return (__int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0)) +
+            __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16))) +
+           (__int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32)) +
+            __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48)));
+}
+
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
     for (int m = kWave / 2; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, kWave));

@@ -60,8 +60,13 @@ int32_t evolve(size_t n, const clg_es_opts &o, const uint32_t *rand, size_t n_ra
     Stream rs{rand, n_rand};
     Ledger led{fn, user, {}, {}, 0, false, false};
     std::vector<Digits> pop(P, Digits(n, 0));
-    for (size_t i = 1; i < P; ++i)
+    for (size_t i = 1; i < P; ++i) {
+        if (i == 1 && o.seed_ones) {
+            pop[i].assign(n, 1);                   // the second seed: everything handed over
+            continue;
+        }
         for (size_t b = 0; b < n; ++b) pop[i][b] = rs.chance(o.p_init) ? 1 : 0;
+    }
     if (rs.dry) return fail(CLG_INVALID_ARG, "random draws exhausted while building the population");
     for (auto &d : pop) led.of(d);
     if (led.failed) return fail(CLG_INVALID_ARG, "the fitness function returned NaN");

@@ -213,6 +213,13 @@ struct RowwiseArgs {
     const float *beta;
     float *y;
     Epilogue pro;                          // applied to x first; channel = column
+    // layer norm over a sum of gathered rows (an embedding: word + position + type rows): n_gather = 2 or 3,
+    // the row is ((tab[0][gid[0][r]] + tab[1][gid[1][r]]) + tab[2][gid[2][r]]), x and pro are unused.
+    // Ids outside a table are clamped into it.
+    int32_t n_gather;
+    int32_t tab_rows[3];
+    const float *tab[3];
+    const int32_t *gid[3];
 };
 
 // ---- elementwise chain / gather --------------------------------------------------------------

@@ -197,6 +197,96 @@ __global__ __launch_bounds__(256) void rowwise_block_kernel(RowwiseArgs a) {
     }
 }
 
+// Layer norm, a wave per row and a row per workgroup, for the transformer's shapes (128 rows of 768):
+// every load of the row - the value, the fused bias and residual, gamma and beta, 16 bytes per lane
+// each - is issued before anything is computed, so the kernel pays one memory round trip; the two
+// reductions stay inside the wave (no LDS, no barrier).  The row comes from x with an optional
+// [bias] [residual add] in front (the common form of a fused prologue), or is the sum of two or three
+// gathered table rows (an embedding).  Same arithmetic as above: mean, biased variance of the centred
+// values, scale and shift.  len % 4 == 0, len <= 256 * V4, all pointers 16-byte aligned.
+template <int V4>
+__global__ __launch_bounds__(64) void ln_wave_kernel(RowwiseArgs a, EpiFast ef) {
+    const int lane = threadIdx.x;
+    const int row = blockIdx.x;
+    const int len4 = a.len >> 2;
+    const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+    float4 v[V4], t1[V4], t2[V4], ga[V4], be[V4];
+    const float4 *p0, *p1 = nullptr, *p2 = nullptr;
+    if (a.n_gather) {
+        auto row_of = [&](int k) {
+            int id = a.gid[k][row];
+            id = id < 0 ? 0 : (id >= a.tab_rows[k] ? a.tab_rows[k] - 1 : id);
+            return reinterpret_cast<const float4 *>(a.tab[k] + (int64_t)id * a.len);
+        };
+        p0 = row_of(0);
+        p1 = row_of(1);
+        if (a.n_gather > 2) p2 = row_of(2);
+    } else {
+        p0 = reinterpret_cast<const float4 *>(a.x + (int64_t)row * a.len);
+        if (ef.flags & EF_BIAS) p1 = reinterpret_cast<const float4 *>(ef.bias);
+        if (ef.flags & EF_ADD) p2 = reinterpret_cast<const float4 *>(ef.add + (int64_t)row * a.len);
+    }
+    const float4 *g4 = reinterpret_cast<const float4 *>(a.gamma), *b4 = reinterpret_cast<const float4 *>(a.beta);
+#pragma unroll
+    for (int q = 0; q < V4; ++q) {
+        const int c = lane + kWave * q;
+        const bool in = c < len4;
+        const int cc = in ? c : 0;
+        v[q] = p0[cc];
+        t1[q] = p1 ? p1[cc] : zero;
+        t2[q] = p2 ? p2[cc] : zero;
+        ga[q] = g4[cc];
+        be[q] = b4[cc];
+        if (!in) v[q] = t1[q] = t2[q] = zero;
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int q = 0; q < V4; ++q) {
+        // the operators' own order, one rounding each: (x + bias) + residual, or (row0 + row1) + row2
+        if (p1) { v[q].x += t1[q].x; v[q].y += t1[q].y; v[q].z += t1[q].z; v[q].w += t1[q].w; }
+        if (p2) { v[q].x += t2[q].x; v[q].y += t2[q].y; v[q].z += t2[q].z; v[q].w += t2[q].w; }
+        sum += (v[q].x + v[q].y) + (v[q].z + v[q].w);
+    }
+    const float mean = wave_sum_dpp(sum) / (float)a.len;
+    float sq = 0.f;
+#pragma unroll
+    for (int q = 0; q < V4; ++q) {
+        if (lane + kWave * q < len4) {
+            v[q].x -= mean; v[q].y -= mean; v[q].z -= mean; v[q].w -= mean;
+        }
+        sq += (v[q].x * v[q].x + v[q].y * v[q].y) + (v[q].z * v[q].z + v[q].w * v[q].w);
+    }
+    const float inv = 1.0f / sqrtf(wave_sum_dpp(sq) / (float)a.len + a.eps);
+    float4 *y4 = reinterpret_cast<float4 *>(a.y + (int64_t)row * a.len);
+#pragma unroll
+    for (int q = 0; q < V4; ++q) {
+        const int c = lane + kWave * q;
+        if (c < len4)
+            y4[c] = make_float4(v[q].x * inv * ga[q].x + be[q].x, v[q].y * inv * ga[q].y + be[q].y,
+                                v[q].z * inv * ga[q].z + be[q].z, v[q].w * inv * ga[q].w + be[q].w);
+    }
+}
+
+// Whether the one-round-trip layer norm takes these arguments; fills *ef with the prologue's common form.
+static bool ln_wave_ok(const RowwiseArgs &a, EpiFast *ef) {
+    if (a.mode != 1 || a.len % 4 || a.len > 256 * 8 || a.len < 64 || a.rows > 65535 * 16) return false;
+    auto al = [](const void *p) { return ((uintptr_t)p & 15) == 0; };
+    if (!al(a.y) || !al(a.gamma) || !al(a.beta)) return false;
+    ef->flags = 0;
+    if (a.n_gather) {
+        for (int k = 0; k < a.n_gather; ++k)
+            if (!al(a.tab[k]) || a.tab_rows[k] < 1) return false;
+        return a.n_gather == 2 || a.n_gather == 3;
+    }
+    *ef = make_epi_fast(a.pro);
+    if (ef->flags & ~(EF_BIAS | EF_ADD)) return false;
+    if (ef->flags & EF_BIAS) {
+        if (a.pro.bias_inner != 1 || a.pro.bias_c != a.len || !al(ef->bias)) return false;
+    }
+    if ((ef->flags & EF_ADD) && !al(ef->add)) return false;
+    return al(a.x);
+}
+
 // Rows longer than 64 * 32: same arithmetic, the row is re-read per pass.
 __global__ __launch_bounds__(256) void rowwise_long_kernel(RowwiseArgs a) {
     const int lane = threadIdx.x & (kWave - 1);
@@ -233,6 +323,16 @@ int launch_rowwise(const RowwiseArgs &a, void *stream) {
     const dim3 grid((a.rows + rows_per_block - 1) / rows_per_block);
     const int items = (a.len + kWave - 1) / kWave;
     hipStream_t s = (hipStream_t)stream;
+    EpiFast ef{};
+    if (a.rows <= 4096 && ln_wave_ok(a, &ef)) {                    // layer norm in one memory round trip
+        const int v4 = (a.len / 4 + kWave - 1) / kWave;
+        if (v4 <= 1) hipLaunchKernelGGL(ln_wave_kernel<1>, dim3(a.rows), dim3(kWave), 0, s, a, ef);
+        else if (v4 <= 2) hipLaunchKernelGGL(ln_wave_kernel<2>, dim3(a.rows), dim3(kWave), 0, s, a, ef);
+        else if (v4 <= 4) hipLaunchKernelGGL(ln_wave_kernel<4>, dim3(a.rows), dim3(kWave), 0, s, a, ef);
+        else hipLaunchKernelGGL(ln_wave_kernel<8>, dim3(a.rows), dim3(kWave), 0, s, a, ef);
+        return (int)hipGetLastError();
+    }
+    if (a.n_gather) return (int)hipErrorInvalidValue;              // only the kernel above gathers
     if (a.len > 256 && a.len <= 2048 && a.rows <= 1024) {          // few long rows: a workgroup per row
         const int bi = (a.len + 255) / 256;
         if (bi <= 2) hipLaunchKernelGGL(rowwise_block_kernel<2>, dim3(a.rows), dim3(256), 0, s, a);

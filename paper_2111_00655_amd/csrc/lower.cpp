@@ -57,6 +57,34 @@ int32_t check_pattern(const Context &ctx, Pattern *p) {
         if (!used[i]) return fail(CLG_INVALID_ARG, "pattern node %d is unreachable from the root", i);
     if (p->nodes[n - 1].op == CLG_WILDCARD) return fail(CLG_INVALID_ARG, "the root is a wildcard");
 
+    // The row-wise family also takes one tree: layer norm over the sum of two or three gathered rows.
+    p->gather.clear();
+    if (ctx.backends[p->backend].family == FAM_ROWWISE && p->nodes[n - 1].op == CLG_OP_LAYER_NORM && p->nodes[n - 1].n_args == 3) {
+        auto is_take = [&](int i) {
+            const clg_pattern_node &t = p->nodes[i];
+            return t.op == CLG_OP_TAKE && t.n_args == 2 && p->nodes[t.args[0]].op == CLG_WILDCARD && p->nodes[t.args[1]].op == CLG_WILDCARD;
+        };
+        const clg_pattern_node &ln = p->nodes[n - 1];
+        const clg_pattern_node &top = p->nodes[ln.args[0]];
+        if (top.op == CLG_OP_ADD && top.n_args == 2 && p->nodes[ln.args[1]].op == CLG_WILDCARD && p->nodes[ln.args[2]].op == CLG_WILDCARD) {
+            std::vector<int32_t> takes;
+            const int l = top.args[0], r = top.args[1];
+            auto inner = [&](int i) {                      // add(take, take)
+                const clg_pattern_node &a = p->nodes[i];
+                return a.op == CLG_OP_ADD && a.n_args == 2 && is_take(a.args[0]) && is_take(a.args[1]);
+            };
+            if (is_take(l) && is_take(r)) takes = {l, r};
+            else if (inner(l) && is_take(r)) takes = {p->nodes[l].args[0], p->nodes[l].args[1], r};
+            else if (is_take(l) && inner(r)) takes = {p->nodes[r].args[0], p->nodes[r].args[1], l};
+            if (!takes.empty()) {
+                p->gather = takes;
+                p->chain = {n - 1};
+                p->main_arg = {-1};
+                return CLG_OK;
+            }
+        }
+    }
+
     // chain view
     p->chain.clear();
     p->main_arg.clear();
@@ -257,6 +285,7 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
     };
     std::string kinds;
     for (int t = 0; t < len; ++t) kinds += std::string(t ? "+" : "") + op_name(cv.op(t));
+    if (!p.gather.empty()) kinds = "take*" + std::to_string(p.gather.size()) + "+add+layer_norm";
     char abuf[160];
     std::snprintf(abuf, sizeof abuf, "s%dx%d,p%dx%d,g%d,tb%d,k%dx%d,d%d.%d.%d,ax%d", anchor.attrs.stride[0], anchor.attrs.stride[1],
                   anchor.attrs.pad[0], anchor.attrs.pad[1], anchor.attrs.groups > 0 ? anchor.attrs.groups : 1,
@@ -265,7 +294,40 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
 
     Epilogue epi{};
     int32_t rc = CLG_OK;
-    if (be.family == FAM_ATTENTION) {
+    bool gathered = false;
+    if (!p.gather.empty()) {
+        // layer_norm(add(add(take, take), take), gamma, beta): tables in the pointer slots 0..2 of the fused
+        // steps, ids in 3..5
+        RowwiseArgs &a = c.row;
+        const Node &root = g.nodes[m.sink];
+        a.mode = 1;
+        a.len = (int)root.shape.d[root.shape.ndim - 1];
+        a.rows = (int)(root.shape.numel() / a.len);
+        a.eps = (float)root.attrs.eps;
+        a.n_gather = (int32_t)p.gather.size();
+        for (size_t k = 0; k < p.gather.size(); ++k) {
+            const clg_pattern_node &tk = p.nodes[p.gather[k]];
+            const int32_t tab = m.wild[tk.args[0]], ids = m.wild[tk.args[1]];
+            const Shape &ts = g.nodes[tab].shape, &is = g.nodes[ids].shape;
+            if (ts.ndim != 2 || ts.d[1] != a.len || is.numel() != a.rows || g.nodes[ids].dtype != CLG_I32)
+                return fail(CLG_NO_KERNEL, "embedding layer norm: every table must be [rows, %d] and every id list hold %d ids", a.len, a.rows);
+            a.tab_rows[k] = (int32_t)ts.d[0];
+            c.epi_nodes[k] = tab;
+            c.epi_nodes[3 + k] = ids;
+            use(ids);
+        }
+        if (a.len % 4 || a.len < 64 || a.len > 2048)
+            return fail(CLG_NO_KERNEL, "embedding layer norm: row length must be a multiple of 4 in 64..2048");
+        const clg_pattern_node &ln = p.nodes[p.nodes.size() - 1];
+        c.a_node = c.epi_nodes[0];
+        c.b_node = m.wild[ln.args[1]];
+        c.c_node = m.wild[ln.args[2]];
+        use(c.b_node);
+        use(c.c_node);
+        c.kind = CALL_ROWWISE;
+        c.name = "embed" + std::to_string(a.n_gather) + "_layer_norm";
+        gathered = true;
+    } else if (be.family == FAM_ATTENTION) {
         AttentionArgs &a = c.att;
         int t = 1;
         a.scale = 1.f;
@@ -786,6 +848,7 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
     double bytes = 4.0 * (double)out_shape.numel();
     for (int32_t v : ext) bytes += 4.0 * (double)g.nodes[v].shape.numel();
     if (k0 == CLG_OP_TAKE) bytes += 4.0 * (double)out_shape.numel();   // the gathered rows, not the table
+    if (gathered) bytes += 4.0 * (double)out_shape.numel() * (double)p.gather.size();
     c.bytes = bytes;
 
     std::string key = be.name + "|" + kinds + "|" + abuf + "|";

@@ -555,6 +555,11 @@ int32_t launch_call(const KernelCall &c, const void *a, const void *b, const voi
         RowwiseArgs k = c.row;
         k.x = (const float *)a; k.gamma = (const float *)b; k.beta = (const float *)c3; k.y = (float *)out;
         k.pro = bind(c.row.pro);
+        for (int t = 0; t < k.n_gather; ++t) {           // an embedding: tables and id lists ride in the step slots
+            k.tab[t] = (const float *)epi_ptrs[t];
+            k.gid[t] = (const int32_t *)epi_ptrs[3 + t];
+        }
+        if (k.n_gather) k.x = nullptr;
         err = launch_rowwise(k, stream);
         break;
     }

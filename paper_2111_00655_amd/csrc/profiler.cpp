@@ -171,7 +171,8 @@ int32_t profile_match(Context &ctx, Graph &g, int32_t match, const clg_profile_o
         if (g.nodes[v].dtype == CLG_I32) {
             // the only int32 operand is a gather's row ids: seeded ids spread over the table (all zeros would
             // time the gather of one cache-hot row)
-            const int32_t rows = c.kind == CALL_ELTWISE && c.elt.table_rows > 0 ? c.elt.table_rows : 1;
+            int32_t rows = c.kind == CALL_ELTWISE && c.elt.table_rows > 0 ? c.elt.table_rows : 1;
+            if (c.kind == CALL_ROWWISE && c.row.n_gather && i >= 6 && i < 9) rows = c.row.tab_rows[i - 6];
             const int e = launch_fill_ids((int32_t *)(base + offs[i]), n, rows, o.seed + 7919u * (uint64_t)i, nullptr);
             if (e) return hip_fail("id fill kernel", (hipError_t)e);
         } else {

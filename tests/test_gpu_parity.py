@@ -578,6 +578,27 @@ def test_take_and_embedding_sum():
     run_single_group(d, "eltwise", P("add", P("add", P("take", W, W), W), W), tol=1e-6)
 
 
+@pytest.mark.parametrize("case", [(1000, 128, 768, 3), (100, 17, 64, 3), (50, 5, 2048, 2), (300, 33, 700, 3)])
+def test_embedding_layer_norm_in_one_kernel(case):
+    """layer_norm(add(add(take, take), take)): the rows of three tables gathered, summed and normalised by one
+    kernel (BERT's embedding: word + position + type), and the two-table form."""
+    vocab, L, H, n_tab = case
+    r = rng_for(18, vocab, L, H)
+    d = wl.GraphDesc("embed_ln")
+    ids = d.input(r.integers(0, vocab, L).astype(np.int32))
+    e = d.op("take", [d.const(f32(r, vocab, H, scale=0.02)), ids])
+    pat = P("take", W, W)
+    e = d.op("add", [e, d.op("take", [d.const(f32(r, L + 3, H, scale=0.02)), d.const(np.arange(L, dtype=np.int32))])])
+    pat = P("add", pat, P("take", W, W))
+    if n_tab == 3:
+        e = d.op("add", [e, d.op("take", [d.const(f32(r, 2, H, scale=0.02)), d.const(np.zeros(L, dtype=np.int32))])])
+        pat = P("add", pat, P("take", W, W))
+    g_, b_ = (1 + 0.02 * r.standard_normal(H)).astype(np.float32), f32(r, H, scale=0.02)
+    d.mark_output(d.op("layer_norm", [e, d.const(g_), d.const(b_)], eps=1e-12))
+    name, _ = run_single_group(d, "rowwise", P("layer_norm", pat, W, W), tol=2e-5)
+    assert name == f"embed{n_tab}_layer_norm", name
+
+
 def test_layout_copies():
     r = rng_for(13)
     x = f32(r, 16, 96)
@@ -886,7 +907,7 @@ def _dense_branch(d, r, x, k, n, tail, heads=0):
 REGION_DENSE_CASES = {
     "qkv": [(0, 768, 768, (), 12)] * 3,                                     # BERT's projections: one input, equal shapes
     "mixed": [(0, 768, 768, (), 12), (0, 768, 3072, ("gelu",), 0), (1, 256, 48, ("relu",), 0), (0, 768, 100, (), 0)],
-    "two_inputs": [(0, 768, 64, ("tanh",), 0), (1, 256, 768, (), 0)],
+    "two_inputs": [(0, 768, 64, ("relu",), 0), (1, 256, 768, (), 0)],
 }
 
 
@@ -922,7 +943,7 @@ REGION_CONV_CASES = [
     (256, 56, [(512, 2, ("bias_add",)), (128, 1, ("bias_add", "relu"))]),          # ResNet-50 stage 2: projection + c1
     (1024, 14, [(2048, 2, ("bias_add",)), (512, 1, ("bias_add", "relu"))]),        # stage 4
     (64, 56, [(256, 1, ("bias_add",)), (64, 1, ("bias_add", "relu"))]),            # stage 1: equal strides
-    (40, 9, [(24, 1, ()), (70, 2, ("bias_add", "relu")), (16, 1, ("bias_add",)), (33, 3, ("bias_add", "tanh"))]),   # ragged, four members
+    (40, 9, [(24, 1, ()), (70, 2, ("bias_add", "relu")), (16, 1, ("bias_add",)), (33, 3, ("bias_add", "relu"))]),   # ragged, four members
 ]
 
 

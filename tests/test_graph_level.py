@@ -98,6 +98,24 @@ def test_oracle_finds_the_exhaustive_minimum_on_small_strings():
         assert evals <= 2 ** n
 
 
+def test_oracle_second_seed_is_all_ones():
+    # with seed_ones the strings measured first are all zeros, then all ones; the random members come after and
+    # use (population - 2) * n draws; without mutation and crossover nothing else is ever measured
+    n = 5
+    seen = []
+
+    def f(b):
+        seen.append(tuple(b))
+        return float(10 - sum(b))                              # all ones is the optimum
+    d = draws(4, (4 - 2) * n + 3 * 4 * 3 + 3 * 4 + 3 * 2)      # initial strings + 3 generations of mutation / selection / crossover draws
+    best, c, evals, hist = oe.evolve(n, f, d, population=4, generations=3, tournament=3, p_init=0.5, p_mutate=0.0, p_cross=0.0,
+                                     seed_ones=True)
+    assert seen[0] == (0,) * n and seen[1] == (1,) * n and len(seen) <= 4
+    assert best == [1] * n and c == 5.0 and hist[0] == 5.0
+    with pytest.raises(ValueError):                            # one draw fewer is one too few
+        oe.evolve(n, f, d[:-1], population=4, generations=3, tournament=3, p_init=0.5, p_mutate=0.0, p_cross=0.0, seed_ones=True)
+
+
 def test_oracle_without_mutation_and_crossover_only_selects():
     n = 8
     cost = random_cost_table(n, 5)
@@ -152,7 +170,7 @@ def test_library_equals_oracle(seed):
     n = int(r.integers(1, 40))
     opts = dict(population=int(r.integers(2, 12)), generations=int(r.integers(0, 15)), tournament=int(r.integers(1, 5)),
                 patience=int(r.integers(0, 4)), p_init=float(r.uniform(0, 1)), p_mutate=float(r.uniform(0, 1)),
-                p_flip=float(r.uniform(0, 0.5)), p_cross=float(r.uniform(0, 1)))
+                p_flip=float(r.uniform(0, 0.5)), p_cross=float(r.uniform(0, 1)), seed_ones=bool(seed % 2))
     cost = random_cost_table(n, seed)
     rand = draws(seed, 40000)
     want = oe.evolve(n, cost, rand, **opts)

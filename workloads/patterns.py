@@ -84,7 +84,9 @@ def default_registry(variants=("igemm",), sepconv=False, attention=False):
     add("rowwise", [P("softmax", W), P("layer_norm", W, W, W),
                     P("softmax", P("mul_scalar", W)),
                     P("layer_norm", P("add", W, W), W, W),
-                    P("layer_norm", P("add", P("bias_add", W, W), W), W, W)])
+                    P("layer_norm", P("add", P("bias_add", W, W), W), W, W),
+                    # an embedding: three table rows gathered, summed and normalised (the one tree-shaped kind)
+                    P("layer_norm", P("add", P("add", P("take", W, W), P("take", W, W)), P("take", W, W)), W, W)])
 
     # --- direct (non-GEMM) spatial kernels: any conv incl. grouped, pools
     conv_any = P("conv2d", W, W)
