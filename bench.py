@@ -27,7 +27,7 @@ PEAK_MFMA_F32_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
 PEAK_HBM_GBPS = 8000.0            # MI355X HBM3E
 # the MFMA kernel variants registered as separate backends; the search picks one per fused subgraph
 VARIANTS = ("igemm", "igemm_s", "igemm_s8", "igemm_s16", "igemm_m", "igemm_l", "igemm_s_nk", "igemm_s8_nk",
-            "igemm_s16_nk", "igemm_r32", "igemm_r16")
+            "igemm_s16_nk", "igemm_r32", "igemm_r16", "igemm_r32_w4", "igemm_r32_w8", "igemm_r16_w4", "igemm_r16_w8")
 
 
 # HBM-side traffic of the fp32 MFMA kernels of one ResNet-50 step, from two rocprofv3 --pmc runs of this file
@@ -344,6 +344,8 @@ def main():
                     help="also price a few compute-bound single operators (large dense, batch-32 3x3 convolutions) under every "
                          "MFMA kernel variant with the library's measurer and write TFLOP/s per variant to FILE: what the "
                          "kernels reach where launch and memory latency do not bound them")
+    ap.add_argument("--variants", default="", metavar="NAME,...",
+                    help="register only these MFMA kernel-variant backends instead of all of them")
     ap.add_argument("--summary", default="", metavar="FILE",
                     help="write a short text summary of the run (headline figure, and whichever of --ablation, --batch-sweep, "
                          "--graph-level were asked for, and the measurer's run-to-run spread) with the command that made it")
@@ -363,7 +365,8 @@ def main():
     import workloads as wl
     from paper_2111_00655_amd import binding as B
 
-    reg = wl.default_registry(VARIANTS, sepconv=True, attention=True)
+    variants = tuple(args.variants.split(",")) if args.variants else VARIANTS
+    reg = wl.default_registry(variants, sepconv=True, attention=True)
     opts = B.ProfileOpts(warmup=10, batches=5, min_batch_us=200, max_launches=500)
 
     rules = ()

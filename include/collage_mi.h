@@ -246,6 +246,12 @@ int32_t clg_graph_node_shape(const clg_graph *g, int32_t node, int32_t *dtype,
  *              waves of a workgroup.  What they do not run (batch_matmul,
  *              non-constant weights, tails outside scale/bias/add/activation)
  *              falls back to the "igemm_s8" kernels.
+ *   "igemm_r32_w4", "igemm_r32_w8", "igemm_r16_w4", "igemm_r16_w8"   the same
+ *              kernels with at most 4 / 8 waves per workgroup sharing K: a wave
+ *              then owns several chunks of MFMAs and keeps the loads of up to
+ *              four of them in flight at once (fewer waves to dispatch and to
+ *              meet, longer MFMA chains per wave); "igemm_r32" / "igemm_r16"
+ *              give every wave one chunk (up to 16 waves)
  *   "sepconv"  separable convolution in one kernel: [relu] -> depthwise
  *              conv2d -> 1x1 conv2d -> elementwise tail, or relu -> 1x1 conv2d
  *              (any stride) -> tail; both weights constants, the depthwise

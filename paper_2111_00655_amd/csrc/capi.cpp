@@ -184,12 +184,14 @@ int32_t clg_graph_node_shape(const clg_graph *g, int32_t node, int32_t *dtype, i
 int32_t clg_register_backend(clg_ctx *ctx, const char *name, int32_t *backend) {
     CLG_TRY
     NEED(ctx); NEED(name); NEED(backend);
-    static const struct { const char *name; int32_t family, tile, no_split; } kKnown[] = {
-        {"igemm", FAM_IGEMM, TILE_AUTO, 0}, {"igemm_s", FAM_IGEMM, TILE_S, 0}, {"igemm_m", FAM_IGEMM, TILE_M, 0},
-        {"igemm_l", FAM_IGEMM, TILE_L, 0}, {"igemm_s8", FAM_IGEMM, TILE_S8, 0}, {"igemm_s16", FAM_IGEMM, TILE_S16, 0},
-        {"igemm_r32", FAM_IGEMM, TILE_R32, 1}, {"igemm_r16", FAM_IGEMM, TILE_R16, 1},
-        {"igemm_s_nk", FAM_IGEMM, TILE_S, 1}, {"igemm_s8_nk", FAM_IGEMM, TILE_S8, 1}, {"igemm_s16_nk", FAM_IGEMM, TILE_S16, 1},
-        {"sepconv", FAM_SEPCONV, 0, 0}, {"attention", FAM_ATTENTION, 0, 0}, {"direct", FAM_DIRECT, 0, 0}, {"rowwise", FAM_ROWWISE, 0, 0}, {"eltwise", FAM_ELTWISE, 0, 0}};
+    static const struct { const char *name; int32_t family, tile, no_split, rf_waves; } kKnown[] = {
+        {"igemm", FAM_IGEMM, TILE_AUTO, 0, 0}, {"igemm_s", FAM_IGEMM, TILE_S, 0, 0}, {"igemm_m", FAM_IGEMM, TILE_M, 0, 0},
+        {"igemm_l", FAM_IGEMM, TILE_L, 0, 0}, {"igemm_s8", FAM_IGEMM, TILE_S8, 0, 0}, {"igemm_s16", FAM_IGEMM, TILE_S16, 0, 0},
+        {"igemm_r32", FAM_IGEMM, TILE_R32, 1, 0}, {"igemm_r16", FAM_IGEMM, TILE_R16, 1, 0},
+        {"igemm_r32_w4", FAM_IGEMM, TILE_R32, 1, 4}, {"igemm_r32_w8", FAM_IGEMM, TILE_R32, 1, 8},
+        {"igemm_r16_w4", FAM_IGEMM, TILE_R16, 1, 4}, {"igemm_r16_w8", FAM_IGEMM, TILE_R16, 1, 8},
+        {"igemm_s_nk", FAM_IGEMM, TILE_S, 1, 0}, {"igemm_s8_nk", FAM_IGEMM, TILE_S8, 1, 0}, {"igemm_s16_nk", FAM_IGEMM, TILE_S16, 1, 0},
+        {"sepconv", FAM_SEPCONV, 0, 0, 0}, {"attention", FAM_ATTENTION, 0, 0, 0}, {"direct", FAM_DIRECT, 0, 0, 0}, {"rowwise", FAM_ROWWISE, 0, 0, 0}, {"eltwise", FAM_ELTWISE, 0, 0, 0}};
     const std::string s(name);
     for (size_t i = 0; i < ctx->c.backends.size(); ++i)
         if (ctx->c.backends[i].name == s) {
@@ -198,7 +200,7 @@ int32_t clg_register_backend(clg_ctx *ctx, const char *name, int32_t *backend) {
         }
     for (auto &k : kKnown)
         if (s == k.name) {
-            ctx->c.backends.push_back(Backend{s, k.family, k.tile, k.no_split});
+            ctx->c.backends.push_back(Backend{s, k.family, k.tile, k.no_split, k.rf_waves});
             *backend = (int32_t)ctx->c.backends.size() - 1;
             return CLG_OK;
         }

@@ -97,6 +97,7 @@ struct Backend {
     int32_t family = 0;
     int32_t tile = 0;                 // igemm: GemmTile
     int32_t no_split = 0;             // igemm: 1 = never split K across workgroups
+    int32_t rf_waves = 0;             // register-fed kernels: at most this many K-waves per workgroup (0: one chunk per wave)
 };
 
 struct Pattern {

@@ -189,32 +189,43 @@ __device__ __forceinline__ void conv_rf_body(const GemmArgs &p, const int bx, co
         // vector arithmetic per load (offsets within an image fit 32 bits: checked on the host)
         const uint32_t lane_off = (uint32_t)(s * CS + ih0 * p.W + iw0);
         const uint32_t cq_step = (uint32_t)(NSLOT * CS);
-        f32x4 a[2][4];
-        float b[2][16];
+        // Up to PF chunks of loads are in flight before the first MFMA: a wave that owns one to four
+        // chunks pays one memory round trip for all of them (the K loop of these kernels is a few
+        // hundred MFMA cycles against a microsecond of memory latency).  Sixteen waves per workgroup
+        // leave a wave 128 registers: two chunks then.
+        constexpr int PF = WGK >= 16 ? 2 : 4;
+        f32x4 a[PF][4];
+        float b[PF][16];
 #define CLG_RF_LOAD(set, c)                                                                   \
     do {                                                                                      \
-        const int ch_ = min((c), nch - 1) + c0;                                               \
+        const int ch_ = (c) + c0;                                                             \
         _Pragma("unroll") for (int u = 0; u < 4; ++u) a[set][u] = (Ab + (uint32_t)(ch_ * 4 + u) * kWave)[lane_u]; \
         _Pragma("unroll") for (int u = 0; u < 16; ++u) {                                      \
             const int cq_ = min(ch_ * 16 + u, cq_last);                                       \
             b[set][u] = (x_img + (uint32_t)cq_ * cq_step)[lane_off];                          \
         }                                                                                     \
-        __builtin_amdgcn_sched_barrier(0);   /* all loads of a chunk go out before its MFMAs */ \
     } while (0)
 #define CLG_RF_MMA(set)                                                                       \
     do {                                                                                      \
         _Pragma("unroll") for (int u = 0; u < 16; ++u)                                        \
             acc = MF::mma(a[set][u / 4][u % 4], PRELU ? fmaxf(b[set][u], 0.f) : b[set][u], acc); \
     } while (0)
-        CLG_RF_LOAD(0, 0);
-        int c = 0;
-        for (; c + 1 < nch; c += 2) {
-            CLG_RF_LOAD(1, c + 1);
+        for (int c = 0; c < nch; c += PF) {
+            const int left = nch - c;                        // wave-uniform
+            CLG_RF_LOAD(0, c);
+            if (left > 1) CLG_RF_LOAD(1, c + 1);
+            if constexpr (PF > 2) {
+                if (left > 2) CLG_RF_LOAD(2, c + 2);
+                if (left > 3) CLG_RF_LOAD(3, c + 3);
+            }
+            __builtin_amdgcn_sched_barrier(0);               // every load of the round goes out before its first MFMA
             CLG_RF_MMA(0);
-            CLG_RF_LOAD(0, c + 2);
-            CLG_RF_MMA(1);
+            if (left > 1) CLG_RF_MMA(1);
+            if constexpr (PF > 2) {
+                if (left > 2) CLG_RF_MMA(2);
+                if (left > 3) CLG_RF_MMA(3);
+            }
         }
-        if (c < nch) CLG_RF_MMA(0);
 #undef CLG_RF_LOAD
 #undef CLG_RF_MMA
     } else if constexpr (TAPK == 9) {
@@ -229,38 +240,51 @@ __device__ __forceinline__ void conv_rf_body(const GemmArgs &p, const int bx, co
             voff[t] = (uint32_t)((FOLD ? 0 : s * CS) + (ok[t] ? ih * p.W + iw : 0));
         }
         const uint32_t cq_step = (uint32_t)(NSLOT * CS);
-        for (int c = 0; c < nch; ++c) {
-            const int ch = c0 + c;
-            f32x4 a[9];
-            float b[36];
-            bool okd[4] = {true, true, true, true};
-#pragma unroll
-            for (int u = 0; u < 9; ++u) a[u] = (Ab + (uint32_t)(ch * 9 + u) * kWave)[lane_u];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float *xc;
-                if constexpr (FOLD) {
-                    // this lane's folded channel c * KD + kd: plane (c, id0 + kd) of the volume
-                    const uint32_t chq = (uint32_t)(min(ch * 4 + q, cq_last) * NSLOT + s);
-                    const uint32_t cc = (uint32_t)(((uint64_t)chq * p.rf_kd_magic) >> 32);
-                    const int idd = id0 + (int)(chq - cc * (uint32_t)p.KD);
-                    okd[q] = idd >= 0 && idd < p.D;
-                    xc = x_img + (cc * (uint32_t)p.D + (uint32_t)(okd[q] ? idd : 0)) * (uint32_t)HW;
-                } else {
-                    xc = x_img + (uint32_t)min(ch * 4 + q, cq_last) * cq_step;
-                }
-#pragma unroll
-                for (int t = 0; t < 9; ++t) {
-                    const float v = xc[voff[t]];
-                    b[q * 9 + t] = v;
-                }
+        // two chunks of loads in flight (2 x 45 loads) before the first MFMA of a round; one with
+        // sixteen waves per workgroup (128 registers per wave)
+        constexpr int PF = WGK >= 16 ? 1 : 2;
+        f32x4 a[PF][9];
+        float b[PF][36];
+        bool okd[PF][4];
+#define CLG_RF_LOAD(set, c)                                                                   \
+    do {                                                                                      \
+        const int ch = c0 + (c);                                                              \
+        _Pragma("unroll") for (int u = 0; u < 9; ++u) a[set][u] = (Ab + (uint32_t)(ch * 9 + u) * kWave)[lane_u]; \
+        _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                       \
+            const float *xc;                                                                  \
+            okd[set][q] = true;                                                               \
+            if constexpr (FOLD) {                                                             \
+                /* this lane's folded channel c * KD + kd: plane (c, id0 + kd) of the volume */ \
+                const uint32_t chq = (uint32_t)(min(ch * 4 + q, cq_last) * NSLOT + s);        \
+                const uint32_t cc = (uint32_t)(((uint64_t)chq * p.rf_kd_magic) >> 32);        \
+                const int idd = id0 + (int)(chq - cc * (uint32_t)p.KD);                       \
+                okd[set][q] = idd >= 0 && idd < p.D;                                          \
+                xc = x_img + (cc * (uint32_t)p.D + (uint32_t)(okd[set][q] ? idd : 0)) * (uint32_t)HW; \
+            } else {                                                                          \
+                xc = x_img + (uint32_t)min(ch * 4 + q, cq_last) * cq_step;                    \
+            }                                                                                 \
+            _Pragma("unroll") for (int t = 0; t < 9; ++t) b[set][q * 9 + t] = xc[voff[t]];    \
+        }                                                                                     \
+    } while (0)
+#define CLG_RF_MMA(set)                                                                       \
+    do {                                                                                      \
+        _Pragma("unroll") for (int u = 0; u < 36; ++u) b[set][u] = (ok[u % 9] && okd[set][u / 9]) ? b[set][u] : 0.f; \
+        _Pragma("unroll") for (int u = 0; u < 36; ++u) acc = MF::mma(a[set][u / 4][u % 4], b[set][u], acc); \
+    } while (0)
+        for (int c = 0; c < nch; c += PF) {
+            const int left = nch - c;                        // wave-uniform
+            CLG_RF_LOAD(0, c);
+            if constexpr (PF > 1) {
+                if (left > 1) CLG_RF_LOAD(1, c + 1);
             }
-            __builtin_amdgcn_sched_barrier(0);       // all 45 loads go out before the first MFMA waits
-#pragma unroll
-            for (int u = 0; u < 36; ++u) b[u] = (ok[u % 9] && okd[u / 9]) ? b[u] : 0.f;
-#pragma unroll
-            for (int u = 0; u < 36; ++u) acc = MF::mma(a[u / 4][u % 4], b[u], acc);
+            __builtin_amdgcn_sched_barrier(0);               // all loads of the round go out before the first MFMA waits
+            CLG_RF_MMA(0);
+            if constexpr (PF > 1) {
+                if (left > 1) CLG_RF_MMA(1);
+            }
         }
+#undef CLG_RF_LOAD
+#undef CLG_RF_MMA
     } else if constexpr (TAPK == 4) {
         // ---- 2x2 (a phase of a k4 s2 transposed convolution): like 3x3, a chunk is four
         // channel groups x four taps

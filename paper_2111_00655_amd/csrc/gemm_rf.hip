@@ -173,6 +173,9 @@ int pick_waves(int chunks, int64_t tiles, int forced, bool cap_grid) {
     if (forced == 1 || forced == 2 || forced == 4 || forced == 8 || forced == 16) return forced;
     int wgk = 1;
     while (wgk < 16 && wgk < chunks) wgk *= 2;
+    // a negative count is an upper bound: waves with several chunks each keep all their loads in flight
+    // (a kernel variant of its own for the placement search to price)
+    if (forced == -1 || forced == -2 || forced == -4 || forced == -8 || forced == -16) return wgk < -forced ? wgk : -forced;
     if (!cap_grid) return wgk;
     int cap = 1;
     while (cap < 16 && (int64_t)cap * 2 * tiles <= 4096) cap *= 2;

@@ -266,7 +266,8 @@ size_t gemm_scratch_bytes(const GemmArgs &a);
 // Register-fed convolution: decides whether the kernel runs this GM_CONV
 // problem with tile edge `ts` (32 or 16) and a tail of `epi_flags`
 // (EpiFastFlags); if so fills the rf_* fields and the split and returns true.
-// `waves` = 1, 2, 4, 8 or 16 fixes the K-waves per workgroup; 0 lets the kernel choose.
+// `waves` = 1, 2, 4, 8 or 16 fixes the K-waves per workgroup; 0 lets the kernel choose (one chunk of
+// MFMAs per wave, at most 16 waves); -w: as 0, but at most w waves (several chunks per wave then).
 bool rf_resolve(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves = 0);
 // The same for GM_NT dense (A = activations [M,K], B = weights [N,K], no batch).
 bool rf_resolve_dense(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves = 0);

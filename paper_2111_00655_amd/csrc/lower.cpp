@@ -277,6 +277,7 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
     const Shape &out_shape = g.nodes[m.sink].shape;
     const int32_t k0 = cv.op(0);
     const Node &anchor = g.nodes[cv.node(0)];
+    const int rfw = be.rf_waves ? -be.rf_waves : 0;          // the backend's bound on K-waves per workgroup
 
     // operands counted once each for the algorithmic byte count
     std::vector<int32_t> ext;
@@ -438,7 +439,7 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
             ga.lda = ga.K;
             ga.rf_groups = 1;
             if (ok2 && (!e2.bias_c || (e2.bias_inner == (int64_t)ga.HO * ga.WO && e2.bias_c == ga.Cout)) &&
-                rf_resolve(&ga, 16, epi_fast_flags(e2), ctx.n_cus) && ga.rf_tapk == 1) {
+                rf_resolve(&ga, 16, epi_fast_flags(e2), ctx.n_cus, rfw) && ga.rf_tapk == 1) {
                 ga.rf_prelu = 1;
                 c.gemm = ga;
                 for (int s2 = 0; s2 < e2.n; ++s2) {
@@ -552,7 +553,7 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
                     a.cs_stride = (int64_t)a.M * rs.shape.d[2];
                 }
                 if (want_rf && g.nodes[wb].kind == NODE_CONST)
-                    rf = rf_resolve_dense(&a, a.tile == TILE_R32 ? 32 : 16, epi_fast_flags(epi), ctx.n_cus);
+                    rf = rf_resolve_dense(&a, a.tile == TILE_R32 ? 32 : 16, epi_fast_flags(epi), ctx.n_cus, rfw);
                 if (rf) c.pack_bytes = rf_pack_bytes(a);
             } else if (k0 == CLG_OP_BATCH_MATMUL) {
                 const bool tb = anchor.attrs.transpose_b != 0;
@@ -590,7 +591,7 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
                 a.rf_groups = 1;
                 if ((int64_t)a.Nimg * a.DO > 65535) return fail(CLG_NO_KERNEL, "conv3d: too many (image, depth) slices");
                 if (a.KD == 1 && a.pd != 0) return fail(CLG_NO_KERNEL, "conv3d: depth padding needs more than one depth tap");
-                rf = rf_resolve(&a, a.tile == TILE_R32 ? 32 : 16, epi_fast_flags(epi), ctx.n_cus);
+                rf = rf_resolve(&a, a.tile == TILE_R32 ? 32 : 16, epi_fast_flags(epi), ctx.n_cus, rfw);
                 if (!rf) return fail(CLG_NO_KERNEL, "conv3d: the register-fed kernel does not take this shape or tail");
                 c.pack_bytes = rf_pack_bytes(a);
                 c.name = "conv3d";
@@ -611,7 +612,7 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
                     a.M = a.Cout; a.N = a.Nimg * a.HO * a.WO; a.K = a.Cin * a.KH * a.KW;
                     a.lda = a.K;
                     a.rf_groups = G;
-                    rf = rf_resolve(&a, a.tile == TILE_R32 ? 32 : 16, epi_fast_flags(epi), ctx.n_cus);
+                    rf = rf_resolve(&a, a.tile == TILE_R32 ? 32 : 16, epi_fast_flags(epi), ctx.n_cus, rfw);
                 }
                 if (G != 1 && !rf)
                     return fail(CLG_NO_KERNEL, "the register-fed conv runs %d groups only with constant weights, a common-form "
@@ -647,7 +648,7 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
                 c.gemm_swap = true;
                 c.name = "convt_igemm";
                 if (want_rf && g.nodes[wb].kind == NODE_CONST)
-                    rf = rf_resolve_convt(&a, a.tile == TILE_R32 ? 32 : 16, epi_fast_flags(epi), ctx.n_cus);
+                    rf = rf_resolve_convt(&a, a.tile == TILE_R32 ? 32 : 16, epi_fast_flags(epi), ctx.n_cus, rfw);
                 if (rf) c.pack_bytes = rf_pack_bytes(a);
             }
             macs = (double)a.batch * a.M * a.N * a.K;

@@ -14,6 +14,17 @@
 // so the undisturbed batch is the fastest one.)  The figure is launch-inclusive
 // (it contains the dispatch gap between consecutive kernels), so the search
 // can use eps = 0.
+//
+// Operands rotate: inside a network a kernel finds neither its weights nor its
+// input in the L2 of the compute die it runs on (the weights of a whole model
+// pass through between two uses; the input was just written by another
+// kernel), while the same launch repeated on the same buffers finds everything
+// there and looks up to a third cheaper - and looks cheaper by different
+// amounts for different kernel variants, which misleads the search.  So the
+// measurer keeps several copies of the large operands (inputs, output, packed
+// or plain weights), 64 MB in all or at most 32 copies, and launch i works on
+// copy i mod R: every launch misses the L2 and hits the memory-side cache, as
+// in the network.
 #include <algorithm>
 #include <cmath>
 #include <cstdio>
@@ -60,9 +71,10 @@ int32_t hip_fail(const char *what, hipError_t e) {
     return fail(CLG_HIP_ERROR, "%s: %s", what, hipGetErrorString(e));
 }
 
-// Times `launch` (which enqueues the kernel once on the default stream).
+// Times `launch(i)` (which enqueues the kernel once on the default stream; i counts the launches).
 template <class F>
 int32_t time_launches(const Opts &o, F &&launch, int64_t *cost_ns) {
+    int launched = 0;
     hipEvent_t e0, e1;
     hipError_t he;
     if ((he = hipEventCreate(&e0)) != hipSuccess) return hip_fail("hipEventCreate", he);
@@ -71,7 +83,7 @@ int32_t time_launches(const Opts &o, F &&launch, int64_t *cost_ns) {
     auto run = [&](int n, double *ms_total) -> int32_t {
         (void)hipEventRecord(e0, nullptr);
         for (int i = 0; i < n; ++i) {
-            const int32_t r = launch();
+            const int32_t r = launch(launched++);
             if (r != CLG_OK) return r;
         }
         (void)hipEventRecord(e1, nullptr);
@@ -106,7 +118,7 @@ int32_t time_launches(const Opts &o, F &&launch, int64_t *cost_ns) {
 int32_t profile_empty(Context &ctx, const clg_profile_opts *opts, int64_t *cost_ns) {
     if (ctx.device < 0) return fail(CLG_HIP_ERROR, "host-only context: no device to profile on");
     const Opts o = resolve(opts);
-    return time_launches(o, [&]() -> int32_t {
+    return time_launches(o, [&](int) -> int32_t {
         const int e = launch_empty(nullptr);
         return e ? hip_fail("empty kernel launch", (hipError_t)e) : CLG_OK;
     }, cost_ns);
@@ -130,68 +142,77 @@ int32_t profile_match(Context &ctx, Graph &g, int32_t match, const clg_profile_o
             return CLG_OK;
         }
     }
-    // operands: constants in place, everything else in one scratch block
+    // operands: small constants in place; inputs, output, scratch and the large constant operand (the
+    // weights, packed or plain) in R rotating copies inside one scratch block
     std::vector<int32_t> vals;
     for (int32_t v : {c.a_node, c.b_node, c.c_node}) vals.push_back(v);
     for (int32_t v : c.epi_nodes) vals.push_back(v);
     vals.push_back(c.out_node);
-    std::vector<size_t> offs(vals.size(), 0);
-    size_t total = 0;
+    const size_t nv = vals.size();
     auto up = [](size_t b) { return (b + 255) / 256 * 256; };
-    for (size_t i = 0; i < vals.size(); ++i) {
+    constexpr size_t kRotateBytes = (size_t)64 << 20, kBigConst = (size_t)256 << 10;
+    std::vector<size_t> offs(nv, 0);
+    std::vector<char> rotated(nv, 0);
+    size_t set_bytes = 0;
+    for (size_t i = 0; i < nv; ++i) {
         const int32_t v = vals[i];
         if (v < 0) continue;
-        const bool is_out = i + 1 == vals.size();
+        const bool is_out = i + 1 == nv;
+        const size_t bytes = 4 * (size_t)g.nodes[v].shape.numel();
         if (!is_out && g.nodes[v].kind == NODE_CONST) {
             if (!g.nodes[v].dev_ptr) return fail(CLG_INVALID_ARG, "constant node %d has no device pointer", v);
-            continue;
+            // the weights a kernel reads in place get copies too; packed ones are copied as packed (below);
+            // a gather's table is not read as a whole and stays where it is
+            const bool table = (c.kind == CALL_ELTWISE && c.elt.table_rows > 0 && i == 0) || (c.kind == CALL_ROWWISE && c.row.n_gather);
+            if (i != 1 || c.pack_bytes || bytes < kBigConst || table) continue;
         }
-        offs[i] = total;
-        total += up(4 * (size_t)g.nodes[v].shape.numel());
+        rotated[i] = 1;
+        offs[i] = set_bytes;
+        set_bytes += up(bytes);
     }
-    const size_t scratch_off = total;
-    total += up(c.scratch_bytes);
-    const size_t pack_off = total;
-    total += up(c.pack_bytes);
-    int32_t rc = ensure_block(ctx, std::max<size_t>(total, 256));
+    const size_t scratch_off = set_bytes;
+    set_bytes += up(c.scratch_bytes);
+    const size_t pack_off = set_bytes;
+    set_bytes += up(c.pack_bytes);
+    set_bytes = std::max<size_t>(set_bytes, 256);
+    const int R = (int)std::min<size_t>(32, std::max<size_t>(1, (kRotateBytes + set_bytes - 1) / set_bytes));
+    int32_t rc = ensure_block(ctx, set_bytes * (size_t)R);
     if (rc != CLG_OK) return rc;
     char *base = (char *)ctx.prof_ptr;
-    std::vector<const void *> ptrs(vals.size(), nullptr);
-    for (size_t i = 0; i < vals.size(); ++i) {
-        const int32_t v = vals[i];
-        if (v < 0) continue;
-        const bool is_out = i + 1 == vals.size();
-        if (!is_out && g.nodes[v].kind == NODE_CONST) {
-            ptrs[i] = g.nodes[v].dev_ptr;
-            continue;
+    if (c.pack_bytes && g.nodes[c.b_node].kind != NODE_CONST) return fail(CLG_INVALID_ARG, "packed weights must be a constant");
+    for (int r = 0; r < R; ++r) {
+        char *set = base + (size_t)r * set_bytes;
+        for (size_t i = 0; i < nv; ++i) {
+            const int32_t v = vals[i];
+            if (v < 0 || !rotated[i] || i + 1 == nv) continue;
+            const int64_t n = g.nodes[v].shape.numel();
+            if (g.nodes[v].kind == NODE_CONST) {
+                const hipError_t he = hipMemcpyAsync(set + offs[i], g.nodes[v].dev_ptr, 4 * (size_t)n, hipMemcpyDeviceToDevice, nullptr);
+                if (he != hipSuccess) return hip_fail("copy of a constant operand", he);
+            } else if (g.nodes[v].dtype == CLG_I32) {
+                // the only int32 operand is a gather's row ids: seeded ids spread over the table (all zeros would
+                // time the gather of one cache-hot row)
+                int32_t rows = c.kind == CALL_ELTWISE && c.elt.table_rows > 0 ? c.elt.table_rows : 1;
+                if (c.kind == CALL_ROWWISE && c.row.n_gather && i >= 6 && i < 9) rows = c.row.tab_rows[i - 6];
+                const int e = launch_fill_ids((int32_t *)(set + offs[i]), n, rows, o.seed + 7919u * (uint64_t)i + 104729u * (uint64_t)r, nullptr);
+                if (e) return hip_fail("id fill kernel", (hipError_t)e);
+            } else {
+                const int e = launch_fill((float *)(set + offs[i]), n, o.seed + 7919u * (uint64_t)i, nullptr);
+                if (e) return hip_fail("fill kernel", (hipError_t)e);
+            }
         }
-        ptrs[i] = base + offs[i];
-        if (is_out) continue;
-        const int64_t n = g.nodes[v].shape.numel();
-        if (g.nodes[v].dtype == CLG_I32) {
-            // the only int32 operand is a gather's row ids: seeded ids spread over the table (all zeros would
-            // time the gather of one cache-hot row)
-            int32_t rows = c.kind == CALL_ELTWISE && c.elt.table_rows > 0 ? c.elt.table_rows : 1;
-            if (c.kind == CALL_ROWWISE && c.row.n_gather && i >= 6 && i < 9) rows = c.row.tab_rows[i - 6];
-            const int e = launch_fill_ids((int32_t *)(base + offs[i]), n, rows, o.seed + 7919u * (uint64_t)i, nullptr);
-            if (e) return hip_fail("id fill kernel", (hipError_t)e);
-        } else {
-            const int e = launch_fill((float *)(base + offs[i]), n, o.seed + 7919u * (uint64_t)i, nullptr);
-            if (e) return hip_fail("fill kernel", (hipError_t)e);
+        if (c.pack_bytes) {                  // one-time weight re-packing is not part of the measured cost
+            rc = pack_weights(c, g.nodes[c.b_node].dev_ptr, set + pack_off, nullptr);
+            if (rc != CLG_OK) return rc;
         }
     }
-    void *scratch = c.scratch_bytes ? base + scratch_off : nullptr;
-    const void *packed = nullptr;
-    if (c.pack_bytes) {                      // one-time weight re-packing is not part of the measured cost
-        if (g.nodes[c.b_node].kind != NODE_CONST) return fail(CLG_INVALID_ARG, "packed weights must be a constant");
-        rc = pack_weights(c, ptrs[1], base + pack_off, nullptr);
-        if (rc != CLG_OK) return rc;
-        packed = base + pack_off;
-    }
-    const void *epi[kMaxEpi];
-    for (int s = 0; s < kMaxEpi; ++s) epi[s] = ptrs[3 + s];
-    rc = time_launches(o, [&]() -> int32_t {
-        return launch_call(c, ptrs[0], ptrs[1], ptrs[2], const_cast<void *>(ptrs.back()), epi, scratch, packed, nullptr);
+    rc = time_launches(o, [&](int launch_no) -> int32_t {
+        char *set = base + (size_t)(launch_no % R) * set_bytes;
+        const void *ptrs[3 + kMaxEpi + 1];
+        for (size_t i = 0; i < nv; ++i)
+            ptrs[i] = vals[i] < 0 ? nullptr : (rotated[i] ? (const void *)(set + offs[i]) : g.nodes[vals[i]].dev_ptr);
+        return launch_call(c, ptrs[0], ptrs[1], ptrs[2], const_cast<void *>(ptrs[nv - 1]), ptrs + 3,
+                           c.scratch_bytes ? set + scratch_off : nullptr, c.pack_bytes ? set + pack_off : nullptr, nullptr);
     }, cost_ns);
     if (rc != CLG_OK) return rc;
     if (o.cache) ctx.cost_log[c.key] = *cost_ns;

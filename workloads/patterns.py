@@ -15,7 +15,7 @@ from __future__ import annotations
 W = "*"
 
 # igemm variants whose conv2d patterns carry no groups = 1 constraint
-GROUPED_CONV_BACKENDS = ("igemm_r32", "igemm_r16")
+GROUPED_CONV_BACKENDS = ("igemm_r32", "igemm_r16", "igemm_r32_w4", "igemm_r32_w8", "igemm_r16_w4", "igemm_r16_w8")
 
 # attribute names a constraint may refer to, in the order of the C enum
 ATTR_NAMES = ("groups", "kernel_h", "kernel_w", "stride_h", "stride_w",
