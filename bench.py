@@ -285,9 +285,12 @@ def measurer_spread(s, plan, repeats=5):
             continue
         seen.add(key)
         c = [B.clg_profile_match(s.ctx, s.graph, k["match"], nocache) for _ in range(repeats)]
-        rel.append((max(c) - min(c)) / float(np.median(c)))
-    return dict(kernels=len(rel), repeats=repeats, median_rel_spread=round(float(np.median(rel)), 4),
-                p90_rel_spread=round(float(np.quantile(rel, 0.9)), 4), max_rel_spread=round(float(max(rel)), 4))
+        rel.append(((max(c) - min(c)) / float(np.median(c)), k["name"], [int(x) for x in c]))
+    vals = [r[0] for r in rel]
+    worst = sorted(rel, reverse=True)[:3]
+    return dict(kernels=len(rel), repeats=repeats, median_rel_spread=round(float(np.median(vals)), 4),
+                p90_rel_spread=round(float(np.quantile(vals, 0.9)), 4), max_rel_spread=round(float(max(vals)), 4),
+                widest=[dict(kernel=w[1], ns=w[2]) for w in worst])
 
 
 def cpu_baseline(desc):

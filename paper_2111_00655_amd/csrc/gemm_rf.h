@@ -87,7 +87,16 @@ struct RfMfma<16> {
 // part of a four-microsecond kernel.
 // The body takes its tile number as (bx of gx) instead of reading blockIdx.x, so that one launch can
 // run the tiles of several convolutions (conv_rf_multi_kernel below); grid.y and grid.z are read as usual.
-template <int TS, int TAPK, int WGK, int GEO>
+// Loads in flight per wave, in chunks: a wave that owns several chunks issues the loads of up to
+// rf_depth<TAPK, WGK>() of them before its first MFMA.  A kernel whose waves own one chunk each is
+// instantiated with PF = 1 instead: the deeper variant holds its extra operand registers whether it
+// uses them or not, and fewer registers mean more resident waves.
+template <int TAPK, int WGK>
+constexpr int rf_depth() {
+    return TAPK == 1 ? (WGK >= 16 ? 2 : 4) : (TAPK == 9 ? (WGK >= 16 ? 1 : 2) : 1);
+}
+
+template <int TS, int TAPK, int WGK, int GEO, int PF>
 __device__ __forceinline__ void conv_rf_body(const GemmArgs &p, const int bx, const int gx) {
     using MF = RfMfma<TS>;
     typedef typename MF::acc_t acc_t;
@@ -193,7 +202,6 @@ __device__ __forceinline__ void conv_rf_body(const GemmArgs &p, const int bx, co
         // chunks pays one memory round trip for all of them (the K loop of these kernels is a few
         // hundred MFMA cycles against a microsecond of memory latency).  Sixteen waves per workgroup
         // leave a wave 128 registers: two chunks then.
-        constexpr int PF = WGK >= 16 ? 2 : 4;
         f32x4 a[PF][4];
         float b[PF][16];
 #define CLG_RF_LOAD(set, c)                                                                   \
@@ -213,14 +221,18 @@ __device__ __forceinline__ void conv_rf_body(const GemmArgs &p, const int bx, co
         for (int c = 0; c < nch; c += PF) {
             const int left = nch - c;                        // wave-uniform
             CLG_RF_LOAD(0, c);
-            if (left > 1) CLG_RF_LOAD(1, c + 1);
+            if constexpr (PF > 1) {
+                if (left > 1) CLG_RF_LOAD(1, c + 1);
+            }
             if constexpr (PF > 2) {
                 if (left > 2) CLG_RF_LOAD(2, c + 2);
                 if (left > 3) CLG_RF_LOAD(3, c + 3);
             }
             __builtin_amdgcn_sched_barrier(0);               // every load of the round goes out before its first MFMA
             CLG_RF_MMA(0);
-            if (left > 1) CLG_RF_MMA(1);
+            if constexpr (PF > 1) {
+                if (left > 1) CLG_RF_MMA(1);
+            }
             if constexpr (PF > 2) {
                 if (left > 2) CLG_RF_MMA(2);
                 if (left > 3) CLG_RF_MMA(3);
@@ -242,7 +254,6 @@ __device__ __forceinline__ void conv_rf_body(const GemmArgs &p, const int bx, co
         const uint32_t cq_step = (uint32_t)(NSLOT * CS);
         // two chunks of loads in flight (2 x 45 loads) before the first MFMA of a round; one with
         // sixteen waves per workgroup (128 registers per wave)
-        constexpr int PF = WGK >= 16 ? 1 : 2;
         f32x4 a[PF][9];
         float b[PF][36];
         bool okd[PF][4];
@@ -387,9 +398,9 @@ __device__ __forceinline__ void conv_rf_body(const GemmArgs &p, const int bx, co
     }
 }
 
-template <int TS, int TAPK, int WGK, int GEO>
+template <int TS, int TAPK, int WGK, int GEO, int PF>
 __global__ __launch_bounds__(WGK *kWave) void conv_rf_kernel(GemmArgs p) {
-    conv_rf_body<TS, TAPK, WGK, GEO>(p, blockIdx.x, gridDim.x);
+    conv_rf_body<TS, TAPK, WGK, GEO, PF>(p, blockIdx.x, gridDim.x);
 }
 
 // Several independent problems of one kernel shape in ONE launch (a region of sibling kernels,
@@ -405,7 +416,7 @@ __global__ __launch_bounds__(WGK *kWave) void conv_rf_multi_kernel(RfMultiArgs m
 #pragma unroll
     for (int i = 0; i + 1 < kMaxRegion; ++i) k += (i + 1 < m.n && bx >= m.tile_end[i]) ? 1 : 0;
     const int start = k ? m.tile_end[k - 1] : 0;
-    conv_rf_body<TS, 1, WGK, GEO>(m.p[k], bx - start, m.tile_end[k] - start);
+    conv_rf_body<TS, 1, WGK, GEO, rf_depth<1, WGK>()>(m.p[k], bx - start, m.tile_end[k] - start);
 }
 
 // ---- dense: y[m][n] = sum_k x[m][k] * w[n][k] -------------------------------------------------

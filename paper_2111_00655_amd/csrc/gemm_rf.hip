@@ -15,7 +15,11 @@ int launch_rf_one_t(const GemmArgs &a, hipStream_t s) {
     const int gz = a.rf_convt ? a.sh * a.sw : a.splitk;      // sub-pixel phases, or K splits
     const int gy = a.Nimg * (a.DO > 1 ? a.DO : 1);           // images, or (image, output depth) pairs
     if (gy > 65535) return (int)hipErrorInvalidValue;
-    hipLaunchKernelGGL((conv_rf_kernel<TS, TAPK, WGK, GEO>), dim3(tiles, gy, gz), dim3(WGK * kWave), lds, s, a);
+    constexpr int DEEP = rf_depth<TAPK, WGK>();
+    if (DEEP > 1 && a.rf_nch > 1)
+        hipLaunchKernelGGL((conv_rf_kernel<TS, TAPK, WGK, GEO, DEEP>), dim3(tiles, gy, gz), dim3(WGK * kWave), lds, s, a);
+    else
+        hipLaunchKernelGGL((conv_rf_kernel<TS, TAPK, WGK, GEO, 1>), dim3(tiles, gy, gz), dim3(WGK * kWave), lds, s, a);
     return (int)hipGetLastError();
 }
 

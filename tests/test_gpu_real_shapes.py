@@ -110,7 +110,9 @@ def test_resnext50_grouped_convolutions_at_their_real_shapes(ci):
     r = np.random.default_rng([102, ci])
     d, pat = conv_graph("conv2d", r, 1, c, c, (h, h), (3, 3), (s, s), (1, 1), BR, groups=32)
     names = under_every_variant(d, pat, RESNEXT50_GROUPED[ci], must_run=("igemm_r32", "igemm_r16"), extra=("direct",))
-    assert set(names) == {"igemm_r32", "igemm_r16", "direct"}, names        # the LDS-tiled kernels take one group only
+    import bench
+    register_fed = {b for b in bench.VARIANTS if b.startswith("igemm_r")}
+    assert set(names) == register_fed | {"direct"}, names        # the LDS-tiled kernels take one group only
 
 
 @pytest.mark.gpu
