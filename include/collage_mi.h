@@ -252,6 +252,11 @@ int32_t clg_graph_node_shape(const clg_graph *g, int32_t node, int32_t *dtype,
  *              four of them in flight at once (fewer waves to dispatch and to
  *              meet, longer MFMA chains per wave); "igemm_r32" / "igemm_r16"
  *              give every wave one chunk (up to 16 waves)
+ *   "igemm_r16x2_w4", "igemm_r16x2_w8"   dense only: a wave owns two 16x16
+ *              tiles (32 output columns, 16 rows) that share the activation
+ *              operand, so that each value loaded and shuffled feeds two MFMAs
+ *              (other operators registered under these names run as under
+ *              "igemm_r16_w4" / "_w8")
  *   "sepconv"  separable convolution in one kernel: [relu] -> depthwise
  *              conv2d -> 1x1 conv2d -> elementwise tail, or relu -> 1x1 conv2d
  *              (any stride) -> tail; both weights constants, the depthwise

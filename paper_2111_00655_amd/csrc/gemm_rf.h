@@ -563,6 +563,132 @@ __global__ __launch_bounds__(WGK *kWave) void dense_rf_multi_kernel(RfMultiArgs 
     dense_rf_body<TS, WGK>(m.p[k], bx - start, m.tile_end[k] - start);
 }
 
+// Two weight tiles per wave.  Every MFMA of the kernel above needs 16 bytes per lane of weights and
+// 16 bytes per lane of activations for four MFMAs, and a lane shuffle per MFMA: at the matrix cores'
+// full rate that is the whole bandwidth of the vector memory path.  Here a wave owns 32 output
+// columns (two 16-row tiles of packed weights) and 16 activation rows: the activation operand and its
+// shuffle are shared by two MFMAs with independent accumulators (a quarter less load traffic, half the
+// shuffles, two MFMA chains in flight).  Same packed weights, same k order, TS = 16.
+template <int WGK>
+__device__ __forceinline__ void dense_rf2_body(const GemmArgs &p, const int bx, const int gx) {
+    using MF = RfMfma<16>;
+    using PK = RfPark<16>;
+    typedef MF::acc_t acc_t;
+    constexpr int TS = 16, NSLOT = 4, NACC = 4;
+    constexpr int NT = WGK * kWave;
+    constexpr int OUTS = 2 * TS * TS;
+    constexpr int EPT = (OUTS + NT - 1) / NT;
+    extern __shared__ float red[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int w = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int r = lane % TS, s = lane / TS;
+
+    const int tile = xcd_remap(bx, gx);
+    const int t_hi = (int)(((uint64_t)(uint32_t)tile * p.rf_tile_magic) >> 32), t_lo = tile - t_hi * p.rf_tile_div;
+    const int mp = p.rf_jmajor ? t_lo : t_hi;     // pair of weight-row tiles
+    const int nt = p.rf_jmajor ? t_hi : t_lo;     // activation-row tile
+    const int i0 = mp * 2 * TS, j0 = nt * TS;
+    const int tiles_m = (p.N + TS - 1) / TS;
+    const int m1 = min(mp * 2 + 1, tiles_m - 1);  // an odd tile count: the last pair's second tile repeats the first (its outputs are masked)
+
+    const f32x4 *const Ab0 = reinterpret_cast<const f32x4 *>(p.B) + (int64_t)(mp * 2) * p.rf_ngtot * kWave;
+    const f32x4 *const Ab1 = reinterpret_cast<const f32x4 *>(p.B) + (int64_t)m1 * p.rf_ngtot * kWave;
+    const f32x4 *const Xb = reinterpret_cast<const f32x4 *>(p.A);
+    const uint32_t lane_u = (uint32_t)lane;
+    const int lrow = lane / NSLOT, lpart = lane % NSLOT;
+    const uint32_t x_lane = (uint32_t)(min(j0 + lrow, p.M - 1) * (p.lda / 4) + lpart);      // in 16-byte units
+    const int src_lane4 = (r * NSLOT + s) * 4;
+    const int nch = p.rf_nch;
+    const int c0 = w * nch;
+    const int g_last = p.K / (4 * NSLOT) - 1;
+
+    int64_t e_off[EPT];
+    float e_bias[EPT], e_add[EPT];
+    int e_idx[EPT];
+#pragma unroll
+    for (int t = 0; t < EPT; ++t) {
+        const int e = min(tid + t * NT, OUTS - 1);
+        const int sub = e / (TS * TS), in = e % (TS * TS);
+        const int row = in % TS, col = in / TS;
+        const int it = i0 + sub * TS;                 // first output column of this tile
+        const int tile_base = p.cs_len ? (it / p.cs_len) * (int)p.cs_stride + it % p.cs_len : it;
+        e_idx[t] = sub * PK::PERW + PK::of(row, col);
+        const bool ok = tid + t * NT < OUTS && it + row < p.N && j0 + col < p.M;
+        e_off[t] = ok ? (int64_t)(j0 + col) * p.ldc + tile_base + row : -1;
+        e_bias[t] = 0.f;
+        e_add[t] = 0.f;
+        if (ok) {
+            if (p.ef.flags & EF_BIAS) e_bias[t] = p.ef.bias[it + row];
+            if (p.ef.flags & EF_ADD) e_add[t] = p.ef.add[e_off[t]];
+        }
+    }
+
+    acc_t acc0, acc1;
+#pragma unroll
+    for (int g = 0; g < NACC; ++g) acc0[g] = acc1[g] = 0.f;
+
+    f32x4 a0[2][4], a1[2][4], b[2][4];
+#define CLG_RFD_LOAD(set, c)                                                                  \
+    do {                                                                                      \
+        const int ch_ = min((c), nch - 1) + c0;                                               \
+        _Pragma("unroll") for (int u = 0; u < 4; ++u) a0[set][u] = (Ab0 + (uint32_t)(ch_ * 4 + u) * kWave)[lane_u]; \
+        _Pragma("unroll") for (int u = 0; u < 4; ++u) a1[set][u] = (Ab1 + (uint32_t)(ch_ * 4 + u) * kWave)[lane_u]; \
+        _Pragma("unroll") for (int u = 0; u < 4; ++u) b[set][u] = (Xb + (uint32_t)min(ch_ * 4 + u, g_last) * NSLOT)[x_lane]; \
+        __builtin_amdgcn_sched_barrier(0);                                                    \
+    } while (0)
+#define CLG_RFD_MMA(set)                                                                      \
+    do {                                                                                      \
+        _Pragma("unroll") for (int u = 0; u < 16; ++u) {                                      \
+            const float own_ = b[set][u / 4][u % 4];                                          \
+            const float bv_ = __int_as_float(__builtin_amdgcn_ds_bpermute(src_lane4, __float_as_int(own_))); \
+            acc0 = MF::mma(a0[set][u / 4][u % 4], bv_, acc0);                                 \
+            acc1 = MF::mma(a1[set][u / 4][u % 4], bv_, acc1);                                 \
+        }                                                                                     \
+    } while (0)
+    CLG_RFD_LOAD(0, 0);
+    int c = 0;
+    for (; c + 1 < nch; c += 2) {
+        CLG_RFD_LOAD(1, c + 1);
+        CLG_RFD_MMA(0);
+        CLG_RFD_LOAD(0, c + 2);
+        CLG_RFD_MMA(1);
+    }
+    if (c < nch) CLG_RFD_MMA(0);
+#undef CLG_RFD_LOAD
+#undef CLG_RFD_MMA
+
+#pragma unroll
+    for (int g = 0; g < NACC; ++g) {
+        red[w * 2 * PK::PERW + PK::at(g, s, r)] = acc0[g];
+        red[w * 2 * PK::PERW + PK::PERW + PK::at(g, s, r)] = acc1[g];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < EPT; ++t) {
+        float v = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < WGK; ++ww) v += red[ww * 2 * PK::PERW + e_idx[t]];
+        if (e_off[t] >= 0) p.C[e_off[t]] = finish_value(p, v, e_bias[t], e_add[t]);
+    }
+}
+
+template <int WGK>
+__global__ __launch_bounds__(WGK *kWave) void dense_rf2_kernel(GemmArgs p) {
+    dense_rf2_body<WGK>(p, blockIdx.x, gridDim.x);
+}
+
+template <int WGK>
+__global__ __launch_bounds__(WGK *kWave) void dense_rf2_multi_kernel(RfMultiArgs m) {
+    const int bx = blockIdx.x;
+    int k = 0;
+#pragma unroll
+    for (int i = 0; i + 1 < kMaxRegion; ++i) k += (i + 1 < m.n && bx >= m.tile_end[i]) ? 1 : 0;
+    const int start = k ? m.tile_end[k - 1] : 0;
+    dense_rf2_body<WGK>(m.p[k], bx - start, m.tile_end[k] - start);
+}
+
 // Dense weights w [N][K] -> [n-tile][group][lane][4] in the k order above.
 template <int TS>
 __global__ void rf_pack_dense_kernel(const float *w, float *dst, GemmArgs p, int64_t total) {

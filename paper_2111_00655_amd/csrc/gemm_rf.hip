@@ -7,6 +7,8 @@ namespace clg {
 
 namespace {
 
+int dense_tiles(const GemmArgs &a);
+
 template <int TS, int TAPK, int WGK, int GEO>
 int launch_rf_one_t(const GemmArgs &a, hipStream_t s) {
     const int npix = a.rf_convt ? (a.HO / a.sh) * (a.WO / a.sw) : a.HO * a.WO;
@@ -67,6 +69,42 @@ int launch_rf_tap(const GemmArgs &a, hipStream_t s) {
     }
 }
 
+template <int WGK>
+int launch_rfd2_one(const GemmArgs &a, hipStream_t s) {
+    const size_t lds = (size_t)WGK * 2 * RfPark<16>::PERW * sizeof(float);      // at most 40 KB
+    hipLaunchKernelGGL((dense_rf2_kernel<WGK>), dim3(dense_tiles(a), 1, 1), dim3(WGK * kWave), lds, s, a);
+    return (int)hipGetLastError();
+}
+
+int launch_rfd2_wgk(const GemmArgs &a, hipStream_t s) {
+    switch (a.rf_wgk) {
+    case 1: return launch_rfd2_one<1>(a, s);
+    case 2: return launch_rfd2_one<2>(a, s);
+    case 4: return launch_rfd2_one<4>(a, s);
+    case 8: return launch_rfd2_one<8>(a, s);
+    case 16: return launch_rfd2_one<16>(a, s);
+    default: return (int)hipErrorInvalidValue;
+    }
+}
+
+template <int WGK>
+int launch_rfd2_multi_t(const RfMultiArgs &m, hipStream_t s) {
+    const size_t lds = (size_t)WGK * 2 * RfPark<16>::PERW * sizeof(float);
+    hipLaunchKernelGGL((dense_rf2_multi_kernel<WGK>), dim3(m.tile_end[m.n - 1], 1, 1), dim3(WGK * kWave), lds, s, m);
+    return (int)hipGetLastError();
+}
+
+int launch_rfd2_multi_wgk(const RfMultiArgs &m, int wgk, hipStream_t s) {
+    switch (wgk) {
+    case 1: return launch_rfd2_multi_t<1>(m, s);
+    case 2: return launch_rfd2_multi_t<2>(m, s);
+    case 4: return launch_rfd2_multi_t<4>(m, s);
+    case 8: return launch_rfd2_multi_t<8>(m, s);
+    case 16: return launch_rfd2_multi_t<16>(m, s);
+    default: return (int)hipErrorInvalidValue;
+    }
+}
+
 template <int TS, int WGK>
 int launch_rfd_one(const GemmArgs &a, hipStream_t s) {
     const int tiles = ((a.N + TS - 1) / TS) * ((a.M + TS - 1) / TS);
@@ -109,7 +147,10 @@ int conv_tiles(const GemmArgs &a) {
     return ((a.Cout + a.rf_ts - 1) / a.rf_ts) * ((npix + a.rf_ts - 1) / a.rf_ts);
 }
 
-int dense_tiles(const GemmArgs &a) { return ((a.N + a.rf_ts - 1) / a.rf_ts) * ((a.M + a.rf_ts - 1) / a.rf_ts); }
+int dense_tiles(const GemmArgs &a) {
+    const int wt = (a.N + a.rf_ts - 1) / a.rf_ts;            // weight-row tiles; a wave may own two of them
+    return (a.rf_nb == 2 ? (wt + 1) / 2 : wt) * ((a.M + a.rf_ts - 1) / a.rf_ts);
+}
 
 template <int TS, int WGK, int GEO>
 int launch_rf_multi_t(const RfMultiArgs &m, int gy, hipStream_t s) {
@@ -201,6 +242,7 @@ int chunk_groups(int tapk) { return tapk == 1 || tapk == 4 ? 4 : (tapk == 9 ? 9 
 int launch_rf_conv(const GemmArgs &a, hipStream_t s) {
     if (a.rf_tapk == -1) {
         if (((uintptr_t)a.A & 15) != 0) return (int)hipErrorInvalidValue;      // activations are read 16 bytes at a time
+        if (a.rf_nb == 2) return a.rf_ts == 16 && a.splitk == 1 ? launch_rfd2_wgk(a, s) : (int)hipErrorInvalidValue;
         return a.rf_ts == 32 ? launch_rfd_wgk<32>(a, s) : launch_rfd_wgk<16>(a, s);
     }
     return a.rf_ts == 32 ? launch_rf_tap<32>(a, s) : launch_rf_tap<16>(a, s);
@@ -209,7 +251,7 @@ int launch_rf_conv(const GemmArgs &a, hipStream_t s) {
 bool rf_same_launch_shape(const GemmArgs &a, const GemmArgs &b) {
     if (!a.rf_ts || a.rf_ts != b.rf_ts || a.rf_tapk != b.rf_tapk || a.rf_wgk != b.rf_wgk) return false;
     if (a.splitk != 1 || b.splitk != 1) return false;
-    if (a.rf_tapk == -1) return true;                         // dense: grid.y = grid.z = 1
+    if (a.rf_tapk == -1) return a.rf_nb == b.rf_nb;           // dense: grid.y = grid.z = 1
     if (a.rf_tapk != 1) return false;                         // of the convolutions the 1x1 path is built as a region kernel
     const int ga = rf_geo(a), gb = rf_geo(b);
     if (ga != gb || (ga != 0 && ga != 3 && ga != 4)) return false;
@@ -231,6 +273,7 @@ int launch_rf_multi(const GemmArgs *members, int n, hipStream_t s) {
         m.p[k] = members[k];
     }
     for (int k = n; k < kMaxRegion; ++k) m.tile_end[k] = end;
+    if (dense && a.rf_nb == 2) return launch_rfd2_multi_wgk(m, a.rf_wgk, s);
     if (dense) return a.rf_ts == 32 ? launch_rfd_multi_wgk<32>(m, a.rf_wgk, s) : launch_rfd_multi_wgk<16>(m, a.rf_wgk, s);
     const int gy = a.Nimg * (a.DO > 1 ? a.DO : 1);
     if (gy > 65535) return (int)hipErrorInvalidValue;
@@ -238,17 +281,20 @@ int launch_rf_multi(const GemmArgs *members, int n, hipStream_t s) {
                          : launch_rf_multi_wgk<16>(m, a.rf_wgk, rf_geo(a), gy, s);
 }
 
-bool rf_resolve_dense(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves) {
+bool rf_resolve_dense(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves, int nb) {
     (void)n_cus;
     if (a->mode != GM_NT || a->batch != 1 || (epi_flags & EF_GENERIC)) return false;
+    if (nb != 1 && !(nb == 2 && ts == 16)) return false;
     const int nslot = ts == 32 ? 2 : 4;
     if (a->K % (4 * nslot) || a->lda % 4) return false;
     if ((int64_t)a->M * a->lda >= ((int64_t)1 << 31)) return false;     // 32-bit lane offsets
     if (a->cs_len && a->cs_len % ts) return false;           // a tile's columns must stay within one block of the split
     const int ng = a->K / (4 * nslot);                       // weight groups (4 MFMAs each)
     const int nc = (ng + 3) / 4;                             // chunks per tile
-    const int wgk = pick_waves(nc, (int64_t)((a->M + ts - 1) / ts) * ((a->N + ts - 1) / ts), waves, true);
+    const int wtiles = nb == 2 ? ((a->N + ts - 1) / ts + 1) / 2 : (a->N + ts - 1) / ts;      // tiles (or pairs of tiles) of weight rows
+    const int wgk = pick_waves(nc, (int64_t)((a->M + ts - 1) / ts) * wtiles, waves, true);
     a->rf_ts = ts;
+    a->rf_nb = nb;
     a->rf_tapk = -1;
     a->rf_wgk = wgk;
     a->rf_nch = (nc + wgk - 1) / wgk;
@@ -256,8 +302,9 @@ bool rf_resolve_dense(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves) 
     a->rf_ngtot = wgk * a->splitk * a->rf_nch * 4;
     a->rf_nm = ng * 4;
     a->rf_jmajor = a->M > a->N ? 1 : 0;
-    if (set_tile_order(a, (a->N + ts - 1) / ts, (a->M + ts - 1) / ts)) return true;
+    if (set_tile_order(a, wtiles, (a->M + ts - 1) / ts)) return true;
     a->rf_ts = 0;
+    a->rf_nb = 0;
     return false;
 }
 

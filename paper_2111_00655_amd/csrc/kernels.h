@@ -68,7 +68,8 @@ enum GemmMode : int32_t {
 
 enum GemmTile : int32_t {
     TILE_AUTO = 0, TILE_S = 1, TILE_M = 2, TILE_L = 3, TILE_S8 = 4, TILE_S16 = 5,
-    TILE_R32 = 6, TILE_R16 = 7     // register-fed convolution kernels, 32x32 / 16x16 tiles (gemm_rf.h)
+    TILE_R32 = 6, TILE_R16 = 7,    // register-fed convolution kernels, 32x32 / 16x16 tiles (gemm_rf.h)
+    TILE_R16X2 = 8                 // register-fed dense: a wave owns two 16x16 tiles that share the activations
 };
 
 struct GemmArgs {
@@ -104,6 +105,7 @@ struct GemmArgs {
     int32_t cs_len, ldb;
     int32_t mode, tile, batch;
     int32_t rf_ts, rf_tapk, rf_wgk;        // tile edge 32|16, tap mode 1|9|4|0 (-1: dense), K-waves per workgroup
+    int32_t rf_nb;                         // dense: 16-row weight tiles per wave (1, or 2 sharing the activation operand)
     int32_t rf_convt;                      // 1: transposed convolution, one sub-pixel phase per grid.z slice
     int32_t bias_on_row;                   // 1: channel = i (conv), 0: channel = j (dense)
     int32_t gemv;                          // 1: GM_NT with at most 8 rows runs the matrix-vector kernel (a wave per column)
@@ -270,7 +272,8 @@ size_t gemm_scratch_bytes(const GemmArgs &a);
 // MFMAs per wave, at most 16 waves); -w: as 0, but at most w waves (several chunks per wave then).
 bool rf_resolve(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves = 0);
 // The same for GM_NT dense (A = activations [M,K], B = weights [N,K], no batch).
-bool rf_resolve_dense(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves = 0);
+// nb = 2 (ts = 16 only): a wave computes two weight tiles against one tile of activation rows.
+bool rf_resolve_dense(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves = 0, int nb = 1);
 // The same for GM_CONVT (kernel and output sizes divisible by the stride).
 bool rf_resolve_convt(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves = 0);
 size_t rf_pack_bytes(const GemmArgs &a);

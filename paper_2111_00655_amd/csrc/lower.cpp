@@ -531,7 +531,7 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
         } else {
             GemmArgs &a = c.gemm;
             a.tile = be.tile;
-            const bool want_rf = a.tile == TILE_R32 || a.tile == TILE_R16;
+            const bool want_rf = a.tile == TILE_R32 || a.tile == TILE_R16 || a.tile == TILE_R16X2;
             bool rf = false;
             a.batch = 1;
             a.epi = epi;
@@ -553,7 +553,8 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
                     a.cs_stride = (int64_t)a.M * rs.shape.d[2];
                 }
                 if (want_rf && g.nodes[wb].kind == NODE_CONST)
-                    rf = rf_resolve_dense(&a, a.tile == TILE_R32 ? 32 : 16, epi_fast_flags(epi), ctx.n_cus, rfw);
+                    rf = rf_resolve_dense(&a, a.tile == TILE_R32 ? 32 : 16, epi_fast_flags(epi), ctx.n_cus, rfw,
+                                           a.tile == TILE_R16X2 ? 2 : 1);
                 if (rf) c.pack_bytes = rf_pack_bytes(a);
             } else if (k0 == CLG_OP_BATCH_MATMUL) {
                 const bool tb = anchor.attrs.transpose_b != 0;
@@ -658,7 +659,7 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
             c.bound = 0;
             if (rf) {
                 c.scratch_bytes = gemm_scratch_bytes(a);
-                c.name = (a.rf_tapk == -1 ? "dense_rf" + std::to_string(a.rf_ts)
+                c.name = (a.rf_tapk == -1 ? "dense_rf" + std::to_string(a.rf_ts) + (a.rf_nb == 2 ? "x2" : "")
                                           : std::string(a.rf_convt ? "convt_rf" : (a.D > 1 ? "conv3d_rf" : "conv_rf")) + std::to_string(a.rf_ts) + "_t" +
                                                 std::to_string(a.rf_tapk)) +
                          "_w" + std::to_string(a.rf_wgk) + (a.cs_len ? "_split" : "");

@@ -63,11 +63,12 @@ bool relower_for(const Context &ctx, const KernelCall &leader, const KernelCall 
     *out = c;
     GemmArgs &a = out->gemm;
     const int ts = leader.gemm.rf_ts, wgk = leader.gemm.rf_wgk;
-    if (a.rf_ts != ts || a.rf_wgk != wgk) {
+    if (a.rf_ts != ts || a.rf_wgk != wgk || a.rf_nb != leader.gemm.rf_nb) {
         const int flags = epi_fast_flags(a.epi);
         const bool dense = a.rf_tapk == -1;
         if (!dense && (a.KD > 1 || a.rf_fold)) return false;
-        const bool ok = dense ? rf_resolve_dense(&a, ts, flags, ctx.n_cus, wgk) : rf_resolve(&a, ts, flags, ctx.n_cus, wgk);
+        const bool ok = dense ? rf_resolve_dense(&a, ts, flags, ctx.n_cus, wgk, leader.gemm.rf_nb == 2 ? 2 : 1)
+                              : rf_resolve(&a, ts, flags, ctx.n_cus, wgk);
         if (!ok) return false;
         out->pack_bytes = rf_pack_bytes(a);
         out->scratch_bytes = gemm_scratch_bytes(a);

@@ -19,6 +19,8 @@ OP_TOL = 1e-4
 NET_TOL = 1e-3
 IGEMM = ("igemm", "igemm_s", "igemm_s8", "igemm_s16", "igemm_m", "igemm_l")
 RF = ("igemm_r32", "igemm_r16")          # register-fed convolution kernels (packed weights)
+RFW = ("igemm_r32_w4", "igemm_r16_w8")   # the same with a bound on the K-waves per workgroup (several chunks per wave)
+RFD = RF + RFW + ("igemm_r16x2_w4", "igemm_r16x2_w8")     # ... and the dense kernels with two tiles per wave
 
 
 def rng_for(*key):
@@ -95,12 +97,12 @@ def conv_desc(case, seed, batch=1, groups=1):
     return d, tail_pattern(P("conv2d", W, W), tail)
 
 
-@pytest.mark.parametrize("backend", IGEMM + RF + ("direct",))
+@pytest.mark.parametrize("backend", IGEMM + RF + RFW + ("direct",))
 @pytest.mark.parametrize("ci", range(len(CONV_CASES)))
 def test_conv2d_fused(ci, backend):
     d, pat = conv_desc(CONV_CASES[ci], 10 + ci)
     name, _ = run_single_group(d, backend, pat)
-    if backend in RF:
+    if backend in RF + RFW:
         assert name.startswith("conv_rf"), name
 
 
@@ -415,7 +417,7 @@ DENSE_CASES = [(128, 768, 768, ("bias_add",)), (128, 768, 3072, ("bias_add", "ge
 DENSE_RF = {0, 1, 2, 3, 4, 7, 8}          # (K = 2100 and K = 100 are not multiples of 8 / 16)
 
 
-@pytest.mark.parametrize("backend", IGEMM + RF)
+@pytest.mark.parametrize("backend", IGEMM + RFD)
 @pytest.mark.parametrize("ci", range(len(DENSE_CASES)))
 def test_dense_fused(ci, backend):
     m, k, n, tail = DENSE_CASES[ci]
@@ -432,14 +434,15 @@ def test_dense_fused(ci, backend):
             y = d.op(op, [y])
     d.mark_output(y)
     name, _ = run_single_group(d, backend, tail_pattern(P("dense", W, W), tail))
-    if backend in RF:
+    if backend in RFD:
         assert name.startswith("dense_rf") == (ci in DENSE_RF), name
+        assert ("x2" in name) == (backend.startswith("igemm_r16x2") and ci in DENSE_RF), name
     else:
         assert (name == "gemv_nt") == (m <= 8 and k % 4 == 0 and k >= 512), name
 
 
-@pytest.mark.parametrize("backend", ("igemm", "igemm_s", "igemm_s8", "igemm_s16") + RF)
-@pytest.mark.parametrize("case", [(128, 768, 12, 64), (70, 64, 3, 32), (5, 128, 2, 16)])
+@pytest.mark.parametrize("backend", ("igemm", "igemm_s", "igemm_s8", "igemm_s16") + RFD)
+@pytest.mark.parametrize("case", [(128, 768, 12, 64), (70, 64, 3, 32), (5, 128, 2, 16), (33, 256, 5, 48)])
 def test_dense_stored_split_into_heads(case, backend):
     """transpose(reshape(bias_add(dense))) as one kernel: [M, H*D] is stored as [H, M, D]."""
     m, k, h, dd = case
@@ -911,7 +914,7 @@ REGION_DENSE_CASES = {
 }
 
 
-@pytest.mark.parametrize("backend", RF)
+@pytest.mark.parametrize("backend", RF + ("igemm_r16_w4", "igemm_r16x2_w4"))
 @pytest.mark.parametrize("case", sorted(REGION_DENSE_CASES))
 def test_region_of_sibling_dense_layers(case, backend):
     """Independent dense layers as one launch (graph-level backend, Sec. 4.3): every subset of the region

@@ -17,6 +17,10 @@ W = "*"
 # igemm variants whose conv2d patterns carry no groups = 1 constraint
 GROUPED_CONV_BACKENDS = ("igemm_r32", "igemm_r16", "igemm_r32_w4", "igemm_r32_w8", "igemm_r16_w4", "igemm_r16_w8")
 
+# igemm variants that exist for dense layers only (registering their convolution patterns would only
+# repeat what the plain 16x16 variants do)
+DENSE_ONLY_BACKENDS = ("igemm_r16x2_w4", "igemm_r16x2_w8")
+
 # attribute names a constraint may refer to, in the order of the C enum
 ATTR_NAMES = ("groups", "kernel_h", "kernel_w", "stride_h", "stride_w",
               "pad_h", "pad_w", "transpose_b", "axis")
@@ -113,12 +117,16 @@ def default_registry(variants=("igemm",), sepconv=False, attention=False):
 
     # --- MFMA implicit GEMM / GEMM variants
     for be in variants:
+        dense = P("dense", W, W)
+        if be in DENSE_ONLY_BACKENDS:
+            add(be, _tails(dense, [(), ("bias_add",), ("bias_add", "relu"), ("bias_add", "gelu"), ("bias_add", "add")]))
+            add(be, [P("transpose", P("reshape", P("bias_add", dense, W)))])
+            continue
         # the register-fed kernels also run grouped convolutions
         conv = P("conv2d", W, W) if be in GROUPED_CONV_BACKENDS else P("conv2d", W, W, groups=(1, 1))
         add(be, _tails(conv, [(), ("bias_add",), ("bias_add", "relu"),
                               ("bias_add", "add"),
                               ("bias_add", "add", "relu")]))
-        dense = P("dense", W, W)
         add(be, _tails(dense, [(), ("bias_add",), ("bias_add", "relu"),
                                ("bias_add", "gelu"), ("bias_add", "add"),
                                ("bias_add", "relu", "reshape")]))
