@@ -411,7 +411,7 @@ def main():
             roof2 = roofline_of(r2, ms2 * 1e6)
             roof2["algorithmic_bytes"] = int(sum(r["bytes"] for r in r2 if r["bound"] == "mfma"))
             roof2["algorithmic_flops"] = int(sum(r["flops"] for r in r2 if r["bound"] == "mfma"))
-            extra[name] = dict(ms_per_step=round(ms2, 4), kernels=p2.n_launches,
+            extra[name] = dict(ms_per_step=round(ms2, 4), cold_cache_ms=round(cold_cache_ms(p2, steps=10), 4), kernels=p2.n_launches,
                                kernel_only_ms=round(sum(r["ns"] for r in r2) / 1e6, 4),
                                mfma_tflops=roof2["achieved"], roofline=roof2, graph_level=gl2, optimise_s=round(sum(
                                    v for k, v in t2.items() if k.endswith("_s")) + gl2["search_s"], 2))

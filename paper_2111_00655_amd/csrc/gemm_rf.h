@@ -43,6 +43,21 @@ namespace clg {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
+// Phase time stamps, compiled in only for the phase probe (rf_phase_probe.hip, built with
+// -DCLG_RF_STAMPS): thread 0 of every workgroup writes the device's 100 MHz wall clock at five points
+// of the convolution kernel into g_rf_stamps[workgroup * 8 + point].  The library itself is built
+// without the macro and carries none of this.
+#ifdef CLG_RF_STAMPS
+static __device__ long long *g_rf_stamps;
+#define CLG_STAMP(i)                                                                                          \
+    do {                                                                                                      \
+        if (threadIdx.x == 0)                                                                                 \
+            g_rf_stamps[((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 8 + (i)] = wall_clock64(); \
+    } while (0)
+#else
+#define CLG_STAMP(i) do { } while (0)
+#endif
+
 template <int TS>
 struct RfMfma;
 
@@ -110,6 +125,7 @@ __device__ __forceinline__ void conv_rf_body(const GemmArgs &p, const int bx, co
     constexpr bool DEPTH = GEO == 2 || GEO == 3;
     constexpr bool PRELU = GEO == 4;
 
+    CLG_STAMP(0);                                            // entry
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int w = __builtin_amdgcn_readfirstlane(tid / kWave);
@@ -191,6 +207,7 @@ __device__ __forceinline__ void conv_rf_body(const GemmArgs &p, const int bx, co
     acc_t acc;
 #pragma unroll
     for (int g = 0; g < NACC; ++g) acc[g] = 0.f;
+    CLG_STAMP(1);                                            // arguments read, indices and tail operands set up
 
     if constexpr (TAPK == 1) {
         // ---- 1x1: MFMA n contracts channels n*NSLOT .. n*NSLOT+NSLOT-1 at this lane's pixel
@@ -375,11 +392,20 @@ __device__ __forceinline__ void conv_rf_body(const GemmArgs &p, const int bx, co
     }
 
     // ---- the K-waves add their accumulators in LDS, in wave order
+#ifdef CLG_RF_STAMPS
+    if (threadIdx.x == 0) {                                  // the first wave's accumulator is final: its K loop is over
+        float sink = 0.f;
+        for (int g = 0; g < NACC; ++g) sink += acc[g];
+        asm volatile("" ::"v"(sink));
+    }
+#endif
+    CLG_STAMP(2);                                            // K loop of the first wave done
     if constexpr (WGK > 1) {
 #pragma unroll
         for (int g = 0; g < NACC; ++g) red[w * PER_WAVE + g * kWave + lane] = acc[g];
         __syncthreads();
     }
+    CLG_STAMP(3);                                            // all K-waves have arrived
 #pragma unroll
     for (int t = 0; t < EPT; ++t) {
         float v;
@@ -396,6 +422,10 @@ __device__ __forceinline__ void conv_rf_body(const GemmArgs &p, const int bx, co
             else p.C[e_off[t]] = finish_value(p, v, e_bias[t], e_add[t]);
         }
     }
+#ifdef CLG_RF_STAMPS
+    __builtin_amdgcn_s_waitcnt(0);                           // the stores have left the wave
+#endif
+    CLG_STAMP(4);                                            // sums taken, tail applied, stores issued
 }
 
 template <int TS, int TAPK, int WGK, int GEO, int PF>
@@ -739,6 +769,9 @@ __global__ void rf_pack_kernel(const float *w, float *dst, GemmArgs p, int64_t t
 }
 
 // gemm_rf.hip
+#ifdef CLG_RF_STAMPS
+void rf_set_stamps(long long *dev);      // where the stamps go (device memory, 8 values per workgroup)
+#endif
 int launch_rf_conv(const GemmArgs &a, hipStream_t s);
 int launch_rf_multi(const GemmArgs *members, int n, hipStream_t s);
 

@@ -239,6 +239,10 @@ int chunk_groups(int tapk) { return tapk == 1 || tapk == 4 ? 4 : (tapk == 9 ? 9 
 
 }  // namespace
 
+#ifdef CLG_RF_STAMPS
+void rf_set_stamps(long long *dev) { (void)hipMemcpyToSymbol(HIP_SYMBOL(g_rf_stamps), &dev, sizeof(dev)); }
+#endif
+
 int launch_rf_conv(const GemmArgs &a, hipStream_t s) {
     if (a.rf_tapk == -1) {
         if (((uintptr_t)a.A & 15) != 0) return (int)hipErrorInvalidValue;      // activations are read 16 bytes at a time
