@@ -101,6 +101,7 @@ def graph_level(plan, steps, warmup, seed=0):
     rg = plan.regions()
     return dict(op_level_ms=round(op_ms, 4), graph_level_ms=round(gl_ms, 4), launches_before=launches_before,
                 launches_after=plan.n_launches, regions=max(rg) + 1 if rg else 0, kernels=n, handed_over=int(sum(best)),
+                digits=[int(b) for b in best],
                 search_seed_ns=int(seed_ns), search_best_ns=int(best_ns), strings_measured=evals,
                 history_ms=[round(h / 1e6, 4) for h in hist], search_s=round(search_s, 2))
 
@@ -217,8 +218,11 @@ def ablation(desc, variants, opts, cost_log, steps, warmup):
     single variant, next to the search over all of them (paper Sec. 5.5 studies
     the same question for its backends)."""
     import workloads as wl
+    from workloads import patterns as wp
     out = {}
     for v in variants:
+        if v in wp.DENSE_ONLY_BACKENDS:        # a variant for dense layers only covers no network by itself
+            continue
         reg = wl.default_registry((v,))
         try:
             s, plan, _, _, t = optimise(desc, reg, opts, cost_log)
@@ -348,6 +352,12 @@ def main():
                     help="also price a few compute-bound single operators (large dense, batch-32 3x3 convolutions) under every "
                          "MFMA kernel variant with the library's measurer and write TFLOP/s per variant to FILE: what the "
                          "kernels reach where launch and memory latency do not bound them")
+    ap.add_argument("--digits", default="", metavar="FILE",
+                    help="graph-level digits: written to FILE after the search; with --passes-only read from it instead of searching")
+    ap.add_argument("--passes-only", action="store_true",
+                    help="for hardware-counter runs: op-level placement from the cost log, graph-level digits from --digits, then "
+                         "nothing but warm-up + steps passes of the final plan (no per-kernel timing, graph replay, cold-cache "
+                         "leg or other workloads), so that every dispatch of the run belongs to one of warmup + steps equal passes")
     ap.add_argument("--variants", default="", metavar="NAME,...",
                     help="register only these MFMA kernel-variant backends instead of all of them")
     ap.add_argument("--summary", default="", metavar="FILE",
@@ -380,8 +390,27 @@ def main():
     desc = wl.MODEL_BUILDERS[args.model](0)
     s, plan, costs, ids, timing = optimise(desc, reg, opts, args.cost_log, rules)
     timing["n_patterns"] = B.clg_num_patterns(s.ctx)
+    if args.passes_only:
+        digits = [int(c) for c in open(args.digits).read().strip()] if args.digits else [0] * plan.n_kernels
+        plan.bind()
+        plan.set_handover(digits, lanes=1)
+        ms = time_steps(plan, args.steps, args.warmup)
+        if args.calib_copy:
+            n = args.calib_copy * 1024 * 1024 // 4
+            src = torch.ones(n, dtype=torch.float32, device="cuda")
+            dst = torch.empty_like(src)
+            for _ in range(3):
+                dst.copy_(src)
+            torch.cuda.synchronize()
+        print(json.dumps({"metric": f"batch-1 fp32 latency (ms) {args.model}", "value": round(ms, 4), "unit": "ms", "passes":
+                          args.steps + args.warmup, "launches_per_pass": plan.n_launches,
+                          "kernels": [k["name"] for k in plan.kernels()]}))
+        return
     # op-level placement done; the graph-level search (Sec. 4.3) then decides which sibling kernels share a launch
     gl_main = graph_level(plan, max(50, args.steps // 2), args.warmup)
+    if args.digits:
+        with open(args.digits, "w") as f:
+            f.write("".join(str(int(b)) for b in gl_main["digits"]) + "\n")
     timing["graph_level_s"] = gl_main["search_s"]
     ms_per_step = time_steps(plan, args.steps, args.warmup)
     rows = kernel_table(plan)

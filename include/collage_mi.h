@@ -344,7 +344,10 @@ int32_t clg_match_all(clg_ctx *ctx, clg_graph *g, clg_match *out, size_t cap,
  * A match the backend cannot run costs CLG_COST_INF. */
 int32_t clg_profile_match(clg_ctx *ctx, clg_graph *g, int32_t match,
                           const clg_profile_opts *opts, int64_t *cost_ns);
-/* cost_ns: host array with one entry per match of the last clg_match_all. */
+/* cost_ns: host array with one entry per match of the last clg_match_all.
+ * With the cost log on, every kernel this call has to measure is measured
+ * twice, in two passes over the matches, and the smaller figure is kept (a
+ * whole measurement is now and then inflated by the device's clocks). */
 int32_t clg_profile_all(clg_ctx *ctx, clg_graph *g,
                         const clg_profile_opts *opts, int64_t *cost_ns,
                         size_t cap);

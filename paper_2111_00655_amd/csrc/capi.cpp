@@ -2,6 +2,7 @@
 #include <cstdio>
 #include <new>
 #include <string>
+#include <vector>
 
 #include <hip/hip_runtime_api.h>
 
@@ -297,7 +298,27 @@ int32_t clg_profile_all(clg_ctx *ctx, clg_graph *g, const clg_profile_opts *opts
     if (g->g.ctx != &ctx->c) return fail(CLG_INVALID_ARG, "graph belongs to another context");
     if (!g->g.matched) return fail(CLG_INVALID_ARG, "clg_match_all has not been called on this graph");
     if (cap < g->g.matches.size()) return fail(CLG_BUFFER_TOO_SMALL, "%zu matches, room for %zu", g->g.matches.size(), cap);
-    for (size_t i = 0; i < g->g.matches.size(); ++i) {
+    // Two passes some seconds apart, the smaller figure kept: now and then a whole measurement (all its
+    // batches) comes out 1.3 - 1.6 times too long (the device's clocks, for some milliseconds), and a
+    // candidate priced that way would lose the search for no reason.  The second pass measures what the
+    // first one measured (not what the cost log already held) and serves everything else from the log.
+    const size_t n = g->g.matches.size();
+    std::vector<char> fresh(n, 0);
+    for (size_t i = 0; i < n; ++i) {
+        bool f = false;
+        const int32_t rc = profile_match(ctx->c, g->g, (int32_t)i, opts, &cost_ns[i], &f);
+        if (rc != CLG_OK) return rc;
+        fresh[i] = f ? 1 : 0;
+    }
+    const bool cached = !opts || opts->no_cache == 0;
+    for (size_t i = 0; i < n && cached; ++i) {
+        if (fresh[i]) {
+            const int32_t rc = profile_match(ctx->c, g->g, (int32_t)i, opts, &cost_ns[i], nullptr, true);
+            if (rc != CLG_OK) return rc;
+        }
+    }
+    for (size_t i = 0; i < n && cached; ++i) {          // matches that share a key share the final figure
+        if (cost_ns[i] >= CLG_COST_INF) continue;
         const int32_t rc = profile_match(ctx->c, g->g, (int32_t)i, opts, &cost_ns[i]);
         if (rc != CLG_OK) return rc;
     }

@@ -248,7 +248,10 @@ int32_t execute_plan(Plan &p, const void *const *inputs, void *const *outputs, v
 // static_ws.hip: execution with the library's own fixed workspace (no allocation anywhere)
 int32_t static_workspace_init(int32_t device);
 int32_t execute_plan_static(Plan &p, const void *const *inputs, void *const *outputs, void *stream);
-int32_t profile_match(Context &ctx, Graph &g, int32_t match, const clg_profile_opts *opts, int64_t *cost_ns);
+// fresh (may be null): set to whether this call measured (false: served from the cost log, or no kernel).
+// again: measure even if the log has the key, and keep the smaller of the two figures.
+int32_t profile_match(Context &ctx, Graph &g, int32_t match, const clg_profile_opts *opts, int64_t *cost_ns,
+                      bool *fresh = nullptr, bool again = false);
 int32_t profile_empty(Context &ctx, const clg_profile_opts *opts, int64_t *cost_ns);
 int32_t cost_log_load(Context &ctx, const char *path);
 int32_t cost_log_save(const Context &ctx, const char *path);

@@ -3,9 +3,10 @@
 // i.e. one kernel, at a time; pricing means building the kernel and running it
 // several times on the device, and every result is kept in a log for reuse.
 //
-// Protocol: a few launches to size the batches, one untimed batch (the
-// measurer's host work between two candidates leaves the GPU idle long enough
-// for its clocks to drop; a whole batch of launches brings them back up), then
+// Protocol: a few launches to size the batches, untimed batches until two in a
+// row agree within a tenth (the measurer's host work between two candidates
+// leaves the GPU idle long enough for its clocks to drop; launches bring them
+// back up), then
 // `batches` timed batches of back-to-back launches between two HIP events; the
 // cost is the smallest batch time per launch, rounded once to integer
 // nanoseconds.  (The smallest, not the median:
@@ -100,7 +101,15 @@ int32_t time_launches(const Opts &o, F &&launch, int64_t *cost_ns) {
         const double per_us = std::max(ms * 1000.0 / o.warmup, 0.05);
         n = (int)std::min<double>(o.max_launches, std::max(5.0, std::ceil(o.min_batch_us / per_us)));
     }
-    if (rc == CLG_OK) rc = run(n, &ms);          // untimed: clocks and caches reach their steady state
+    // untimed batches until two in a row agree within a tenth (at most six): the fills and packing in
+    // front of a measurement and the host work between candidates let the clocks drop, and short kernels
+    // would otherwise be timed while they ramp up again (whole measurements came out at twice their value)
+    double prev = -1;
+    for (int settle = 0; settle < 6 && rc == CLG_OK; ++settle) {
+        rc = run(n, &ms);
+        if (prev > 0 && std::fabs(ms - prev) <= 0.1 * std::min(ms, prev)) break;
+        prev = ms;
+    }
     std::vector<double> per;
     for (int b = 0; b < o.batches && rc == CLG_OK; ++b) {
         rc = run(n, &ms);
@@ -124,7 +133,9 @@ int32_t profile_empty(Context &ctx, const clg_profile_opts *opts, int64_t *cost_
     }, cost_ns);
 }
 
-int32_t profile_match(Context &ctx, Graph &g, int32_t match, const clg_profile_opts *opts, int64_t *cost_ns) {
+int32_t profile_match(Context &ctx, Graph &g, int32_t match, const clg_profile_opts *opts, int64_t *cost_ns, bool *fresh,
+                      bool again) {
+    if (fresh) *fresh = false;
     if (ctx.device < 0) return fail(CLG_HIP_ERROR, "host-only context: no device to profile on");
     if (!g.matched) return fail(CLG_INVALID_ARG, "clg_match_all has not been called on this graph");
     const Opts o = resolve(opts);
@@ -135,7 +146,7 @@ int32_t profile_match(Context &ctx, Graph &g, int32_t match, const clg_profile_o
         return CLG_OK;
     }
     if (lrc != CLG_OK) return lrc;
-    if (o.cache) {
+    if (o.cache && !again) {
         auto it = ctx.cost_log.find(c.key);
         if (it != ctx.cost_log.end()) {
             *cost_ns = it->second;
@@ -215,7 +226,12 @@ int32_t profile_match(Context &ctx, Graph &g, int32_t match, const clg_profile_o
                            c.scratch_bytes ? set + scratch_off : nullptr, c.pack_bytes ? set + pack_off : nullptr, nullptr);
     }, cost_ns);
     if (rc != CLG_OK) return rc;
-    if (o.cache) ctx.cost_log[c.key] = *cost_ns;
+    if (fresh) *fresh = true;
+    if (o.cache) {
+        auto it = ctx.cost_log.find(c.key);
+        if (again && it != ctx.cost_log.end()) *cost_ns = std::min(*cost_ns, it->second);
+        ctx.cost_log[c.key] = *cost_ns;
+    }
     return CLG_OK;
 }
 
