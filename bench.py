@@ -31,12 +31,15 @@ VARIANTS = ("igemm", "igemm_s", "igemm_s8", "igemm_s16", "igemm_m", "igemm_l", "
             "igemm_r16x2_w4", "igemm_r16x2_w8")
 
 
-# HBM-side traffic of the fp32 MFMA kernels of one ResNet-50 step, from two rocprofv3 --pmc runs of this file
-# (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch, summed over the 56 such dispatches of a step (53 fused convolutions, 3 split-K reductions) and averaged over
-# the steps of the run).  Scale factors from the 256 MiB plain device copy of --calib-copy in the same runs:
-# WRITE_SIZE read 262144.0 KiB for it (factor 1.000), FETCH_SIZE 131083.5 KiB (factor 2.000).  The figures hold
-# for the kernel sources they were taken with; after any change to them `traffic` is reported as null.
-TRAFFIC = {"resnet50": {"sources": "73eadad6ff06c17b", "fetch_bytes": 296.50e6, "write_bytes": 46.86e6}}
+# HBM-side traffic of the fp32 MFMA kernels of one step, from two rocprofv3 --pmc runs of this file with
+# --passes-only (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch, summed over the MFMA-kernel dispatches and divided
+# by the warm-up + steps passes of the run: ResNet-50 54 such dispatches per pass - 51 convolution launches, two of
+# them regions of two, and 3 split-K reductions; BERT-base 60).  Scale factors from the 256 MiB plain device
+# copy of --calib-copy in the same runs: WRITE_SIZE read 262144.0 KiB for it (factor 1.000), FETCH_SIZE
+# 131083.5 KiB (factor 2.000).  profiles/*_pmc_summary.txt hold the runs.  The figures hold for the kernel sources
+# they were taken with; after any change to them `traffic` is reported as null.
+TRAFFIC = {"resnet50": {"sources": "e5c2f7a36c4075df", "fetch_bytes": 290.93e6, "write_bytes": 46.87e6},
+           "bert_base": {"sources": "e5c2f7a36c4075df", "fetch_bytes": 689.35e6, "write_bytes": 47.19e6}}
 
 
 def kernel_sources_fingerprint():
@@ -268,10 +271,11 @@ def roofline_of(rows, step_ns=None):
     t = sum(r["ns"] for r in mf) * scale
     fl = sum(r["flops"] for r in mf)
     achieved = fl / t / 1e3 if t > 0 else 0.0
+    n_launch = sum(1 for r in mf if r["ns"] > 0)       # the members of a fused region count once (the first carries the time)
     return dict(bound="mfma", achieved=round(achieved, 3), peak=PEAK_MFMA_F32_TFLOPS, unit="TFLOP/s",
                 frac=round(achieved / PEAK_MFMA_F32_TFLOPS, 5), traffic=None,
-                kernel="fp32 MFMA convolution / GEMM kernels (all their launches of one step)", launches=len(mf),
-                avg_launch_us=round(t / max(len(mf), 1) / 1e3, 3),
+                kernel="fp32 MFMA convolution / GEMM kernels (all their launches of one step)", launches=n_launch,
+                avg_launch_us=round(t / max(n_launch, 1) / 1e3, 3),
                 share_of_kernel_time=round(t / max(total * scale, 1), 4))
 
 
@@ -440,6 +444,9 @@ def main():
             roof2 = roofline_of(r2, ms2 * 1e6)
             roof2["algorithmic_bytes"] = int(sum(r["bytes"] for r in r2 if r["bound"] == "mfma"))
             roof2["algorithmic_flops"] = int(sum(r["flops"] for r in r2 if r["bound"] == "mfma"))
+            tr2 = TRAFFIC.get(name)
+            if tr2 and tr2["sources"] == kernel_sources_fingerprint():
+                roof2["traffic"] = int(tr2["fetch_bytes"] + tr2["write_bytes"])
             extra[name] = dict(ms_per_step=round(ms2, 4), cold_cache_ms=round(cold_cache_ms(p2, steps=10), 4), kernels=p2.n_launches,
                                kernel_only_ms=round(sum(r["ns"] for r in r2) / 1e6, 4),
                                mfma_tflops=roof2["achieved"], roofline=roof2, graph_level=gl2, optimise_s=round(sum(
