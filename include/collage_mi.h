@@ -338,7 +338,13 @@ int32_t clg_match_all(clg_ctx *ctx, clg_graph *g, clg_match *out, size_t cap,
 /* Times one match as one kernel on the device and returns integer nanoseconds
  * per launch (fastest of several batches of back-to-back launches between two
  * HIP events, after warm-up).  Non-constant operands are scratch tensors the
- * library allocates and fills from opts->seed; constants are read in place.
+ * library allocates and fills from opts->seed (row ids of a gather: seeded ids
+ * spread over the table); small constants are read in place.  The large
+ * operands - inputs, output, weights - exist in several copies (64 MB in all,
+ * at most 32) and consecutive launches rotate through them, so that every
+ * launch finds its operands in the memory-side cache and not in the L2, as a
+ * kernel does inside a network (the library's scratch block grows to hold the
+ * copies; weight re-packing for the copies is not part of the cost).
  * Results are cached by (backend, fused kind, attributes, shapes): the cost
  * log.  opts may be NULL (all defaults, cache on).  Synchronises the device.
  * A match the backend cannot run costs CLG_COST_INF. */

@@ -841,12 +841,16 @@ def test_profiler_is_repeatable_and_cached():
     ms = s.match()
     conv = [i for i, m in enumerate(ms) if m.n_nodes == 3 and reg[m.pattern][0] == "igemm"][0]
     nocache = B.ProfileOpts(no_cache=1)
-    a = [B.clg_profile_match(s.ctx, s.graph, conv, nocache) for _ in range(5)]
-    assert (max(a) - min(a)) / float(np.median(a)) < 0.25, a
+    a = sorted(B.clg_profile_match(s.ctx, s.graph, conv, nocache) for _ in range(7))
+    # The paper reports < 3 % spread for its measurements (Sec. 5.2).  Here about one measurement in thirty is
+    # inflated as a whole (clocks), so: five of seven within 5 % of the smallest, and clg_profile_all below
+    # (two passes, smaller figure) within 5 % of it too.
+    assert a[4] <= 1.05 * a[0], a
     assert B.clg_cost_log_size(s.ctx) == 0
     c1 = B.clg_profile_match(s.ctx, s.graph, conv)
     assert B.clg_cost_log_size(s.ctx) == 1
     assert B.clg_profile_match(s.ctx, s.graph, conv) == c1            # served from the log
+    assert c1 <= 1.10 * a[0] and a[0] <= 1.10 * c1, (c1, a)
     assert B.clg_profile_empty(s.ctx) > 0
     s.close()
 
