@@ -109,6 +109,18 @@ def graph_level(plan, steps, warmup, seed=0):
                 history_ms=[round(h / 1e6, 4) for h in hist], search_s=round(search_s, 2))
 
 
+def weight_memory(plan):
+    """Device memory of the weights: the plan's packed copies, and the caller's copies that no execution of the
+    plan reads any more (clg_plan_reads_constant): capacity that could be released, not traffic."""
+    import numpy as np
+    nr = plan.constants_not_read()
+    d = plan.s.desc
+    return dict(packed_mb=round(sum(nr.values()) / 1e6, 1),
+                caller_copies_not_read_mb=round(sum(4.0 * float(np.prod(d.nodes[n]["shape"])) for n in nr) / 1e6, 1),
+                caller_constants_read_mb=round(sum(4.0 * float(np.prod(nd["shape"])) for n, nd in enumerate(d.nodes)
+                                                   if nd["kind"] == "const" and n not in nr) / 1e6, 1))
+
+
 def large_shapes(path):
     """Single operators large enough to be bound by the matrix cores, priced under every MFMA variant backend by the
     library's measurer (launch-inclusive time of back-to-back launches).  Returns {case: {backend: TFLOP/s}}."""
@@ -449,7 +461,8 @@ def main():
                 roof2["traffic"] = int(tr2["fetch_bytes"] + tr2["write_bytes"])
             extra[name] = dict(ms_per_step=round(ms2, 4), cold_cache_ms=round(cold_cache_ms(p2, steps=10), 4), kernels=p2.n_launches,
                                kernel_only_ms=round(sum(r["ns"] for r in r2) / 1e6, 4),
-                               mfma_tflops=roof2["achieved"], roofline=roof2, graph_level=gl2, optimise_s=round(sum(
+                               mfma_tflops=roof2["achieved"], roofline=roof2, graph_level=gl2, weights=weight_memory(p2),
+                               optimise_s=round(sum(
                                    v for k, v in t2.items() if k.endswith("_s")) + gl2["search_s"], 2))
             p2.destroy()
             s2.close()
@@ -577,6 +590,7 @@ def main():
         "large_shapes_tflops": large,
         "graph_level": gl_main,
         "graph_level_search": graph_level_rows,
+        "weights": weight_memory(plan),
         "empty_launch_ns": int(empty_ns),
         "measurer_spread": spread,
         "optimise": {k: (round(v, 4) if isinstance(v, float) else v) for k, v in timing.items()},

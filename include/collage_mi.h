@@ -517,6 +517,16 @@ int32_t clg_search_stats(const clg_graph *g, int64_t stats[5]);
 int32_t clg_compile(clg_ctx *ctx, clg_graph *g, const int32_t *matches,
                     size_t n, clg_plan **out);
 int32_t clg_plan_destroy(clg_plan *plan);
+/* Whether executions of the plan read the caller's device buffer of constant
+ * `node` (*reads = 1) or only the plan's own packed copy of it, made by
+ * clg_compile (*reads = 0; also for a constant no kernel of the plan uses).  A
+ * constant that is not read may be released or overwritten by the caller as
+ * far as this plan is concerned (the measurer and later clg_compile calls on
+ * the graph still read it).  *packed_bytes (may be NULL) receives the size of
+ * the plan's packed copies of that constant.  UNKNOWN_ID if node is no
+ * constant of the plan's graph. */
+int32_t clg_plan_reads_constant(const clg_plan *plan, int32_t node, int32_t *reads,
+                                size_t *packed_bytes);
 int32_t clg_plan_workspace_bytes(const clg_plan *plan, size_t *bytes);
 int32_t clg_plan_num_kernels(const clg_plan *plan, size_t *n);
 int32_t clg_plan_kernel_info(const clg_plan *plan, size_t index,

@@ -148,6 +148,7 @@ SYMBOLS = {
     "clg_evolve": (C.c_int32, [C.c_size_t, C.POINTER(EsOpts), C.POINTER(C.c_uint32), C.c_size_t, FITNESS_FN,
                                C.c_void_p, C.POINTER(C.c_uint8), C.POINTER(C.c_double), C.POINTER(C.c_int64),
                                C.POINTER(C.c_double), _i32p]),
+    "clg_plan_reads_constant": (C.c_int32, [_P, C.c_int32, _i32p, C.POINTER(C.c_size_t)]),
     "clg_plan_num_launches": (C.c_int32, [_P, C.POINTER(C.c_size_t)]),
     "clg_plan_region_of": (C.c_int32, [_P, C.c_size_t, _i32p]),
     "clg_execute": (C.c_int32, [_P, C.POINTER(_P), C.POINTER(_P), _P, C.c_size_t, _P]),
@@ -501,6 +502,13 @@ def clg_execute(plan, inputs, outputs, workspace, ws_bytes, stream=0):
     """inputs / outputs: sequences of device addresses (ints); workspace: device address."""
     _check(lib().clg_execute(plan, _ptr_array(inputs), _ptr_array(outputs), _P(int(workspace) or None),
                              int(ws_bytes), _P(int(stream) or None)))
+
+
+def clg_plan_reads_constant(plan, node):
+    """(whether executions read the caller's buffer of this constant, bytes of the plan's packed copies of it)"""
+    reads, packed = C.c_int32(0), C.c_size_t(0)
+    _check(lib().clg_plan_reads_constant(plan, int(node), C.byref(reads), C.byref(packed)))
+    return bool(reads.value), packed.value
 
 
 def clg_plan_num_launches(plan):

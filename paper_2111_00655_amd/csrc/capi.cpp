@@ -416,6 +416,29 @@ int32_t clg_plan_destroy(clg_plan *plan) {
     return CLG_OK;
 }
 
+int32_t clg_plan_reads_constant(const clg_plan *plan, int32_t node, int32_t *reads, size_t *packed_bytes) {
+    CLG_TRY
+    NEED(plan); NEED(reads);
+    const Plan &p = plan->p;
+    if (node < 0 || node >= (int32_t)p.graph->nodes.size() || p.graph->nodes[node].kind != NODE_CONST)
+        return fail(CLG_UNKNOWN_ID, "node %d is not a constant of the plan's graph", node);
+    *reads = 0;
+    size_t packed = 0;
+    for (size_t i = 0; i < p.calls.size(); ++i) {
+        const KernelCall &c = p.calls[i];
+        if (c.pack_bytes && c.b_node == node) packed += c.pack_bytes;      // this kernel reads its packed copy instead
+        else if (c.a_node == node || c.b_node == node || c.c_node == node) *reads = 1;
+        for (int32_t v : c.epi_nodes)
+            if (v == node) *reads = 1;
+    }
+    for (const Region &r : p.regions)
+        for (size_t k = 0; k < r.members.size(); ++k)
+            if (r.packed[k] && r.fused[k].b_node == node) packed += r.fused[k].pack_bytes;
+    if (packed_bytes) *packed_bytes = packed;
+    return CLG_OK;
+    CLG_CATCH
+}
+
 int32_t clg_plan_workspace_bytes(const clg_plan *plan, size_t *bytes) {
     NEED(plan); NEED(bytes);
     *bytes = plan->p.workspace_bytes;

@@ -25,6 +25,7 @@ class Session:
         self.graph = B.clg_graph_create(self.ctx)
         self._torch = None
         self._keep = []          # device tensors the graph borrows
+        self.const_tensors = {}  # constant node -> its device tensor
         self.matches = None
         self._plans = []         # plans compiled from the graph: it cannot go before they do
         if device is not None:
@@ -51,6 +52,7 @@ class Session:
                 if self._torch is not None:
                     t = self._torch.from_numpy(arr).to(f"cuda:{device}")
                     self._keep.append(t)
+                    self.const_tensors[nid] = t
                     ptr = t.data_ptr()
                 got = B.clg_graph_const(self.graph, dt, arr.shape, ptr)
             else:
@@ -124,6 +126,17 @@ class Plan:
         """Launches of one execution under the current digits: the kernel list without the concatenations
         planned as aliases, the handed-over members of a region counted once."""
         return B.clg_plan_num_launches(self.h)
+
+    def constants_not_read(self):
+        """{constant node: bytes of the plan's packed copies} for the constants whose device buffer no execution
+        of this plan reads (the kernels read the packed copies)."""
+        out = {}
+        for nid, nd in enumerate(self.s.desc.nodes):
+            if nd["kind"] == "const":
+                reads, packed = B.clg_plan_reads_constant(self.h, nid)
+                if not reads and packed:
+                    out[nid] = packed
+        return out
 
     def regions(self):
         """Region index of every kernel (-1: in none)."""

@@ -1010,6 +1010,29 @@ def test_model_with_every_region_fused(name):
     s.close()
 
 
+@pytest.mark.parametrize("name", ["resnet50", "bert_base"])
+def test_a_plan_never_reads_the_weights_it_has_packed(name):
+    """What clg_plan_reads_constant reports as not read can be overwritten after clg_compile: the plan's outputs do
+    not change (the model's hot set is the packed copies, not both)."""
+    import torch
+    desc = wl.resnet50(0, image=64, width=16, blocks=(2, 1), classes=10) if name == "resnet50" else \
+        wl.bert_base(0, layers=2, seq=32, hidden=128, heads=2, ffn=256, vocab=60, max_pos=32)
+    s, plan = _per_operator_plan(desc, "igemm_r16")
+    before = plan.run()
+    gone = plan.constants_not_read()
+    assert len(gone) >= 4
+    for nid in gone:
+        s.const_tensors[nid].fill_(float("nan"))
+    torch.cuda.synchronize()
+    plan.set_handover([1] * plan.n_kernels, lanes=1)        # the region kernels read packed copies too
+    fused = plan.run()
+    plan.set_handover([0] * plan.n_kernels, lanes=1)
+    after = plan.run()
+    assert all(np.array_equal(a, b) for a, b in zip(before, after))
+    assert max(norm_err(a, b) for a, b in zip(fused, before)) <= 1e-5
+    s.close()
+
+
 @pytest.mark.parametrize("lanes", [1, 3])
 @pytest.mark.parametrize("name", ["resnet_small", "tiny_cnn"])
 def test_graph_level_search_keeps_outputs_and_never_loses_to_the_seed(name, lanes):

@@ -398,3 +398,36 @@ def test_a_graph_with_plans_can_neither_go_nor_change():
     n = B.clg_graph_num_nodes(s.graph)
     assert B.clg_graph_op(s.graph, "relu", [d.outputs[0]]) == n        # open again
     s.close()
+
+
+def test_which_constants_a_plan_still_reads():
+    d = wl.tiny_cnn(0, image=8)
+    reg = wl.default_registry(("igemm_s8", "igemm_r16"))
+    s = clg.Session(d, reg, device=None)
+    ms = s.match()
+    costs = []
+    for i, m in enumerate(ms):
+        try:
+            clg.clg_match_key(s.ctx, s.graph, i)
+            costs.append((10 if reg[m.pattern][0] == "igemm_r16" else 1000) * m.n_nodes)
+        except clg.ClgError:
+            costs.append(B.COST_INF)
+    _, ids = s.search(costs, 0)
+    plan = s.compile(ids)
+    kinds = {}
+    for nid, nd in enumerate(d.nodes):
+        if nd["kind"] == "const":
+            kinds[nid] = B.clg_plan_reads_constant(plan.h, nid)
+    weights = [nid for nid in kinds if len(d.nodes[nid]["shape"]) >= 2]
+    small = [nid for nid in kinds if len(d.nodes[nid]["shape"]) == 1]
+    assert weights and small
+    for nid in weights:                      # convolution / dense weights: the register-fed kernels read packed copies
+        reads, packed = kinds[nid]
+        assert not reads and packed >= 4 * int(np.prod(d.nodes[nid]["shape"])), (nid, kinds[nid])
+    for nid in small:                        # biases are read in place
+        assert kinds[nid] == (True, 0)
+    assert set(plan.constants_not_read()) == set(weights)
+    with pytest.raises(clg.ClgError) as e:
+        B.clg_plan_reads_constant(plan.h, d.outputs[0])
+    assert e.value.status == "UNKNOWN_ID"
+    s.close()
