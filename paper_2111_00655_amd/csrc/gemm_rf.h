@@ -183,31 +183,40 @@ __device__ __forceinline__ void conv_rf_body(const GemmArgs &p, const int bx, co
     const int c0 = (ks * WGK + w) * nch;                     // this wave's first chunk
     const int cq_last = (cin + NSLOT - 1) / NSLOT - 1;
 
-    // outputs this thread finishes, and the operands of their fused tail
+    // outputs this thread finishes, and the operands of their fused tail.  In the 1x1 path with 16x16 tiles
+    // this runs behind the first round of operand loads: those are what the kernel waits for, and they
+    // should leave before anything that is only needed at the end (measured: 0.35 - 1.0 us off the deep
+    // layers; with 32x32 tiles, sixteen outputs per thread, and in the 3x3 path it cost 0.2 - 0.4 us instead).
+    // (transposed convolution: the phase's pixel (oh', ow') is output pixel (a_h + s oh', a_w + s ow'))
+    constexpr bool LATE_TAIL = TAPK == 1 && TS == 16;
     int64_t e_off[EPT];
     float e_bias[EPT], e_add[EPT];
-#pragma unroll
-    for (int t = 0; t < EPT; ++t) {
-        const int e = tid + t * NT;
-        const int l = e % kWave, g = e / kWave;
-        const int i = i0 + MF::row(g, l / TS), j = j0 + l % TS;
-        e_off[t] = (e < PER_WAVE && i < p.Cout && j < npix) ? (((int64_t)img * p.Cout + i) * DOe + od) * npix + j : -1;
-        if (CONVT && e_off[t] >= 0) {                 // the phase's pixel (oh', ow') is output pixel (a_h + s oh', a_w + s ow')
-            const int ohh = (int)(((uint64_t)(uint32_t)j * p.rf_wo_magic) >> 32), oww = j - ohh * WOe;
-            e_off[t] = (((int64_t)img * p.Cout + i) * p.HO + a_h + p.sh * ohh) * p.WO + a_w + p.sw * oww;
-        }
-        e_bias[t] = 0.f;
-        e_add[t] = 0.f;
-        if (p.splitk == 1 && e_off[t] >= 0) {
-            if (p.ef.flags & EF_BIAS) e_bias[t] = p.ef.bias[i];
-            if (p.ef.flags & EF_ADD) e_add[t] = p.ef.add[e_off[t]];
-        }
-    }
+#define CLG_RF_TAIL_SETUP()                                                                   \
+    do {                                                                                      \
+    _Pragma("unroll")                                                                         \
+        for (int t = 0; t < EPT; ++t) {                                                       \
+            const int e = tid + t * NT;                                                       \
+            const int l = e % kWave, g = e / kWave;                                           \
+            const int i = i0 + MF::row(g, l / TS), j = j0 + l % TS;                           \
+            e_off[t] = (e < PER_WAVE && i < p.Cout && j < npix) ? (((int64_t)img * p.Cout + i) * DOe + od) * npix + j : -1;\
+            if (CONVT && e_off[t] >= 0) {                                                     \
+                const int ohh = (int)(((uint64_t)(uint32_t)j * p.rf_wo_magic) >> 32), oww = j - ohh * WOe;\
+                e_off[t] = (((int64_t)img * p.Cout + i) * p.HO + a_h + p.sh * ohh) * p.WO + a_w + p.sw * oww;\
+            }                                                                                 \
+            e_bias[t] = 0.f;                                                                  \
+            e_add[t] = 0.f;                                                                   \
+            if (p.splitk == 1 && e_off[t] >= 0) {                                             \
+                if (p.ef.flags & EF_BIAS) e_bias[t] = p.ef.bias[i];                           \
+                if (p.ef.flags & EF_ADD) e_add[t] = p.ef.add[e_off[t]];                       \
+            }                                                                                 \
+        }                                                                                     \
+    } while (0)
+    if constexpr (!LATE_TAIL) CLG_RF_TAIL_SETUP();
 
     acc_t acc;
 #pragma unroll
     for (int g = 0; g < NACC; ++g) acc[g] = 0.f;
-    CLG_STAMP(1);                                            // arguments read, indices and tail operands set up
+    CLG_STAMP(1);                                            // arguments read, indices set up
 
     if constexpr (TAPK == 1) {
         // ---- 1x1: MFMA n contracts channels n*NSLOT .. n*NSLOT+NSLOT-1 at this lane's pixel
@@ -244,6 +253,9 @@ __device__ __forceinline__ void conv_rf_body(const GemmArgs &p, const int bx, co
             if constexpr (PF > 2) {
                 if (left > 2) CLG_RF_LOAD(2, c + 2);
                 if (left > 3) CLG_RF_LOAD(3, c + 3);
+            }
+            if constexpr (LATE_TAIL) {
+                if (c == 0) CLG_RF_TAIL_SETUP();
             }
             __builtin_amdgcn_sched_barrier(0);               // every load of the round goes out before its first MFMA
             CLG_RF_MMA(0);
@@ -426,6 +438,7 @@ __device__ __forceinline__ void conv_rf_body(const GemmArgs &p, const int bx, co
     __builtin_amdgcn_s_waitcnt(0);                           // the stores have left the wave
 #endif
     CLG_STAMP(4);                                            // sums taken, tail applied, stores issued
+#undef CLG_RF_TAIL_SETUP
 }
 
 template <int TS, int TAPK, int WGK, int GEO, int PF>
