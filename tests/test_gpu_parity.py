@@ -981,6 +981,73 @@ def test_region_of_sibling_1x1_convolutions(ci, backend):
     s.close()
 
 
+def _random_sibling_graph(seed):
+    """A random DAG over [1, C, 12, 12] tensors in which 1x1 convolutions (with bias / relu / residual tails, some
+    strided), 3x3 convolutions, adds and relus read any earlier value of a fitting shape: many kernels that do not
+    depend on each other, in an order that makes the region finder move members past unrelated kernels."""
+    r = rng_for(91, seed)
+    d = wl.GraphDesc(f"siblings_{seed}")
+    vals = {}                                  # (channels, size) -> values of that shape
+
+    def put(v, c, h):
+        vals.setdefault((c, h), []).append(v)
+        return v
+    x = put(d.input(f32(r, 1, 8, 12, 12)), 8, 12)
+    used = set()
+    for step in range(int(r.integers(8, 15))):
+        (c, h), pool = list(vals.items())[int(r.integers(0, len(vals)))]
+        src = pool[int(r.integers(0, len(pool)))]
+        kind = r.random()
+        if kind < 0.6:                         # 1x1 convolution, the fusable kind
+            cout = int(r.choice([8, 16, 24, 40]))
+            stride = 2 if (r.random() < 0.3 and h % 2 == 0) else 1
+            y = d.op("conv2d", [src, d.const(f32(r, cout, c, 1, 1, scale=(2.0 / c) ** 0.5))], stride=(stride, stride), pad=(0, 0), groups=1)
+            ho = (h - 1) // stride + 1
+            if r.random() < 0.7:
+                y = d.op("bias_add", [y, d.const(f32(r, cout))], axis=1)
+                if r.random() < 0.4 and (cout, ho) in vals:
+                    other = vals[(cout, ho)][int(r.integers(0, len(vals[(cout, ho)])))]
+                    y = d.op("add", [y, other])
+                    used.add(other)
+                if r.random() < 0.6:
+                    y = d.op("relu", [y])
+            put(y, cout, ho)
+        elif kind < 0.75:
+            y = d.op("conv2d", [src, d.const(f32(r, c, c, 3, 3, scale=(2.0 / (9 * c)) ** 0.5))], stride=(1, 1), pad=(1, 1), groups=1)
+            put(d.op("relu", [d.op("bias_add", [y, d.const(f32(r, c))], axis=1)]), c, h)
+        elif kind < 0.9 and len(pool) > 1:
+            other = pool[int(r.integers(0, len(pool)))]
+            put(d.op("add", [src, other]), c, h)
+            used.add(other)
+        else:
+            put(d.op("relu", [src]), c, h)
+        used.add(src)
+    for pool in vals.values():
+        for v in pool:
+            if v not in used and d.nodes[v]["kind"] != "input":
+                d.mark_output(v)
+    if not d.outputs:
+        d.mark_output(list(vals.values())[-1][-1])
+    return d
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_regions_on_random_graphs_of_sibling_kernels(seed):
+    """Whatever the topology: with every kernel handed over (regions fused, members moved next to each other, one
+    workspace for all digit strings), with none, and with every other one, the outputs equal the oracle's."""
+    from parity_util import check_outputs
+    d = _random_sibling_graph(seed)
+    s, plan = _per_operator_plan(d, "igemm_r16" if seed % 2 else "igemm_r32")
+    ref = Graph(d).run()
+    n = plan.n_kernels
+    n_regions = max(plan.regions() + [-1]) + 1
+    for digits in ([1] * n, [0] * n, [i % 2 for i in range(n)], [1] * n):
+        plan.set_handover(digits, lanes=1)
+        check_outputs(plan.run(), ref, OP_TOL * 4, (seed, digits))      # a few fused operators deep
+    print("seed", seed, "kernels", n, "regions", n_regions, "launches all-ones", plan.n_launches)
+    s.close()
+
+
 @pytest.mark.parametrize("name", ["resnet50", "bert_base", "resnext50", "resnet3d_50", "nasnet_a"])
 def test_model_with_every_region_fused(name):
     """Full size, the benchmark's registry: the searched op-level plan, then every kernel handed over so that

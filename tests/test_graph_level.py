@@ -326,3 +326,31 @@ def test_region_members_never_depend_on_each_other():
                         if u not in inside and u in produced:
                             assert produced[u] < members[0], (d.name, r, i)
         s.close()
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_regions_on_random_graphs_compile_and_keep_their_invariants(seed):
+    """Host-only twin of the GPU test on random graphs of sibling kernels: the plan compiles (every operand produced
+    before its reader, after members were moved next to each other), members are adjacent and independent, launches
+    drop by members - 1 per region under all ones, and the workspace does not depend on the digits."""
+    from test_gpu_parity import _random_sibling_graph
+    d = _random_sibling_graph(seed)
+    s, ms, plan = _plan_on_register_fed_kernels(d)
+    ks, rg = plan.kernels(), plan.regions()
+    produced = {ms[k["match"]].sink: i for i, k in enumerate(ks)}
+    saved = 0
+    for r in set(rg) - {-1}:
+        members = [i for i in range(len(ks)) if rg[i] == r]
+        assert 2 <= len(members) <= 4 and members == list(range(members[0], members[-1] + 1))
+        saved += len(members) - 1
+        for i in members:
+            m = ms[ks[i]["match"]]
+            inside = set(m.nodes[:m.n_nodes])
+            for v in m.nodes[:m.n_nodes]:
+                for u in d.nodes[v]["inputs"]:
+                    if u not in inside and u in produced:
+                        assert produced[u] < members[0], (seed, r, i)
+    ws = plan.ws_bytes
+    plan.set_handover([1] * len(ks), lanes=1)
+    assert plan.n_launches == len(ks) - saved and B.clg_plan_workspace_bytes(plan.h) == ws
+    s.close()
