@@ -95,6 +95,15 @@ struct RfMfma<16> {
 // phase, each with its own packed (tap-flipped) weights.  k4 s2 p1 gives four
 // 2x2 phases.
 
+// Transposed convolution with few output channels (DCGAN's last layer, 64 -> 3): one phase is a GEMM
+// with 3 rows, and a 16-row tile wastes 13 of them.  For k4 s2 p1 the four phases of output pixel block
+// (2i + a, 2j + b) read the same 3x3 neighbourhood of input pixel (i, j) - tap kh = a + 1 - 2 dh of the
+// filter sits at neighbour dh in {-1, 0, 1}, two of the three per axis - so the whole layer is ONE 3x3
+// stride-1 pad-1 convolution over the input with 4 * Cout rows (row = 4 * channel + 2 a + b), zero
+// weights where a phase does not meet a neighbour, and a store that puts row (channel, a, b) of input
+// pixel (i, j) at output pixel (2i + a, 2j + b): 12 of 16 rows useful instead of 3, 9 operand loads per
+// channel group for all four phases instead of 16.  GEO = 5.
+//
 // GEO: 0 = 2-D convolution, 1 = transposed convolution, 2 = 3-D convolution with the depth taps
 // folded into the channel index, 3 = 3-D convolution with a single depth tap, 4 = 2-D 1x1 convolution
 // with a relu on its input (the operand values are clamped on their way into the MFMA).  The depth code is
@@ -124,6 +133,7 @@ __device__ __forceinline__ void conv_rf_body(const GemmArgs &p, const int bx, co
     constexpr bool FOLD = GEO == 2;
     constexpr bool DEPTH = GEO == 2 || GEO == 3;
     constexpr bool PRELU = GEO == 4;
+    constexpr bool D2S = GEO == 5;
 
     CLG_STAMP(0);                                            // entry
     const int tid = threadIdx.x;
@@ -147,8 +157,16 @@ __device__ __forceinline__ void conv_rf_body(const GemmArgs &p, const int bx, co
         HOe = p.HO / p.sh;
         WOe = p.WO / p.sw;
     }
+    if constexpr (D2S) {                                     // the 3x3 convolution over the input that stands for the layer
+        KHe = KWe = 3;
+        she = swe = 1;
+        phe = pwe = 1;
+        HOe = p.H;
+        WOe = p.W;
+    }
+    const int CoutE = D2S ? 4 * p.Cout : p.Cout;              // rows of the GEMM
     const int npix = HOe * WOe;
-    const int tiles_m = (p.Cout + TS - 1) / TS;
+    const int tiles_m = (CoutE + TS - 1) / TS;
     const int tile = xcd_remap(bx, gx);
     // neighbouring workgroups share the larger operand: weights rows (i-major) or pixels (j-major);
     // tile / rf_tile_div by multiply-high (an integer division costs some thirty instructions)
@@ -198,7 +216,11 @@ __device__ __forceinline__ void conv_rf_body(const GemmArgs &p, const int bx, co
             const int e = tid + t * NT;                                                       \
             const int l = e % kWave, g = e / kWave;                                           \
             const int i = i0 + MF::row(g, l / TS), j = j0 + l % TS;                           \
-            e_off[t] = (e < PER_WAVE && i < p.Cout && j < npix) ? (((int64_t)img * p.Cout + i) * DOe + od) * npix + j : -1;\
+            e_off[t] = (e < PER_WAVE && i < CoutE && j < npix) ? (((int64_t)img * p.Cout + i) * DOe + od) * npix + j : -1;\
+            if (D2S && e_off[t] >= 0) {                                                       \
+                const int ohh = (int)(((uint64_t)(uint32_t)j * p.rf_wo_magic) >> 32), oww = j - ohh * WOe;\
+                e_off[t] = (((int64_t)img * p.Cout + (i >> 2)) * p.HO + 2 * ohh + ((i >> 1) & 1)) * p.WO + 2 * oww + (i & 1);\
+            }                                                                                 \
             if (CONVT && e_off[t] >= 0) {                                                     \
                 const int ohh = (int)(((uint64_t)(uint32_t)j * p.rf_wo_magic) >> 32), oww = j - ohh * WOe;\
                 e_off[t] = (((int64_t)img * p.Cout + i) * p.HO + a_h + p.sh * ohh) * p.WO + a_w + p.sw * oww;\
@@ -206,7 +228,7 @@ __device__ __forceinline__ void conv_rf_body(const GemmArgs &p, const int bx, co
             e_bias[t] = 0.f;                                                                  \
             e_add[t] = 0.f;                                                                   \
             if (p.splitk == 1 && e_off[t] >= 0) {                                             \
-                if (p.ef.flags & EF_BIAS) e_bias[t] = p.ef.bias[i];                           \
+                if (p.ef.flags & EF_BIAS) e_bias[t] = p.ef.bias[D2S ? i >> 2 : i];            \
                 if (p.ef.flags & EF_ADD) e_add[t] = p.ef.add[e_off[t]];                       \
             }                                                                                 \
         }                                                                                     \
@@ -753,9 +775,9 @@ __global__ void rf_pack_kernel(const float *w, float *dst, GemmArgs p, int64_t t
     constexpr int NSLOT = RfMfma<TS>::NSLOT;
     const int64_t d = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (d >= total) return;
-    const int KHe = p.rf_convt ? p.KH / p.sh : p.KH, KWe = p.rf_convt ? p.KW / p.sw : p.KW;
+    const int KHe = p.rf_d2s ? 3 : (p.rf_convt ? p.KH / p.sh : p.KH), KWe = p.rf_d2s ? 3 : (p.rf_convt ? p.KW / p.sw : p.KW);
     const int taps = KHe * KWe;
-    const int tiles_m = (p.Cout + TS - 1) / TS;
+    const int tiles_m = ((p.rf_d2s ? 4 * p.Cout : p.Cout) + TS - 1) / TS;
     const int q = (int)(d & 3), lane = (int)((d >> 2) & 63);
     const int64_t gg = d >> 8;
     const int g = (int)(gg % p.rf_ngtot);
@@ -764,7 +786,14 @@ __global__ void rf_pack_kernel(const float *w, float *dst, GemmArgs p, int64_t t
     const int cq = n / taps, t = n - cq * taps;
     const int i = mt * TS + lane % TS, cl = cq * NSLOT + lane / TS;      // output channel, channel within the tile's span
     float v = 0.f;
-    if (n < p.rf_nm && i < p.Cout && cl < p.rf_cin_tile) {
+    if (p.rf_d2s) {
+        // row i = (channel i / 4, phase a = (i / 2) % 2, b = i % 2); tap t = (dh + 1) * 3 + (dw + 1) of the 3x3
+        // neighbourhood meets filter tap kh = a + 1 - 2 dh, kw = b + 1 - 2 dw of w [Cin][Cout][4][4] if that exists
+        const int co = i >> 2, a_h = (i >> 1) & 1, a_w = i & 1;
+        const int kh = a_h + 1 - 2 * (t / 3 - 1), kw = a_w + 1 - 2 * (t % 3 - 1);
+        if (n < p.rf_nm && co < p.Cout && cl < p.Cin && kh >= 0 && kh < 4 && kw >= 0 && kw < 4)
+            v = w[(((int64_t)cl * p.Cout + co) * 4 + kh) * 4 + kw];
+    } else if (n < p.rf_nm && i < p.Cout && cl < p.rf_cin_tile) {
         if (p.rf_convt) {
             // w is [Cin][Cout][KH][KW]; tap u' of the phase is kernel tap r + s * (KH/s - 1 - u')
             const int a_h = phase / p.sw, a_w = phase - a_h * p.sw;

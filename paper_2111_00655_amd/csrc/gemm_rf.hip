@@ -11,8 +11,8 @@ int dense_tiles(const GemmArgs &a);
 
 template <int TS, int TAPK, int WGK, int GEO>
 int launch_rf_one_t(const GemmArgs &a, hipStream_t s) {
-    const int npix = a.rf_convt ? (a.HO / a.sh) * (a.WO / a.sw) : a.HO * a.WO;
-    const int tiles = ((a.Cout + TS - 1) / TS) * ((npix + TS - 1) / TS);
+    const int npix = a.rf_d2s ? a.H * a.W : (a.rf_convt ? (a.HO / a.sh) * (a.WO / a.sw) : a.HO * a.WO);
+    const int tiles = (((a.rf_d2s ? 4 * a.Cout : a.Cout) + TS - 1) / TS) * ((npix + TS - 1) / TS);
     const size_t lds = WGK > 1 ? (size_t)WGK * RfMfma<TS>::NACC * kWave * sizeof(float) : 0;
     const int gz = a.rf_convt ? a.sh * a.sw : a.splitk;      // sub-pixel phases, or K splits
     const int gy = a.Nimg * (a.DO > 1 ? a.DO : 1);           // images, or (image, output depth) pairs
@@ -35,6 +35,10 @@ int launch_rf_one(const GemmArgs &a, hipStream_t s) {
     if constexpr (TAPK == 9 || TAPK == 0) {
         if (a.rf_fold && !a.rf_convt) return launch_rf_one_t<TS, TAPK, WGK, 2>(a, s);
     }
+    if constexpr (TAPK == 9 && TS == 16) {
+        if (a.rf_d2s) return launch_rf_one_t<TS, TAPK, WGK, 5>(a, s);
+    }
+    if (a.rf_d2s) return (int)hipErrorInvalidValue;
     if (a.rf_convt || a.rf_fold) return (int)hipErrorInvalidValue;
     if constexpr (TAPK == 1) {
         if (a.rf_prelu && a.D <= 1) return launch_rf_one_t<TS, TAPK, WGK, 4>(a, s);
@@ -137,6 +141,7 @@ int launch_rfd_wgk(const GemmArgs &a, hipStream_t s) {
 // geometry variant of the convolution kernel that runs `a` (its fourth template argument)
 int rf_geo(const GemmArgs &a) {
     if (a.rf_convt) return 1;
+    if (a.rf_d2s) return 5;
     if (a.rf_fold) return 2;
     if (a.rf_prelu) return 4;
     return a.D > 1 ? 3 : 0;
@@ -382,9 +387,41 @@ bool rf_resolve_convt(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves) 
     for (int pw = 0; pw < a->sw; ++pw)
         if (kwe - 1 - (pw + a->pw) / a->sw < 0) return false;
     const int nslot = ts == 32 ? 2 : 4;
+    if ((int64_t)a->Cin * a->H * a->W >= ((int64_t)1 << 30)) return false;
+    // few output channels, 4x4 filter, stride 2, pad 1: the layer as one 3x3 convolution over the input whose rows are
+    // (channel, phase)
+    if (ts == 16 && a->KH == 4 && a->KW == 4 && a->sh == 2 && a->sw == 2 && a->ph == 1 && a->pw == 1 && 4 * a->Cout <= 16 &&
+        a->Cin % nslot == 0 && a->HO == 2 * a->H && a->WO == 2 * a->W && (int64_t)a->H * a->W * a->W < ((int64_t)1 << 32)) {
+        const int nm = (a->Cin / nslot) * 9;
+        const int nc = (nm + 35) / 36;
+        const int64_t tiles2 = (int64_t)(((int64_t)a->H * a->W + ts - 1) / ts) * a->Nimg;
+        const int wgk = pick_waves(nc, tiles2, waves, false);
+        a->rf_ts = ts;
+        a->rf_tapk = 9;
+        a->rf_wgk = wgk;
+        a->rf_nch = (nc + wgk - 1) / wgk;
+        a->splitk = 1;
+        a->rf_ngtot = wgk * a->rf_nch * 9;
+        a->rf_nm = nm;
+        a->rf_groups = 1;
+        a->rf_cin_tile = a->Cin;
+        a->rf_convt = 0;
+        a->rf_d2s = 1;
+        a->D = a->KD = a->sd = a->DO = 1;
+        a->pd = 0;
+        a->rf_fold = 0;
+        a->rf_cs = a->H * a->W;
+        a->rf_img_stride = (int64_t)a->Cin * a->rf_cs;
+        a->rf_kd_magic = 0;
+        a->rf_jmajor = 1;
+        a->rf_wo_magic = (((uint64_t)1 << 32) / (uint64_t)a->W) + 1;
+        if (set_tile_order(a, 1, (int)(((int64_t)a->H * a->W + ts - 1) / ts))) return true;
+        a->rf_ts = 0;
+        a->rf_d2s = 0;
+        return false;
+    }
     const int64_t npix = (int64_t)hoe * woe;
     if (npix * woe >= ((int64_t)1 << 32)) return false;
-    if ((int64_t)a->Cin * a->H * a->W >= ((int64_t)1 << 30)) return false;
     const int taps = khe * kwe;
     const int ncq = (a->Cin + nslot - 1) / nslot;
     const int tapk = (khe == 2 && kwe == 2 && a->Cin % nslot == 0) ? 4 : 0;
@@ -418,7 +455,7 @@ bool rf_resolve_convt(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves) 
 
 size_t rf_pack_bytes(const GemmArgs &a) {
     if (!a.rf_ts) return 0;
-    const size_t tiles_m = (size_t)((a.rf_tapk == -1 ? a.N : a.Cout) + a.rf_ts - 1) / a.rf_ts;
+    const size_t tiles_m = (size_t)((a.rf_tapk == -1 ? a.N : (a.rf_d2s ? 4 * a.Cout : a.Cout)) + a.rf_ts - 1) / a.rf_ts;
     return (a.rf_convt ? (size_t)a.sh * a.sw : 1) * tiles_m * (size_t)a.rf_ngtot * 256 * sizeof(float);
 }
 

@@ -107,6 +107,8 @@ struct GemmArgs {
     int32_t rf_ts, rf_tapk, rf_wgk;        // tile edge 32|16, tap mode 1|9|4|0 (-1: dense), K-waves per workgroup
     int32_t rf_nb;                         // dense: 16-row weight tiles per wave (1, or 2 sharing the activation operand)
     int32_t rf_convt;                      // 1: transposed convolution, one sub-pixel phase per grid.z slice
+    int32_t rf_d2s;                        // 1: k4 s2 p1 transposed convolution with few output channels as ONE 3x3 convolution
+                                           //    over the input whose 4 * Cout rows are (channel, sub-pixel phase)
     int32_t bias_on_row;                   // 1: channel = i (conv), 0: channel = j (dense)
     int32_t gemv;                          // 1: GM_NT with at most 8 rows runs the matrix-vector kernel (a wave per column)
     int32_t patch_sz;                      // 3x3 kernel: floats per channel of the LDS input patch

@@ -660,7 +660,7 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
             if (rf) {
                 c.scratch_bytes = gemm_scratch_bytes(a);
                 c.name = (a.rf_tapk == -1 ? "dense_rf" + std::to_string(a.rf_ts) + (a.rf_nb == 2 ? "x2" : "")
-                                          : std::string(a.rf_convt ? "convt_rf" : (a.D > 1 ? "conv3d_rf" : "conv_rf")) + std::to_string(a.rf_ts) + "_t" +
+                                          : std::string((a.rf_convt || a.rf_d2s) ? "convt_rf" : (a.D > 1 ? "conv3d_rf" : "conv_rf")) + std::to_string(a.rf_ts) + "_t" +
                                                 std::to_string(a.rf_tapk)) +
                          "_w" + std::to_string(a.rf_wgk) + (a.cs_len ? "_split" : "");
             } else {

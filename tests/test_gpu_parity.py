@@ -388,7 +388,9 @@ def convt_desc(case, k=4, stride=2, pad=1):
 @pytest.mark.parametrize("backend", IGEMM + RF)
 @pytest.mark.parametrize("case", [(1, 64, 32, 4, ("bias_add", "relu")), (2, 32, 16, 8, ("bias_add", "relu")),
                                   (3, 16, 3, 16, ("bias_add", "tanh")), (1, 24, 40, 5, ()),
-                                  (2, 7, 5, 6, ("bias_add", "relu"))])
+                                  (2, 7, 5, 6, ("bias_add", "relu")),
+                                  # few output channels: the layer as one 3x3 convolution with (channel, phase) rows
+                                  (2, 8, 4, 5, ("bias_add", "relu")), (1, 12, 1, 7, ()), (5, 64, 2, 9, ("bias_add", "tanh"))])
 def test_conv2d_transpose_fused(case, backend):
     d, pat = convt_desc(case)
     name, _ = run_single_group(d, backend, pat)
