@@ -38,8 +38,8 @@ VARIANTS = ("igemm", "igemm_s", "igemm_s8", "igemm_s16", "igemm_m", "igemm_l", "
 # copy of --calib-copy in the same runs: WRITE_SIZE read 262144.0 KiB for it (factor 1.000), FETCH_SIZE
 # 131083.5 KiB (factor 2.000).  profiles/*_pmc_summary.txt hold the runs.  The figures hold for the kernel sources
 # they were taken with; after any change to them `traffic` is reported as null.
-TRAFFIC = {"resnet50": {"sources": "7c6c1b2d79f9cf52", "fetch_bytes": 290.30e6, "write_bytes": 46.87e6},
-           "bert_base": {"sources": "7c6c1b2d79f9cf52", "fetch_bytes": 689.39e6, "write_bytes": 47.19e6}}
+TRAFFIC = {"resnet50": {"sources": "64b60e4ba4347dca", "fetch_bytes": 293.81e6, "write_bytes": 46.86e6},
+           "bert_base": {"sources": "64b60e4ba4347dca", "fetch_bytes": 689.17e6, "write_bytes": 47.19e6}}
 
 
 def kernel_sources_fingerprint():
