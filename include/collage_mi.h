@@ -196,7 +196,8 @@ int32_t clg_destroy(clg_ctx *ctx);
 /* Message of the last failing call on this thread; library-owned storage,
  * valid until the next failing call on the thread.  Never NULL. */
 const char *clg_last_error(void);
-/* ABI version of this header (major * 100 + minor). */
+/* ABI version of this header (major * 100 + minor).  101: clg_es_opts.seed_ones, regions (clg_plan_set_handover
+ * with lanes = 1, clg_plan_num_launches, clg_plan_region_of), clg_execute_static, clg_plan_reads_constant. */
 int32_t clg_version(void);
 
 /* ---- computation graph G (Sec. 4.1: a DAG of tensor operators) ------------ */
