@@ -96,7 +96,7 @@ def graph_level(plan, steps, warmup, seed=0):
     rand = np.random.default_rng(seed).integers(0, 2 ** 32, 1 << 20, dtype=np.uint64).tolist()
     t0 = time.perf_counter()
     best, best_ns, seed_ns, evals, hist = plan.search_graph_level(
-        B.make_es_opts(population=8, generations=8, tournament=3, patience=4, p_init=0.5, p_mutate=0.5, p_flip=0.1, p_cross=0.5,
+        B.make_es_opts(population=12, generations=12, tournament=3, patience=5, p_init=0.5, p_mutate=0.5, p_flip=0.1, p_cross=0.5,
                        seed_ones=True),
         rand, lanes=1, warmup=3, batches=3, reps=20)
     search_s = time.perf_counter() - t0
@@ -105,7 +105,7 @@ def graph_level(plan, steps, warmup, seed=0):
     return dict(op_level_ms=round(op_ms, 4), graph_level_ms=round(gl_ms, 4), launches_before=launches_before,
                 launches_after=plan.n_launches, regions=max(rg) + 1 if rg else 0, kernels=n, handed_over=int(sum(best)),
                 digits=[int(b) for b in best],
-                search_seed_ns=int(seed_ns), search_best_ns=int(best_ns), strings_measured=evals,
+                search_seed_ns=int(seed_ns), search_best_ns=int(best_ns), strings_priced=evals,
                 history_ms=[round(h / 1e6, 4) for h in hist], search_s=round(search_s, 2))
 
 
@@ -623,7 +623,7 @@ def main():
             for n, v in graph_level_rows.items():
                 lines.append(f"  {n:12s} {v['op_level_ms']:11.4f} {v['graph_level_ms']:14.4f} {v['op_level_ms'] / v['graph_level_ms']:6.3f} "
                              f"{str(v.get('launches_before', '')) + '->' + str(v.get('launches_after', '')):>9s} {v['handed_over']:8d} "
-                             f"{v['strings_measured']:7d} {v['search_s']:8.2f}")
+                             f"{v['strings_priced']:7d} {v['search_s']:8.2f}")
             lines += [""]
         lines += [f"Measurer: {spread['kernels']} distinct kernels priced {spread['repeats']} times each with the cost log off; "
                   f"(max - min) / median per kernel: median {spread['median_rel_spread']:.4f}, 90th percentile "

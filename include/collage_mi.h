@@ -465,7 +465,10 @@ int32_t clg_evolve(size_t n, const clg_es_opts *opts, const uint32_t *rand,
  * two events on `stream`; the smallest batch mean.  Arguments as clg_execute;
  * blocks until done.
  * clg_search_graph_level: clg_evolve over the plan's kernels with that
- * measurement as the fitness; every distinct string is set, timed and kept.
+ * measurement as the fitness; every distinct string is set, timed and kept
+ * (with lanes = 1, strings that give the same launches, i.e. that differ only
+ * in digits of kernels outside regions or alone in theirs, are timed once and
+ * share the figure).
  * best: host, clg_plan_num_kernels bytes; *best_ns its time; *seed_ns (may be
  * null) the time of the all-zero string, i.e. of the op-level placement, so
  * *best_ns <= *seed_ns.  On return the plan is set to `best`; after an error
