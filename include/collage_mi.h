@@ -266,8 +266,11 @@ int32_t clg_graph_node_shape(const clg_graph *g, int32_t node, int32_t *dtype,
  *              -> [mul_scalar] -> softmax -> batch_matmul [-> transpose ->
  *              reshape that puts the heads side by side]; head sizes 32, 64,
  *              128, up to 512 keys; the scores never leave the chip
- *   "direct"   direct convolution (any groups), max / average pooling (window
- *              pools also with an elementwise tail), global average pooling
+ *   "direct"   direct convolution (any groups), transposed convolution of any
+ *              filter size, stride and pad (the MFMA kernels take those whose
+ *              filter and output sizes the stride divides), max / average
+ *              pooling (window pools also with an elementwise tail), global
+ *              average pooling
  *   "rowwise"  softmax and layer norm with fused elementwise prologue; also
  *              layer_norm(add(add(take, take), take), gamma, beta) and the
  *              two-table form: an embedding's rows gathered, summed and

@@ -526,15 +526,14 @@ struct GraphLevelJob {
 // other member of that region is handed over too.  Strings that differ elsewhere run the very same launches:
 // they are timed once and share the figure, so the search spends its measurements on distinct sequences and
 // is not steered by the noise between two timings of one sequence.
-std::vector<uint8_t> launch_sequence_key(const Plan &p, const uint8_t *digits, size_t n) {
-    std::vector<uint8_t> key(n, 0);
+void launch_sequence_key(const Plan &p, const uint8_t *digits, size_t n, std::vector<uint8_t> &key) {
+    key.assign(n, 0);
     for (const Region &r : p.regions) {
         int in = 0;
         for (int32_t c : r.members) in += digits[c] ? 1 : 0;
         if (in >= 2)
             for (int32_t c : r.members) key[(size_t)c] = digits[c] ? 1 : 0;
     }
-    return key;
 }
 
 // fitness of the evolutionary search: set the string, time the whole sequence
@@ -544,7 +543,7 @@ double graph_level_cost(const uint8_t *digits, size_t n, void *user) {
     int64_t ns = 0;
     std::vector<uint8_t> key;
     if (j.lanes == 1 && n == j.plan->p.calls.size()) {
-        key = launch_sequence_key(j.plan->p, digits, n);
+        launch_sequence_key(j.plan->p, digits, n, key);
         const auto it = j.timed.find(key);
         if (it != j.timed.end()) return (double)it->second;
     }
@@ -572,7 +571,7 @@ int32_t clg_search_graph_level(clg_plan *plan, const void *const *inputs, void *
     int32_t rc = check_es_opts(opts);
     if (rc == CLG_OK) rc = check_measure_opts(measure);
     if (rc != CLG_OK) return rc;
-    GraphLevelJob job{plan, inputs, outputs, workspace, workspace_bytes, stream, lanes, *measure, CLG_OK, {}, -1};
+    GraphLevelJob job{plan, inputs, outputs, workspace, workspace_bytes, stream, lanes, *measure, CLG_OK, {}, -1, {}};
     const size_t n = plan->p.calls.size();
     double cost = 0;
     rc = evolve(n, *opts, rand, n_rand, graph_level_cost, &job, best, &cost, evaluations, history, generations_run);

@@ -138,13 +138,14 @@ bool rf_same_launch_shape(const GemmArgs &a, const GemmArgs &b);
 // Launches the members (GemmArgs with all pointers bound and ef filled) as one kernel.
 int launch_gemm_region(const GemmArgs *members, int n, void *stream);
 
-// ---- direct convolution (any groups) -----------------------------------------------------
+// ---- direct convolution (any groups) and transposed convolution (any geometry) -----------------------------------------------------
 struct DirectConvArgs {
     const float *x;
     const float *w;
     float *y;
     int32_t N, C, H, W, O, KH, KW, sh, sw, ph, pw, G, HO, WO;
     int32_t pro_relu;                      // relu on x first; only the depthwise kernel (G = C = O, 3x3 / 5x5 / 7x7) takes it
+    int32_t transposed;                    // conv2d_transpose (w is [C][O][KH][KW], G = 1) instead of conv2d
     EpiFast ef;                            // filled by launch_direct_conv from epi
     Epilogue epi;
 };

@@ -392,6 +392,37 @@ __global__ __launch_bounds__(256) void direct_conv_kernel(DirectConvArgs a) {
     }
 }
 
+// Transposed convolution of any filter size, stride and pad (w is [C][O][KH][KW]), gather form: one
+// thread per output pixel, blockIdx.y = output channel, blockIdx.z = image.  Output row oh takes
+// filter row kh from input row (oh + ph - kh) / sh where that division is exact and the row exists;
+// the same along the width.  The kernel that runs what the phase-decomposed MFMA kernels refuse
+// (a filter size that the stride does not divide).
+__global__ __launch_bounds__(256) void direct_convt_kernel(DirectConvArgs a) {
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    const int npix = a.HO * a.WO;
+    const int co = blockIdx.y, n = blockIdx.z;
+    if (p >= npix) return;
+    const int oh = p / a.WO, ow = p % a.WO;
+    const float *xn = a.x + (int64_t)n * a.C * a.H * a.W;
+    const float *wo = a.w + (int64_t)co * a.KH * a.KW;
+    const int64_t xstride = (int64_t)a.H * a.W, wstride = (int64_t)a.O * a.KH * a.KW;
+    float acc = 0.f;
+    for (int kh = 0; kh < a.KH; ++kh) {
+        const int th = oh + a.ph - kh;
+        if (th < 0 || th % a.sh != 0 || th / a.sh >= a.H) continue;
+        const int ih = th / a.sh;
+        for (int kw = 0; kw < a.KW; ++kw) {
+            const int tw = ow + a.pw - kw;
+            if (tw < 0 || tw % a.sw != 0 || tw / a.sw >= a.W) continue;
+            const float *xp = xn + (int64_t)ih * a.W + tw / a.sw;
+            const float *wp = wo + kh * a.KW + kw;
+            for (int ci = 0; ci < a.C; ++ci) acc = fmaf(xp[ci * xstride], wp[ci * wstride], acc);
+        }
+    }
+    const int64_t off = ((int64_t)n * a.O + co) * npix + p;
+    a.y[off] = apply_steps(a.epi, acc, off, co);
+}
+
 // Depthwise convolution (one input channel per output channel), square filter KS: one output per
 // thread, taps unrolled, loads without branches (clamped addresses, masked values) so that they all
 // go out together; optional relu on the input, fused tail.
@@ -454,7 +485,7 @@ __global__ __launch_bounds__(256) void depthwise_kernel(DirectConvArgs a) {
 }
 
 bool depthwise_fast_ok(const DirectConvArgs &a) {
-    return a.G == a.C && a.O == a.C && a.KH == a.KW && (a.KH == 3 || a.KH == 5 || a.KH == 7) &&
+    return !a.transposed && a.G == a.C && a.O == a.C && a.KH == a.KW && (a.KH == 3 || a.KH == 5 || a.KH == 7) &&
            (int64_t)a.N * a.C * a.HO * a.WO < ((int64_t)1 << 31) && (int64_t)a.H * a.W < ((int64_t)1 << 31);
 }
 
@@ -474,6 +505,11 @@ int launch_direct_conv(const DirectConvArgs &a_in, void *stream) {
     const int Og = a.O / a.G;
     const int block = npix >= 256 ? 256 : (npix > 64 ? 128 : 64);
     hipStream_t s = (hipStream_t)stream;
+    if (a.transposed) {
+        if (a.G != 1 || a.O > 65535 || a.N > 65535) return (int)hipErrorInvalidValue;
+        hipLaunchKernelGGL(direct_convt_kernel, dim3((npix + block - 1) / block, a.O, a.N), dim3(block), 0, s, a);
+        return (int)hipGetLastError();
+    }
     if (Og % 4 == 0) {
         const dim3 grid((npix + block - 1) / block, a.O / 4, a.N);
         hipLaunchKernelGGL(direct_conv_kernel<4>, grid, dim3(block), 0, s, a);

@@ -165,7 +165,7 @@ int32_t check_pattern(const Context &ctx, Pattern *p) {
         break;
     }
     case FAM_DIRECT:
-        ok = ((k0 == CLG_OP_CONV2D || k0 == CLG_OP_MAX_POOL2D || k0 == CLG_OP_AVG_POOL2D || k0 == CLG_OP_MAX_POOL3D) &&
+        ok = ((k0 == CLG_OP_CONV2D || k0 == CLG_OP_CONV2D_TRANSPOSE || k0 == CLG_OP_MAX_POOL2D || k0 == CLG_OP_AVG_POOL2D || k0 == CLG_OP_MAX_POOL3D) &&
               tail_ok(1, len) && kl != CLG_OP_RESHAPE) ||
              (len == 1 && (k0 == CLG_OP_GLOBAL_AVG_POOL2D || k0 == CLG_OP_GLOBAL_AVG_POOL3D));
         break;
@@ -515,18 +515,22 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
         }
         double macs = 0;
         if (be.family == FAM_DIRECT) {
-            if (k0 != CLG_OP_CONV2D) return fail(CLG_NO_KERNEL, "direct backend runs conv2d only");
+            if (k0 != CLG_OP_CONV2D && k0 != CLG_OP_CONV2D_TRANSPOSE)
+                return fail(CLG_NO_KERNEL, "direct backend runs conv2d and conv2d_transpose only");
             DirectConvArgs &a = c.dconv;
+            a.transposed = k0 == CLG_OP_CONV2D_TRANSPOSE;
             a.N = (int)xs.d[0]; a.C = (int)xs.d[1]; a.H = (int)xs.d[2]; a.W = (int)xs.d[3];
-            a.O = (int)ws.d[0]; a.KH = (int)ws.d[2]; a.KW = (int)ws.d[3];
+            a.O = (int)ws.d[a.transposed ? 1 : 0]; a.KH = (int)ws.d[2]; a.KW = (int)ws.d[3];
             a.sh = anchor.attrs.stride[0]; a.sw = anchor.attrs.stride[1];
             a.ph = anchor.attrs.pad[0]; a.pw = anchor.attrs.pad[1];
-            a.G = anchor.attrs.groups > 0 ? anchor.attrs.groups : 1;
+            a.G = (!a.transposed && anchor.attrs.groups > 0) ? anchor.attrs.groups : 1;
             a.HO = (int)ys.d[2]; a.WO = (int)ys.d[3];
+            if (a.transposed && (a.O > 65535 || a.N > 65535))
+                return fail(CLG_NO_KERNEL, "the direct transposed convolution takes up to 65535 output channels and images");
             a.epi = epi;
             c.kind = CALL_DIRECT_CONV;
-            c.name = "direct_conv";
-            macs = (double)ys.numel() * (a.C / a.G) * a.KH * a.KW;
+            c.name = a.transposed ? "direct_convt" : "direct_conv";
+            macs = a.transposed ? (double)xs.numel() * a.O * a.KH * a.KW : (double)ys.numel() * (a.C / a.G) * a.KH * a.KW;
             c.bound = 1;
         } else {
             GemmArgs &a = c.gemm;

@@ -409,8 +409,26 @@ def test_conv2d_transpose_other_geometries(geom, backend):
     assert name.startswith("convt_rf"), name
 
 
+@pytest.mark.parametrize("geom", [(3, 2, 1), (5, 2, 2), (3, 3, 0), (5, 3, 1), (4, 2, 1), (1, 2, 0), (7, 4, 3)])
+@pytest.mark.parametrize("case", [(2, 8, 12, 5, ("bias_add", "relu")), (1, 33, 3, 9, ("bias_add", "tanh")), (3, 5, 70, 4, ())])
+def test_conv2d_transpose_of_any_geometry_in_the_direct_kernel(case, geom):
+    """Filter sizes the stride does not divide have no phase decomposition: the MFMA backends refuse
+    them and the direct kernel runs them (and every other geometry)."""
+    k, s, p = geom
+    d, pat = convt_desc(case, k=k, stride=s, pad=p)
+    name, ref = run_single_group(d, "direct", pat)
+    assert name == "direct_convt", name
+    if k % s:
+        for backend in ("igemm", "igemm_r16"):
+            s_ = clg.Session(d, [(backend, pat)], device=0)
+            with pytest.raises(clg.ClgError) as e:
+                s_.compile([i for i, m in enumerate(s_.match()) if m.n_nodes == len(d.op_nodes())])
+            assert e.value.status == "NO_KERNEL"
+            s_.close()
+
+
 # ------------------------------------------------------------- dense / bmm
-DENSE_CASES = [(128, 768, 768, ("bias_add",)), (128, 768, 3072, ("bias_add", "gelu")),
+DENSE_CASES =[(128, 768, 768, ("bias_add",)), (128, 768, 3072, ("bias_add", "gelu")),
                (128, 3072, 768, ("bias_add", "add")), (1, 2048, 1000, ("bias_add",)),
                (1, 32, 10, ("bias_add",)), (5, 100, 130, ("bias_add", "relu")), (130, 27, 70, ()),
                (70, 4096, 50, ("bias_add", "relu")), (33, 48, 40, ("bias_add", "tanh")),

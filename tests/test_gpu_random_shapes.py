@@ -1,0 +1,111 @@
+"""GPU parity on seeded random single operators at odd shapes: ragged tiles,
+non-square images and filters, unequal strides, pads up to the filter size,
+grouped and depthwise convolutions, every fused tail, each as ONE kernel under
+every kernel-variant backend that takes it, against the oracle at the
+per-operator bar.  The fixed cases of the other files cover the shapes of the
+workloads; these cover what nobody thought of.
+"""
+import numpy as np
+import pytest
+
+import workloads as wl
+from workloads.patterns import P, W
+from parity_util import run_group
+from test_gpu_real_shapes import conv_graph, BR, BAR, B_, BT
+
+pytestmark = pytest.mark.gpu
+
+TAILS = [(), B_, BR, BAR, ("relu",), BT]
+DENSE_TAILS = [(), ("bias_add",), ("bias_add", "relu"), ("bias_add", "gelu"), ("bias_add", "add"), ("bias_add", "tanh")]
+CASES_PER_SEED = 6
+
+
+def _backends():
+    import bench
+    return tuple(bench.VARIANTS) + ("direct",)
+
+
+def _run(d, pat, what):
+    import paper_2111_00655_amd as clg
+    ref, ran = None, 0
+    for be in _backends():
+        try:
+            name, ref = run_group(d, be, pat, ref=ref, what=what)
+        except clg.ClgError as e:                       # the backend has no kernel for this fused kind at all
+            assert e.status == "NO_KERNEL", (what, be, str(e))
+            continue
+        ran += name is not None
+    assert ran >= 1, (what, "no backend ran it")
+
+
+def random_conv2d(r, scale):
+    g = int(r.choice([1, 1, 1, 2, 3, 4, 8]))
+    cin, cout = g * int(r.integers(1, 24 * scale)), g * int(r.integers(1, 24 * scale))
+    if r.random() < 0.15:
+        g = cin = cout = int(r.integers(2, 40))         # depthwise
+    h, w = int(r.integers(1, 34 * min(scale, 2))), int(r.integers(1, 34 * min(scale, 2)))
+    kh, kw = (int(r.choice([1, 2, 3, 5, 7])),) * 2 if r.random() < 0.7 else (int(r.integers(1, 6)), int(r.integers(1, 6)))
+    sh, sw = (int(r.integers(1, 4)),) * 2 if r.random() < 0.8 else (int(r.integers(1, 4)), int(r.integers(1, 4)))
+    ph, pw = int(r.integers(0, kh)), int(r.integers(0, kw))
+    if h + 2 * ph < kh or w + 2 * pw < kw:
+        h, w = h + kh, w + kw
+    n = int(r.choice([1, 1, 2, 3]))
+    tail = TAILS[int(r.integers(len(TAILS)))]
+    return ("conv2d", n, cin, cout, h, w, kh, kw, sh, sw, ph, pw, g, tail), \
+        conv_graph("conv2d", r, n, cin, cout, (h, w), (kh, kw), (sh, sw), (ph, pw), tail, groups=g)
+
+
+def random_conv2d_transpose(r, scale):
+    cin, cout = int(r.integers(1, 40 * scale)), int(r.integers(1, 40 * scale))
+    h, w = int(r.integers(1, 18)), int(r.integers(1, 18))
+    k, s, p = [(4, 2, 1), (6, 3, 0), (2, 2, 0), (3, 1, 1), (4, 1, 0), (3, 2, 1), (5, 2, 2), (4, 4, 0)][int(r.integers(8))]
+    if (min(h, w) - 1) * s - 2 * p + k < 1:
+        h, w = h + 2, w + 2
+    n = int(r.choice([1, 2, 5]))
+    tail = TAILS[int(r.integers(len(TAILS)))]
+    return ("conv2d_transpose", n, cin, cout, h, w, k, s, p, tail), \
+        conv_graph("conv2d_transpose", r, n, cin, cout, (h, w), (k, k), (s, s), (p, p), tail, wscale=0.1)
+
+
+def random_conv3d(r, scale):
+    cin, cout = int(r.integers(1, 20 * scale)), int(r.integers(1, 20 * scale))
+    k = tuple(int(x) for x in r.choice([1, 3], 3))
+    sp = tuple(int(x) + kk - 1 for x, kk in zip(r.integers(1, 12, 3), k))
+    s = tuple(int(x) for x in r.integers(1, 3, 3))
+    p = tuple(int(r.integers(0, kk)) for kk in k)
+    tail = TAILS[int(r.integers(len(TAILS) - 1))]
+    return ("conv3d", cin, cout, sp, k, s, p, tail), conv_graph("conv3d", r, 1, cin, cout, sp, k, s, p, tail)
+
+
+def random_dense(r, scale):
+    m, n = int(r.integers(1, 150 * scale)), int(r.integers(1, 150 * scale))
+    k = int(r.integers(1, 80 * scale)) * int(r.choice([1, 1, 4, 16]))
+    tail = DENSE_TAILS[int(r.integers(len(DENSE_TAILS)))]
+    d = wl.GraphDesc("dense")
+    x = d.input(r.standard_normal((m, k)).astype(np.float32))
+    y = d.op("dense", [x, d.const((r.standard_normal((n, k)) * k ** -0.5).astype(np.float32))])
+    pat = P("dense", W, W)
+    for op in tail:
+        if op == "bias_add":
+            y = d.op("bias_add", [y, d.const(r.standard_normal(n).astype(np.float32))], axis=-1)
+            pat = P("bias_add", pat, W)
+        elif op == "add":
+            y = d.op("add", [y, d.input(r.standard_normal((m, n)).astype(np.float32))])
+            pat = P("add", pat, W)
+        else:
+            y = d.op(op, [y])
+            pat = P(op, pat)
+    d.mark_output(y)
+    return ("dense", m, k, n, tail), (d, pat)
+
+
+MAKERS = (random_conv2d, random_conv2d, random_dense, random_conv2d_transpose, random_conv3d, random_dense)
+
+
+@pytest.mark.parametrize("scale", [1, 6])
+@pytest.mark.parametrize("seed", range(16))
+def test_random_single_operators_under_every_backend(seed, scale):
+    for i in range(CASES_PER_SEED):
+        r = np.random.default_rng([2111, scale, seed, i])
+        what, (d, pat) = MAKERS[i % len(MAKERS)](r, scale)
+        _run(d, pat, what)

@@ -97,6 +97,7 @@ def default_registry(variants=("igemm",), sepconv=False, attention=False):
     add("direct", _tails(conv_any, [(), ("bias_add",), ("bias_add", "relu"),
                                     ("bias_add", "add"),
                                     ("bias_add", "add", "relu")]))
+    add("direct", _tails(P("conv2d_transpose", W, W), [(), ("bias_add",), ("bias_add", "relu"), ("bias_add", "tanh")]))
     add("direct", [P("max_pool2d", W), P("global_avg_pool2d", W)])
     add("direct", [P("avg_pool2d", W), P("add", P("avg_pool2d", W), W), P("add", P("max_pool2d", W), W)])
     add("direct", [P("max_pool3d", W), P("global_avg_pool3d", W)])
