@@ -109,3 +109,41 @@ def test_random_single_operators_under_every_backend(seed, scale):
         r = np.random.default_rng([2111, scale, seed, i])
         what, (d, pat) = MAKERS[i % len(MAKERS)](r, scale)
         _run(d, pat, what)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_graphs_under_searched_and_random_placements(seed):
+    """Search-then-compile-then-run on random DAGs (chains, branches, diamonds, values with several consumers):
+    the op-level search's optimum under several seeded cost tables and a handful of other covers of the match
+    list, executed and compared with the oracle; every placement of one graph must give the same outputs."""
+    import paper_2111_00655_amd as clg
+    from oracle.graph import Graph, norm_err
+    from oracle.match import enumerate_matches
+    from oracle import search
+    d = wl.random_dag(seed, n_ops=6 + seed % 9, ch=(4, 16, 20, 33)[seed % 4], image=(6, 9, 14)[seed % 3])
+    reg = wl.default_registry(("igemm", "igemm_s8_nk", "igemm_r16", "igemm_r32_w4"))
+    s = clg.Session(d, reg, device=0)
+    ms = s.match()
+    g = Graph(d)
+    ref = g.run()
+    placements = []
+    for cs in range(3):
+        costs = wl.synthetic_costs(len(ms), 131 * seed + cs, ties=(cs == 1))
+        placements.append(s.search(costs, 0)[1])
+    oms = enumerate_matches(g, reg)
+    assert len(oms) == len(ms)
+    r = np.random.default_rng([7, seed])
+    for cs in range(4):                                 # covers the search would not pick: optimum of a random table in the oracle
+        costs = [int(c) for c in r.integers(1, 1000, len(oms))]
+        placements.append(search.dp(g, reg, oms, costs, 0)[1])
+    ran = 0
+    for ids in placements:
+        plan = s.compile(ids)
+        got = plan.run()
+        ran += 1
+        for a, b in zip(got, ref):
+            assert a.shape == b.shape
+            assert norm_err(a, b) <= 1e-3, (seed, ids, plan.kernels())
+        plan.destroy()
+    assert ran == len(placements)
+    s.close()
