@@ -184,6 +184,7 @@ struct Plan {
     Graph *graph = nullptr;            // read at every execution: the graph outlives its plans, unchanged
     bool counted = false;              // this plan is among graph->live_plans
     std::vector<KernelCall> calls;
+    PlaneMultiArgs plane_args{};           // argument block of a region of thread-per-output kernels, refilled per launch
     std::vector<int64_t> value_offset;     // node -> workspace byte offset, -1 none
     std::vector<int32_t> value_output;     // node -> index in outputs[] of the buffer it lives in, -1 none
     std::vector<int64_t> value_delta;      // node -> byte offset inside that output buffer (a piece of a concatenation)

@@ -160,6 +160,24 @@ struct PoolArgs {
     Epilogue epi;                          // fused elementwise tail of a window pool
 };
 
+// ---- several thread-per-output problems in one launch (a region of sibling depthwise convolutions
+// and window pools).  kind: 3 / 5 / 7 = depthwise convolution with that filter size (p[k].dw is read),
+// 10 = max pool, 11 = average pool (p[k].pool is read); block_end is filled by the launcher.
+constexpr int kMaxPlaneRegion = 8;
+union PlaneMember {
+    DirectConvArgs dw;
+    PoolArgs pool;
+};
+struct PlaneMultiArgs {
+    int32_t n;                             // problems, 2..kMaxPlaneRegion
+    int32_t block_end[kMaxPlaneRegion];    // problem k owns workgroups block_end[k-1] .. block_end[k] - 1
+    int32_t kind[kMaxPlaneRegion];
+    int32_t pad_[3];
+    PlaneMember p[kMaxPlaneRegion];
+};
+bool plane_region_pool_ok(const PoolArgs &a);
+int launch_plane_region(const PlaneMultiArgs &m, void *stream);
+
 // ---- separable convolution in one kernel (sepconv.hip) -----------------------------------------
 // y = tail(Wp * dw(relu?(x))) with dw a depthwise KH x KW convolution (stride, pad) or, when wd is
 // null, the plain stride-sh/sw sub-sampling of a 1x1 convolution (KH = KW = 1, pad 0).

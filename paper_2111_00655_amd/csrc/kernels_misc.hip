@@ -427,10 +427,10 @@ __global__ __launch_bounds__(256) void direct_convt_kernel(DirectConvArgs a) {
 // thread, taps unrolled, loads without branches (clamped addresses, masked values) so that they all
 // go out together; optional relu on the input, fused tail.
 template <int KS>
-__global__ __launch_bounds__(256) void depthwise_kernel(DirectConvArgs a) {
+__device__ __forceinline__ void depthwise_body(const DirectConvArgs &a, const uint32_t block) {
     const uint32_t npix = (uint32_t)(a.HO * a.WO);
     const uint32_t total = (uint32_t)(a.N * a.C) * npix;
-    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    const uint32_t i = block * 256u + threadIdx.x;
     if (i >= total) return;
     const uint32_t nc = i / npix, p = i - nc * npix;
     const uint32_t c = nc % (uint32_t)a.C;
@@ -484,6 +484,11 @@ __global__ __launch_bounds__(256) void depthwise_kernel(DirectConvArgs a) {
     a.y[i] = v;
 }
 
+template <int KS>
+__global__ __launch_bounds__(256) void depthwise_kernel(DirectConvArgs a) {
+    depthwise_body<KS>(a, blockIdx.x);
+}
+
 bool depthwise_fast_ok(const DirectConvArgs &a) {
     return !a.transposed && a.G == a.C && a.O == a.C && a.KH == a.KW && (a.KH == 3 || a.KH == 5 || a.KH == 7) &&
            (int64_t)a.N * a.C * a.HO * a.WO < ((int64_t)1 << 31) && (int64_t)a.H * a.W < ((int64_t)1 << 31);
@@ -523,10 +528,10 @@ int launch_direct_conv(const DirectConvArgs &a_in, void *stream) {
 // ------------------------------------------------------------------------ pooling
 // One output pixel per thread.  AVG: mean over the window's pixels inside the image.
 template <bool AVG>
-__global__ __launch_bounds__(256) void window_pool_kernel(PoolArgs a) {
+__device__ __forceinline__ void window_pool_body(const PoolArgs &a, const uint32_t block) {
     // 32-bit index arithmetic (the launcher checks the sizes): a 64-bit division is a long routine
     const uint32_t total = (uint32_t)(a.NC * a.DO * a.HO * a.WO);
-    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    const uint32_t i = block * 256u + threadIdx.x;
     if (i >= total) return;
     const uint32_t q1 = i / (uint32_t)a.WO, q2 = q1 / (uint32_t)a.HO;
     const int ow = (int)(i - q1 * a.WO), oh = (int)(q1 - q2 * a.HO);
@@ -557,6 +562,61 @@ __global__ __launch_bounds__(256) void window_pool_kernel(PoolArgs a) {
     if (AVG) acc = cnt ? acc / (float)cnt : 0.f;
     if (a.epi.n) acc = apply_steps(a.epi, acc, i, a.epi.bias_c ? (int)((i / (uint32_t)a.epi.bias_inner) % (uint32_t)a.epi.bias_c) : 0);
     a.y[i] = acc;
+}
+
+template <bool AVG>
+__global__ __launch_bounds__(256) void window_pool_kernel(PoolArgs a) {
+    window_pool_body<AVG>(a, blockIdx.x);
+}
+
+// Several independent thread-per-output problems in one launch: the depthwise convolutions and window
+// pools that the branches of a cell apply to the same few tensors.  Workgroup -> problem by a
+// wave-uniform look-up, then exactly the code the problem runs alone (same results bit for bit).
+__global__ __launch_bounds__(256) void plane_multi_kernel(PlaneMultiArgs m) {
+    const int bx = blockIdx.x;
+    int k = 0;
+#pragma unroll
+    for (int i = 0; i + 1 < kMaxPlaneRegion; ++i) k += (i + 1 < m.n && bx >= m.block_end[i]) ? 1 : 0;
+    const uint32_t block = (uint32_t)(bx - (k ? m.block_end[k - 1] : 0));
+    switch (m.kind[k]) {
+    case 3: depthwise_body<3>(m.p[k].dw, block); break;
+    case 5: depthwise_body<5>(m.p[k].dw, block); break;
+    case 7: depthwise_body<7>(m.p[k].dw, block); break;
+    case 10: window_pool_body<false>(m.p[k].pool, block); break;
+    default: window_pool_body<true>(m.p[k].pool, block); break;
+    }
+}
+
+bool plane_region_pool_ok(const PoolArgs &a) {
+    return (a.mode == 0 || a.mode == 2) && a.D >= 1 && a.KD >= 1 && a.sd >= 1 && a.DO >= 1 &&
+           (int64_t)a.NC * a.DO * a.HO * a.WO < ((int64_t)1 << 31) && (int64_t)a.D * a.H * a.W < ((int64_t)1 << 31);
+}
+
+int launch_plane_region(const PlaneMultiArgs &m_in, void *stream) {
+    PlaneMultiArgs m = m_in;
+    if (m.n < 2 || m.n > kMaxPlaneRegion) return (int)hipErrorInvalidValue;
+    int64_t end = 0;
+    for (int k = 0; k < m.n; ++k) {
+        int64_t total;
+        if (m.kind[k] == 3 || m.kind[k] == 5 || m.kind[k] == 7) {
+            DirectConvArgs &a = m.p[k].dw;
+            if (!depthwise_fast_ok(a) || a.KH != m.kind[k]) return (int)hipErrorInvalidValue;
+            a.ef = make_epi_fast(a.epi);
+            total = (int64_t)a.N * a.C * a.HO * a.WO;
+        } else if (m.kind[k] == 10 || m.kind[k] == 11) {
+            const PoolArgs &a = m.p[k].pool;
+            if (!plane_region_pool_ok(a) || a.mode != (m.kind[k] == 10 ? 0 : 2)) return (int)hipErrorInvalidValue;
+            total = (int64_t)a.NC * a.DO * a.HO * a.WO;
+        } else {
+            return (int)hipErrorInvalidValue;
+        }
+        end += (total + 255) / 256;
+        if (end >= ((int64_t)1 << 31)) return (int)hipErrorInvalidValue;
+        m.block_end[k] = (int32_t)end;
+    }
+    for (int k = m.n; k < kMaxPlaneRegion; ++k) m.block_end[k] = (int32_t)end;
+    hipLaunchKernelGGL(plane_multi_kernel, dim3((unsigned)end), dim3(256), 0, (hipStream_t)stream, m);
+    return (int)hipGetLastError();
 }
 
 // one wave per (n, c) plane

@@ -50,17 +50,23 @@ std::vector<int32_t> operands_of(const KernelCall &c) {
 }
 
 // ---- regions (the graph-level backend, paper Sec. 4.3) -------------------------------------------
-// Whether the call runs a register-fed kernel that also exists in a several-problems-per-launch form.
-bool region_kind(const KernelCall &c) {
-    if (c.kind != CALL_GEMM || !c.gemm.rf_ts || c.gemm.splitk != 1 || !c.pack_bytes) return false;
+// Which several-problems-per-launch kernel could run the call beside siblings of the same class
+// (0: none): 1 register-fed dense, 2 register-fed 1x1 convolution, 3 thread-per-output kernels
+// (depthwise convolution with its unrolled-tap kernel, window pools).
+enum RegionClass { RC_NONE = 0, RC_DENSE = 1, RC_CONV1X1 = 2, RC_PLANE = 3 };
+int region_class(const KernelCall &c) {
+    if (c.kind == CALL_DIRECT_CONV) return depthwise_fast_ok(c.dconv) ? RC_PLANE : RC_NONE;
+    if (c.kind == CALL_POOL) return plane_region_pool_ok(c.pool) ? RC_PLANE : RC_NONE;
+    if (c.kind != CALL_GEMM || !c.gemm.rf_ts || c.gemm.splitk != 1 || !c.pack_bytes) return RC_NONE;
     const GemmArgs &a = c.gemm;
-    if (a.rf_tapk == -1) return true;                                  // dense
-    return a.rf_tapk == 1 && !a.rf_convt && !a.rf_fold;               // 1x1 convolution
+    if (a.rf_tapk == -1) return RC_DENSE;
+    return a.rf_tapk == 1 && !a.rf_convt && !a.rf_fold ? RC_CONV1X1 : RC_NONE;
 }
 
 // Lowers member `c` again for the leader's kernel shape (tile edge, K-waves per workgroup).
 bool relower_for(const Context &ctx, const KernelCall &leader, const KernelCall &c, KernelCall *out) {
     *out = c;
+    if (c.kind != CALL_GEMM) return true;                    // thread-per-output kernels: every member runs as it is
     GemmArgs &a = out->gemm;
     const int ts = leader.gemm.rf_ts, wgk = leader.gemm.rf_wgk;
     if (a.rf_ts != ts || a.rf_wgk != wgk || a.rf_nb != leader.gemm.rf_nb) {
@@ -90,11 +96,12 @@ void find_regions(const Context &ctx, const Graph &g, Plan *plan) {
     struct Found { std::vector<int32_t> members; std::vector<KernelCall> fused; };
     std::vector<Found> found;
     for (size_t i = 0; i < nc; ++i) {
-        if (reg_of[i] >= 0 || !region_kind(calls[i])) continue;
-        const bool dense = calls[i].gemm.rf_tapk == -1;
+        const int cls = region_class(calls[i]);
+        if (reg_of[i] >= 0 || cls == RC_NONE) continue;
         std::vector<int32_t> cand{(int32_t)i};
-        for (size_t j = i + 1; j < nc && cand.size() < (size_t)kMaxRegion; ++j) {
-            if (reg_of[j] >= 0 || !region_kind(calls[j]) || (calls[j].gemm.rf_tapk == -1) != dense) continue;
+        const size_t cap = cls == RC_PLANE ? (size_t)kMaxPlaneRegion : (size_t)kMaxRegion;
+        for (size_t j = i + 1; j < nc && cand.size() < cap; ++j) {
+            if (reg_of[j] >= 0 || region_class(calls[j]) != cls) continue;
             bool free = true;
             for (int32_t v : operands_of(calls[j]))
                 if (g.nodes[v].is_op() && produced_at[v] >= (int32_t)i) free = false;
@@ -675,8 +682,10 @@ int32_t execute_plan(Plan &p, const void *const *inputs, void *const *outputs, v
         if (fuse && done[i]) continue;
         if (fuse && p.region_of[i] >= 0 && p.handed[i]) {
             const Region &r = p.regions[(size_t)p.region_of[i]];
+            const bool plane = c.kind != CALL_GEMM;      // a region of thread-per-output kernels
             GemmArgs members[kMaxRegion];
-            size_t idx[kMaxRegion];
+            PlaneMultiArgs &pm = p.plane_args;           // (part of the plan: nothing this large goes on the stack per call)
+            size_t idx[kMaxPlaneRegion];
             int nm = 0;
             for (size_t k = 0; k < r.members.size(); ++k) {
                 const size_t ci = (size_t)r.members[k];
@@ -684,16 +693,35 @@ int32_t execute_plan(Plan &p, const void *const *inputs, void *const *outputs, v
                 const KernelCall &fc = r.fused[k];
                 const void *fepi[kMaxEpi];
                 for (int s = 0; s < kMaxEpi; ++s) fepi[s] = ptr_of(fc.epi_nodes[s]);
-                const void *pk = r.packed[k] ? r.packed[k] : p.packed[ci];
-                rc = bind_gemm(fc, ptr_of(fc.a_node), ptr_of(fc.b_node), const_cast<void *>(ptr_of(fc.out_node)), fepi,
-                               nullptr, pk, &members[nm]);
+                if (plane) {
+                    if (fc.kind == CALL_DIRECT_CONV) {
+                        DirectConvArgs &k2 = pm.p[nm].dw;
+                        k2 = fc.dconv;
+                        k2.x = (const float *)ptr_of(fc.a_node); k2.w = (const float *)ptr_of(fc.b_node);
+                        k2.y = (float *)const_cast<void *>(ptr_of(fc.out_node));
+                        for (int s = 0; s < k2.epi.n; ++s) k2.epi.s[s].ptr = (const float *)fepi[s];
+                        pm.kind[nm] = k2.KH;
+                    } else {
+                        PoolArgs &k2 = pm.p[nm].pool;
+                        k2 = fc.pool;
+                        k2.x = (const float *)ptr_of(fc.a_node);
+                        k2.y = (float *)const_cast<void *>(ptr_of(fc.out_node));
+                        for (int s = 0; s < k2.epi.n; ++s) k2.epi.s[s].ptr = (const float *)fepi[s];
+                        pm.kind[nm] = k2.mode == 0 ? 10 : 11;
+                    }
+                } else {
+                    const void *pk = r.packed[k] ? r.packed[k] : p.packed[ci];
+                    rc = bind_gemm(fc, ptr_of(fc.a_node), ptr_of(fc.b_node), const_cast<void *>(ptr_of(fc.out_node)), fepi,
+                                   nullptr, pk, &members[nm]);
+                }
                 if (rc != CLG_OK) break;
                 idx[nm++] = ci;
             }
             if (rc != CLG_OK) break;
             if (nm >= 2) {
                 if (kernel_ns) (void)hipEventRecord(ev[2 * i], (hipStream_t)stream);
-                const int err = launch_gemm_region(members, nm, stream);
+                pm.n = nm;
+                const int err = plane ? launch_plane_region(pm, stream) : launch_gemm_region(members, nm, stream);
                 if (kernel_ns) (void)hipEventRecord(ev[2 * i + 1], (hipStream_t)stream);
                 if (err != 0) rc = fail(CLG_HIP_ERROR, "launch of the region around %s failed: %s", c.name.c_str(),
                                         hipGetErrorString((hipError_t)err));

@@ -1001,6 +1001,62 @@ def test_region_of_sibling_1x1_convolutions(ci, backend):
     s.close()
 
 
+PLANE_REGION_CASES = [
+    # batch, channels, height, width, branches: (kind, filter, stride, relu in front, tail)
+    (1, 44, 28, 28, [("dw", 3, 1, True, ("bias_add",)), ("dw", 5, 1, True, ("bias_add",)), ("avg", 3, 1, False, ()), ("max", 3, 1, False, ("add",)),
+                     ("dw", 7, 1, False, ("bias_add", "add")), ("avg", 3, 1, False, ("add",))]),          # a cell's first stage: two regions
+    (2, 22, 15, 13, [("dw", 5, 2, True, ()), ("max", 3, 2, False, ()), ("dw", 3, 2, False, ("bias_add",))]),   # strided, ragged, batch 2
+    (1, 7, 9, 9, [("avg", 2, 1, False, ()), ("dw", 3, 1, True, ("bias_add", "add"))]),
+]
+
+
+@pytest.mark.parametrize("ci", range(len(PLANE_REGION_CASES)))
+def test_region_of_sibling_depthwise_convolutions_and_pools(ci):
+    """The thread-per-output kernels of a cell's branches (depthwise convolutions with and without a relu in front,
+    window pools with and without a fused add) that read the same tensor run as one launch per region; the outputs are
+    those of the kernels run one by one, bit for bit."""
+    from parity_util import check_outputs
+    n_img, c, h, w, branches = PLANE_REGION_CASES[ci]
+    r = rng_for(73, ci)
+    d = wl.GraphDesc("region_plane")
+    x = d.input(f32(r, n_img, c, h, w))
+    for kind, k, stride, pre, tail in branches:
+        ho, wo = (h + 2 * (k // 2) - k) // stride + 1, (w + 2 * (k // 2) - k) // stride + 1
+        if kind == "dw":
+            y = d.op("relu", [x]) if pre else x
+            y = d.op("conv2d", [y, d.const(f32(r, c, 1, k, k, scale=1.0 / k))], stride=(stride, stride), pad=(k // 2, k // 2), groups=c)
+        else:
+            y = d.op("avg_pool2d" if kind == "avg" else "max_pool2d", [x], kernel=(k, k), stride=(stride, stride), pad=(k // 2, k // 2))
+        for op in tail:
+            y = d.op("bias_add", [y, d.const(f32(r, c))], axis=1) if op == "bias_add" else d.op("add", [y, d.input(f32(r, n_img, c, ho, wo))])
+        d.mark_output(y)
+    tails = [(), ("bias_add",), ("bias_add", "add")]
+    reg = [("sepconv", tail_pattern(P("conv2d", P("relu", W), W), t)) for t in tails]
+    reg += [("direct", tail_pattern(P("conv2d", W, W), t)) for t in tails]
+    reg += [("direct", P(k, W)) for k in ("avg_pool2d", "max_pool2d")] + [("direct", P("add", P(k, W), W)) for k in ("avg_pool2d", "max_pool2d")]
+    reg += [("eltwise", P("relu", W)), ("eltwise", P("add", W, W)), ("eltwise", P("bias_add", W, W))]
+    s = clg.Session(d, reg, device=0)
+    ms = s.match()
+    _, ids = s.search([100] * len(ms), 0)                   # fewest kernels: every branch is one kernel
+    plan = s.compile(ids).bind()
+    n = plan.n_kernels
+    assert n == len(branches), [k["name"] for k in plan.kernels()]
+    regions = plan.regions()
+    assert all(g >= 0 for g in regions[:4 * (n // 4) + (n % 4 if n % 4 > 1 else 0)]), regions
+    n_regions = max(regions) + 1
+    ref = Graph(d).run()
+    plan.set_handover([0] * n, lanes=1)
+    one_by_one = plan.run()
+    check_outputs(one_by_one, ref, OP_TOL, (ci, "one by one"))
+    for digits in ([1] * n, [i % 2 for i in range(n)], [1, 1] + [0] * (n - 2), [1] * n):
+        plan.set_handover(digits, lanes=1)
+        fused_members = sum(max(sum(dg for dg, g in zip(digits, regions) if g == q) - 1, 0) for q in range(n_regions))
+        assert plan.n_launches == n - fused_members, (digits, regions, plan.n_launches)
+        got = plan.run()
+        assert all(np.array_equal(a, b) for a, b in zip(got, one_by_one)), (ci, digits)
+    s.close()
+
+
 def _random_sibling_graph(seed):
     """A random DAG over [1, C, 12, 12] tensors in which 1x1 convolutions (with bias / relu / residual tails, some
     strided), 3x3 convolutions, adds and relus read any earlier value of a fitting shape: many kernels that do not
