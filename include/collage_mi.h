@@ -443,12 +443,14 @@ int32_t clg_evolve(size_t n, const clg_es_opts *opts, const uint32_t *rand,
  *  lanes = 1  REGIONS (the paper's cross-kernel optimisation, Sec. 4.3, with
  *    our own kernels).  clg_compile groups kernels that do not depend on each
  *    other and run the same kind of kernel into regions: register-fed MFMA
- *    kernels (dense layers with constant weights; 1x1 convolutions; at most 4
+ *    kernels (dense layers with constant weights; 1x1 convolutions; at most 8
  *    per region), e.g. the query, key and value projections of an attention
  *    layer, or the projection shortcut and the first 1x1 convolution of a
- *    residual block; and thread-per-output kernels (depthwise 3x3 / 5x5 / 7x7
- *    convolutions, window pools, with their fused tails; at most 8 per region,
- *    run unchanged, bit for bit), e.g. the branches of a NasNet cell.  The
+ *    residual block; thread-per-output kernels (depthwise 3x3 / 5x5 / 7x7
+ *    convolutions, window pools, with their fused tails; at most 8 per region)
+ *    and one-kernel separable convolutions of one filter size and workgroup
+ *    size (at most 4), e.g. the branches of a NasNet cell; the latter two
+ *    kinds run unchanged inside a region, bit for bit.  The
  *    handed-over members of a region, if there are two or more, run as ONE
  *    launch of a kernel that works on several problems at once (all members in
  *    one common tile shape, that of the member with the most flops; members

@@ -43,7 +43,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // ---- common-form epilogue -------------------------------------------------------------
 // (a tail that is not in the common form is not run by these kernels: the
 // launcher sends it to the general kernel, which interprets any step list)
-__device__ __forceinline__ float finish_value(const GemmArgs &p, float v, float bias_v, float add_v) {
+__device__ __forceinline__ float finish_value(const GemmCore &p, float v, float bias_v, float add_v) {
     const int f = p.ef.flags;
     if (f & EF_SCALE) v *= p.ef.scale;
     v += bias_v;

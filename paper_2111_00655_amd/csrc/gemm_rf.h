@@ -121,7 +121,7 @@ constexpr int rf_depth() {
 }
 
 template <int TS, int TAPK, int WGK, int GEO, int PF>
-__device__ __forceinline__ void conv_rf_body(const GemmArgs &p, const int bx, const int gx) {
+__device__ __forceinline__ void conv_rf_body(const GemmCore &p, const int bx, const int gx) {
     using MF = RfMfma<TS>;
     typedef typename MF::acc_t acc_t;
     constexpr int NSLOT = MF::NSLOT, NACC = MF::NACC;
@@ -508,7 +508,7 @@ struct RfPark<16> {
 };
 
 template <int TS, int WGK>
-__device__ __forceinline__ void dense_rf_body(const GemmArgs &p, const int bx, const int gx) {
+__device__ __forceinline__ void dense_rf_body(const GemmCore &p, const int bx, const int gx) {
     using MF = RfMfma<TS>;
     using PK = RfPark<TS>;
     typedef typename MF::acc_t acc_t;
@@ -636,7 +636,7 @@ __global__ __launch_bounds__(WGK *kWave) void dense_rf_multi_kernel(RfMultiArgs 
 // shuffle are shared by two MFMAs with independent accumulators (a quarter less load traffic, half the
 // shuffles, two MFMA chains in flight).  Same packed weights, same k order, TS = 16.
 template <int WGK>
-__device__ __forceinline__ void dense_rf2_body(const GemmArgs &p, const int bx, const int gx) {
+__device__ __forceinline__ void dense_rf2_body(const GemmCore &p, const int bx, const int gx) {
     using MF = RfMfma<16>;
     using PK = RfPark<16>;
     typedef MF::acc_t acc_t;

@@ -72,7 +72,9 @@ enum GemmTile : int32_t {
     TILE_R16X2 = 8                 // register-fed dense: a wave owns two 16x16 tiles that share the activations
 };
 
-struct GemmArgs {
+// GemmCore is what a kernel reads on the device; GemmArgs adds the step list that the host turns into `ef`
+// (or that the general kernel interprets).  A region's argument block holds cores only.
+struct GemmCore {
     // The order is by who reads what: a kernel fetches its arguments with scalar loads, one cache
     // line of 64 bytes at a time, before it can do anything else, and the register-fed kernels are
     // a few microseconds long.  What they read comes first (three lines); moving the fast epilogue
@@ -113,7 +115,6 @@ struct GemmArgs {
     int32_t gemv;                          // 1: GM_NT with at most 8 rows runs the matrix-vector kernel (a wave per column)
     int32_t patch_sz;                      // 3x3 kernel: floats per channel of the LDS input patch
     int64_t strideA, strideB, strideC;     // per batch, in elements
-    Epilogue epi;
     // 3-D convolution on the register-fed kernels: one grid.y slice per (image, output depth);
     // the depth taps are folded into the channel index (channel' = c * KD + kd, Cin holds Cin * KD)
     int32_t D, KD, sd, pd, DO;             // input depth, depth taps, depth stride / padding, output depth (1, 1, 1, 0, 1 for 2-D)
@@ -123,14 +124,17 @@ struct GemmArgs {
     int64_t rf_img_stride;                 // elements between two images of x
     uint64_t rf_kd_magic;                  // floor(2^32 / KD) + 1
 };
+struct GemmArgs : GemmCore {
+    Epilogue epi;
+};
 
 // Several register-fed problems of one kernel shape in one launch (a region of sibling kernels).
-constexpr int kMaxRegion = 4;
+constexpr int kMaxRegion = 8;
 struct RfMultiArgs {
     int32_t n;                             // problems, 2..kMaxRegion
     int32_t tile_end[kMaxRegion];          // problem k owns workgroups tile_end[k-1] .. tile_end[k] - 1 of grid.x
     int32_t pad_[3];
-    GemmArgs p[kMaxRegion];
+    GemmCore p[kMaxRegion];
 };
 // Whether `a` and `b` (both resolved for a register-fed kernel) can share a launch: same kernel
 // instantiation (tile, tap mode, K-waves, geometry variant) and the same grid.y / grid.z extent.
@@ -200,6 +204,17 @@ size_t sepconv_pack_bytes(const SepConvArgs &a);
 size_t sepconv_lds_bytes(const SepConvArgs &a);
 int launch_sepconv_pack(const SepConvArgs &a, const float *w, float *dst, void *stream);
 int launch_sepconv(const SepConvArgs &a, void *stream);
+// Several separable convolutions in one launch (a region of sibling kernels): the members share the
+// kernel instantiation, i.e. sepconv_region_key (filter-size class and waves per workgroup).
+constexpr int kMaxSepRegion = 4;
+struct SepMultiArgs {
+    int32_t n;                             // problems, 2..kMaxSepRegion
+    int32_t block_end[kMaxSepRegion];      // problem k owns workgroups block_end[k-1] .. block_end[k] - 1
+    int32_t pad_[3];
+    SepConvArgs p[kMaxSepRegion];
+};
+int sepconv_region_key(const SepConvArgs &a);
+int launch_sepconv_region(const SepConvArgs *members, int n, void *stream);
 
 // ---- scaled-dot-product attention in one kernel (attention.hip) -----------------------------
 // y[h] = softmax(scale * q[h] k[h]^T) v[h]; q [B][Sq][d], k and v [B][Sk][d]; y [B][Sq][d], or with

@@ -52,9 +52,10 @@ std::vector<int32_t> operands_of(const KernelCall &c) {
 // ---- regions (the graph-level backend, paper Sec. 4.3) -------------------------------------------
 // Which several-problems-per-launch kernel could run the call beside siblings of the same class
 // (0: none): 1 register-fed dense, 2 register-fed 1x1 convolution, 3 thread-per-output kernels
-// (depthwise convolution with its unrolled-tap kernel, window pools).
-enum RegionClass { RC_NONE = 0, RC_DENSE = 1, RC_CONV1X1 = 2, RC_PLANE = 3 };
+// (depthwise convolution with its unrolled-tap kernel, window pools), 100 and up separable convolutions.
+enum RegionClass { RC_NONE = 0, RC_DENSE = 1, RC_CONV1X1 = 2, RC_PLANE = 3, RC_SEPCONV = 100 };
 int region_class(const KernelCall &c) {
+    if (c.kind == CALL_SEPCONV) return RC_SEPCONV + sepconv_region_key(c.sep);      // one class per kernel instantiation
     if (c.kind == CALL_DIRECT_CONV) return depthwise_fast_ok(c.dconv) ? RC_PLANE : RC_NONE;
     if (c.kind == CALL_POOL) return plane_region_pool_ok(c.pool) ? RC_PLANE : RC_NONE;
     if (c.kind != CALL_GEMM || !c.gemm.rf_ts || c.gemm.splitk != 1 || !c.pack_bytes) return RC_NONE;
@@ -99,7 +100,7 @@ void find_regions(const Context &ctx, const Graph &g, Plan *plan) {
         const int cls = region_class(calls[i]);
         if (reg_of[i] >= 0 || cls == RC_NONE) continue;
         std::vector<int32_t> cand{(int32_t)i};
-        const size_t cap = cls == RC_PLANE ? (size_t)kMaxPlaneRegion : (size_t)kMaxRegion;
+        const size_t cap = cls == RC_PLANE ? (size_t)kMaxPlaneRegion : (cls >= RC_SEPCONV ? (size_t)kMaxSepRegion : (size_t)kMaxRegion);
         for (size_t j = i + 1; j < nc && cand.size() < cap; ++j) {
             if (reg_of[j] >= 0 || region_class(calls[j]) != cls) continue;
             bool free = true;
@@ -682,8 +683,10 @@ int32_t execute_plan(Plan &p, const void *const *inputs, void *const *outputs, v
         if (fuse && done[i]) continue;
         if (fuse && p.region_of[i] >= 0 && p.handed[i]) {
             const Region &r = p.regions[(size_t)p.region_of[i]];
-            const bool plane = c.kind != CALL_GEMM;      // a region of thread-per-output kernels
+            const bool sep = c.kind == CALL_SEPCONV;
+            const bool plane = c.kind != CALL_GEMM && !sep;          // a region of thread-per-output kernels
             GemmArgs members[kMaxRegion];
+            SepConvArgs smembers[kMaxSepRegion];
             PlaneMultiArgs &pm = p.plane_args;           // (part of the plan: nothing this large goes on the stack per call)
             size_t idx[kMaxPlaneRegion];
             int nm = 0;
@@ -693,7 +696,15 @@ int32_t execute_plan(Plan &p, const void *const *inputs, void *const *outputs, v
                 const KernelCall &fc = r.fused[k];
                 const void *fepi[kMaxEpi];
                 for (int s = 0; s < kMaxEpi; ++s) fepi[s] = ptr_of(fc.epi_nodes[s]);
-                if (plane) {
+                if (sep) {
+                    if (!p.packed[ci]) rc = fail(CLG_INVALID_ARG, "%s needs packed weights, none were prepared", fc.name.c_str());
+                    SepConvArgs &k2 = smembers[nm];
+                    k2 = fc.sep;
+                    k2.x = (const float *)ptr_of(fc.a_node); k2.wp = (const float *)p.packed[ci];
+                    k2.wd = (const float *)ptr_of(fc.c_node);
+                    k2.y = (float *)const_cast<void *>(ptr_of(fc.out_node));
+                    for (int s = 0; s < k2.epi.n; ++s) k2.epi.s[s].ptr = (const float *)fepi[s];
+                } else if (plane) {
                     if (fc.kind == CALL_DIRECT_CONV) {
                         DirectConvArgs &k2 = pm.p[nm].dw;
                         k2 = fc.dconv;
@@ -721,7 +732,8 @@ int32_t execute_plan(Plan &p, const void *const *inputs, void *const *outputs, v
             if (nm >= 2) {
                 if (kernel_ns) (void)hipEventRecord(ev[2 * i], (hipStream_t)stream);
                 pm.n = nm;
-                const int err = plane ? launch_plane_region(pm, stream) : launch_gemm_region(members, nm, stream);
+                const int err = sep ? launch_sepconv_region(smembers, nm, stream)
+                                    : (plane ? launch_plane_region(pm, stream) : launch_gemm_region(members, nm, stream));
                 if (kernel_ns) (void)hipEventRecord(ev[2 * i + 1], (hipStream_t)stream);
                 if (err != 0) rc = fail(CLG_HIP_ERROR, "launch of the region around %s failed: %s", c.name.c_str(),
                                         hipGetErrorString((hipError_t)err));

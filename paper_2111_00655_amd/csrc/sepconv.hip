@@ -52,7 +52,7 @@ constexpr int sep_round_channels(int ks, int nw) {
 // without branches: clamped addresses, masked values), -1 = any other filter.
 // NW = 4, 8 or 16 waves per workgroup: enough threads that phase 1 is one or two rounds of loads.
 template <int KS, int NW>
-__global__ __launch_bounds__(NW * 64) void sepconv_kernel(SepConvArgs a) {
+__device__ __forceinline__ void sepconv_body(const SepConvArgs &a, const int block_x, const int block_y) {
     constexpr int kPre = KS == 0 ? 8 : 4;   // channel groups whose A operands a wave holds in registers per round
     extern __shared__ float lds[];       // B tile [cpad][16] | meeting area [waves][256] | depthwise weights [C][KS*KS]
     constexpr int nt = NW * 64, nw = NW;
@@ -79,7 +79,7 @@ __global__ __launch_bounds__(NW * 64) void sepconv_kernel(SepConvArgs a) {
     // this wave's part of phase 2, and its first A operands (in flight during phase 1)
     const int mi = wave % a.mt_per_wg, kw = wave / a.mt_per_wg;
     const int kparts = nw / a.mt_per_wg;
-    const int mt = blockIdx.y * a.mt_per_wg + mi;
+    const int mt = block_y * a.mt_per_wg + mi;
     const bool have_tile = mt < a.m_tiles;
     const int g0 = kw * a.ngroups / kparts, g1 = (kw + 1) * a.ngroups / kparts;
     const float4 *ap = reinterpret_cast<const float4 *>(a.wp) + ((int64_t)(have_tile ? mt : 0) * a.ngroups) * 64 + lane;
@@ -98,7 +98,7 @@ __global__ __launch_bounds__(NW * 64) void sepconv_kernel(SepConvArgs a) {
     float e_bias[4] = {0.f, 0.f, 0.f, 0.f}, e_add[4] = {0.f, 0.f, 0.f, 0.f};
     int64_t e_off[4] = {-1, -1, -1, -1};
     if (have_tile && kw == 0) {
-        const int p = blockIdx.x * kPix + (lane & 15);
+        const int p = block_x * kPix + (lane & 15);
         if (p < total_pix) {
             const int n_img = p / hwo, rem = p - n_img * hwo;
 #pragma unroll
@@ -115,7 +115,7 @@ __global__ __launch_bounds__(NW * 64) void sepconv_kernel(SepConvArgs a) {
     // ---- phase 1: B[c][pixel]
     {
         const int px = tid & 15;
-        const int p = blockIdx.x * kPix + px;
+        const int p = block_x * kPix + px;
         const bool valid = p < total_pix;
         const int pc = valid ? p : total_pix - 1;
         const int n_img = pc / hwo, rem = pc - n_img * hwo;
@@ -263,6 +263,26 @@ __global__ __launch_bounds__(NW * 64) void sepconv_kernel(SepConvArgs a) {
     }
 }
 
+template <int KS, int NW>
+__global__ __launch_bounds__(NW * 64) void sepconv_kernel(SepConvArgs a) {
+    sepconv_body<KS, NW>(a, blockIdx.x, blockIdx.y);
+}
+
+// Several separable convolutions of one kernel shape (filter size, waves per workgroup) in one launch:
+// sibling branches of a cell.  Workgroup -> problem by a wave-uniform look-up, then the problem's own
+// (pixel tile, channel-tile block) and exactly the code it runs alone.
+template <int KS, int NW>
+__global__ __launch_bounds__(NW * 64) void sepconv_multi_kernel(SepMultiArgs m) {
+    const int bx = blockIdx.x;
+    int k = 0;
+#pragma unroll
+    for (int i = 0; i + 1 < kMaxSepRegion; ++i) k += (i + 1 < m.n && bx >= m.block_end[i]) ? 1 : 0;
+    const int local = bx - (k ? m.block_end[k - 1] : 0);
+    const int nt = m.p[k].n_tiles;
+    const int by = local / nt;
+    sepconv_body<KS, NW>(m.p[k], local - by * nt, by);
+}
+
 }  // namespace
 
 // Launch shape for these sizes.  Waves per workgroup: as many as it takes for phase 1 to be about one
@@ -301,6 +321,47 @@ int launch_sepconv_pack(const SepConvArgs &a, const float *w, float *dst, void *
     const int64_t total = (int64_t)a.m_tiles * a.ngroups * 256;
     hipLaunchKernelGGL(sepconv_pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
                        w, dst, a.Cout, a.C, a.ngroups, total);
+    return (int)hipGetLastError();
+}
+
+static int sep_ks(const SepConvArgs &a) {
+    return !a.has_dw ? 0 : ((a.KH == a.KW && (a.KH == 3 || a.KH == 5 || a.KH == 7)) ? a.KH : -1);
+}
+
+int sepconv_region_key(const SepConvArgs &a) { return (sep_ks(a) + 1) * 100 + a.nwaves; }
+
+int launch_sepconv_region(const SepConvArgs *members, int n, void *stream) {
+    if (n < 2 || n > kMaxSepRegion) return (int)hipErrorInvalidValue;
+    SepMultiArgs m{};
+    m.n = n;
+    size_t lds = 0;
+    int64_t end = 0;
+    const int ks = sep_ks(members[0]), nw = members[0].nwaves;
+    for (int k = 0; k < n; ++k) {
+        SepConvArgs &a = m.p[k];
+        a = members[k];
+        a.ef = make_epi_fast(a.epi);
+        if (sep_ks(a) != ks || a.nwaves != nw || (a.has_dw != 0) != (a.wd != nullptr)) return (int)hipErrorInvalidValue;
+        lds = std::max(lds, sepconv_lds_bytes(a));
+        end += (int64_t)a.n_tiles * ((a.m_tiles + a.mt_per_wg - 1) / a.mt_per_wg);
+        if (end >= ((int64_t)1 << 31)) return (int)hipErrorInvalidValue;
+        m.block_end[k] = (int32_t)end;
+    }
+    for (int k = n; k < kMaxSepRegion; ++k) m.block_end[k] = (int32_t)end;
+    if (lds > 160 * 1024) return (int)hipErrorInvalidValue;
+    void (*kern)(SepMultiArgs) = nullptr;
+#define CLG_SEP_PICK(KS_, NW_) if (ks == KS_ && nw == NW_) kern = sepconv_multi_kernel<KS_, NW_>;
+    CLG_SEP_PICK(-1, 4) CLG_SEP_PICK(-1, 8) CLG_SEP_PICK(-1, 16)
+    CLG_SEP_PICK(0, 4) CLG_SEP_PICK(0, 8) CLG_SEP_PICK(0, 16)
+    CLG_SEP_PICK(3, 4) CLG_SEP_PICK(3, 8) CLG_SEP_PICK(3, 16)
+    CLG_SEP_PICK(5, 4) CLG_SEP_PICK(5, 8) CLG_SEP_PICK(7, 4) CLG_SEP_PICK(7, 8)
+#undef CLG_SEP_PICK
+    if (!kern) return (int)hipErrorInvalidValue;
+    if (lds > 64 * 1024) {
+        const hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return (int)e;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)end), dim3(nw * 64), lds, (hipStream_t)stream, m);
     return (int)hipGetLastError();
 }
 

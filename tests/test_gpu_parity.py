@@ -1057,6 +1057,64 @@ def test_region_of_sibling_depthwise_convolutions_and_pools(ci):
     s.close()
 
 
+SEP_REGION_CASES = [
+    # batch, channels, height, width, branches: (filter, stride, relu in front, output channels, tail)
+    (1, 44, 28, 28, [(3, 1, True, 44, ("bias_add",)), (3, 1, True, 44, ("bias_add", "add")), (3, 1, False, 44, ("bias_add",)), (5, 1, True, 44, ("bias_add",)),
+                     (5, 1, True, 44, ("bias_add", "relu"))]),       # three 3x3 share a launch, two 5x5 another
+    (2, 20, 9, 9, [(3, 2, True, 50, ()), (3, 2, True, 20, ("bias_add",))]),              # strided, ragged, batch 2, unequal output channels
+    (1, 176, 7, 7, [(7, 1, True, 176, ("bias_add",)), (7, 1, False, 176, ("bias_add", "add")), (3, 1, True, 176, ())]),
+]
+
+
+@pytest.mark.parametrize("ci", range(len(SEP_REGION_CASES)))
+def test_region_of_sibling_separable_convolutions(ci):
+    """One-kernel separable convolutions of a cell's branches that read the same tensor and share the kernel shape
+    (filter size, waves per workgroup) run as one launch; outputs are those of the kernels run one by one, bit for bit."""
+    from parity_util import check_outputs
+    n_img, c, h, w, branches = SEP_REGION_CASES[ci]
+    r = rng_for(74, ci)
+    d = wl.GraphDesc("region_sep")
+    x = d.input(f32(r, n_img, c, h, w))
+    for k, stride, pre, cout, tail in branches:
+        ho, wo = (h + 2 * (k // 2) - k) // stride + 1, (w + 2 * (k // 2) - k) // stride + 1
+        y = d.op("relu", [x]) if pre else x
+        y = d.op("conv2d", [y, d.const(f32(r, c, 1, k, k, scale=1.0 / k))], stride=(stride, stride), pad=(k // 2, k // 2), groups=c)
+        y = d.op("conv2d", [y, d.const(f32(r, cout, c, 1, 1, scale=c ** -0.5))], stride=(1, 1), pad=(0, 0), groups=1)
+        for op in tail:
+            if op == "bias_add":
+                y = d.op("bias_add", [y, d.const(f32(r, cout))], axis=1)
+            elif op == "add":
+                y = d.op("add", [y, d.input(f32(r, n_img, cout, ho, wo))])
+            else:
+                y = d.op(op, [y])
+        d.mark_output(y)
+    tails = [(), ("bias_add",), ("bias_add", "add"), ("bias_add", "relu")]
+    reg = [("sepconv", tail_pattern(P("conv2d", P("conv2d", P("relu", W), W), W), t)) for t in tails]
+    reg += [("sepconv", tail_pattern(P("conv2d", P("conv2d", W, W), W), t)) for t in tails]
+    reg += wl.default_registry(("igemm_s8",))
+    s = clg.Session(d, reg, device=0)
+    ms = s.match()
+    _, ids = s.search([100 if reg[m.pattern][0] == "sepconv" else 1000 * m.n_nodes for m in ms], 0)
+    plan = s.compile(ids).bind()
+    n = plan.n_kernels
+    names = [k["name"] for k in plan.kernels()]
+    assert n == len(branches) and all("sepconv" in nm for nm in names), names
+    regions = plan.regions()
+    n_regions = max(regions) + 1
+    assert n_regions >= 1, (regions, names)
+    ref = Graph(d).run()
+    plan.set_handover([0] * n, lanes=1)
+    one_by_one = plan.run()
+    check_outputs(one_by_one, ref, OP_TOL, (ci, "one by one"))
+    for digits in ([1] * n, [i % 2 for i in range(n)], [1, 1] + [0] * (n - 2), [1] * n):
+        plan.set_handover(digits, lanes=1)
+        fused_members = sum(max(sum(dg for dg, g in zip(digits, regions) if g == q) - 1, 0) for q in range(n_regions))
+        assert plan.n_launches == n - fused_members, (digits, regions, plan.n_launches)
+        got = plan.run()
+        assert all(np.array_equal(a, b) for a, b in zip(got, one_by_one)), (ci, digits)
+    s.close()
+
+
 def _random_sibling_graph(seed):
     """A random DAG over [1, C, 12, 12] tensors in which 1x1 convolutions (with bias / relu / residual tails, some
     strided), 3x3 convolutions, adds and relus read any earlier value of a fitting shape: many kernels that do not
