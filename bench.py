@@ -33,13 +33,13 @@ VARIANTS = ("igemm", "igemm_s", "igemm_s8", "igemm_s16", "igemm_m", "igemm_l", "
 
 # HBM-side traffic of the fp32 MFMA kernels of one step, from two rocprofv3 --pmc runs of this file with
 # --passes-only (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch, summed over the MFMA-kernel dispatches and divided
-# by the warm-up + steps passes of the run: ResNet-50 54 such dispatches per pass - 51 convolution launches, two of
+# by the warm-up + steps passes of the run: ResNet-50 53 such dispatches per pass - 50 convolution launches, three of
 # them regions of two, and 3 split-K reductions; BERT-base 60).  Scale factors from the 256 MiB plain device
 # copy of --calib-copy in the same runs: WRITE_SIZE read 262144.0 KiB for it (factor 1.000), FETCH_SIZE
 # 131083.5 KiB (factor 2.000).  profiles/*_pmc_summary.txt hold the runs.  The figures hold for the kernel sources
 # they were taken with; after any change to them `traffic` is reported as null.
-TRAFFIC = {"resnet50": {"sources": "64b60e4ba4347dca", "fetch_bytes": 293.81e6, "write_bytes": 46.86e6},
-           "bert_base": {"sources": "64b60e4ba4347dca", "fetch_bytes": 689.17e6, "write_bytes": 47.19e6}}
+TRAFFIC = {"resnet50": {"sources": "fc52196fa71e6787", "fetch_bytes": 290.37e6, "write_bytes": 46.87e6},
+           "bert_base": {"sources": "fc52196fa71e6787", "fetch_bytes": 689.36e6, "write_bytes": 47.19e6}}
 
 
 def kernel_sources_fingerprint():
@@ -618,7 +618,7 @@ def main():
             lines += [""]
         if graph_level_rows is not None:
             lines += ["Graph-level search (evolutionary, seeded with the op-level placement; region backend: the handed-over",
-                      "members of a region of independent register-fed kernels share one launch), ms per step before / after:",
+                      "members of a region of independent kernels of one kind share one launch), ms per step before / after:",
                       f"  {'workload':12s} {'op-level ms':>11s} {'graph-level ms':>14s} {'gain':>6s} {'launches':>9s} {'digits=1':>8s} {'strings':>7s} {'search s':>8s}"]
             for n, v in graph_level_rows.items():
                 lines.append(f"  {n:12s} {v['op_level_ms']:11.4f} {v['graph_level_ms']:14.4f} {v['op_level_ms'] / v['graph_level_ms']:6.3f} "
