@@ -1211,6 +1211,48 @@ def test_model_with_every_region_fused(name):
     s.close()
 
 
+SMALL_CELL_NETS = [dict(image=24, stem=4, filters=4, cells=1, classes=5), dict(image=40, stem=8, filters=11, cells=2, classes=7),
+                   dict(image=33, stem=6, filters=20, cells=1, classes=3, batch=2), dict(image=56, stem=16, filters=44, cells=1, classes=10)]
+
+
+@pytest.mark.parametrize("prefer", ["one_kernel", "split"])
+@pytest.mark.parametrize("ci", range(len(SMALL_CELL_NETS)))
+def test_regions_of_every_kind_on_small_cell_networks(ci, prefer):
+    """Small NasNet-A-like networks (odd sizes, batch 2) under two placements - separable convolutions as one kernel
+    each, or split into depthwise + 1x1 kernels - with all regions fused, none, and every other kernel handed over:
+    each string's outputs against the oracle, and all-zero against all-one strings to the rounding of the register-fed
+    members' common tile shape."""
+    desc = wl.nasnet_a(ci, **SMALL_CELL_NETS[ci])
+    reg = wl.default_registry(("igemm_s8", "igemm_r16"), sepconv=True)
+    s = clg.Session(desc, reg, device=0)
+    ms = s.match()
+    costs = []
+    for i, m in enumerate(ms):
+        try:
+            clg.clg_match_key(s.ctx, s.graph, i)
+        except clg.ClgError:
+            costs.append(B.COST_INF)
+            continue
+        be = reg[m.pattern][0]
+        base = {"sepconv": 30 if prefer == "one_kernel" else 3000, "igemm_r16": 40, "direct": 50}.get(be, 100)
+        costs.append(base * m.n_nodes if be != "sepconv" else base)
+    _, ids = s.search(costs, 0)
+    plan = s.compile(ids).bind()
+    n = plan.n_kernels
+    regions = plan.regions()
+    names = [k["name"] for k in plan.kernels()]
+    kinds = {("sep" if "sepconv" in names[i] else "plane" if names[i].split("_epi")[0] in
+              ("avg_pool", "max_pool", "direct_conv", "relu_dwconv3", "relu_dwconv5", "relu_dwconv7") else "mfma")
+             for i in range(n) if regions[i] >= 0}
+    assert "mfma" in kinds and ("sep" if prefer == "one_kernel" else "plane") in kinds, (kinds, sorted(set(names)))
+    ref = Graph(desc).run()
+    for digits in ([1] * n, [0] * n, [i % 2 for i in range(n)], [(i // 3) % 2 for i in range(n)], [1] * n):
+        plan.set_handover(digits, lanes=1)
+        got = plan.run()
+        assert max(norm_err(a, b) for a, b in zip(got, ref)) <= NET_TOL, (ci, prefer, digits[:8])
+    s.close()
+
+
 @pytest.mark.parametrize("name", ["resnet50", "bert_base"])
 def test_a_plan_never_reads_the_weights_it_has_packed(name):
     """What clg_plan_reads_constant reports as not read can be overwritten after clg_compile: the plan's outputs do
