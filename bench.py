@@ -28,7 +28,7 @@ PEAK_HBM_GBPS = 8000.0            # MI355X HBM3E
 # the MFMA kernel variants registered as separate backends; the search picks one per fused subgraph
 VARIANTS = ("igemm", "igemm_s", "igemm_s8", "igemm_s16", "igemm_m", "igemm_l", "igemm_s_nk", "igemm_s8_nk",
             "igemm_s16_nk", "igemm_r32", "igemm_r16", "igemm_r32_w4", "igemm_r32_w8", "igemm_r16_w4", "igemm_r16_w8",
-            "igemm_r16x2_w4", "igemm_r16x2_w8")
+            "igemm_r16x2_w4", "igemm_r16x2_w8", "igemm_r16_sk", "igemm_r16_sk_w4", "igemm_r32_sk")
 
 
 # HBM-side traffic of the fp32 MFMA kernels of one step, from two rocprofv3 --pmc runs of this file with

@@ -253,6 +253,13 @@ int32_t clg_graph_node_shape(const clg_graph *g, int32_t node, int32_t *dtype,
  *              four of them in flight at once (fewer waves to dispatch and to
  *              meet, longer MFMA chains per wave); "igemm_r32" / "igemm_r16"
  *              give every wave one chunk (up to 16 waves)
+ *   "igemm_r16_sk", "igemm_r16_sk_w4", "igemm_r32_sk"   the register-fed
+ *              convolution kernels (conv2d with one group, conv3d) with the
+ *              reduction also cut across workgroups where the output has so
+ *              few tiles that most of the chip would idle (a long K over a
+ *              few pixels): partial tiles go to the plan's workspace and a
+ *              second kernel adds them in slice order and applies the tail;
+ *              _w4: at most 4 waves per workgroup share K, so more workgroups
  *   "igemm_r16x2_w4", "igemm_r16x2_w8"   dense only: a wave owns two 16x16
  *              tiles (32 output columns, 16 rows) that share the activation
  *              operand, so that each value loaded and shuffled feeds two MFMAs

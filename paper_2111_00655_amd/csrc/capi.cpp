@@ -193,6 +193,7 @@ int32_t clg_register_backend(clg_ctx *ctx, const char *name, int32_t *backend) {
         {"igemm_r32_w4", FAM_IGEMM, TILE_R32, 1, 4}, {"igemm_r32_w8", FAM_IGEMM, TILE_R32, 1, 8},
         {"igemm_r16_w4", FAM_IGEMM, TILE_R16, 1, 4}, {"igemm_r16_w8", FAM_IGEMM, TILE_R16, 1, 8},
         {"igemm_r16x2_w4", FAM_IGEMM, TILE_R16X2, 1, 4}, {"igemm_r16x2_w8", FAM_IGEMM, TILE_R16X2, 1, 8},
+        {"igemm_r16_sk", FAM_IGEMM, TILE_R16, 0, 0}, {"igemm_r16_sk_w4", FAM_IGEMM, TILE_R16, 0, 4}, {"igemm_r32_sk", FAM_IGEMM, TILE_R32, 0, 0},
         {"igemm_s_nk", FAM_IGEMM, TILE_S, 1, 0}, {"igemm_s8_nk", FAM_IGEMM, TILE_S8, 1, 0}, {"igemm_s16_nk", FAM_IGEMM, TILE_S16, 1, 0},
         {"sepconv", FAM_SEPCONV, 0, 0, 0}, {"attention", FAM_ATTENTION, 0, 0, 0}, {"direct", FAM_DIRECT, 0, 0, 0}, {"rowwise", FAM_ROWWISE, 0, 0, 0}, {"eltwise", FAM_ELTWISE, 0, 0, 0}};
     const std::string s(name);

@@ -317,7 +317,7 @@ bool rf_resolve_dense(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves, 
     return false;
 }
 
-bool rf_resolve(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves) {
+bool rf_resolve(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves, bool split) {
     (void)n_cus;
     if (a->mode != GM_CONV || (epi_flags & EF_GENERIC)) return false;
     const int nslot = ts == 32 ? 2 : 4;
@@ -362,8 +362,16 @@ bool rf_resolve(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves) {
     a->rf_ts = ts;
     a->rf_tapk = tapk;
     a->rf_wgk = wgk;
-    a->rf_nch = (nc + wgk - 1) / wgk;
-    a->splitk = 1;
+    // K split across workgroups (grid.z) for a long reduction over few output tiles: partial tiles go to scratch
+    // memory in slice order and a second kernel adds them and applies the tail.  As long as the grid stays within
+    // two workgroups per compute unit and every wave keeps a whole chunk.
+    int splitk = 1;
+    if (split && groups == 1) {
+        const int64_t wgs = (int64_t)((a->Cout + ts - 1) / ts) * ((npix + ts - 1) / ts) * a->Nimg * a->DO;
+        while (splitk < 16 && wgs * splitk * 2 <= 512 && wgk * splitk * 2 <= nc) splitk *= 2;
+    }
+    a->rf_nch = (nc + wgk * splitk - 1) / (wgk * splitk);
+    a->splitk = splitk;
     a->rf_ngtot = wgk * a->splitk * a->rf_nch * chunk_groups(tapk);
     a->rf_nm = nm;
     a->rf_jmajor = (int64_t)a->Cin * a->H * a->W > (int64_t)a->Cout * a->K ? 1 : 0;
@@ -372,6 +380,7 @@ bool rf_resolve(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves) {
     a->rf_ts = 0;
     a->rf_convt = 0;
     a->rf_fold = 0;
+    a->splitk = 1;
     a->Cin = cin_real;
     return false;
 }

@@ -306,7 +306,7 @@ size_t gemm_scratch_bytes(const GemmArgs &a);
 // (EpiFastFlags); if so fills the rf_* fields and the split and returns true.
 // `waves` = 1, 2, 4, 8 or 16 fixes the K-waves per workgroup; 0 lets the kernel choose (one chunk of
 // MFMAs per wave, at most 16 waves); -w: as 0, but at most w waves (several chunks per wave then).
-bool rf_resolve(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves = 0);
+bool rf_resolve(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves = 0, bool split = false);
 // The same for GM_NT dense (A = activations [M,K], B = weights [N,K], no batch).
 // nb = 2 (ts = 16 only): a wave computes two weight tiles against one tile of activation rows.
 bool rf_resolve_dense(GemmArgs *a, int ts, int epi_flags, int n_cus, int waves = 0, int nb = 1);

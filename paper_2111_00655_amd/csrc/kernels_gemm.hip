@@ -435,7 +435,13 @@ int launch_gemm(const GemmArgs &a_in, void *stream) {
     hipStream_t s = (hipStream_t)stream;
     GemmArgs a = a_in;
     a.ef = make_epi_fast(a.epi);
-    if (a.rf_ts) return launch_rf_conv(a, s);
+    if (a.rf_ts) {
+        const int e = launch_rf_conv(a, s);
+        if (e || a.splitk <= 1 || a.rf_convt) return e;      // (a transposed convolution's grid.z counts phases)
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((a.c_numel + 255) / 256)), dim3(256), 0, s,
+                           a.partial, a.C, a.c_numel, a.splitk, a.epi);
+        return (int)hipGetLastError();
+    }
     if (a.gemv) {
         if (!al16(a.A) || !al16(a.B)) return (int)hipErrorInvalidValue;       // rows are read 16 bytes at a time
         hipLaunchKernelGGL(gemv_nt_kernel, dim3((unsigned)((a.N + 3) / 4)), dim3(256), 0, s, a);

@@ -596,7 +596,7 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
                 a.rf_groups = 1;
                 if ((int64_t)a.Nimg * a.DO > 65535) return fail(CLG_NO_KERNEL, "conv3d: too many (image, depth) slices");
                 if (a.KD == 1 && a.pd != 0) return fail(CLG_NO_KERNEL, "conv3d: depth padding needs more than one depth tap");
-                rf = rf_resolve(&a, a.tile == TILE_R32 ? 32 : 16, epi_fast_flags(epi), ctx.n_cus, rfw);
+                rf = rf_resolve(&a, a.tile == TILE_R32 ? 32 : 16, epi_fast_flags(epi), ctx.n_cus, rfw, !be.no_split);
                 if (!rf) return fail(CLG_NO_KERNEL, "conv3d: the register-fed kernel does not take this shape or tail");
                 c.pack_bytes = rf_pack_bytes(a);
                 c.name = "conv3d";
@@ -617,7 +617,7 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
                     a.M = a.Cout; a.N = a.Nimg * a.HO * a.WO; a.K = a.Cin * a.KH * a.KW;
                     a.lda = a.K;
                     a.rf_groups = G;
-                    rf = rf_resolve(&a, a.tile == TILE_R32 ? 32 : 16, epi_fast_flags(epi), ctx.n_cus, rfw);
+                    rf = rf_resolve(&a, a.tile == TILE_R32 ? 32 : 16, epi_fast_flags(epi), ctx.n_cus, rfw, !be.no_split);
                 }
                 if (G != 1 && !rf)
                     return fail(CLG_NO_KERNEL, "the register-fed conv runs %d groups only with constant weights, a common-form "
@@ -666,7 +666,7 @@ int32_t lower_match(const Context &ctx, const Graph &g, int32_t match_id, Kernel
                 c.name = (a.rf_tapk == -1 ? "dense_rf" + std::to_string(a.rf_ts) + (a.rf_nb == 2 ? "x2" : "")
                                           : std::string((a.rf_convt || a.rf_d2s) ? "convt_rf" : (a.D > 1 ? "conv3d_rf" : "conv_rf")) + std::to_string(a.rf_ts) + "_t" +
                                                 std::to_string(a.rf_tapk)) +
-                         "_w" + std::to_string(a.rf_wgk) + (a.cs_len ? "_split" : "");
+                         "_w" + std::to_string(a.rf_wgk) + (a.cs_len ? "_split" : "") + (a.splitk > 1 ? "_k" + std::to_string(a.splitk) : "");
             } else {
                 if (want_rf) a.tile = TILE_S8;           // what the register-fed kernels do not run goes to the LDS-tiled ones
                 gemm_resolve(&a, ctx.n_cus);

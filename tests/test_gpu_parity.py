@@ -191,6 +191,35 @@ def test_conv3d_register_fed(case, backend):
     assert name.startswith("conv3d_rf"), name
 
 
+RF_SPLIT = ("igemm_r16_sk", "igemm_r16_sk_w4", "igemm_r32_sk")
+SPLIT_K_CASES = [
+    # kind, batch, cin, cout, spatial, kernel, stride, pad, tail: long reductions over few output tiles
+    ("conv3d", 1, 512, 64, (2, 4, 4), (3, 3, 3), (1, 1, 1), (1, 1, 1), ("bias_add", "relu")),        # 3D-ResNet50's last stage, narrower
+    ("conv3d", 1, 96, 40, (3, 7, 7), (3, 3, 3), (2, 2, 2), (1, 1, 1), ("bias_add", "add", "relu")),
+    ("conv2d", 1, 512, 96, (7, 7), (3, 3), (1, 1), (1, 1), ("bias_add", "relu")),
+    ("conv2d", 2, 1024, 48, (4, 4), (1, 1), (1, 1), (0, 0), ("bias_add", "add")),
+    ("conv2d", 1, 200, 24, (5, 6), (5, 5), (1, 1), (2, 2), ("bias_add",)),                           # any-filter path
+    ("conv2d", 1, 64, 64, (56, 56), (3, 3), (1, 1), (1, 1), ("bias_add", "relu")),                   # a full grid: no split
+]
+
+
+@pytest.mark.parametrize("backend", RF_SPLIT)
+@pytest.mark.parametrize("ci", range(len(SPLIT_K_CASES)))
+def test_register_fed_convolution_with_k_split_across_workgroups(ci, backend):
+    """The register-fed kernels with the reduction cut across workgroups where the grid would otherwise leave most
+    of the chip idle: partial tiles in scratch memory, added in slice order by the reduction kernel with the tail."""
+    from test_gpu_real_shapes import conv_graph
+    from parity_util import run_group
+    kind, batch, cin, cout, sp, k, st, pd, tail = SPLIT_K_CASES[ci]
+    r = rng_for(33, ci)
+    d, pat = conv_graph(kind, r, batch, cin, cout, sp, k, st, pd, tail)
+    name, _ = run_group(d, backend, pat, what=(SPLIT_K_CASES[ci], backend))
+    assert "_rf" in name, name
+    split = "_k" in name.split("_w")[-1]
+    assert not (split and ci == 5), name
+    assert split or ci == 5 or backend != "igemm_r16_sk_w4", name      # with four K-waves every long reduction here is split
+
+
 def test_pools_3d():
     r = rng_for(32)
     d = wl.GraphDesc("maxpool3d")

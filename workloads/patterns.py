@@ -15,7 +15,8 @@ from __future__ import annotations
 W = "*"
 
 # igemm variants whose conv2d patterns carry no groups = 1 constraint
-GROUPED_CONV_BACKENDS = ("igemm_r32", "igemm_r16", "igemm_r32_w4", "igemm_r32_w8", "igemm_r16_w4", "igemm_r16_w8")
+GROUPED_CONV_BACKENDS = ("igemm_r32", "igemm_r16", "igemm_r32_w4", "igemm_r32_w8", "igemm_r16_w4", "igemm_r16_w8",
+                         "igemm_r16_sk", "igemm_r16_sk_w4", "igemm_r32_sk")
 
 # igemm variants that exist for dense layers only (registering their convolution patterns would only
 # repeat what the plain 16x16 variants do)
