@@ -33,13 +33,13 @@ VARIANTS = ("igemm", "igemm_s", "igemm_s8", "igemm_s16", "igemm_m", "igemm_l", "
 
 # HBM-side traffic of the fp32 MFMA kernels of one step, from two rocprofv3 --pmc runs of this file with
 # --passes-only (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch, summed over the MFMA-kernel dispatches and divided
-# by the warm-up + steps passes of the run: ResNet-50 53 such dispatches per pass - 50 convolution launches, three of
+# by the warm-up + steps passes of the run: ResNet-50 54 such dispatches per pass - 51 convolution launches, two of
 # them regions of two, and 3 split-K reductions; BERT-base 60).  Scale factors from the 256 MiB plain device
 # copy of --calib-copy in the same runs: WRITE_SIZE read 262144.0 KiB for it (factor 1.000), FETCH_SIZE
 # 131083.5 KiB (factor 2.000).  profiles/*_pmc_summary.txt hold the runs.  The figures hold for the kernel sources
 # they were taken with; after any change to them `traffic` is reported as null.
-TRAFFIC = {"resnet50": {"sources": "fc52196fa71e6787", "fetch_bytes": 290.37e6, "write_bytes": 46.87e6},
-           "bert_base": {"sources": "fc52196fa71e6787", "fetch_bytes": 689.36e6, "write_bytes": 47.19e6}}
+TRAFFIC = {"resnet50": {"sources": "95fd1455c2556476", "fetch_bytes": 290.96e6, "write_bytes": 45.06e6},
+           "bert_base": {"sources": "95fd1455c2556476", "fetch_bytes": 689.36e6, "write_bytes": 47.19e6}}
 
 
 def kernel_sources_fingerprint():
