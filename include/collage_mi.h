@@ -197,7 +197,9 @@ int32_t clg_destroy(clg_ctx *ctx);
  * valid until the next failing call on the thread.  Never NULL. */
 const char *clg_last_error(void);
 /* ABI version of this header (major * 100 + minor).  101: clg_es_opts.seed_ones, regions (clg_plan_set_handover
- * with lanes = 1, clg_plan_num_launches, clg_plan_region_of), clg_execute_static, clg_plan_reads_constant. */
+ * with lanes = 1, clg_plan_num_launches, clg_plan_region_of), clg_execute_static, clg_plan_reads_constant.
+ * 102 (no new symbol): backends igemm_r16_sk, igemm_r16_sk_w4, igemm_r32_sk; "direct" runs conv2d_transpose; regions
+ * of thread-per-output kernels and of separable convolutions, register-fed regions of up to 8. */
 int32_t clg_version(void);
 
 /* ---- computation graph G (Sec. 4.1: a DAG of tensor operators) ------------ */

@@ -24,7 +24,7 @@ using namespace clg;
 
 extern "C" {
 
-int32_t clg_version(void) { return 101; }
+int32_t clg_version(void) { return 102; }
 const char *clg_last_error(void) { return last_error(); }
 
 int32_t clg_create(clg_ctx **out, int32_t device) {
